@@ -1,0 +1,154 @@
+"""TEST INFRASTRUCTURE -- tolerance-aware agreement check against the oracle.
+
+The grouped head is an exactly defined computation, so a device result must
+reproduce the oracle's groups and candidate ids bit for bit wherever the
+oracle's neighbouring values are further apart than the float tolerance, and
+may differ only inside such near-ties.  Rules checked per token (tol is the
+logit tolerance, gate_tol the gate-score tolerance):
+
+  groups   position i of the device's selection holds a group whose oracle
+           score is within gate_tol of the oracle's i-th best score; the groups
+           are distinct.  If the device's groups differ from the oracle's, the
+           oracle is re-run with the device's groups forced, and the candidate
+           rules below are checked against that run.
+  (i)      every returned id has oracle logit >= z_k - tol (z_k: oracle's k-th)
+  (ii)     every id with oracle logit > z_k + tol is returned
+  (iii)    |device logit - oracle logit of the same id| <= tol
+  (iv)     device logits are non-increasing; bitwise-equal device logits are in
+           ascending id order; any inversion against the oracle's order is
+           between ids whose oracle logits differ by < tol
+  (v)      ids are distinct and belong to the token's selected groups
+  exact    if every adjacent gap among the oracle's top k+1 logits exceeds
+           2*tol, the id list must equal the oracle's exactly
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import dense as oracle_dense
+from . import grouped as oracle_grouped
+from . import logits_rows, rank_groups
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+GATE_TOL = {"bf16": 1e-4, "f32": 1e-6}
+
+
+@dataclass
+class Report:
+    tokens: int = 0
+    exact_tokens: int = 0          # tokens held to bit-exact ids
+    forced_tokens: int = 0         # tokens whose groups differed inside a near-tie
+    max_abs_err: float = 0.0
+    notes: list = field(default_factory=list)
+
+
+def _check_topk_token(m, dev_ids, dev_z, ref_ids, ref_z, next_z, oz_dev, tol, rep,
+                      member=None):
+    k = len(ref_ids)
+    zk = ref_z[k - 1]
+    assert len(dev_ids) == k
+    assert len(set(dev_ids.tolist())) == k, f"token {m}: duplicate ids {dev_ids}"
+    if member is not None:
+        assert member(dev_ids).all(), f"token {m}: id outside the selected groups {dev_ids}"
+    assert np.all(np.isfinite(dev_z)), f"token {m}: non-finite logit {dev_z}"
+    # (i)
+    assert np.all(oz_dev >= zk - tol), \
+        f"token {m}: returned id below the k-th logit by more than tol: {oz_dev} vs {zk}"
+    # (ii)
+    must = ref_ids[ref_z > zk + tol]
+    missing = np.setdiff1d(must, dev_ids)
+    assert missing.size == 0, f"token {m}: ids clearly inside the top-k missing: {missing}"
+    # (iii)
+    err = np.abs(dev_z.astype(np.float64) - oz_dev)
+    rep.max_abs_err = max(rep.max_abs_err, float(err.max()))
+    assert np.all(err <= tol), f"token {m}: logit error {err.max()} > {tol}"
+    # (iv)
+    d = np.diff(dev_z.astype(np.float64))
+    assert np.all(d <= 0), f"token {m}: logits not descending {dev_z}"
+    eq = np.nonzero(d == 0)[0]
+    for i in eq:
+        assert dev_ids[i] < dev_ids[i + 1], f"token {m}: equal logits not in id order"
+    for i in range(k):
+        for j in range(i + 1, k):
+            assert oz_dev[i] > oz_dev[j] - tol or (oz_dev[i] == oz_dev[j]), \
+                f"token {m}: order inversion beyond tol at ranks {i},{j}"
+    # exact
+    chain = np.concatenate([ref_z, [next_z]])
+    if np.all(-np.diff(chain) > 2 * tol):
+        assert np.array_equal(dev_ids, ref_ids), \
+            f"token {m}: ids differ with no near-tie: {dev_ids} vs {ref_ids}"
+        rep.exact_tokens += 1
+    rep.tokens += 1
+
+
+def check_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                  dev_ids, dev_logits, dev_sel, tol=None, gate_tol=None) -> Report:
+    tol = TOL[dtype] if tol is None else tol
+    gate_tol = GATE_TOL[dtype] if gate_tol is None else gate_tol
+    rep = Report()
+    dev_ids = np.asarray(dev_ids)
+    dev_logits = np.asarray(dev_logits)
+    dev_sel = np.asarray(dev_sel)
+    M = hidden.shape[0]
+    G = gate_W.shape[0]
+    V = lm_W.shape[0]
+    assert dev_ids.shape == (M, k) and dev_logits.shape == (M, k) and dev_sel.shape == (M, g)
+    assert dev_ids.dtype == np.int32 and dev_sel.dtype == np.int32
+    assert dev_logits.dtype == np.float32
+
+    ref = oracle_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype)
+    order = rank_groups(ref.s)
+    need_forced = False
+    for m in range(M):
+        sel = dev_sel[m]
+        assert np.all((sel >= 0) & (sel < G)), f"token {m}: group id out of range {sel}"
+        assert len(set(sel.tolist())) == g, f"token {m}: duplicate groups {sel}"
+        if np.array_equal(sel, ref.sel[m]):
+            continue
+        best = ref.s[m, order[m, :g]]
+        got = ref.s[m, sel]
+        assert np.all(np.abs(got - best) < gate_tol), \
+            f"token {m}: groups {sel} differ from {ref.sel[m]} beyond the gate tolerance"
+        rep.forced_tokens += 1
+        need_forced = True
+    if need_forced:
+        rep.notes.append("oracle re-run with the device's groups forced")
+        ref = oracle_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                             forced_sel=dev_sel)
+
+    group_of = np.empty(V, dtype=np.int32)
+    for n in range(G):
+        group_of[rows[offsets[n]:offsets[n + 1]]] = n
+    for m in range(M):
+        ids = dev_ids[m]
+        assert np.all((ids >= 0) & (ids < V)), f"token {m}: id out of range {ids}"
+        oz = logits_rows(hidden[m], lm_W, ids, dtype)
+        sel_m = dev_sel[m]
+        _check_topk_token(m, ids, dev_logits[m], ref.topk_ids[m], ref.topk_z[m],
+                          ref.next_z[m], oz, tol, rep,
+                          member=lambda i, s=sel_m: np.isin(group_of[i], s))
+    return rep
+
+
+def check_dense(hidden, lm_W, k, dtype, dev_ids, dev_logits, tol=None, tokens=None) -> Report:
+    """tokens: optional subset of token indices to check (each costs V dot products)."""
+    tol = TOL[dtype] if tol is None else tol
+    rep = Report()
+    dev_ids = np.asarray(dev_ids)
+    dev_logits = np.asarray(dev_logits)
+    M = hidden.shape[0]
+    V = lm_W.shape[0]
+    assert dev_ids.shape == (M, k) and dev_logits.shape == (M, k)
+    assert dev_ids.dtype == np.int32 and dev_logits.dtype == np.float32
+    toks = list(range(M)) if tokens is None else list(tokens)
+    sub = np.ascontiguousarray(hidden[toks])
+    ref = oracle_dense(sub, lm_W, k, dtype)
+    for i, m in enumerate(toks):
+        ids = dev_ids[m]
+        assert np.all((ids >= 0) & (ids < V)), f"token {m}: id out of range {ids}"
+        oz = logits_rows(hidden[m], lm_W, ids, dtype)
+        _check_topk_token(m, ids, dev_logits[m], ref.topk_ids[i], ref.topk_z[i],
+                          ref.next_z[i], oz, tol, rep)
+    return rep
