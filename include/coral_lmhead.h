@@ -1,0 +1,141 @@
+/*
+ * coral_lmhead.h -- C ABI of the weight-grouped LM head for a speculative-decoding
+ * draft model on AMD MI355X (gfx950).
+ *
+ * The operation is the "LM head router" of the paper's section 3.3: the LM head
+ * weight [V,H] is divided into G groups of vocabulary rows; per draft token a
+ * router scores the groups, the g best groups are activated, logits are computed
+ * over the rows of those groups only, and the k best candidates per token are
+ * handed to tree expansion (appendix "Discussion on LM Head Router", paragraph
+ * "Tree decoding").  The dense head (every row a candidate, the "N/A" row of the
+ * router ablation, Table 4) is exported beside it for comparison.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked [device] are HIP device memory, [host] ordinary host memory.
+ *   - All matrices are row-major and dense (no padding between rows).
+ *   - Ownership: the caller owns every buffer.  The library allocates nothing,
+ *     frees nothing and keeps no state between calls; inputs are only read.
+ *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns without
+ *     synchronising.  Outputs are valid once the stream reaches that point.
+ *   - Errors: every argument check is done on the host before anything is
+ *     enqueued; a call that returns a status other than CORAL_OK has enqueued
+ *     nothing.  No exceptions cross the boundary.
+ *   - Limits (reported as CORAL_ERR_UNSUPPORTED, never silently mishandled):
+ *     1 <= M <= 64, 1 <= k <= 64, 1 <= G <= 1024; H a multiple of 8 (bf16) or
+ *     of 4 (f32); hidden, gate_W and lm_W 16-byte aligned.
+ *   - NaN inputs give unspecified results.
+ */
+#ifndef CORAL_LMHEAD_H
+#define CORAL_LMHEAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CORAL_OK = 0,
+    CORAL_ERR_NULL = 1,          /* a required pointer is NULL                       */
+    CORAL_ERR_SHAPE = 2,         /* a size is out of range or inconsistent           */
+    CORAL_ERR_GROUP_INDEX = 3,   /* the group index is not a partition of 0..V-1     */
+    CORAL_ERR_UNSUPPORTED = 4,   /* valid request outside the kernels' stated limits */
+    CORAL_ERR_WORKSPACE = 5,     /* workspace missing, misaligned or too small       */
+    CORAL_ERR_HIP = 6            /* the HIP runtime refused a launch                 */
+} coral_status;
+
+/* Storage type of hidden, gate_W and lm_W (all three share it).  Products are
+ * accumulated in fp32 for both; outputs are always fp32 logits and int32 ids. */
+typedef enum {
+    CORAL_F32 = 0,
+    CORAL_BF16 = 1
+} coral_dtype;
+
+/*
+ * Partition of the vocabulary into G groups (section 3.3: "we divide the LM head
+ * equally into N groups"; here any partition in CSR form, the equal contiguous
+ * split being one case).  Group n owns vocabulary rows
+ *     group_rows[group_offsets[n] .. group_offsets[n+1])
+ * The struct itself is host memory.  The offsets are needed on both sides: the
+ * host copy sizes the launch, the device copy is read by the kernels; the two
+ * must hold the same values.
+ */
+typedef struct {
+    int32_t G;                          /* number of groups (paper's N)               */
+    const int32_t *group_offsets_host;  /* [host]   [G+1], [0] = 0, [G] = V, ascending */
+    const int32_t *group_offsets;       /* [device] [G+1], same values                */
+    const int32_t *group_rows;          /* [device] [V], a permutation of 0..V-1      */
+} coral_group_index;
+
+/* Human-readable name of a status code; never NULL. */
+const char *coral_status_string(coral_status st);
+
+/*
+ * Host-side check that (offsets, rows) is a partition of 0..V-1 into G groups
+ * (section 3.3).  Both arrays are [host].  Off the hot path: O(V) time and V
+ * bytes of temporary host memory (the only allocation the library ever makes).
+ * Returns CORAL_OK, CORAL_ERR_NULL, CORAL_ERR_SHAPE or CORAL_ERR_GROUP_INDEX.
+ */
+coral_status coral_group_index_validate(const int32_t *host_offsets,
+                                        const int32_t *host_rows, int G, int V);
+
+/*
+ * Bytes of device workspace that coral_lmhead_grouped / coral_lmhead_dense need
+ * for these sizes (pass G = g = 0 for the dense head).  The bound holds for any
+ * partition of V rows into G groups.  Returns 0 if the sizes are invalid.
+ */
+size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
+                                    coral_dtype dt);
+
+/*
+ * Grouped LM head for one draft step (section 3.3, Eq. 7 and Eq. 8; appendix
+ * "Tree decoding").  For each token m = 0..M-1:
+ *   s[m,n]   = sum_j gate_W[n,j] * hidden[m,j] (+ gate_bias[n])      n = 0..G-1
+ *              (the W2 projection of the router; the softmax of Eq. 7 is
+ *              monotone, so selection is taken on s)
+ *   sel[m,:] = the g groups with the largest s[m,.], best first; equal scores:
+ *              lower group id first
+ *   z[m,r]   = sum_j lm_W[r,j] * hidden[m,j]   for the rows r of sel[m,:] only
+ *   output   = the k largest z[m,.] among those rows, best first; equal logits:
+ *              lower vocabulary id first
+ * Weight rows of a group selected by several tokens are read once for all of
+ * them.  The logits row is never written to memory.
+ *
+ *   hidden      [device] [M,H]  draft hidden states
+ *   gate_W      [device] [G,H]  router projection (paper's W2)
+ *   gate_bias   [device] [G] fp32, or NULL for none
+ *   lm_W        [device] [V,H]  LM head weight
+ *   gi          [host]   partition, see coral_group_index
+ *   M,H,V       sizes; g active groups per token (1..G); k candidates per token
+ *               (1..64, and at most g times the smallest group's row count)
+ *   topk_ids    [device] out [M,k] int32 vocabulary ids
+ *   topk_logits [device] out [M,k] fp32 logits of those ids
+ *   sel_groups  [device] out [M,g] int32 selected groups, or NULL if not wanted
+ *   workspace   [device] at least coral_lmhead_workspace_bytes(...) bytes,
+ *               256-byte aligned; contents need not be preserved between calls,
+ *               but two calls in flight at once must not share it
+ */
+coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
+                                  const float *gate_bias, const void *lm_W,
+                                  const coral_group_index *gi, int M, int H, int V,
+                                  int g, int k, coral_dtype dt, int32_t *topk_ids,
+                                  float *topk_logits, int32_t *sel_groups,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/*
+ * Dense LM head: z[m,r] for every r = 0..V-1, then the k best per token with the
+ * same ordering rules (the no-router baseline of Table 4; the head whose latency
+ * the appendix paragraph "Backends" measures).  Arguments as above; k <= V.
+ */
+coral_status coral_lmhead_dense(const void *hidden, const void *lm_W, int M, int H,
+                                int V, int k, coral_dtype dt, int32_t *topk_ids,
+                                float *topk_logits, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CORAL_LMHEAD_H */

@@ -1,0 +1,221 @@
+"""Thin Python binding of libcoral_lmhead.so (argument marshalling only).
+
+Every step of the grouped / dense LM head (paper section 3.3 and the appendix on
+the LM head router) runs in the HIP kernels behind the C ABI declared in
+include/coral_lmhead.h.  PyTorch is used for device memory and the current
+stream, nothing else.  There is no CPU fallback: if the built library is missing
+the import of this package fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcoral_lmhead.so")
+
+CORAL_OK = 0
+CORAL_F32 = 0
+CORAL_BF16 = 1
+
+
+class CoralError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"coral_lmhead status {status}: {message}")
+        self.status = status
+
+
+class _GroupIndexStruct(ctypes.Structure):
+    _fields_ = [("G", ctypes.c_int32),
+                ("group_offsets_host", ctypes.c_void_p),
+                ("group_offsets", ctypes.c_void_p),
+                ("group_rows", ctypes.c_void_p)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    L.coral_status_string.restype = c.c_char_p
+    L.coral_status_string.argtypes = [c.c_int]
+    L.coral_group_index_validate.restype = c.c_int
+    L.coral_group_index_validate.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int]
+    L.coral_lmhead_workspace_bytes.restype = c.c_size_t
+    L.coral_lmhead_workspace_bytes.argtypes = [c.c_int] * 7
+    L.coral_lmhead_grouped.restype = c.c_int
+    L.coral_lmhead_grouped.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                       c.POINTER(_GroupIndexStruct)] + [c.c_int] * 6 + \
+                                      [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
+                                       c.c_void_p]
+    L.coral_lmhead_dense.restype = c.c_int
+    L.coral_lmhead_dense.argtypes = [c.c_void_p, c.c_void_p] + [c.c_int] * 5 + \
+                                    [c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    return L
+
+
+_L = _load()
+
+
+def coral_status_string(status: int) -> str:
+    return _L.coral_status_string(int(status)).decode()
+
+
+def _raise(status: int):
+    if status != CORAL_OK:
+        raise CoralError(status, coral_status_string(status))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return CORAL_BF16
+    if t.dtype == torch.float32:
+        return CORAL_F32
+    raise TypeError(f"hidden/gate_W/lm_W must be bfloat16 or float32, got {t.dtype}")
+
+
+def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous (row-major, no padding)")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def device_tensor(a: np.ndarray, storage: str, device="cuda") -> torch.Tensor:
+    """Upload a host array; storage 'bf16' takes uint16 bit patterns, 'f32' float32."""
+    if storage == "bf16":
+        if a.dtype != np.uint16:
+            raise TypeError("bf16 storage expects uint16 bit patterns")
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    if storage == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    raise ValueError(f"unknown storage {storage!r}")
+
+
+class GroupIndex:
+    """CSR partition of the vocabulary into groups: host offsets + device copies."""
+
+    def __init__(self, group_offsets: np.ndarray, group_rows, device="cuda", validate=True):
+        self.offsets_host = np.ascontiguousarray(group_offsets, dtype=np.int32)
+        self.G = int(self.offsets_host.size - 1)
+        if isinstance(group_rows, torch.Tensor):
+            if validate:
+                raise ValueError("validation needs the rows on the host; pass a numpy array")
+            self.rows = group_rows
+        else:
+            rows_host = np.ascontiguousarray(group_rows, dtype=np.int32)
+            if validate:
+                group_index_validate(self.offsets_host, rows_host)
+            self.rows = torch.from_numpy(rows_host).to(device)
+        self.V = int(self.rows.numel())
+        self.offsets = torch.from_numpy(self.offsets_host).to(device)
+        self._struct = _GroupIndexStruct(self.G, self.offsets_host.ctypes.data,
+                                         _dev_ptr(self.offsets, "group_offsets", torch.int32),
+                                         _dev_ptr(self.rows, "group_rows", torch.int32))
+
+    def struct(self):
+        return ctypes.byref(self._struct)
+
+
+def group_index_validate(group_offsets: np.ndarray, group_rows: np.ndarray) -> None:
+    off = np.ascontiguousarray(group_offsets, dtype=np.int32)
+    rows = np.ascontiguousarray(group_rows, dtype=np.int32)
+    _raise(_L.coral_group_index_validate(off.ctypes.data, rows.ctypes.data, off.size - 1, rows.size))
+
+
+def coral_lmhead_workspace_bytes(M: int, H: int, V: int, G: int, g: int, k: int, dt: int) -> int:
+    return int(_L.coral_lmhead_workspace_bytes(M, H, V, G, g, k, dt))
+
+
+def alloc_workspace(M, H, V, G, g, k, dt, device="cuda") -> torch.Tensor:
+    n = coral_lmhead_workspace_bytes(M, H, V, G, g, k, dt)
+    if n == 0:
+        raise ValueError("invalid sizes for the workspace")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
+                         gate_bias: Optional[torch.Tensor], lm_W: torch.Tensor, gi: GroupIndex,
+                         g: int, k: int, topk_ids: Optional[torch.Tensor] = None,
+                         topk_logits: Optional[torch.Tensor] = None,
+                         sel_groups: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None
+                         ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    dt = _dtype_code(hidden)
+    if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
+        raise TypeError("hidden, gate_W and lm_W must share one dtype")
+    if hidden.dim() != 2 or gate_W.dim() != 2 or lm_W.dim() != 2:
+        raise ValueError("hidden, gate_W and lm_W must be 2-D")
+    M, H = hidden.shape
+    V = lm_W.shape[0]
+    if lm_W.shape[1] != H or gate_W.shape != (gi.G, H) or gi.V != V:
+        raise ValueError("inconsistent shapes")
+    if gate_bias is not None and gate_bias.shape != (gi.G,):
+        raise ValueError("gate_bias must be [G]")
+    dev = hidden.device
+    if topk_ids is None:
+        topk_ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    if topk_logits is None:
+        topk_logits = torch.empty((M, k), dtype=torch.float32, device=dev)
+    if sel_groups is None:
+        sel_groups = torch.empty((M, g), dtype=torch.int32, device=dev)
+    if topk_ids.shape != (M, k) or topk_logits.shape != (M, k) or sel_groups.shape != (M, g):
+        raise ValueError("output shapes must be [M,k], [M,k], [M,g]")
+    if workspace is None:
+        workspace = alloc_workspace(M, H, V, gi.G, g, k, dt, dev)
+    st = _L.coral_lmhead_grouped(
+        _dev_ptr(hidden, "hidden"), _dev_ptr(gate_W, "gate_W"),
+        _dev_ptr(gate_bias, "gate_bias", torch.float32), _dev_ptr(lm_W, "lm_W"), gi.struct(),
+        M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
+        _dev_ptr(topk_logits, "topk_logits", torch.float32),
+        _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _raise(st)
+    return topk_ids, topk_logits, sel_groups
+
+
+def coral_lmhead_dense(hidden: torch.Tensor, lm_W: torch.Tensor, k: int,
+                       topk_ids: Optional[torch.Tensor] = None,
+                       topk_logits: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None
+                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+    dt = _dtype_code(hidden)
+    if lm_W.dtype != hidden.dtype:
+        raise TypeError("hidden and lm_W must share one dtype")
+    if hidden.dim() != 2 or lm_W.dim() != 2 or lm_W.shape[1] != hidden.shape[1]:
+        raise ValueError("inconsistent shapes")
+    M, H = hidden.shape
+    V = lm_W.shape[0]
+    dev = hidden.device
+    if topk_ids is None:
+        topk_ids = torch.empty((M, k), dtype=torch.int32, device=dev)
+    if topk_logits is None:
+        topk_logits = torch.empty((M, k), dtype=torch.float32, device=dev)
+    if topk_ids.shape != (M, k) or topk_logits.shape != (M, k):
+        raise ValueError("output shapes must be [M,k]")
+    if workspace is None:
+        workspace = alloc_workspace(M, H, V, 0, 0, k, dt, dev)
+    st = _L.coral_lmhead_dense(
+        _dev_ptr(hidden, "hidden"), _dev_ptr(lm_W, "lm_W"), M, H, V, k, dt,
+        _dev_ptr(topk_ids, "topk_ids", torch.int32),
+        _dev_ptr(topk_logits, "topk_logits", torch.float32), _dev_ptr(workspace, "workspace"),
+        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _raise(st)
+    return topk_ids, topk_logits

@@ -1,0 +1,157 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol
+the header declares, and rejects bad arguments before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2502_16880_amd as coral
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "coral_lmhead.h")
+
+OK, NULL, SHAPE, GROUP_INDEX, UNSUPPORTED, WORKSPACE, HIP = range(7)
+F32, BF16 = 0, 1
+FAKE = 0x7000_0000_1000          # never dereferenced: every check below fails before a launch
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(coral_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"coral_lmhead_grouped", "coral_lmhead_dense", "coral_lmhead_workspace_bytes",
+            "coral_group_index_validate", "coral_status_string"} <= set(names)
+    lib = ctypes.CDLL(coral.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_status_strings():
+    seen = {coral.coral_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and coral.coral_status_string(0) == "ok"
+    assert "unknown" in coral.coral_status_string(99)
+
+
+def test_group_index_validate():
+    L = coral._L
+    off = np.array([0, 3, 6], dtype=np.int32)
+    rows = np.array([5, 0, 2, 1, 4, 3], dtype=np.int32)
+    v = lambda o, r, G, V: L.coral_group_index_validate(o.ctypes.data, r.ctypes.data, G, V)
+    assert v(off, rows, 2, 6) == OK
+    assert L.coral_group_index_validate(None, rows.ctypes.data, 2, 6) == NULL
+    assert v(off, rows, 0, 6) == SHAPE
+    bad = rows.copy(); bad[0] = 0
+    assert v(off, bad, 2, 6) == GROUP_INDEX            # id 0 twice, id 5 missing
+    bad = rows.copy(); bad[1] = 6
+    assert v(off, bad, 2, 6) == GROUP_INDEX            # id out of range
+    assert v(np.array([0, 4, 3], np.int32), rows, 2, 6) == GROUP_INDEX   # not ascending / end != V
+    assert v(np.array([1, 3, 6], np.int32), rows, 2, 6) == GROUP_INDEX
+    ragged = np.array([0, 1, 6], dtype=np.int32)       # ragged groups are a valid partition
+    assert v(ragged, rows, 2, 6) == OK
+
+
+def test_workspace_bytes():
+    wb = coral.coral_lmhead_workspace_bytes
+    a = wb(1, 4096, 128256, 32, 4, 10, BF16)
+    b = wb(16, 4096, 128256, 32, 4, 10, BF16)
+    assert 0 < a < b
+    assert wb(4, 256, 8192, 0, 0, 8, F32) > 0          # dense
+    assert wb(0, 256, 8192, 16, 2, 8, F32) == 0
+    assert wb(4, 256, 8192, 16, 0, 8, F32) == 0        # G without g
+    assert wb(4, 256, 8192, 4, 5, 8, F32) == 0         # g > G
+    assert b % 256 == 0
+
+
+class Call:
+    """A grouped call with plausible arguments; tests override one at a time."""
+
+    def __init__(self):
+        self.G, self.v = 16, 512
+        self.off = (np.arange(self.G + 1) * self.v).astype(np.int32)
+        self.a = dict(hidden=FAKE, gate_W=FAKE + 0x100000, gate_bias=None, lm_W=FAKE + 0x200000,
+                      M=4, H=256, V=8192, g=2, k=8, dt=F32, ids=FAKE + 0x300000,
+                      logits=FAKE + 0x400000, sel=None, ws=FAKE + 0x500000, ws_bytes=1 << 30)
+        self.gi = coral._GroupIndexStruct(self.G, self.off.ctypes.data, FAKE + 0x600000,
+                                          FAKE + 0x700000)
+
+    def grouped(self, gi="default", **kw):
+        a = dict(self.a, **kw)
+        gip = ctypes.byref(self.gi) if gi == "default" else gi
+        return coral._L.coral_lmhead_grouped(a["hidden"], a["gate_W"], a["gate_bias"], a["lm_W"],
+                                             gip, a["M"], a["H"], a["V"], a["g"], a["k"], a["dt"],
+                                             a["ids"], a["logits"], a["sel"], a["ws"],
+                                             a["ws_bytes"], None)
+
+    def dense(self, **kw):
+        a = dict(self.a, **kw)
+        return coral._L.coral_lmhead_dense(a["hidden"], a["lm_W"], a["M"], a["H"], a["V"], a["k"],
+                                           a["dt"], a["ids"], a["logits"], a["ws"], a["ws_bytes"],
+                                           None)
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(hidden=None), NULL), (dict(gate_W=None), NULL), (dict(lm_W=None), NULL),
+    (dict(ids=None), NULL), (dict(logits=None), NULL),
+    (dict(M=0), SHAPE), (dict(k=0), SHAPE), (dict(g=0), SHAPE), (dict(g=17), SHAPE),
+    (dict(dt=7), SHAPE), (dict(V=8191), GROUP_INDEX),
+    (dict(M=65), UNSUPPORTED), (dict(k=65), UNSUPPORTED),
+    (dict(H=254), UNSUPPORTED), (dict(H=260, dt=BF16), UNSUPPORTED),
+    (dict(hidden=FAKE + 8), UNSUPPORTED), (dict(lm_W=FAKE + 4), UNSUPPORTED),
+    (dict(gate_W=FAKE + 2), UNSUPPORTED),
+    (dict(ws=None), WORKSPACE), (dict(ws=FAKE + 64), WORKSPACE), (dict(ws_bytes=1024), WORKSPACE),
+])
+def test_grouped_rejects_bad_arguments_before_any_launch(kw, want):
+    assert Call().grouped(**kw) == want
+
+
+def test_grouped_group_index_errors():
+    c = Call()
+    assert c.grouped(gi=None) == NULL
+    c.gi.group_rows = None
+    assert c.grouped() == NULL
+    c = Call()
+    c.off[3] = c.off[2] - 1                            # descending offsets
+    assert c.grouped() == GROUP_INDEX
+    c = Call()
+    c.gi.G = 2000
+    assert c.grouped(g=2) in (UNSUPPORTED, SHAPE)
+    c = Call()
+    c.off[0] = 1
+    assert c.grouped() == GROUP_INDEX
+
+
+def test_k_larger_than_the_candidate_count():
+    c = Call()
+    c.off[:] = [0, 3, 6] + list(range(7, 7 + 13)) + [8192]    # two groups of 3 rows, many of 1
+    assert c.grouped(g=2, k=3) == SHAPE                # the two smallest groups hold 2 rows
+    assert c.grouped(g=2, k=2, ws=None) == WORKSPACE   # k = 2 passes that check
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(hidden=None), NULL), (dict(lm_W=None), NULL), (dict(ids=None), NULL),
+    (dict(M=0), SHAPE), (dict(k=0), SHAPE), (dict(V=4, k=8), SHAPE),
+    (dict(M=65), UNSUPPORTED), (dict(k=65), UNSUPPORTED), (dict(H=258), UNSUPPORTED),
+    (dict(ws=None), WORKSPACE), (dict(ws_bytes=16), WORKSPACE),
+])
+def test_dense_rejects_bad_arguments_before_any_launch(kw, want):
+    assert Call().dense(**kw) == want
+
+
+def test_binding_rejects_host_tensors_and_mixed_dtypes():
+    import torch
+    h = torch.zeros(2, 64)
+    with pytest.raises(ValueError):
+        coral.coral_lmhead_dense(h, torch.zeros(128, 64), 4,
+                                 topk_ids=torch.zeros(2, 4, dtype=torch.int32),
+                                 topk_logits=torch.zeros(2, 4),
+                                 workspace=torch.zeros(1 << 20, dtype=torch.uint8))
+    with pytest.raises(TypeError):
+        coral.coral_lmhead_dense(h, torch.zeros(128, 64, dtype=torch.bfloat16), 4)
+    with pytest.raises(TypeError):
+        coral.coral_lmhead_dense(h.double(), torch.zeros(128, 64).double(), 4)

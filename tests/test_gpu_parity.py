@@ -1,0 +1,233 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 CPU oracle, on a real MI355X.
+
+Bar: groups and ids bit-exact wherever the oracle's neighbouring values are more than
+the float tolerance apart; logits within 2e-3 (bf16 storage, fp32 accumulation) or 1e-5
+(fp32 storage).  The rules are in oracle/compare.py.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from coral_inputs import CONFIGS, Head, HeadConfig, make_head, make_hidden  # noqa: E402
+from oracle import compare  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def coral():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2502_16880_amd as c
+    return c
+
+
+class DeviceHead:
+    def __init__(self, coral, head: Head):
+        c = head.cfg
+        self.head = head
+        self.gate_W = coral.device_tensor(head.gate_W, c.dtype)
+        self.lm_W = coral.device_tensor(head.lm_W, c.dtype)
+        self.bias = None if head.gate_bias is None else torch.from_numpy(head.gate_bias).cuda()
+        self.gi = coral.GroupIndex(head.group_offsets, head.group_rows)
+
+
+def run_grouped(coral, dh: DeviceHead, hidden, g, k):
+    c = dh.head.cfg
+    d_hidden = coral.device_tensor(hidden, c.dtype)
+    ids, logits, sel = coral.coral_lmhead_grouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, g, k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), logits.cpu().numpy(), sel.cpu().numpy()
+
+
+def run_dense(coral, dh: DeviceHead, hidden, k):
+    c = dh.head.cfg
+    d_hidden = coral.device_tensor(hidden, c.dtype)
+    ids, logits = coral.coral_lmhead_dense(d_hidden, dh.lm_W, k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), logits.cpu().numpy()
+
+
+def check_grouped(dh, hidden, g, k, out):
+    h = dh.head
+    return compare.check_grouped(hidden, h.gate_W, h.gate_bias, h.lm_W, h.group_offsets,
+                                 h.group_rows, g, k, h.cfg.dtype, *out)
+
+
+def check_dense(dh, hidden, k, out, tokens=None):
+    h = dh.head
+    return compare.check_dense(hidden, h.lm_W, k, h.cfg.dtype, *out, tokens=tokens)
+
+
+# ------------------------------------------------------------------ small and medium cases
+SCALED = [
+    # (config, M values): same recipe as the workload table at sizes the oracle does in
+    # seconds; group sizes leave a ragged last chunk of rows and span many workgroups
+    (CONFIGS["tiny_f32"], (4,)),
+    (CONFIGS["llama2_7b"].scaled(V=16 * 250), (1, 4, 8)),
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203), (1, 4, 8, 16)),
+    (CONFIGS["qwen25_7b"].scaled(V=32 * 297), (1, 8, 16)),
+    (CONFIGS["wide_tree"].scaled(V=64 * 126), (64,)),
+]
+
+
+@pytest.mark.parametrize("cfg,Ms", SCALED, ids=lambda x: x.name if isinstance(x, HeadConfig) else None)
+def test_scaled_configs_grouped_and_dense(coral, cfg, Ms):
+    dh = DeviceHead(coral, make_head(cfg))
+    for M in Ms:
+        for batch in (0, 1):
+            hidden = make_hidden(cfg, M, batch)
+            print(f"case {cfg.name} M={M} batch={batch}", flush=True)
+            rep = check_grouped(dh, hidden, cfg.g, cfg.k, run_grouped(coral, dh, hidden, cfg.g, cfg.k))
+            assert rep.tokens == M
+            rep = check_dense(dh, hidden, cfg.k, run_dense(coral, dh, hidden, cfg.k))
+            assert rep.tokens == M
+
+
+@pytest.mark.parametrize("dtype,H", [("bf16", 8), ("bf16", 264), ("bf16", 1032), ("f32", 4),
+                                     ("f32", 260), ("f32", 1028)])
+def test_hidden_sizes_that_do_not_fill_a_wave(coral, dtype, H):
+    cfg = HeadConfig(f"h{H}", dtype, H, 12 * 70, 12, 3, (5,), 6, 40 + H, dtype == "bf16")
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 5)
+    check_grouped(dh, hidden, cfg.g, cfg.k, run_grouped(coral, dh, hidden, cfg.g, cfg.k))
+    check_dense(dh, hidden, cfg.k, run_dense(coral, dh, hidden, cfg.k))
+
+
+@pytest.mark.parametrize("M,g,k", [(1, 1, 1), (1, 8, 64), (64, 1, 64), (3, 8, 5), (64, 8, 1),
+                                   (7, 2, 33)])
+def test_extreme_m_g_k(coral, M, g, k):
+    cfg = HeadConfig("ext", "bf16", 512, 8 * 130, 8, g, (M,), k, 77, True, bias_std=1.0)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, M)
+    check_grouped(dh, hidden, g, k, run_grouped(coral, dh, hidden, g, k))
+    check_dense(dh, hidden, k, run_dense(coral, dh, hidden, k))
+
+
+def test_all_groups_active_equals_dense_on_device(coral):
+    cfg = HeadConfig("gG", "bf16", 1024, 6 * 111, 6, 6, (9,), 12, 78, True)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 9)
+    gi, gz, _ = run_grouped(coral, dh, hidden, 6, 12)
+    di, dz = run_dense(coral, dh, hidden, 12)
+    assert np.array_equal(gi, di) and np.array_equal(gz, dz)      # same kernels, same order
+
+
+def test_ragged_and_empty_groups(coral):
+    """Any partition is accepted: groups of 1, 31, 32, 33 and 500 rows and an empty one."""
+    sizes = [1, 31, 0, 32, 33, 500, 64, 7]
+    V = sum(sizes)
+    cfg = HeadConfig("rag", "f32", 128, V, len(sizes), 3, (6,), 4, 79, False)
+    rng = np.random.default_rng(79)
+    perm = rng.permutation(V).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(len(sizes))])
+    lm_W = rng.standard_normal((V, cfg.H)).astype(np.float32) * np.float32(0.02)
+    gate_W = rng.standard_normal((len(sizes), cfg.H)).astype(np.float32) * np.float32(0.02)
+    head = Head(cfg, lm_W, gate_W, None, offsets, rows.astype(np.int32))
+    dh = DeviceHead(coral, head)
+    for batch in range(4):
+        hidden = make_hidden(cfg, 6, batch)
+        # the host check is on the g smallest groups: 0 + 1 + 7 = 8 rows >= k = 4
+        check_grouped(dh, hidden, 3, 4, run_grouped(coral, dh, hidden, 3, 4))
+    with pytest.raises(coral.CoralError):                 # 0 + 1 rows < k
+        run_grouped(coral, dh, make_hidden(cfg, 6), 2, 4)
+
+
+def test_duplicate_rows_tie_break_to_the_lower_id(coral):
+    cfg = HeadConfig("dup", "bf16", 256, 4 * 96, 4, 4, (2,), 6, 80, True)
+    head = make_head(cfg)
+    hidden = make_hidden(cfg, 2)
+    dh0 = DeviceHead(coral, head)
+    ids0, _ = run_dense(coral, dh0, hidden, 1)
+    best = int(ids0[0, 0])
+    twins = [(best + 97) % cfg.V, (best + 211) % cfg.V]
+    for t in twins:
+        head.lm_W[t] = head.lm_W[best]
+    dh = DeviceHead(coral, head)
+    ids, z = run_dense(coral, dh, hidden, 6)
+    assert ids[0, :3].tolist() == sorted([best] + twins) and z[0, 0] == z[0, 1] == z[0, 2]
+    check_dense(dh, hidden, 6, (ids, z))
+    out = run_grouped(coral, dh, hidden, 4, 6)
+    assert out[0][0, :3].tolist() == sorted([best] + twins)
+    check_grouped(dh, hidden, 4, 6, out)
+
+
+def test_equal_gate_scores_select_the_lower_group(coral):
+    cfg = HeadConfig("gt", "f32", 64, 8 * 40, 8, 3, (4,), 5, 81, False)
+    head = make_head(cfg)
+    head.gate_W[5] = head.gate_W[2]
+    head.gate_W[7] = head.gate_W[2]
+    dh = DeviceHead(coral, head)
+    hidden = make_hidden(cfg, 4)
+    out = run_grouped(coral, dh, hidden, 3, 5)
+    rep = check_grouped(dh, hidden, 3, 5, out)
+    assert rep.forced_tokens == 0                          # identical rows: identical fp32 scores
+    for row in out[2].tolist():                            # 2 before 5 before 7 whenever present
+        pos = [row.index(n) for n in (2, 5, 7) if n in row]
+        assert pos == sorted(pos)
+
+
+def test_two_runs_are_bit_identical(coral):
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 16)
+    a = run_grouped(coral, dh, hidden, cfg.g, cfg.k)
+    b = run_grouped(coral, dh, hidden, cfg.g, cfg.k)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    a = run_dense(coral, dh, hidden, cfg.k)
+    b = run_dense(coral, dh, hidden, cfg.k)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_caller_buffers_and_streams(coral):
+    """Outputs land in the caller's tensors, on the caller's stream; the workspace is reusable."""
+    cfg = CONFIGS["tiny_f32"]
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 4)
+    d_hidden = coral.device_tensor(hidden, "f32")
+    ws = coral.alloc_workspace(4, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_F32)
+    ws.fill_(0xAB)
+    ids = torch.full((4, cfg.k), -7, dtype=torch.int32, device="cuda")
+    z = torch.zeros((4, cfg.k), device="cuda")
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        for _ in range(3):
+            r = coral.coral_lmhead_grouped(d_hidden, dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                           topk_ids=ids, topk_logits=z, workspace=ws)
+    st.synchronize()
+    assert r[0] is ids and r[1] is z
+    check_grouped(dh, hidden, cfg.g, cfg.k, (ids.cpu().numpy(), z.cpu().numpy(), r[2].cpu().numpy()))
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(coral.CoralError) as e:
+        coral.coral_lmhead_dense(d_hidden, dh.lm_W, cfg.k, workspace=small)
+    assert e.value.status == 5
+
+
+# ------------------------------------------------------------------ full-size workloads
+FULL = [("llama2_7b", (1, 8)), ("llama3_8b", (1, 16)), ("qwen25_7b", (1, 16)), ("wide_tree", (64,))]
+
+
+@pytest.mark.parametrize("name,Ms", FULL)
+def test_full_size_workloads(coral, name, Ms):
+    """The benchmark's shapes and launch configuration.  The grouped head is compared in
+    full (the oracle needs g*v rows per token); the dense head on sampled tokens."""
+    cfg = CONFIGS[name]
+    print(f"generating {name}", flush=True)
+    dh = DeviceHead(coral, make_head(cfg))
+    for M in Ms:
+        hidden = make_hidden(cfg, M)
+        print(f"case {name} M={M} grouped", flush=True)
+        rep = check_grouped(dh, hidden, cfg.g, cfg.k, run_grouped(coral, dh, hidden, cfg.g, cfg.k))
+        print(f"  exact {rep.exact_tokens}/{rep.tokens} forced {rep.forced_tokens} "
+              f"max|err| {rep.max_abs_err:.2e}", flush=True)
+        assert rep.tokens == M
+        print(f"case {name} M={M} dense", flush=True)
+        toks = sorted({0, M - 1})
+        rep = check_dense(dh, hidden, cfg.k, run_dense(coral, dh, hidden, cfg.k), tokens=toks)
+        print(f"  dense exact {rep.exact_tokens}/{rep.tokens} max|err| {rep.max_abs_err:.2e}",
+              flush=True)
+    del dh
+    torch.cuda.empty_cache()
