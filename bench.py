@@ -1,0 +1,308 @@
+#!/usr/bin/env python3
+"""Benchmark of the weight-grouped LM head on one MI355X.
+
+A step is one call of coral_lmhead_grouped (gate projection, per-token top-g, logits
+over the activated groups' rows, fused top-k) on one batch of M synthetic draft hidden
+states at the Llama3-8B draft-head shape (H=4096, V=128256, 32 groups of 4008 rows,
+4 active groups per token, k=10, bf16 weights, fp32 accumulation).  All inputs are
+resident in HBM before the timed region.
+
+Protocol: a cycle of R distinct hidden batches is captured once into a HIP graph and
+replayed; consecutive batches of a cycle select disjoint groups whenever the active set
+is smaller than the last-level cache, so the weight rows come from HBM and not from the
+256 MB cache.  The roofline of the dominant kernel (the one that streams the weight
+rows) is taken from HIP events the library records around that kernel on its stream.
+The fp64 CPU oracle is timed beside it on a few of the same batches (a reported
+baseline, not a target).
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+LLC_BYTES = 256 << 20
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", default="llama3_8b")
+    ap.add_argument("--M", type=int, default=1, help="draft tokens per step of the headline line")
+    ap.add_argument("--cases", default="default",
+                    help="'default': also time the config's other M values and the dense head with "
+                         "fewer steps; 'none': headline only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eager", action="store_true", help="no HIP graph: one host call per step")
+    return ap.parse_args()
+
+
+def weight_bytes_per_elt(dtype):
+    return 2 if dtype == "bf16" else 4
+
+
+def algorithmic_bytes(cfg, M, U):
+    """Bytes one grouped step must move: the rows of the U activated groups once, the
+    row ids of those groups, the hidden states, the gate matrix and the outputs."""
+    w = weight_bytes_per_elt(cfg.dtype)
+    return (U * cfg.v * cfg.H * w + U * cfg.v * 4 + M * cfg.H * w + cfg.G * cfg.H * w
+            + M * cfg.k * 8)
+
+
+def dense_bytes(cfg, M):
+    w = weight_bytes_per_elt(cfg.dtype)
+    return cfg.V * cfg.H * w + M * cfg.H * w + M * cfg.k * 8
+
+
+class Bench:
+    def __init__(self, cfg):
+        import torch
+        import paper_2502_16880_amd as coral
+        from coral_inputs import make_head
+        self.torch, self.coral, self.cfg = torch, coral, cfg
+        t0 = time.time()
+        self.head = make_head(cfg)
+        self.gate_W = coral.device_tensor(self.head.gate_W, cfg.dtype)
+        self.lm_W = coral.device_tensor(self.head.lm_W, cfg.dtype)
+        self.bias = None if self.head.gate_bias is None else torch.from_numpy(self.head.gate_bias).cuda()
+        self.gi = coral.GroupIndex(self.head.group_offsets, self.head.group_rows)
+        self.dt = coral.CORAL_BF16 if cfg.dtype == "bf16" else coral.CORAL_F32
+        self.setup_s = time.time() - t0
+
+    # ---------------------------------------------------------------- inputs
+    def schedule(self, M, R, pool=96):
+        """R hidden batches (host array, device tensor, selected groups).  While one
+        step's active set fits the last-level cache, a batch is admitted only if its
+        groups are disjoint from those of the preceding batches that together could
+        still sit in that cache."""
+        from coral_inputs import make_hidden
+        torch, coral, cfg = self.torch, self.coral, self.cfg
+        w = weight_bytes_per_elt(cfg.dtype)
+        group_bytes = cfg.v * cfg.H * w
+        cands = []
+        for b in range(pool):
+            h = make_hidden(cfg, M, b)
+            d = coral.device_tensor(h, cfg.dtype)
+            _, _, sel = coral.coral_lmhead_grouped(d, self.gate_W, self.bias, self.lm_W, self.gi,
+                                                   cfg.g, cfg.k)
+            torch.cuda.synchronize()
+            cands.append((b, h, d, set(sel.cpu().numpy().reshape(-1).tolist())))
+            if len(cands) >= R and M * cfg.g * group_bytes > 2 * LLC_BYTES:
+                break
+        chosen, used = [], set()
+        while len(chosen) < R:
+            pick = None
+            for i, c in enumerate(cands):
+                if i in used:
+                    continue
+                recent, acc = set(), 0
+                for prev in reversed(chosen):
+                    if acc > 1.5 * LLC_BYTES:
+                        break
+                    recent |= prev[3]
+                    acc += len(prev[3]) * group_bytes
+                if not (c[3] & recent):
+                    pick = i
+                    break
+            if pick is None:                       # no disjoint batch left: take the next unused
+                pick = next(i for i in range(len(cands)) if i not in used)
+            used.add(pick)
+            chosen.append(cands[pick])
+            if len(used) == len(cands):
+                break
+        return chosen
+
+    # ---------------------------------------------------------------- timing
+    def time_grouped(self, M, steps, warmup, R=24, eager=False, event_steps=240):
+        torch, coral, cfg = self.torch, self.coral, self.cfg
+        sched = self.schedule(M, R)
+        R = len(sched)
+        ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt)
+        ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+        z = torch.empty((M, cfg.k), dtype=torch.float32, device="cuda")
+        sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+
+        def call(i, events=None):
+            coral.coral_lmhead_grouped(sched[i % R][2], self.gate_W, self.bias, self.lm_W, self.gi,
+                                       cfg.g, cfg.k, topk_ids=ids, topk_logits=z, sel_groups=sel,
+                                       workspace=ws, events=events)
+
+        total_ms = self._timed(call, steps, warmup, R, eager)
+        kernel_us = self._kernel_us(call, min(event_steps, steps))
+        U = sum(len(c[3]) for c in sched) / R
+        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms, kernel_us=kernel_us,
+                    U=U, bytes=algorithmic_bytes(cfg, M, U), batches=R, sched=sched,
+                    out=(ids, z, sel), call=call)
+
+    def time_dense(self, M, steps, warmup, eager=False, event_steps=60):
+        torch, coral, cfg = self.torch, self.coral, self.cfg
+        from coral_inputs import make_hidden
+        hs = [coral.device_tensor(make_hidden(cfg, M, b), cfg.dtype) for b in range(4)]
+        ws = coral.alloc_workspace(M, cfg.H, cfg.V, 0, 0, cfg.k, self.dt)
+        ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+        z = torch.empty((M, cfg.k), dtype=torch.float32, device="cuda")
+
+        def call(i, events=None):
+            coral.coral_lmhead_dense(hs[i % 4], self.lm_W, cfg.k, topk_ids=ids, topk_logits=z,
+                                     workspace=ws, events=events)
+
+        total_ms = self._timed(call, steps, warmup, 4, eager)
+        kernel_us = self._kernel_us(call, min(event_steps, steps))
+        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms, kernel_us=kernel_us,
+                    bytes=dense_bytes(cfg, M))
+
+    def _timed(self, call, steps, warmup, R, eager):
+        """Exactly `steps` steps between two device synchronisations; returns ms."""
+        torch = self.torch
+        for i in range(warmup):
+            call(i)
+        torch.cuda.synchronize()
+        graph = None
+        if not eager and steps >= R:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for i in range(R):
+                    call(i)
+            graph.replay()
+            torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        done = 0
+        if graph is not None:
+            for _ in range(steps // R):
+                graph.replay()
+            done = (steps // R) * R
+        for i in range(done, steps):
+            call(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    def _kernel_us(self, call, n):
+        """Average duration of the weight-streaming kernel from event pairs the library
+        records around it on the launch stream."""
+        torch = self.torch
+        pairs = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(), b.record()                 # creates the handles
+            pairs.append((a, b))
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(pairs):
+            call(i, events=(a.cuda_event, b.cuda_event))
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in pairs) * 1e3 / n
+
+
+def cpu_baseline(bench, res, budget_s=12.0):
+    """The oracle as it stands on the host cores, on the first batches of the same cycle."""
+    import oracle
+    cfg, head = bench.cfg, bench.head
+    n, t0 = 0, time.perf_counter()
+    for c in res["sched"]:
+        oracle.grouped(c[1], head.gate_W, head.gate_bias, head.lm_W, head.group_offsets,
+                       head.group_rows, cfg.g, cfg.k, cfg.dtype)
+        n += 1
+        if time.perf_counter() - t0 > budget_s or n >= 16:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": dt * 1e6 / n, "unit": "us per grouped draft step", "cores": oracle.max_threads(),
+            "kind": "oracle",
+            "sample": f"{n} full steps (batches of M={res['M']}) of the timed cycle, fp64, "
+                      f"{dt:.1f} s of CPU work"}
+
+
+def parity_spot_check(bench, res):
+    """One step of the timed configuration against the oracle (rules of oracle/compare.py)."""
+    from oracle import compare
+    torch, cfg, head = bench.torch, bench.cfg, bench.head
+    res["call"](0)
+    torch.cuda.synchronize()
+    ids, z, sel = (t.cpu().numpy() for t in res["out"])
+    rep = compare.check_grouped(res["sched"][0][1], head.gate_W, head.gate_bias, head.lm_W,
+                                head.group_offsets, head.group_rows, cfg.g, cfg.k, cfg.dtype,
+                                ids, z, sel)
+    return {"tokens": rep.tokens, "exact_tokens": rep.exact_tokens, "max_abs_err": rep.max_abs_err}
+
+
+def read_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py measures one GPU; --gpus {a.gpus} is not supported by this build "
+              "(no collectives are part of it)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from coral_inputs import CONFIGS
+    if not torch.cuda.is_available():
+        print("bench.py needs the GPU (there is no CPU fallback)", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = CONFIGS[a.config]
+    bench = Bench(cfg)
+    res = bench.time_grouped(a.M, a.steps, a.warmup, eager=a.eager)
+    gbps_step = res["bytes"] / (res["us_per_step"] * 1e-6) / 1e9
+    gbps_kernel = res["bytes"] / (res["kernel_us"] * 1e-6) / 1e9
+    workload = f"{cfg.name}_M{a.M}"
+    out = {
+        "metric": "us per grouped LM-head draft step (Llama3-8B shape)" if a.config == "llama3_8b"
+                  else f"us per grouped LM-head draft step ({cfg.name})",
+        "value": res["us_per_step"], "unit": "us", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: H={cfg.H} V={cfg.V} G={cfg.G}x{cfg.v} g={cfg.g} "
+                               f"M={a.M} k={cfg.k}, rotating cycle of {res['batches']} hidden batches",
+                   "avg_activated_groups": res["U"], "graph": not a.eager},
+        "achieved_GBps_whole_step": gbps_step,
+        "roofline": {"bound": "hbm", "kernel": "k_logits (weight-row streaming + fused top-k)",
+                     "achieved": gbps_kernel, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps_kernel / HBM_PEAK_GBPS, "kernel_us": res["kernel_us"],
+                     "algorithmic_bytes": res["bytes"],
+                     "traffic": read_traffic("k_logits", workload)},
+        "parity": parity_spot_check(bench, res),
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(bench, res)
+    if a.cases == "default":
+        cases = []
+        n = max(48, a.steps // 10)
+        for M in cfg.Ms:
+            if M == a.M:
+                continue
+            r = bench.time_grouped(M, n, min(a.warmup, 20), eager=a.eager, event_steps=48)
+            cases.append({"path": "grouped", "M": M, "us_per_step": r["us_per_step"],
+                          "kernel_us": r["kernel_us"], "avg_activated_groups": r["U"],
+                          "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
+                          "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        for M in sorted({1, max(cfg.Ms)}):
+            r = bench.time_dense(M, max(24, n // 4), 4, eager=a.eager, event_steps=24)
+            cases.append({"path": "dense", "M": M, "us_per_step": r["us_per_step"],
+                          "kernel_us": r["kernel_us"],
+                          "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
+                          "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        out["cases"] = cases
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

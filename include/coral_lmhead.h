@@ -135,6 +135,32 @@ coral_status coral_lmhead_dense(const void *hidden, const void *lm_W, int M, int
                                 float *topk_logits, void *workspace,
                                 size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement variants: identical to coral_lmhead_grouped / coral_lmhead_dense
+ * (same operation of section 3.3, same arguments, same results), and in addition
+ * record two caller-created HIP events (hipEvent_t passed as void*, created with
+ * timing enabled) on hip_stream: ev_before immediately before and ev_after
+ * immediately after the launch of the kernel that streams the LM-head weight rows,
+ * which is where the appendix paragraph "Backends" locates the head's time.
+ * hipEventElapsedTime(ev_before, ev_after) after synchronisation gives that
+ * kernel's duration.  Both events are required (CORAL_ERR_NULL otherwise).
+ */
+coral_status coral_lmhead_grouped_profiled(const void *hidden, const void *gate_W,
+                                           const float *gate_bias, const void *lm_W,
+                                           const coral_group_index *gi, int M, int H,
+                                           int V, int g, int k, coral_dtype dt,
+                                           int32_t *topk_ids, float *topk_logits,
+                                           int32_t *sel_groups, void *workspace,
+                                           size_t workspace_bytes, void *hip_stream,
+                                           void *ev_before, void *ev_after);
+
+coral_status coral_lmhead_dense_profiled(const void *hidden, const void *lm_W, int M,
+                                         int H, int V, int k, coral_dtype dt,
+                                         int32_t *topk_ids, float *topk_logits,
+                                         void *workspace, size_t workspace_bytes,
+                                         void *hip_stream, void *ev_before,
+                                         void *ev_after);
+
 #ifdef __cplusplus
 }
 #endif

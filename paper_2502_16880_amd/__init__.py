@@ -57,6 +57,10 @@ def _load():
     L.coral_lmhead_dense.restype = c.c_int
     L.coral_lmhead_dense.argtypes = [c.c_void_p, c.c_void_p] + [c.c_int] * 5 + \
                                     [c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.coral_lmhead_grouped_profiled.restype = c.c_int
+    L.coral_lmhead_grouped_profiled.argtypes = L.coral_lmhead_grouped.argtypes + [c.c_void_p] * 2
+    L.coral_lmhead_dense_profiled.restype = c.c_int
+    L.coral_lmhead_dense_profiled.argtypes = L.coral_lmhead_dense.argtypes + [c.c_void_p] * 2
     return L
 
 
@@ -156,8 +160,9 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
                          g: int, k: int, topk_ids: Optional[torch.Tensor] = None,
                          topk_logits: Optional[torch.Tensor] = None,
                          sel_groups: Optional[torch.Tensor] = None,
-                         workspace: Optional[torch.Tensor] = None, stream=None
+                         workspace: Optional[torch.Tensor] = None, stream=None, events=None
                          ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry."""
     dt = _dtype_code(hidden)
     if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
         raise TypeError("hidden, gate_W and lm_W must share one dtype")
@@ -180,13 +185,16 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
         raise ValueError("output shapes must be [M,k], [M,k], [M,g]")
     if workspace is None:
         workspace = alloc_workspace(M, H, V, gi.G, g, k, dt, dev)
-    st = _L.coral_lmhead_grouped(
-        _dev_ptr(hidden, "hidden"), _dev_ptr(gate_W, "gate_W"),
-        _dev_ptr(gate_bias, "gate_bias", torch.float32), _dev_ptr(lm_W, "lm_W"), gi.struct(),
-        M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
-        _dev_ptr(topk_logits, "topk_logits", torch.float32),
-        _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    args = (_dev_ptr(hidden, "hidden"), _dev_ptr(gate_W, "gate_W"),
+            _dev_ptr(gate_bias, "gate_bias", torch.float32), _dev_ptr(lm_W, "lm_W"), gi.struct(),
+            M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
+            _dev_ptr(topk_logits, "topk_logits", torch.float32),
+            _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if events is None:
+        st = _L.coral_lmhead_grouped(*args)
+    else:
+        st = _L.coral_lmhead_grouped_profiled(*args, events[0], events[1])
     _raise(st)
     return topk_ids, topk_logits, sel_groups
 
@@ -194,7 +202,7 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
 def coral_lmhead_dense(hidden: torch.Tensor, lm_W: torch.Tensor, k: int,
                        topk_ids: Optional[torch.Tensor] = None,
                        topk_logits: Optional[torch.Tensor] = None,
-                       workspace: Optional[torch.Tensor] = None, stream=None
+                       workspace: Optional[torch.Tensor] = None, stream=None, events=None
                        ) -> Tuple[torch.Tensor, torch.Tensor]:
     dt = _dtype_code(hidden)
     if lm_W.dtype != hidden.dtype:
@@ -212,10 +220,13 @@ def coral_lmhead_dense(hidden: torch.Tensor, lm_W: torch.Tensor, k: int,
         raise ValueError("output shapes must be [M,k]")
     if workspace is None:
         workspace = alloc_workspace(M, H, V, 0, 0, k, dt, dev)
-    st = _L.coral_lmhead_dense(
-        _dev_ptr(hidden, "hidden"), _dev_ptr(lm_W, "lm_W"), M, H, V, k, dt,
-        _dev_ptr(topk_ids, "topk_ids", torch.int32),
-        _dev_ptr(topk_logits, "topk_logits", torch.float32), _dev_ptr(workspace, "workspace"),
-        workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    args = (_dev_ptr(hidden, "hidden"), _dev_ptr(lm_W, "lm_W"), M, H, V, k, dt,
+            _dev_ptr(topk_ids, "topk_ids", torch.int32),
+            _dev_ptr(topk_logits, "topk_logits", torch.float32), _dev_ptr(workspace, "workspace"),
+            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if events is None:
+        st = _L.coral_lmhead_dense(*args)
+    else:
+        st = _L.coral_lmhead_dense_profiled(*args, events[0], events[1])
     _raise(st)
     return topk_ids, topk_logits

@@ -580,13 +580,19 @@ extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g
     return make_layout(M, V, G, g, k).total;
 }
 
-extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gate_W,
-                                             const float* gate_bias, const void* lm_W,
-                                             const coral_group_index* gi, int M, int H, int V,
-                                             int g, int k, coral_dtype dt, int32_t* topk_ids,
-                                             float* topk_logits, int32_t* sel_groups,
-                                             void* workspace, size_t workspace_bytes,
-                                             void* hip_stream) {
+namespace {
+
+coral_status record(void* ev, hipStream_t stream) {
+    if (!ev) return CORAL_OK;
+    return hipEventRecord(static_cast<hipEvent_t>(ev), stream) == hipSuccess ? CORAL_OK
+                                                                             : CORAL_ERR_HIP;
+}
+
+coral_status grouped_impl(const void* hidden, const void* gate_W, const float* gate_bias,
+                          const void* lm_W, const coral_group_index* gi, int M, int H, int V,
+                          int g, int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits,
+                          int32_t* sel_groups, void* workspace, size_t workspace_bytes,
+                          void* hip_stream, void* ev_before, void* ev_after) {
     if (!gate_W || !gi) return CORAL_ERR_NULL;
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
@@ -668,6 +674,7 @@ extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gat
     const long long max_union = (long long)M * g < G ? (long long)M * g : G;
     if (chunks < 1) return CORAL_ERR_SHAPE;
     dim3 grid(chunks, (unsigned)max_union);
+    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     if (bf16) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<true, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -680,15 +687,16 @@ extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gat
         hipLaunchKernelGGL((k_logits<false, false>), grid, dim3(kBlock), lds, stream, p);
     }
     if ((st = launch_status()) != CORAL_OK) return st;
+    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
                        gi->group_offsets, g, 0, k, topk_ids, topk_logits);
     return launch_status();
 }
 
-extern "C" coral_status coral_lmhead_dense(const void* hidden, const void* lm_W, int M, int H,
-                                           int V, int k, coral_dtype dt, int32_t* topk_ids,
-                                           float* topk_logits, void* workspace,
-                                           size_t workspace_bytes, void* hip_stream) {
+coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int V, int k,
+                        coral_dtype dt, int32_t* topk_ids, float* topk_logits, void* workspace,
+                        size_t workspace_bytes, void* hip_stream, void* ev_before,
+                        void* ev_after) {
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
     if (k > V) return CORAL_ERR_SHAPE;
@@ -711,6 +719,7 @@ extern "C" coral_status coral_lmhead_dense(const void* hidden, const void* lm_W,
     const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);
     if (lds > 160 * 1024) return CORAL_ERR_UNSUPPORTED;
     const int chunks = (V + kChunkRows - 1) / kChunkRows;
+    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     if (bf16) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<true, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
@@ -723,8 +732,53 @@ extern "C" coral_status coral_lmhead_dense(const void* hidden, const void* lm_W,
         hipLaunchKernelGGL((k_logits<false, true>), dim3(chunks), dim3(kBlock), lds, stream, p);
     }
     if ((st = launch_status()) != CORAL_OK) return st;
+    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, p.part, L.part_stride,
                        (const int32_t*)nullptr, (const int32_t*)nullptr, 0, chunks, k, topk_ids,
                        topk_logits);
     return launch_status();
+}
+
+}  // namespace
+
+extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gate_W,
+                                             const float* gate_bias, const void* lm_W,
+                                             const coral_group_index* gi, int M, int H, int V,
+                                             int g, int k, coral_dtype dt, int32_t* topk_ids,
+                                             float* topk_logits, int32_t* sel_groups,
+                                             void* workspace, size_t workspace_bytes,
+                                             void* hip_stream) {
+    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
+                        nullptr);
+}
+
+extern "C" coral_status coral_lmhead_grouped_profiled(
+    const void* hidden, const void* gate_W, const float* gate_bias, const void* lm_W,
+    const coral_group_index* gi, int M, int H, int V, int g, int k, coral_dtype dt,
+    int32_t* topk_ids, float* topk_logits, int32_t* sel_groups, void* workspace,
+    size_t workspace_bytes, void* hip_stream, void* ev_before, void* ev_after) {
+    if (!ev_before || !ev_after) return CORAL_ERR_NULL;
+    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, ev_before,
+                        ev_after);
+}
+
+extern "C" coral_status coral_lmhead_dense(const void* hidden, const void* lm_W, int M, int H,
+                                           int V, int k, coral_dtype dt, int32_t* topk_ids,
+                                           float* topk_logits, void* workspace,
+                                           size_t workspace_bytes, void* hip_stream) {
+    return dense_impl(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits, workspace,
+                      workspace_bytes, hip_stream, nullptr, nullptr);
+}
+
+extern "C" coral_status coral_lmhead_dense_profiled(const void* hidden, const void* lm_W, int M,
+                                                    int H, int V, int k, coral_dtype dt,
+                                                    int32_t* topk_ids, float* topk_logits,
+                                                    void* workspace, size_t workspace_bytes,
+                                                    void* hip_stream, void* ev_before,
+                                                    void* ev_after) {
+    if (!ev_before || !ev_after) return CORAL_ERR_NULL;
+    return dense_impl(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits, workspace,
+                      workspace_bytes, hip_stream, ev_before, ev_after);
 }
