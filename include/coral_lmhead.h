@@ -19,8 +19,8 @@
  *     void*, NULL = the default stream) and the call returns without
  *     synchronising.  Outputs are valid once the stream reaches that point.
  *   - Errors: every argument check is done on the host before anything is
- *     enqueued; a call that returns a status other than CORAL_OK has enqueued
- *     nothing.  No exceptions cross the boundary.
+ *     enqueued; a call that returns an argument error (any status but CORAL_OK and
+ *     CORAL_ERR_HIP) has enqueued nothing.  No exceptions cross the boundary.
  *   - Limits (reported as CORAL_ERR_UNSUPPORTED, never silently mishandled):
  *     1 <= M <= 64, 1 <= k <= 64, 1 <= G <= 1024; H a multiple of 8 (bf16) or
  *     of 4 (f32); hidden, gate_W and lm_W 16-byte aligned.
@@ -90,6 +90,19 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
                                     coral_dtype dt);
 
 /*
+ * Prepares a freshly allocated workspace: zeroes its control words (a small kernel
+ * on hip_stream, no memset node, so it may be captured in a HIP graph).  Required
+ * once before the first coral_lmhead_grouped / coral_lmhead_dense call that uses the
+ * workspace; every completed call leaves the control words ready for the next one.
+ * The control words count the workgroups that have published their partial top-k
+ * lists, so that the last one can merge them (the per-token top-k of the appendix's
+ * "Tree decoding" paragraph) without a further launch.
+ *   workspace [device], 256-byte aligned, at least 256 bytes.
+ */
+coral_status coral_lmhead_workspace_init(void *workspace, size_t workspace_bytes,
+                                         void *hip_stream);
+
+/*
  * Grouped LM head for one draft step (section 3.3, Eq. 7 and Eq. 8; appendix
  * "Tree decoding").  For each token m = 0..M-1:
  *   s[m,n]   = sum_j gate_W[n,j] * hidden[m,j] (+ gate_bias[n])      n = 0..G-1
@@ -114,8 +127,8 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
  *   topk_logits [device] out [M,k] fp32 logits of those ids
  *   sel_groups  [device] out [M,g] int32 selected groups, or NULL if not wanted
  *   workspace   [device] at least coral_lmhead_workspace_bytes(...) bytes,
- *               256-byte aligned; contents need not be preserved between calls,
- *               but two calls in flight at once must not share it
+ *               256-byte aligned, prepared once by coral_lmhead_workspace_init;
+ *               two calls in flight at once must not share it
  */
 coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
                                   const float *gate_bias, const void *lm_W,

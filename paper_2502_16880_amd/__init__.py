@@ -49,6 +49,8 @@ def _load():
     L.coral_group_index_validate.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int]
     L.coral_lmhead_workspace_bytes.restype = c.c_size_t
     L.coral_lmhead_workspace_bytes.argtypes = [c.c_int] * 7
+    L.coral_lmhead_workspace_init.restype = c.c_int
+    L.coral_lmhead_workspace_init.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p]
     L.coral_lmhead_grouped.restype = c.c_int
     L.coral_lmhead_grouped.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                        c.POINTER(_GroupIndexStruct)] + [c.c_int] * 6 + \
@@ -148,11 +150,20 @@ def coral_lmhead_workspace_bytes(M: int, H: int, V: int, G: int, g: int, k: int,
     return int(_L.coral_lmhead_workspace_bytes(M, H, V, G, g, k, dt))
 
 
+def coral_lmhead_workspace_init(workspace: torch.Tensor, stream=None) -> None:
+    _raise(_L.coral_lmhead_workspace_init(_dev_ptr(workspace, "workspace"),
+                                          workspace.numel() * workspace.element_size(),
+                                          _stream_ptr(stream)))
+
+
 def alloc_workspace(M, H, V, G, g, k, dt, device="cuda") -> torch.Tensor:
+    """A prepared workspace (allocated through PyTorch, control words zeroed)."""
     n = coral_lmhead_workspace_bytes(M, H, V, G, g, k, dt)
     if n == 0:
         raise ValueError("invalid sizes for the workspace")
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    coral_lmhead_workspace_init(ws)
+    return ws
 
 
 def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,

@@ -1,0 +1,125 @@
+// Device helpers shared by the kernels of the grouped LM head (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kRowsPerWave = 8;
+constexpr int kChunkRows = kRowsPerWave * kWavesPerBlock;   // rows one workgroup streams
+constexpr int kRowsInFlight = 2;                            // rows a wave loads together
+constexpr int kTokBatch = 8;                                // tokens staged in LDS at once
+constexpr int kMaxM = 64;
+constexpr int kMaxK = 64;
+constexpr int kMaxG = 1024;
+constexpr int kSelRegs = kMaxG / kWave;
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+struct Cand {
+    float v;
+    int id;
+};
+
+__device__ __forceinline__ bool better(float av, int aid, float bv, int bid) {
+    return av > bv || (av == bv && aid < bid);
+}
+
+// ---------------------------------------------------------------- loads / dots
+__device__ __forceinline__ uint4 load_stream(const uint4* p) {
+    u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <bool BF16>
+__device__ __forceinline__ float dot_vec(uint4 w, uint4 h, float acc) {
+    if (BF16) {
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x),
+                                              __builtin_bit_cast(bf16x2_t, h.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y),
+                                              __builtin_bit_cast(bf16x2_t, h.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z),
+                                              __builtin_bit_cast(bf16x2_t, h.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w),
+                                              __builtin_bit_cast(bf16x2_t, h.w), acc, false);
+    } else {
+        acc = fmaf(__uint_as_float(w.x), __uint_as_float(h.x), acc);
+        acc = fmaf(__uint_as_float(w.y), __uint_as_float(h.y), acc);
+        acc = fmaf(__uint_as_float(w.z), __uint_as_float(h.z), acc);
+        acc = fmaf(__uint_as_float(w.w), __uint_as_float(h.w), acc);
+    }
+    return acc;
+}
+
+// ---------------------------------------------------------------- wave helpers
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+    int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+    return x + __int_as_float(moved);
+}
+
+// Sum over the 64 lanes, returned to every lane (wave-uniform).  Fixed order:
+// inclusive scan inside each row of 16 lanes, then rows 0+1, 2+3, then halves.
+__device__ __forceinline__ float wave_sum(float x) {
+    x = dpp_add<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_add<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_add<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_add<0x118, 0xf>(x);   // row_shr:8  -> lane 15 of each row holds the row total
+    x = dpp_add<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+    x = dpp_add<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the total
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// Value of the lane below (lane 0 keeps its own): one DPP move, no LDS round trip.
+__device__ __forceinline__ int lane_below(int x) {
+    return __builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);
+}
+__device__ __forceinline__ float lane_below(float x) {
+    return __int_as_float(lane_below(__float_as_int(x)));
+}
+
+// Sorted list of the best candidates seen so far, lane i holding rank i.
+// (v, id) is wave-uniform.  Lanes past the wanted k simply hold further ranks.
+__device__ __forceinline__ void list_insert(float& lv, int& li, float v, int id, int lane, int k) {
+    const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lv), k - 1));
+    const int ti = __builtin_amdgcn_readlane(li, k - 1);
+    if (!better(v, id, tv, ti)) return;                // does not reach the k best: wave-uniform
+    const unsigned long long b = __ballot(better(v, id, lv, li));
+    const int pos = __ffsll(b) - 1;                    // >= 0: the k-th entry is beaten
+    const float sv = lane_below(lv);
+    const int si = lane_below(li);
+    if (lane == pos) {
+        lv = v;
+        li = id;
+    } else if (lane > pos) {
+        lv = sv;
+        li = si;
+    }
+}
+
+// Workgroup merge of n_lists sorted lists of k candidates held in `buf`
+// (n_lists*k <= blockDim.x): the rank of a candidate is the number of candidates
+// that beat it (slot index breaks full ties between padding entries), the k best
+// are written to dst in rank order.  Both barriers are reached by every thread.
+__device__ __forceinline__ void block_rank_merge(const Cand* buf, int n, int k, Cand* dst) {
+    __syncthreads();
+    const int tid = threadIdx.x;
+    if (tid < n) {
+        const Cand c = buf[tid];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const Cand o = buf[j];
+            rank += (better(o.v, o.id, c.v, c.id) || (o.v == c.v && o.id == c.id && j < tid)) ? 1 : 0;
+        }
+        if (rank < k) dst[rank] = c;
+    }
+    __syncthreads();
+}
+
+
+}  // namespace

@@ -1,0 +1,738 @@
+// Single-launch path of the grouped / dense LM head.
+//
+// One persistent workgroup of 16 waves per compute unit.  Every workgroup
+//   1. stages the M hidden vectors in LDS,
+//   2. computes the whole gate s[M,G] itself from the L2-resident gate matrix (Eq. 7's
+//      W2 projection; redundant per workgroup, which costs less than a grid-wide
+//      synchronisation would), selects the g best groups per token and builds the list
+//      of activated groups with their token masks,
+//   3. streams its share of the activated rows: global wave w takes row pairs w,
+//      w + #waves, ... of the concatenated activated groups, each row as eight 1 KB
+//      non-temporal wave loads, and dots it with the hidden vectors of the tokens that
+//      selected the row's group (v_dot2c_f32_bf16, fp32 accumulation),
+//   4. keeps per (wave, token) a sorted list of the k best logits in LDS, touched only
+//      when a logit beats the wave's current k-th,
+//   5. merges its waves' lists and publishes one list per token; the workgroup that
+//      arrives last merges all workgroups' lists and writes the result.
+// The logits row never exists in memory.  No workgroup ever waits for another.
+#pragma once
+#include "device_utils.h"
+
+namespace {
+
+constexpr int kFusedWaves = 16;
+constexpr int kFusedBlock = kFusedWaves * kWave;
+constexpr int kFusedRows = 2;          // rows a wave loads together
+constexpr int kFusedSegs = 8;          // 1 KB segments of a row held in registers
+constexpr int kLdsLimit = 160 * 1024;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+constexpr int kMergeAreaBytes = kWave * 8 + kWave * 4;   // merge scratch per wave
+
+struct FusedParams {
+    const uint4* hidden;        // [M, n_vec]
+    const uint4* gate_W;        // [G, n_vec]   (grouped)
+    const float* bias;          // [G] or null  (grouped)
+    const uint4* lm_W;          // [V, n_vec]
+    const int32_t* offsets;     // [G+1]        (grouped)
+    const int32_t* rows;        // [V]          (grouped)
+    int32_t* sel_out;           // [M, g] or null
+    Cand* part;                 // [M, k, gridDim.x] per-workgroup lists, entry-major
+    unsigned int* counter;      // arrival counter, zero between calls
+    int32_t* topk_ids;          // [M, k]
+    float* topk_logits;         // [M, k]
+    int M, V, G, g, k;
+    int n_vec, jp;
+};
+
+struct FusedLds {
+    int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags;
+    int total;
+};
+
+// Byte offsets of the kernel's regions in dynamic LDS (the host sizes the launch with the
+// same function the kernel lays its pointers out with).
+__host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k, int jp, bool dense,
+                                                     bool mfma_gate) {
+    FusedLds L;
+    int off = 0;
+    auto take = [&](size_t bytes) {
+        int at = off;
+        off = (int)((off + bytes + 15) / 16 * 16);
+        return at;
+    };
+    long long um = (long long)M * g < G ? (long long)M * g : G;   // activated groups at most
+    if (dense || um < 1) um = 1;
+    size_t hidden_bytes = (size_t)M * jp * kWave * sizeof(uint4);
+    const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes;
+    if (hidden_bytes < scratch_bytes) hidden_bytes = scratch_bytes;   // reused by the merges
+    L.o_hidden = take(hidden_bytes);
+    size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
+    // the MFMA gate parks its per-wave partial tiles here before the lists are initialised
+    const size_t gate_part_bytes =
+        (!dense && mfma_gate) ? (size_t)kFusedWaves * ((M + 15) / 16) * 256 * sizeof(float) : 0;
+    if (lists_bytes < gate_part_bytes) lists_bytes = gate_part_bytes;
+    L.o_lists = take(lists_bytes);
+    L.o_s = take(dense ? 16 : (size_t)M * G * sizeof(float));
+    L.o_mask = take(dense ? 16 : (size_t)G * sizeof(unsigned long long));
+    L.o_ugroup = take((size_t)um * sizeof(int));
+    L.o_ustart = take((size_t)um * sizeof(int));
+    L.o_uend = take((size_t)um * sizeof(int));
+    L.o_uprefix = take((size_t)(um + 1) * sizeof(int));
+    L.o_umask = take((size_t)um * sizeof(unsigned long long));
+    L.o_flags = take(16);
+    L.total = off;
+    return L;
+}
+
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ unsigned long long uni64(unsigned long long x) {
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)x);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(x >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+
+__device__ __forceinline__ Cand sentinel() {
+    Cand c;
+    c.v = -INFINITY;
+    c.id = INT_MAX;
+    return c;
+}
+
+// Insert the wave-uniform candidate (z, id) of token t into that token's LDS list if it
+// beats the list's k-th entry.  thr_v / thr_i cache the k-th entry of every token's list
+// of this wave, token t in lane t.
+__device__ __forceinline__ void lds_list_insert(Cand* list, int k, int lane, float z, int id,
+                                                float& thr_v, int& thr_i, int t) {
+    const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(thr_v), t));
+    const int ti = __builtin_amdgcn_readlane(thr_i, t);
+    if (!better(z, id, tv, ti)) return;                // wave-uniform
+    Cand c = sentinel();
+    if (lane < k) c = list[lane];
+    const unsigned long long b = __ballot(better(z, id, c.v, c.id));
+    const int pos = __ffsll(b) - 1;                    // <= k-1: the k-th entry is beaten
+    const float sv = lane_below(c.v);
+    const int si = lane_below(c.id);
+    if (lane == pos) {
+        c.v = z;
+        c.id = id;
+    } else if (lane > pos) {
+        c.v = sv;
+        c.id = si;
+    }
+    if (lane < k) list[lane] = c;
+    const float nv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), k - 1));
+    const int ni = __builtin_amdgcn_readlane(c.id, k - 1);
+    if (lane == t) {
+        thr_v = nv;
+        thr_i = ni;
+    }
+}
+
+// Candidate lists that cross workgroups are written and read with agent-scope atomic
+// accesses (they go through to memory, past the per-XCD L2), so that publishing needs
+// no L2 write-back fence.
+__device__ __forceinline__ void publish_cand(Cand* dst, float v, int id) {
+    const unsigned long long bits =
+        ((unsigned long long)(unsigned)id << 32) | (unsigned long long)(unsigned)__float_as_int(v);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(dst), bits, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ Cand fetch_cand(const Cand* src) {
+    const unsigned long long bits = __hip_atomic_load(
+        reinterpret_cast<const unsigned long long*>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    Cand c;
+    c.v = __int_as_float((int)(unsigned)(bits & 0xffffffffull));
+    c.id = (int)(unsigned)(bits >> 32);
+    return c;
+}
+
+// One step of a streamed top-k: every lane offers one candidate; those that beat the
+// current k-th entry of the register list (lane i = rank i) are inserted one by one.
+__device__ __forceinline__ void offer_candidates(float& lv, int& li, Cand c, int k, int lane) {
+    const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lv), k - 1));
+    const int ti = __builtin_amdgcn_readlane(li, k - 1);
+    unsigned long long pass = __ballot(better(c.v, c.id, tv, ti));
+    while (pass) {                                     // wave-uniform
+        const int src = __ffsll(pass) - 1;
+        pass &= pass - 1ull;
+        const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), src));
+        const int id = __builtin_amdgcn_readlane(c.id, src);
+        list_insert(lv, li, v, id, lane, k);
+    }
+}
+
+// ---------------------------------------------------------------- merging sorted lists
+// Order-preserving 64-bit key: key(a) > key(b) exactly when a beats b (larger logit
+// first, then lower id).  -0.0 counts as +0.0, as it does for the float comparison.
+__device__ __forceinline__ unsigned long long cand_key(float v, int id) {
+    unsigned u = __float_as_uint(v + 0.0f);
+    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+    return ((unsigned long long)u << 32) | (unsigned)(~id);
+}
+
+// Rank of this lane's candidate among the candidates of lanes [0, n): the number of
+// those that beat it.  Candidates are distinct under the total order (distinct ids).
+__device__ __forceinline__ int wave_rank(float v, int id, int n) {
+    const unsigned long long key = cand_key(v, id);
+    const int klo = (int)(unsigned)key, khi = (int)(unsigned)(key >> 32);
+    int r = 0;
+    for (int j = 0; j < n; ++j) {                      // wave-uniform
+        const unsigned lo = (unsigned)__builtin_amdgcn_readlane(klo, j);
+        const unsigned hi = (unsigned)__builtin_amdgcn_readlane(khi, j);
+        r += (((unsigned long long)hi << 32) | lo) > key ? 1 : 0;
+    }
+    return r;
+}
+
+__device__ __forceinline__ bool is_real(Cand c) { return c.id != INT_MAX; }
+
+// k-th best of the candidates in lanes [0, n); (tv, ti) is wave-uniform.  Padding entries
+// all compare equal, so with fewer than k real candidates the result is the padding value
+// (a bound that everything reaches).
+__device__ __forceinline__ void wave_kth(float v, int id, int n, int k, int lane, float& tv,
+                                         int& ti) {
+    const int r = wave_rank(v, id, n);
+    const unsigned long long b = __ballot(lane < n && r == k - 1 && id != INT_MAX);
+    tv = -INFINITY;
+    ti = INT_MAX;
+    if (b) {
+        const int src = __ffsll(b) - 1;
+        tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+        ti = __builtin_amdgcn_readlane(id, src);
+    }
+}
+
+// e / k for 0 <= e < 4096 and 1 <= k <= 64 without an integer division.
+__device__ __forceinline__ int div_small(int e, int inv_k) { return (int)(((unsigned)e * (unsigned)inv_k) >> 20); }
+__device__ __forceinline__ int inv_small(int k) { return (1 << 20) / k + 1; }
+
+// Appends the candidates flagged `keep` to scratch[cnt...] in lane order; returns the
+// new count (entries past `cap` are dropped, the caller checks the count).
+__device__ __forceinline__ int wave_append(Cand* scratch, int* tag_scratch, int cnt, int cap,
+                                           bool keep, Cand c, int tag, int lane) {
+    const unsigned long long b = __ballot(keep);
+    if (keep) {
+        const int pos = cnt + __popcll(b & ((1ull << lane) - 1ull));
+        if (pos < cap) {
+            scratch[pos] = c;
+            if (tag_scratch) tag_scratch[pos] = tag;
+        }
+    }
+    return cnt + __popcll(b);
+}
+
+// One wave merges n_lists sorted lists of k candidates (get(list, i), padding entries are
+// sentinels) into the k best, put(rank, candidate) for every rank < k.
+// Fast path: the k-th largest of the lists' first entries is a lower bound of the result's
+// k-th entry, so only lists whose first entry reaches it can contribute, and of those only
+// entries that reach it; the few survivors are ranked by counting.  If a bound does not
+// exist (fewer than k lists, more than 256 lists) or too many survive (64), the lists are
+// streamed through a sorted register list instead.
+template <class Get, class Put>
+__device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Cand* scratch,
+                                                int* tags, Get get, Put put) {
+    constexpr int kCap = kWave;
+    const int inv_k = inv_small(k);
+    bool fast = n_lists >= k && n_lists <= 4 * kWave;
+    int n_s = 0;
+    float tv = -INFINITY;
+    int ti = INT_MAX;
+    if (fast) {
+        Cand mx[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int l = c * kWave + lane;
+            mx[c] = sentinel();
+            if (c * kWave < n_lists && l < n_lists) mx[c] = get(l, 0);
+        }
+        // bound from a sample of first entries (the first 64 lists); if more than 64 lists
+        // reach it, the 64 kept so far are the next, tighter sample
+        Cand sample = mx[0];
+        int n_sample = n_lists < kWave ? n_lists : kWave;
+        int cnt = 0;
+#pragma unroll
+        for (int round = 0; round < 3; ++round) {              // wave-uniform
+            wave_kth(sample.v, sample.id, n_sample, k, lane, tv, ti);
+            cnt = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (c * kWave < n_lists)
+                    cnt = wave_append(scratch, tags, cnt, kCap,
+                                      is_real(mx[c]) && !better(tv, ti, mx[c].v, mx[c].id), mx[c],
+                                      c * kWave + lane, lane);
+            if (cnt <= kCap) break;
+            sample = scratch[lane];
+            n_sample = kCap;
+        }
+        if (cnt > kCap) {
+            fast = false;                                      // no usable bound (ties)
+        } else {
+            Cand s = sentinel();
+            int tag = 0;
+            if (lane < cnt) {
+                s = scratch[lane];
+                tag = tags[lane];
+            }
+            if (n_lists > kWave || cnt > kWave)                // else the sample was everything
+                wave_kth(s.v, s.id, cnt, k, lane, tv, ti);     // exact k-th largest first entry
+            const bool live = lane < cnt && !better(tv, ti, s.v, s.id);
+            const unsigned long long b = __ballot(live);
+            n_s = __popcll(b);
+            if (live) tags[__popcll(b & ((1ull << lane) - 1ull))] = tag;   // compact list ids
+        }
+    }
+    if (fast) {
+        int cnt = 0;
+        const int n_e = n_s * k;
+        for (int base = 0; base < n_e; base += 2 * kWave) {    // wave-uniform; two loads in flight
+            Cand c2[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int e = base + u * kWave + lane;
+                c2[u] = sentinel();
+                if (e < n_e) {
+                    const int sl = div_small(e, inv_k);
+                    c2[u] = get(tags[sl], e - sl * k);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                cnt = wave_append(scratch, nullptr, cnt, kCap,
+                                  is_real(c2[u]) && !better(tv, ti, c2[u].v, c2[u].id), c2[u], 0, lane);
+        }
+        if (cnt <= kCap) {
+            Cand s = sentinel();
+            if (lane < cnt) s = scratch[lane];
+            const int r = wave_rank(s.v, s.id, cnt);
+            if (lane < cnt && r < k) put(r, s);
+            if (lane >= cnt && lane < k) put(lane, sentinel());
+            return;
+        }
+    }
+    // general path
+    Cand seed = sentinel();
+    if (lane < k) seed = get(0, lane);
+    float lv = seed.v;
+    int li = seed.id;
+    const int n_e = n_lists * k;
+    for (int base = k; base < n_e; base += kWave) {
+        const int e = base + lane;
+        Cand c = sentinel();
+        if (e < n_e) {
+            const int l = e / k;                       // n_e may exceed div_small's range here
+            c = get(l, e - l * k);
+        }
+        offer_candidates(lv, li, c, k, lane);
+    }
+    if (lane < k) {
+        Cand o;
+        o.v = lv;
+        o.id = li;
+        put(lane, o);
+    }
+}
+
+template <bool BF16, int NT>
+__device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* hs, Cand* my_lists,
+                                             const uint4 (&w0)[kFusedSegs],
+                                             const uint4 (&w1)[kFusedSegs],
+                                             unsigned long long& rem, int rid0, int rid1, bool has1,
+                                             float& thr_v, int& thr_i) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int hs_stride = p.jp * kWave;
+    int tok[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        tok[i] = __ffsll(rem) - 1;
+        rem &= rem - 1ull;
+    }
+    float a0[NT], a1[NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i) a0[i] = a1[i] = 0.f;
+#pragma unroll
+    for (int j = 0; j < kFusedSegs; ++j) {
+        if (j < p.jp) {                                // uniform
+#pragma unroll
+            for (int i = 0; i < NT; ++i) {
+                const uint4 h = hs[tok[i] * hs_stride + j * kWave + lane];
+                a0[i] = dot_vec<BF16>(w0[j], h, a0[i]);
+                a1[i] = dot_vec<BF16>(w1[j], h, a1[i]);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+        const float z0 = wave_sum(a0[i]);
+        lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z0, rid0, thr_v, thr_i, tok[i]);
+        if (has1) {                                    // uniform
+            const float z1 = wave_sum(a1[i]);
+            lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z1, rid1, thr_v, thr_i, tok[i]);
+        }
+    }
+}
+
+template <bool BF16, bool DENSE, bool MFMA_GATE>
+__global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
+    extern __shared__ uint4 smem[];
+    char* lds = reinterpret_cast<char*>(smem);
+    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, MFMA_GATE);
+    uint4* hs = reinterpret_cast<uint4*>(lds + lay.o_hidden);
+    Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
+    float* s_lds = reinterpret_cast<float*>(lds + lay.o_s);
+    unsigned long long* mask_lds = reinterpret_cast<unsigned long long*>(lds + lay.o_mask);
+    int* ugroup = reinterpret_cast<int*>(lds + lay.o_ugroup);
+    int* ustart = reinterpret_cast<int*>(lds + lay.o_ustart);
+    int* uend = reinterpret_cast<int*>(lds + lay.o_uend);
+    int* uprefix = reinterpret_cast<int*>(lds + lay.o_uprefix);
+    unsigned long long* umask = reinterpret_cast<unsigned long long*>(lds + lay.o_umask);
+    int* flags = reinterpret_cast<int*>(lds + lay.o_flags);
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int hs_stride = p.jp * kWave;
+    const int M = p.M, k = p.k;
+
+    if (threadIdx.x == 0) flags[2] = 0;                // row-pair counter, see step 3
+    // ---- 1. hidden vectors
+    {
+        const int mm = threadIdx.x / hs_stride;            // hs_stride <= 512: at least 2 rows a pass
+        const int vec = threadIdx.x - mm * hs_stride;
+        const int rows_per_pass = kFusedBlock / hs_stride;
+        constexpr int kU = 8;
+        for (int m0 = 0; m0 < M; m0 += rows_per_pass * kU) {
+            uint4 tmp[kU];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int m = m0 + u * rows_per_pass + mm;
+                tmp[u] = make_uint4(0, 0, 0, 0);
+                if (mm < rows_per_pass && m < M && vec < p.n_vec)
+                    tmp[u] = p.hidden[(size_t)m * p.n_vec + vec];
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int m = m0 + u * rows_per_pass + mm;
+                if (mm < rows_per_pass && m < M) hs[m * hs_stride + vec] = tmp[u];
+            }
+        }
+    }
+    Cand* my_lists = lists + (size_t)wave * M * k;
+    float thr_v = -INFINITY;
+    int thr_i = INT_MAX;
+
+    int total_batches;
+    if (DENSE) {
+        total_batches = (p.V + kFusedRows - 1) / kFusedRows;
+        __syncthreads();
+    } else {
+        for (int n = threadIdx.x; n < p.G; n += kFusedBlock) mask_lds[n] = 0ull;
+        if (MFMA_GATE) {
+            // ---- 2a. gate on the matrix cores: s[16 groups x 16 tokens] tiles, the H
+            // columns split over the 16 waves in steps of 32 (v_mfma_f32_16x16x32_bf16:
+            // lane l feeds row l%16, columns 8*(l/16)..+8 of both operands and receives
+            // rows 4*(l/16)..+4, column l%16 of the tile); the waves' partial tiles are
+            // summed in wave order.  The first tile's gate rows are requested before the
+            // barrier that completes the hidden vectors.
+            const int r16 = lane & 15, q4 = lane >> 4;
+            const int n_ks = (p.n_vec + 3) / 4;            // <= 128 because jp <= 8
+            const int n_gt = (p.G + 15) / 16, n_tt = (M + 15) / 16;
+            float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][256]
+            // waves 0-7 work on the even tile of a pair of group tiles, waves 8-15 on the odd
+            // one; each takes two adjacent 32-column steps at a time (one 128-byte line per
+            // gate row) out of every 16
+            const int half = wave >> 3, kw = wave & 7;
+            constexpr int kSteps = 2 * kFusedSegs;
+            uint4 ga[kSteps];
+            // every workgroup reads the same gate matrix at the same time: each starts at a
+            // different column block so that they do not all queue on one L2 channel
+            const int rot = (int)(blockIdx.x % 8u);
+            auto step_of = [&](int i) { return 16 * (((i >> 1) + rot) & 7) + 2 * kw + (i & 1); };
+            auto load_gate_tile = [&](int gt) {
+                const int n = gt * 16 + r16;
+#pragma unroll
+                for (int i = 0; i < kSteps; ++i) {
+                    const int vec = step_of(i) * 4 + q4;
+                    ga[i] = make_uint4(0, 0, 0, 0);
+                    if (vec < p.n_vec && n < p.G) ga[i] = p.gate_W[(size_t)n * p.n_vec + vec];
+                }
+            };
+            load_gate_tile(half);
+            __syncthreads();
+            for (int pair = 0; pair * 2 < n_gt; ++pair) {
+                if (pair) load_gate_tile(pair * 2 + half);
+                for (int tt = 0; tt < n_tt; ++tt) {            // uniform
+                    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                    const int m = tt * 16 + r16;
+                    const int mc = m < M ? m : M - 1;          // clamped: the load is unconditional
+#pragma unroll
+                    for (int i0 = 0; i0 < kSteps; i0 += 2) {
+                        uint4 hb[2];
+#pragma unroll
+                        for (int u = 0; u < 2; ++u) {
+                            const int ks = step_of(i0 + u);
+                            const int vec = ks < n_ks ? ks * 4 + q4 : 0;   // rows are zero padded
+                            hb[u] = hs[mc * hs_stride + vec];
+                            if (m >= M || ks >= n_ks) hb[u] = make_uint4(0, 0, 0, 0);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 2; ++u)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                __builtin_bit_cast(bf16x8_t, ga[i0 + u]),
+                                __builtin_bit_cast(bf16x8_t, hb[u]), acc, 0, 0, 0);
+                    }
+                    *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * 256 + lane * 4) = acc;
+                }
+                __syncthreads();
+                for (int idx = threadIdx.x; idx < 2 * n_tt * 256; idx += kFusedBlock) {
+                    const int hh = idx / (n_tt * 256);
+                    const int rest = idx - hh * n_tt * 256;
+                    const int tt = rest >> 8, e = rest & 255;
+                    const int l = e >> 2, i = e & 3;
+                    const int n = (pair * 2 + hh) * 16 + (l >> 4) * 4 + i;
+                    const int m = tt * 16 + (l & 15);
+                    float sum = 0.f;
+                    for (int w = hh * 8; w < hh * 8 + 8; ++w)
+                        sum += gpart[((size_t)w * n_tt + tt) * 256 + e];
+                    if (n < p.G && m < M) s_lds[m * p.G + n] = sum + (p.bias ? p.bias[n] : 0.f);
+                }
+                __syncthreads();
+            }
+        } else {
+            // ---- 2a. gate on the vector units (fp32 storage, or one or two tokens): each wave takes rows n0 and n0 + 16 per pass; the
+            // loads of the first pass are issued before the barrier that completes the
+            // hidden vectors
+            uint4 ga[kFusedSegs], gb[kFusedSegs];
+            auto load_gate_rows = [&](int n0) {
+                const int n1 = n0 + kFusedWaves;
+#pragma unroll
+                for (int j = 0; j < kFusedSegs; ++j) {
+                    const int vec = j * kWave + lane;
+                    ga[j] = make_uint4(0, 0, 0, 0);
+                    gb[j] = make_uint4(0, 0, 0, 0);
+                    if (j < p.jp && vec < p.n_vec) {
+                        if (n0 < p.G) ga[j] = p.gate_W[(size_t)n0 * p.n_vec + vec];
+                        if (n1 < p.G) gb[j] = p.gate_W[(size_t)n1 * p.n_vec + vec];
+                    }
+                }
+            };
+            load_gate_rows(wave);
+            __syncthreads();
+            for (int n0 = wave; n0 < p.G; n0 += 2 * kFusedWaves) {
+                if (n0 != wave) load_gate_rows(n0);
+                const int n1 = n0 + kFusedWaves;
+                for (int m = 0; m < M; m += 2) {
+                    const int m1 = m + 1 < M ? m + 1 : m;
+                    float a0 = 0.f, b0 = 0.f, a1 = 0.f, b1 = 0.f;
+#pragma unroll
+                    for (int j = 0; j < kFusedSegs; ++j)
+                        if (j < p.jp) {
+                            const uint4 h0 = hs[m * hs_stride + j * kWave + lane];
+                            const uint4 h1 = hs[m1 * hs_stride + j * kWave + lane];
+                            a0 = dot_vec<BF16>(ga[j], h0, a0);
+                            b0 = dot_vec<BF16>(gb[j], h0, b0);
+                            a1 = dot_vec<BF16>(ga[j], h1, a1);
+                            b1 = dot_vec<BF16>(gb[j], h1, b1);
+                        }
+                    a0 = wave_sum(a0);
+                    b0 = wave_sum(b0);
+                    a1 = wave_sum(a1);
+                    b1 = wave_sum(b1);
+                    if (lane == 0) {
+                        const float bias0 = p.bias ? p.bias[n0] : 0.f;
+                        const float bias1 = (p.bias && n1 < p.G) ? p.bias[n1] : 0.f;
+                        s_lds[m * p.G + n0] = a0 + bias0;
+                        s_lds[m1 * p.G + n0] = a1 + bias0;
+                        if (n1 < p.G) {
+                            s_lds[m * p.G + n1] = b0 + bias1;
+                            s_lds[m1 * p.G + n1] = b1 + bias1;
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        // ---- 2b. per-token top-g by rank counting: group n of token m is selected iff
+        // fewer than g groups beat it (larger score first, then lower group id); its rank
+        // is its position in the selection
+        if (p.G <= kWave) {
+            for (int m = wave; m < M; m += kFusedWaves) {  // one wave per token, group n in lane n
+                float v = lane < p.G ? s_lds[m * p.G + lane] : -INFINITY;
+                if (!(v == v)) v = -INFINITY;              // NaN: unspecified, but keep a total order
+                const int rank = wave_rank(v, lane, p.G);
+                if (lane < p.G && rank < p.g) {
+                    atomicOr(&mask_lds[lane], 1ull << m);
+                    if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = lane;
+                }
+            }
+        } else {
+            for (int idx = threadIdx.x; idx < M * p.G; idx += kFusedBlock) {
+                const int m = idx / p.G;
+                const int n = idx - m * p.G;
+                const float* row = s_lds + m * p.G;
+                float v = row[n];
+                if (!(v == v)) v = -INFINITY;
+                int rank = 0;
+                for (int o = 0; o < p.G; ++o) {
+                    float ov = row[o];
+                    if (!(ov == ov)) ov = -INFINITY;
+                    rank += better(ov, o, v, n) ? 1 : 0;
+                }
+                if (rank < p.g) {
+                    atomicOr(&mask_lds[n], 1ull << m);
+                    if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = n;
+                }
+            }
+        }
+        __syncthreads();
+        // ---- 2c. activated groups in ascending id order, their row ranges and batch prefix
+        if (wave == 0) {
+            int count = 0;
+            for (int base = 0; base < p.G; base += kWave) {
+                const int n = base + lane;
+                const unsigned long long gm = n < p.G ? mask_lds[n] : 0ull;
+                const unsigned long long b = __ballot(gm != 0ull);
+                if (gm != 0ull) {
+                    const int u = count + __popcll(b & ((1ull << lane) - 1ull));
+                    ugroup[u] = n;
+                    umask[u] = gm;
+                    ustart[u] = p.offsets[n];
+                    uend[u] = p.offsets[n + 1];
+                }
+                count += __popcll(b);
+            }
+            if (lane == 0) {
+                int acc = 0;
+                for (int u = 0; u < count; ++u) {
+                    uprefix[u] = acc;
+                    acc += (uend[u] - ustart[u] + kFusedRows - 1) / kFusedRows;
+                }
+                uprefix[count] = acc;
+                flags[0] = count;
+            }
+        }
+        __syncthreads();
+        total_batches = uni(uprefix[uni(flags[0])]);
+    }
+
+    // ---- 3./4. stream row pairs (the lists share LDS with the gate's partial tiles, so
+    // they are emptied only now; each wave touches its own lists only)
+    for (int i = lane; i < M * k; i += kWave) my_lists[i] = sentinel();
+    // The workgroup's row pairs are b(i) = (i / 16) * 16 * #workgroups + 16 * blockIdx + i % 16
+    // for i = 0, 1, ...; its waves draw i from an LDS counter, so a wave that the memory
+    // system serves faster takes more of them and all waves finish together.
+    const int stride_batches = gridDim.x * kFusedWaves;
+    auto draw_batch = [&]() {
+        int i = 0;
+        if (lane == 0) i = atomicAdd(&flags[2], 1);
+        i = uni(i);
+        return (i / kFusedWaves) * stride_batches + blockIdx.x * kFusedWaves + (i % kFusedWaves);
+    };
+    const unsigned long long all_tokens = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
+    int u = 0;
+    auto describe = [&](int b, int& rid0, int& rid1, bool& has1, unsigned long long& bm) {
+        if (DENSE) {
+            rid0 = b * kFusedRows;
+            has1 = rid0 + 1 < p.V;
+            rid1 = has1 ? rid0 + 1 : rid0;
+            bm = all_tokens;
+        } else {
+            while (b >= uni(uprefix[u + 1])) ++u;      // b < total_batches = uprefix[count]
+            const int r0 = uni(ustart[u]) + (b - uni(uprefix[u])) * kFusedRows;
+            has1 = r0 + 1 < uni(uend[u]);
+            rid0 = p.rows[r0];
+            rid1 = has1 ? p.rows[r0 + 1] : rid0;
+            bm = uni64(umask[u]);
+        }
+    };
+    int b = draw_batch();
+    int rid0 = 0, rid1 = 0;
+    bool has1 = false;
+    unsigned long long bm = 0ull;
+    if (b < total_batches) describe(b, rid0, rid1, has1, bm);
+    while (b < total_batches) {                        // wave-uniform
+        rid0 = __builtin_amdgcn_readfirstlane(rid0);
+        rid1 = __builtin_amdgcn_readfirstlane(rid1);
+        uint4 w0[kFusedSegs], w1[kFusedSegs];
+        const uint4* p0 = p.lm_W + (size_t)rid0 * p.n_vec;
+        const uint4* p1 = p.lm_W + (size_t)rid1 * p.n_vec;
+#pragma unroll
+        for (int j = 0; j < kFusedSegs; ++j) {
+            const int vec = j * kWave + lane;
+            w0[j] = make_uint4(0, 0, 0, 0);
+            w1[j] = make_uint4(0, 0, 0, 0);
+            if (j < p.jp && vec < p.n_vec) {
+                w0[j] = load_stream(p0 + vec);
+                w1[j] = load_stream(p1 + vec);
+            }
+        }
+        const int nb = draw_batch();
+        int nrid0 = 0, nrid1 = 0;
+        bool nhas1 = false;
+        unsigned long long nbm = 0ull;
+        if (nb < total_batches) describe(nb, nrid0, nrid1, nhas1, nbm);
+
+        unsigned long long rem = bm;
+        while (rem) {                                  // wave-uniform
+            const int cnt = __popcll(rem);
+            if (cnt >= 4)
+                fused_tokens<BF16, 4>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+            else if (cnt >= 2)
+                fused_tokens<BF16, 2>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+            else
+                fused_tokens<BF16, 1>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+        }
+        b = nb;
+        rid0 = nrid0;
+        rid1 = nrid1;
+        has1 = nhas1;
+        bm = nbm;
+    }
+
+    // ---- 5. merge the waves' lists, publish, last workgroup merges all
+    __syncthreads();
+    // the hidden vectors are no longer needed: their LDS is the merge scratch
+    char* wave_area = lds + lay.o_hidden + (size_t)wave * kMergeAreaBytes;
+    Cand* scratch = reinterpret_cast<Cand*>(wave_area);                     // [64]
+    int* tags = reinterpret_cast<int*>(scratch + kWave);                    // [64]
+    const int inv_k = inv_small(k);
+    const int P = gridDim.x;
+    // published lists are entry-major, part[(t*k + i)*P + workgroup]: the first entries of
+    // all workgroups, which bound the result, are contiguous
+    for (int t = wave; t < M; t += kFusedWaves) {
+        Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
+        wave_merge_topk(
+            kFusedWaves, k, lane, scratch, tags,
+            [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
+            [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the published lists are out
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        flags[1] = old == gridDim.x - 1 ? 1 : 0;
+    }
+    __syncthreads();
+    if (!uni(flags[1])) return;                        // block-uniform
+
+    // Last workgroup: one wave per token merges the P published lists.
+    for (int t = wave; t < M; t += kFusedWaves) {
+        const Cand* src = p.part + (size_t)t * k * P;
+        wave_merge_topk(
+            P, k, lane, scratch, tags,
+            [&](int l, int i) { return fetch_cand(src + (size_t)i * P + l); },
+            [&](int r, Cand c) {
+                p.topk_ids[(size_t)t * k + r] = c.id;
+                p.topk_logits[(size_t)t * k + r] = c.v;
+            });
+    }
+    if (threadIdx.x == 0)                              // ready for the next call
+        __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ void k_zero_words(unsigned int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+}  // namespace

@@ -1,0 +1,352 @@
+// General path: one launch per stage (gate, selection, chunked weight streaming with
+// per-workgroup partial top-k, per-token merge).  Handles every supported shape; used
+// when the single-launch path's LDS budget does not fit.
+#pragma once
+#include "device_utils.h"
+
+namespace {
+
+// ---------------------------------------------------------------- parameters
+struct LogitsParams {
+    const uint4* hidden;        // [M, n_vec]
+    const uint4* lm_W;          // [V, n_vec]
+    const int32_t* offsets;     // [G+1]            (grouped)
+    const int32_t* rows;        // [V]              (grouped)
+    const int32_t* sel;         // [M, g]           (grouped)
+    const unsigned long long* group_mask;   // [G]  (grouped)
+    const int32_t* union_list;  // [G]              (grouped)
+    const int32_t* n_union;     // [1]              (grouped)
+    const int32_t* chunk_base;  // [M, g] first partial slot of (token, selected group)
+    Cand* part;                 // [M, part_stride, k]
+    int M, V, G, g, k;
+    int n_vec;                  // 16-byte vectors per row
+    int jp;                     // ceil(n_vec / 64)
+    int tb_max;                 // tokens the LDS staging area holds
+    int part_stride;            // partial lists reserved per token
+};
+
+// Streams the rows [row_begin, row_end) of one chunk for the nt tokens staged in
+// LDS and leaves each wave's best candidates per token in (lv, li).
+template <bool BF16, bool DENSE, int TB>
+__device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4* hs, int nt,
+                                             int row_begin, int row_end, float (&lv)[TB],
+                                             int (&li)[TB]) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int hs_stride = p.jp * kWave;
+    constexpr int R = kRowsInFlight;
+    constexpr int JU = 4;
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        lv[t] = -INFINITY;
+        li[t] = INT_MAX;
+    }
+    for (int rr = 0; rr < kRowsPerWave; rr += R) {
+        const int r0 = row_begin + wave * kRowsPerWave + rr;
+        if (r0 >= row_end) break;                      // wave-uniform
+        int row_id[R];
+        bool valid[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            valid[r] = r0 + r < row_end;
+            const int idx = valid[r] ? r0 + r : row_end - 1;
+            row_id[r] = DENSE ? idx : __builtin_amdgcn_readfirstlane(p.rows[idx]);
+        }
+        float acc[R][TB];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int t = 0; t < TB; ++t) acc[r][t] = 0.f;
+
+        for (int j0 = 0; j0 < p.jp; j0 += JU) {
+            uint4 w[JU][R];
+#pragma unroll
+            for (int ju = 0; ju < JU; ++ju) {
+                const int vec = (j0 + ju) * kWave + lane;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    w[ju][r] = make_uint4(0, 0, 0, 0);
+                    if (vec < p.n_vec)
+                        w[ju][r] = load_stream(p.lm_W + (size_t)row_id[r] * p.n_vec + vec);
+                }
+            }
+#pragma unroll
+            for (int ju = 0; ju < JU; ++ju) {
+                if (j0 + ju < p.jp) {                  // wave-uniform; LDS is padded to jp*64
+                    const int vec = (j0 + ju) * kWave + lane;
+#pragma unroll
+                    for (int t = 0; t < TB; ++t) {
+                        const int tt = t < nt ? t : nt - 1;
+                        const uint4 h = hs[tt * hs_stride + vec];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) acc[r][t] = dot_vec<BF16>(w[ju][r], h, acc[r][t]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (!valid[r]) continue;                   // wave-uniform
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                const float z = wave_sum(acc[r][t]);
+                if (t < nt) list_insert(lv[t], li[t], z, row_id[r], lane, p.k);
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ int nth_set_bit(unsigned long long m, int n) {
+    for (int i = 0; i < n; ++i) m &= m - 1;
+    return __ffsll(m) - 1;
+}
+
+template <bool BF16, bool DENSE, int TB>
+__device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4* hs, Cand* mbuf,
+                                             unsigned long long batch, int nt, int group,
+                                             int chunk, int row_begin, int row_end) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    float lv[TB];
+    int li[TB];
+    stream_chunk<BF16, DENSE, TB>(p, hs, nt, row_begin, row_end, lv, li);
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        if (t >= nt) break;                            // block-uniform
+        const int m = nth_set_bit(batch, t);
+        int slot;
+        if (DENSE) {
+            slot = chunk;
+        } else {
+            int i = 0;
+            while (i < p.g - 1 && p.sel[m * p.g + i] != group) ++i;
+            slot = p.chunk_base[m * p.g + i] + chunk;
+        }
+        if (lane < p.k) {
+            mbuf[wave * p.k + lane].v = lv[t];
+            mbuf[wave * p.k + lane].id = li[t];
+        }
+        block_rank_merge(mbuf, kWavesPerBlock * p.k, p.k,
+                         p.part + ((size_t)m * p.part_stride + slot) * p.k);
+    }
+}
+
+// One workgroup per (chunk of kChunkRows rows, activated group).  Dense: per chunk.
+template <bool BF16, bool DENSE>
+__global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
+    extern __shared__ uint4 smem[];
+    uint4* hs = smem;
+    Cand* mbuf = reinterpret_cast<Cand*>(smem + (size_t)p.tb_max * p.jp * kWave);
+
+    const int chunk = blockIdx.x;
+    unsigned long long mask;
+    int row_begin, row_end, group = 0;
+    if (DENSE) {
+        mask = p.M >= 64 ? ~0ull : ((1ull << p.M) - 1ull);
+        row_begin = chunk * kChunkRows;
+        if (row_begin >= p.V) return;
+        row_end = min(p.V, row_begin + kChunkRows);
+    } else {
+        const int u = blockIdx.y;
+        if (u >= *p.n_union) return;
+        group = p.union_list[u];
+        mask = p.group_mask[group];
+        const int off0 = p.offsets[group], off1 = p.offsets[group + 1];
+        row_begin = off0 + chunk * kChunkRows;
+        if (row_begin >= off1) return;
+        row_end = min(off1, row_begin + kChunkRows);
+    }
+
+    const int hs_stride = p.jp * kWave;
+    unsigned long long rem = mask;
+    while (rem) {                                      // block-uniform
+        unsigned long long batch = 0;
+        int nt = 0;
+        while (rem && nt < p.tb_max) {
+            const unsigned long long low = rem & (~rem + 1ull);
+            batch |= low;
+            rem ^= low;
+            ++nt;
+        }
+        for (int t = 0; t < nt; ++t) {
+            const int m = nth_set_bit(batch, t);
+            for (int vec = threadIdx.x; vec < hs_stride; vec += kBlock)
+                hs[t * hs_stride + vec] = vec < p.n_vec ? p.hidden[(size_t)m * p.n_vec + vec]
+                                                        : make_uint4(0, 0, 0, 0);
+        }
+        __syncthreads();
+        if (nt == 1)
+            chunk_tokens<BF16, DENSE, 1>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+        else if (nt == 2)
+            chunk_tokens<BF16, DENSE, 2>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+        else if (nt <= 4)
+            chunk_tokens<BF16, DENSE, 4>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+        else
+            chunk_tokens<BF16, DENSE, kTokBatch>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+        // chunk_tokens ends on a barrier, so hs may be overwritten now
+    }
+}
+
+// ---------------------------------------------------------------- gate
+// s[m,n] = sum_j gate_W[n,j] hidden[m,j] + bias[n]   (Eq. 7, W2 projection).
+// One workgroup per group n.
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_gate(const uint4* __restrict__ hidden,
+                                                 const uint4* __restrict__ gate_W,
+                                                 const float* __restrict__ bias, int M, int G,
+                                                 int n_vec, float* __restrict__ s) {
+    __shared__ float red[kWavesPerBlock];
+    const int n = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    for (int m = 0; m < M; ++m) {
+        float acc = 0.f;
+        for (int vec = threadIdx.x; vec < n_vec; vec += kBlock)
+            acc = dot_vec<BF16>(gate_W[(size_t)n * n_vec + vec], hidden[(size_t)m * n_vec + vec], acc);
+        acc = wave_sum(acc);
+        __syncthreads();
+        if (lane == 0) red[wave] = acc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float tot = red[0];
+            for (int w = 1; w < kWavesPerBlock; ++w) tot += red[w];
+            s[(size_t)m * G + n] = tot + (bias ? bias[n] : 0.f);
+        }
+    }
+}
+
+// Per-token top-g of the gate scores (larger first, then lower group id), the
+// token mask of every group, the list of activated groups and, per (token,
+// selected group), the first partial-list slot its chunks write to.
+__global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
+                                                   const int32_t* __restrict__ offsets, int M,
+                                                   int G, int g, int32_t* __restrict__ sel,
+                                                   unsigned long long* __restrict__ group_mask,
+                                                   int32_t* __restrict__ union_list,
+                                                   int32_t* __restrict__ n_union,
+                                                   int32_t* __restrict__ chunk_base) {
+    __shared__ unsigned long long mask[kMaxG];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    for (int n = threadIdx.x; n < G; n += kBlock) mask[n] = 0ull;
+    __syncthreads();
+
+    for (int m = wave; m < M; m += kWavesPerBlock) {
+        float sc[kSelRegs];
+        unsigned taken = 0;
+#pragma unroll
+        for (int i = 0; i < kSelRegs; ++i) {
+            const int n = i * kWave + lane;
+            sc[i] = n < G ? s[(size_t)m * G + n] : -INFINITY;
+            if (!(sc[i] == sc[i])) sc[i] = -INFINITY;       // NaN: keeps every round a winner
+            if (n >= G) taken |= 1u << i;
+        }
+        for (int round = 0; round < g; ++round) {
+            float bv = -INFINITY;
+            int bi = INT_MAX;
+#pragma unroll
+            for (int i = 0; i < kSelRegs; ++i) {
+                const int n = i * kWave + lane;
+                if (!((taken >> i) & 1u) && better(sc[i], n, bv, bi)) {
+                    bv = sc[i];
+                    bi = n;
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                if (better(ov, oi, bv, bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            // every lane now holds the same winner (g <= G guarantees one exists)
+            if ((bi & (kWave - 1)) == lane) taken |= 1u << (bi / kWave);
+            if (lane == 0) {
+                sel[m * g + round] = bi;
+                atomicOr(&mask[bi], 1ull << m);
+            }
+        }
+    }
+    __syncthreads();
+    for (int n = threadIdx.x; n < G; n += kBlock) group_mask[n] = mask[n];
+    if (wave == 0) {
+        int count = 0;
+        for (int base = 0; base < G; base += kWave) {
+            const int n = base + lane;
+            const bool on = n < G && mask[n] != 0ull;
+            const unsigned long long b = __ballot(on);
+            if (on) union_list[count + __popcll(b & ((1ull << lane) - 1ull))] = n;
+            count += __popcll(b);
+        }
+        if (lane == 0) *n_union = count;
+    }
+    for (int m = threadIdx.x; m < M; m += kBlock) {
+        int base = 0;
+        for (int i = 0; i < g; ++i) {
+            chunk_base[m * g + i] = base;
+            // sel was written by lane 0 of this block's waves before the barrier above
+            const int n = sel[m * g + i];
+            base += (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- final merge
+// One workgroup per token: streams the token's partial lists through per-wave
+// sorted lists (64 candidates per step, only those beating the current k-th are
+// inserted), merges the four waves and writes the sorted result.
+__global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part, int part_stride,
+                                                  const int32_t* __restrict__ sel,
+                                                  const int32_t* __restrict__ offsets, int g,
+                                                  int dense_chunks, int k,
+                                                  int32_t* __restrict__ topk_ids,
+                                                  float* __restrict__ topk_logits) {
+    __shared__ Cand mbuf[kWavesPerBlock * kMaxK];
+    __shared__ Cand outbuf[kMaxK];
+    const int m = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    int lists = dense_chunks;
+    if (sel) {
+        lists = 0;
+        for (int i = 0; i < g; ++i) {
+            const int n = sel[m * g + i];
+            lists += (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
+        }
+    }
+    const int n_cand = lists * k;
+    const Cand* src = part + (size_t)m * part_stride * k;
+    float lv = -INFINITY;
+    int li = INT_MAX;
+    for (int base = wave * kWave; base < n_cand; base += kBlock) {   // wave-uniform
+        const int i = base + lane;
+        Cand c;
+        c.v = -INFINITY;
+        c.id = INT_MAX;
+        if (i < n_cand) c = src[i];
+        const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lv), k - 1));
+        const int ti = __builtin_amdgcn_readlane(li, k - 1);
+        unsigned long long pass = __ballot(better(c.v, c.id, tv, ti));
+        while (pass) {
+            const int srcl = __ffsll(pass) - 1;
+            pass &= pass - 1ull;
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), srcl));
+            const int id = __builtin_amdgcn_readlane(c.id, srcl);
+            list_insert(lv, li, v, id, lane, k);
+        }
+    }
+    if (lane < k) {
+        mbuf[wave * k + lane].v = lv;
+        mbuf[wave * k + lane].id = li;
+    }
+    block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
+    if (threadIdx.x < k) {
+        topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
+        topk_logits[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
+    }
+}
+
+
+}  // namespace

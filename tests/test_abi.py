@@ -26,6 +26,8 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"coral_lmhead_grouped", "coral_lmhead_dense", "coral_lmhead_workspace_bytes",
+            "coral_lmhead_workspace_init", "coral_lmhead_grouped_profiled",
+            "coral_lmhead_dense_profiled",
             "coral_group_index_validate", "coral_status_string"} <= set(names)
     lib = ctypes.CDLL(coral.LIB_PATH)
     for n in names:
@@ -54,6 +56,13 @@ def test_group_index_validate():
     assert v(np.array([1, 3, 6], np.int32), rows, 2, 6) == GROUP_INDEX
     ragged = np.array([0, 1, 6], dtype=np.int32)       # ragged groups are a valid partition
     assert v(ragged, rows, 2, 6) == OK
+
+
+def test_workspace_init_rejects_bad_arguments():
+    L = coral._L
+    assert L.coral_lmhead_workspace_init(None, 4096, None) == WORKSPACE
+    assert L.coral_lmhead_workspace_init(FAKE + 8, 4096, None) == WORKSPACE
+    assert L.coral_lmhead_workspace_init(FAKE, 16, None) == WORKSPACE
 
 
 def test_workspace_bytes():

@@ -188,7 +188,8 @@ def test_caller_buffers_and_streams(coral):
     hidden = make_hidden(cfg, 4)
     d_hidden = coral.device_tensor(hidden, "f32")
     ws = coral.alloc_workspace(4, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_F32)
-    ws.fill_(0xAB)
+    ws.fill_(0xAB)                                         # stale contents ...
+    coral.coral_lmhead_workspace_init(ws)                  # ... are fine once it is prepared
     ids = torch.full((4, cfg.k), -7, dtype=torch.int32, device="cuda")
     z = torch.zeros((4, cfg.k), device="cuda")
     st = torch.cuda.Stream()
