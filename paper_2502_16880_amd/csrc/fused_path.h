@@ -443,9 +443,10 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             const int half = wave >> 3, kw = wave & 7;
             constexpr int kSteps = 2 * kFusedSegs;
             uint4 ga[kSteps];
-            // every workgroup reads the same gate matrix at the same time: each starts at a
-            // different column block so that they do not all queue on one L2 channel
-            const int rot = (int)(blockIdx.x % 8u);
+            // every workgroup reads the same gate matrix at the same time: those that share
+            // an L2 (workgroup b runs on XCD b % 8) start at different column blocks so that
+            // they do not all queue on one L2 channel
+            const int rot = (int)((blockIdx.x >> 3) & 7u);
             auto step_of = [&](int i) { return 16 * (((i >> 1) + rot) & 7) + 2 * kw + (i & 1); };
             auto load_gate_tile = [&](int gt) {
                 const int n = gt * 16 + r16;
