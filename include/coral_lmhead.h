@@ -90,6 +90,16 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
                                     coral_dtype dt);
 
 /*
+ * Which kernels a call with these sizes will use (dense != 0: coral_lmhead_dense):
+ * 0 = staged general path (one launch per stage), 1 = single-launch path (gate,
+ * selection, row streaming and top-k of section 3.3 in one persistent kernel),
+ * 2 = matrix-core tile path (groups shared by many tokens, the appendix's tree-decoding
+ * case; dense head with 8 or more tokens), -1 = sizes not supported.  Host-only, no
+ * device work; for tests and benchmark reports.
+ */
+int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral_dtype dt);
+
+/*
  * Prepares a freshly allocated workspace: zeroes its control words (a small kernel
  * on hip_stream, no memset node, so it may be captured in a HIP graph).  Required
  * once before the first coral_lmhead_grouped / coral_lmhead_dense call that uses the

@@ -26,6 +26,7 @@
 #include "device_utils.h"
 #include "fused_path.h"
 #include "staged_path.h"
+#include "tile_path.h"
 
 namespace {
 
@@ -167,6 +168,56 @@ bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* 
     return true;
 }
 
+// Matrix-core path: bf16, k <= 32, LDS plan within the limit.
+bool tiles_fit(int M, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
+    if (dt != CORAL_BF16 || k > kTileMaxK || M > 64) return false;
+    long long um = (long long)M * g < G ? (long long)M * g : G;
+    if (um < 1) um = 1;
+    const TileLds T = tile_lds_layout(M, k, (int)um);
+    if (T.total > kLdsLimit) return false;
+    *u_max_out = (int)um;
+    *lds_out = T.total;
+    return true;
+}
+
+// Enqueues k_tiles and the merge of its published lists.  For the grouped head the masks
+// and the list of activated groups must already be enqueued (k_gate, k_select).
+coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
+                          const coral_group_index* gi, const unsigned long long* mask,
+                          const int32_t* union_list, const int32_t* n_union, int M, int H, int V,
+                          int G, int k, int u_max, int lds, int32_t* topk_ids, float* topk_logits,
+                          char* ws, const Layout& L, hipStream_t stream, void* ev_before,
+                          void* ev_after) {
+    int P = compute_units();
+    if (P < 1) return CORAL_ERR_HIP;
+    if (P > kMaxWorkgroups) P = kMaxWorkgroups;
+    TileParams p = {};
+    p.hidden = static_cast<const uint4*>(hidden);
+    p.lm_W = static_cast<const uint4*>(lm_W);
+    p.offsets = gi ? gi->group_offsets : nullptr;
+    p.rows = gi ? gi->group_rows : nullptr;
+    p.group_mask = mask;
+    p.union_list = union_list;
+    p.n_union = n_union;
+    p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
+    p.M = M; p.V = V; p.G = G; p.k = k;
+    p.n_vec = H / 8;
+    p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
+    p.u_max = u_max;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tiles),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return CORAL_ERR_HIP;
+    coral_status st;
+    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
+    hipLaunchKernelGGL(k_tiles, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
+    if ((st = launch_status()) != CORAL_OK) return st;
+    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
+    hipLaunchKernelGGL(k_merge_published, dim3((M + 3) / 4), dim3(256), 0, stream,
+                       reinterpret_cast<const Cand*>(ws + L.fused_part), P, M, k, topk_ids,
+                       topk_logits);
+    return launch_status();
+}
+
 }  // namespace
 
 extern "C" const char* coral_status_string(coral_status st) {
@@ -209,6 +260,27 @@ extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g
     (void)dt;
     if (!sizes_ok(M, H, V, G, g, k)) return 0;
     return make_layout(M, V, G, g, k).total;
+}
+
+extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k,
+                                 coral_dtype dt) {
+    (void)V;
+    if (dt != CORAL_F32 && dt != CORAL_BF16) return -1;
+    if (M < 1 || H < 1 || k < 1 || M > kMaxM || k > kMaxK) return -1;
+    const bool bf16 = dt == CORAL_BF16;
+    if (H % (bf16 ? 8 : 4) != 0) return -1;
+    if (!dense && (G < 1 || g < 1 || g > G || G > kMaxG)) return -1;
+    const int n_vec = H / (bf16 ? 8 : 4);
+    const int jp = (n_vec + kWave - 1) / kWave;
+    int um = 0, lds = 0;
+    const bool tiles = tiles_fit(M, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
+    if (dense && M >= 8 && tiles) return 2;
+    const bool mfma_gate = !dense && bf16 && M > 2;
+    if (jp <= kFusedSegs &&
+        fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense != 0, mfma_gate).total <= kLdsLimit)
+        return 1;
+    if (!dense && tiles) return 2;
+    return 0;
 }
 
 extern "C" coral_status coral_lmhead_workspace_init(void* workspace, size_t workspace_bytes,
@@ -279,6 +351,20 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     const int n_vec = H / (bf16 ? 8 : 4);
     const uint4* hid = static_cast<const uint4*>(hidden);
     const uint4* gw = static_cast<const uint4*>(gate_W);
+    int tile_umax = 0, tile_lds = 0;
+    if (tiles_fit(M, G, g, k, dt, &tile_umax, &tile_lds)) {
+        GateSelParams q = {};
+        q.hidden = hid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
+        q.group_mask = mask; q.union_list = union_list; q.n_union = n_union;
+        q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
+        q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
+        const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
+        hipLaunchKernelGGL(k_gate_select, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
+        if ((st = launch_status()) != CORAL_OK) return st;
+        return launch_tiles(false, hidden, lm_W, gi, mask, union_list, n_union, M, H, V, G, k,
+                            tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
+                            ev_after);
+    }
     if (bf16)
         hipLaunchKernelGGL(k_gate<true>, dim3(G), dim3(kBlock), 0, stream, hid, gw, gate_bias, M, G,
                            n_vec, s);
@@ -344,6 +430,12 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
+    int tile_umax = 0, tile_lds = 0;
+    // many tokens per row: the contraction is no longer cheap on the vector units
+    if (M >= 8 && tiles_fit(M, 0, 0, k, dt, &tile_umax, &tile_lds))
+        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k,
+                            tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
+                            ev_after);
     if (try_fused(true, hidden, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
                   topk_logits, nullptr, ws, L, stream, ev_before, ev_after, &st))
         return st;

@@ -1,0 +1,462 @@
+// Matrix-core path for groups that many tokens selected (wide draft-tree steps) and for
+// the dense head with many tokens: the logits of a block of 64 weight rows for up to 64
+// tokens are 16x16 tiles of v_mfma_f32_16x16x32_bf16.
+//
+// One persistent workgroup of 8 waves per compute unit; wave = (row tile rt = wave/2,
+// half kq = wave%2 of every 512-column chunk).  Per block of 64 rows of one group:
+//   - the weight rows go from HBM straight into the MFMA A operand (lane l: row l%16 of
+//     the tile, 8 columns at 8*(l/16)): four 1 KB wave loads per chunk, a ring of 16 in
+//     flight, the next block's first 16 issued before this block's epilogue;
+//   - the hidden vectors of the tokens that selected the group are staged chunk by chunk
+//     (512 columns, double buffered) in LDS and read as B operands;
+//   - the two half sums of each tile are added in a fixed order through LDS, which
+//     leaves, per token, the block's 64 logits one per lane of a wave; those that beat the
+//     token's current k-th are merged into the workgroup's running list by rank counting.
+// Each workgroup publishes its lists; a second small kernel merges them per token.
+// The logits row is never written to memory.
+#pragma once
+#include "device_utils.h"
+#include "fused_path.h"
+
+namespace {
+
+constexpr int kTileWaves = 8;
+constexpr int kTileSplit = 2;                    // waves that share a row tile (split of a chunk)
+constexpr int kTileSteps = 16 / kTileSplit;      // 32-column steps of a chunk per wave
+constexpr int kTileBlock = kTileWaves * kWave;
+constexpr int kTileRows = 64;                    // weight rows per block (4 row tiles)
+constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-column chunk
+constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
+constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
+constexpr int kTileMaxK = 32;                    // two lists must fit the 64 lanes of a wave
+
+struct TileParams {
+    const uint4* hidden;                    // [M, n_vec]
+    const uint4* lm_W;                      // [V, n_vec]
+    const int32_t* offsets;                 // [G+1]   (grouped)
+    const int32_t* rows;                    // [V]     (grouped)
+    const unsigned long long* group_mask;   // [G]     (grouped)
+    const int32_t* union_list;              // [G]     (grouped)
+    const int32_t* n_union;                 // [1]     (grouped)
+    Cand* part;                             // [M, k, gridDim.x] published lists, entry-major
+    int M, V, G, k;
+    int n_vec, n_chunks;
+    int u_max;                              // capacity of the activated-group arrays
+};
+
+struct TileLds {
+    int o_hbuf, o_lists, o_rowid, o_tokslot, o_scratch, o_ugroup, o_ustart, o_uend, o_uprefix,
+        o_umask, o_flags, total;
+};
+
+__host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
+    TileLds L;
+    int off = 0;
+    auto take = [&](size_t bytes) {
+        int at = off;
+        off = (int)((off + bytes + 15) / 16 * 16);
+        return at;
+    };
+    L.o_hbuf = take((size_t)2 * kHbBufVecs * sizeof(uint4));
+    L.o_lists = take((size_t)M * k * sizeof(Cand));
+    L.o_rowid = take(kTileRows * sizeof(int));
+    L.o_tokslot = take(64 * sizeof(int));
+    L.o_scratch = take((size_t)kTileWaves * kWave * sizeof(Cand));
+    L.o_ugroup = take((size_t)u_max * sizeof(int));
+    L.o_ustart = take((size_t)u_max * sizeof(int));
+    L.o_uend = take((size_t)u_max * sizeof(int));
+    L.o_uprefix = take((size_t)(u_max + 1) * sizeof(int));
+    L.o_umask = take((size_t)u_max * sizeof(unsigned long long));
+    L.o_flags = take(16);
+    L.total = off;
+    return L;
+}
+
+// Merges the block's 64 logits of one token (one per lane, padding = sentinel) into the
+// token's sorted list in LDS.  Only candidates that beat the list's k-th entry take part;
+// at most k of them can matter, so they are first cut to their own k best, then ranked
+// together with the list's entries (2k <= 64 lanes).
+__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c, Cand* scratch) {
+    Cand e = sentinel();
+    if (lane < k) e = list[lane];
+    const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e.v), k - 1));
+    const int ti = __builtin_amdgcn_readlane(e.id, k - 1);
+    bool keep = is_real(c) && better(c.v, c.id, tv, ti);
+    unsigned long long b = __ballot(keep);
+    if (b == 0ull) return;                             // wave-uniform
+    if (__popcll(b) > k) {                             // cut to the k best among themselves
+        Cand s = keep ? c : sentinel();
+        const int r = wave_rank(s.v, s.id, kWave);
+        keep = keep && r < k;
+        b = __ballot(keep);
+    }
+    const int ns = __popcll(b);
+    if (keep) scratch[__popcll(b & ((1ull << lane) - 1ull))] = c;
+    const unsigned long long lb = __ballot(lane < k && is_real(e));
+    const int kr = __popcll(lb);                       // real entries are a prefix of the list
+    if (lane < kr) scratch[ns + lane] = e;
+    const int n = ns + kr;                             // <= 2k <= 64
+    Cand s = sentinel();
+    if (lane < n) s = scratch[lane];
+    const int r = wave_rank(s.v, s.id, n);
+    if (lane < n && r < k) list[r] = s;
+}
+
+__global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
+    extern __shared__ uint4 smem[];
+    char* lds = reinterpret_cast<char*>(smem);
+    const TileLds lay = tile_lds_layout(p.M, p.k, p.u_max);
+    uint4* hbuf = reinterpret_cast<uint4*>(lds + lay.o_hbuf);
+    Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
+    int* rowid = reinterpret_cast<int*>(lds + lay.o_rowid);
+    int* tokslot = reinterpret_cast<int*>(lds + lay.o_tokslot);
+    int* ugroup = reinterpret_cast<int*>(lds + lay.o_ugroup);
+    int* ustart = reinterpret_cast<int*>(lds + lay.o_ustart);
+    int* uend = reinterpret_cast<int*>(lds + lay.o_uend);
+    int* uprefix = reinterpret_cast<int*>(lds + lay.o_uprefix);
+    unsigned long long* umask = reinterpret_cast<unsigned long long*>(lds + lay.o_umask);
+    int* flags = reinterpret_cast<int*>(lds + lay.o_flags);
+
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r16 = lane & 15, q4 = lane >> 4;
+    const int rt = wave / kTileSplit, kq = wave % kTileSplit;
+    const int M = p.M, k = p.k;
+    Cand* scratch = reinterpret_cast<Cand*>(lds + lay.o_scratch) + (size_t)wave * kWave;
+
+    for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
+    int total_blocks;
+    if (dense) {
+        total_blocks = (p.V + kTileRows - 1) / kTileRows;
+        __syncthreads();
+    } else {
+        if (wave == 0) {
+            const int count = *p.n_union;
+            for (int u = lane; u < count; u += kWave) {
+                const int n = p.union_list[u];
+                ugroup[u] = n;
+                umask[u] = p.group_mask[n];
+                ustart[u] = p.offsets[n];
+                uend[u] = p.offsets[n + 1];
+            }
+            if (lane == 0) {                           // LDS is in order within a wave
+                int acc = 0;
+                for (int u = 0; u < count; ++u) {
+                    uprefix[u] = acc;
+                    acc += (uend[u] - ustart[u] + kTileRows - 1) / kTileRows;
+                }
+                uprefix[count] = acc;
+                flags[0] = count;
+            }
+        }
+        __syncthreads();
+        total_blocks = uni(uprefix[uni(flags[0])]);
+    }
+
+    const unsigned long long all_tokens = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
+    int u = 0;
+    // first row and end of the block's group (row indices into p.rows, or vocabulary ids)
+    auto locate = [&](int b, int& first, int& end, unsigned long long& bm) {
+        if (dense) {
+            first = b * kTileRows;
+            end = p.V;
+            bm = all_tokens;
+        } else {
+            while (b >= uni(uprefix[u + 1])) ++u;      // blocks come in increasing order
+            first = uni(ustart[u]) + (b - uni(uprefix[u])) * kTileRows;
+            end = uni(uend[u]);
+            bm = uni64(umask[u]);
+        }
+    };
+    // this lane's weight row: row r16 of tile rt (clamped inside the group; the duplicates
+    // are dropped when the candidates are formed)
+    auto my_row = [&](int first, int end) {
+        int idx = first + rt * 16 + r16;
+        if (idx >= end) idx = end - 1;
+        return dense ? idx : p.rows[idx];
+    };
+    uint4 a[2 * kTileSteps];                           // ring: 2 chunks x 8 steps of 32 columns
+    auto load_a = [&](const uint4* row_ptr, int c, int slot4) {
+#pragma unroll
+        for (int j = 0; j < kTileSteps; ++j) {
+            const int vec = c * kChunkVecs + (kq * kTileSteps + j) * 4 + q4;
+            a[slot4 * kTileSteps + j] = make_uint4(0, 0, 0, 0);
+            if (c < p.n_chunks && vec < p.n_vec) a[slot4 * kTileSteps + j] = load_stream(row_ptr + vec);
+        }
+    };
+
+    int b = blockIdx.x;
+    int first = 0, end = 0;
+    unsigned long long bm = 0ull;
+    int rid = 0;
+    if (b < total_blocks) {
+        locate(b, first, end, bm);
+        rid = my_row(first, end);
+        const uint4* rp = p.lm_W + (size_t)rid * p.n_vec;
+#pragma unroll
+        for (int cc = 0; cc < 2; ++cc) load_a(rp, cc, cc);
+    }
+    while (b < total_blocks) {                         // block-uniform
+        const int n_t = __popcll(bm);
+        const int n_ct = (n_t + 15) >> 4;
+        // token of every slot, and the vocabulary id of every row of the block
+        if (wave == 0) {
+            const bool on = (bm >> lane) & 1ull;
+            if (on) tokslot[__popcll(bm & ((1ull << lane) - 1ull))] = lane;
+        }
+        if (wave == 1) {
+            const int idx = first + lane;
+            rowid[lane] = idx < end ? (dense ? idx : p.rows[idx]) : -1;
+        }
+        __syncthreads();
+        const uint4* rp = p.lm_W + (size_t)rid * p.n_vec;
+
+        // hidden chunk staging: slots wave, wave+16, ... ; lane = vector inside the chunk
+        constexpr int kSlotsPerWave = 64 / kTileWaves;
+        uint4 hst[kSlotsPerWave];
+        auto fetch_hidden = [&](int c) {
+#pragma unroll
+            for (int i = 0; i < kSlotsPerWave; ++i) {
+                const int s = wave + i * kTileWaves;
+                const int vec = c * kChunkVecs + lane;
+                hst[i] = make_uint4(0, 0, 0, 0);
+                if (s < n_t && vec < p.n_vec) hst[i] = p.hidden[(size_t)tokslot[s] * p.n_vec + vec];
+            }
+        };
+        auto store_hidden = [&](int c) {
+            uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs;
+#pragma unroll
+            for (int i = 0; i < kSlotsPerWave; ++i) {
+                const int s = wave + i * kTileWaves;
+                if (s < n_ct * 16) dst[s * kHbStride + lane] = hst[i];   // zero rows pad the tile
+            }
+        };
+        fetch_hidden(0);
+        store_hidden(0);
+        __syncthreads();
+
+        f32x4_t acc[4];
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int c0 = 0; c0 < p.n_chunks; c0 += 2) {
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                const int c = c0 + cc;
+                if (c < p.n_chunks) {                  // block-uniform
+                    if (c + 1 < p.n_chunks) fetch_hidden(c + 1);
+                    const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
+#pragma unroll
+                    for (int j = 0; j < kTileSteps; ++j) {
+                        const int off = (kq * kTileSteps + j) * 4 + q4;
+#pragma unroll
+                        for (int ct = 0; ct < 4; ++ct) {
+                            if (ct < n_ct) {           // block-uniform
+                                const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
+                                acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, a[cc * kTileSteps + j]),
+                                    __builtin_bit_cast(bf16x8_t, hv), acc[ct], 0, 0, 0);
+                            }
+                        }
+                    }
+                    load_a(rp, c + 2, cc);             // refill the ring slot just consumed
+                    if (c + 1 < p.n_chunks) store_hidden(c + 1);
+                    __syncthreads();
+                }
+            }
+        }
+
+        // next block: locate it and start its first 16 weight loads before the epilogue
+        const int nb = b + gridDim.x;
+        int nfirst = 0, nend = 0, nrid = 0;
+        unsigned long long nbm = 0ull;
+        if (nb < total_blocks) {
+            locate(nb, nfirst, nend, nbm);
+            nrid = my_row(nfirst, nend);
+            const uint4* nrp = p.lm_W + (size_t)nrid * p.n_vec;
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) load_a(nrp, cc, cc);
+        }
+
+        // half sums -> LDS (over the staging buffers, free after the last barrier)
+        float* red = reinterpret_cast<float*>(hbuf);   // [wave][ct][256]
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+            if (ct < n_ct)
+                *reinterpret_cast<f32x4_t*>(red + ((size_t)wave * 4 + ct) * 256 + lane * 4) = acc[ct];
+        __syncthreads();
+        // one wave per token slot: lane = (row tile, row) -> the block's 64 logits of the token
+        for (int s = wave; s < n_t; s += kTileWaves) {
+            const int t = tokslot[s];
+            const int crt = lane >> 4, row = lane & 15;
+            const int e = (((row >> 2) * 16 + (s & 15)) << 2) + (row & 3);
+            float z = 0.f;
+#pragma unroll
+            for (int q = 0; q < kTileSplit; ++q)
+                z += red[((size_t)(crt * kTileSplit + q) * 4 + (s >> 4)) * 256 + e];
+            Cand c;
+            c.v = z;
+            c.id = rowid[lane];
+            if (c.id < 0) c = sentinel();
+            tile_merge_token(lists + (size_t)t * k, k, lane, c, scratch);
+        }
+        __syncthreads();
+        b = nb;
+        first = nfirst;
+        end = nend;
+        bm = nbm;
+        rid = nrid;
+    }
+
+    // publish the workgroup's lists (all tokens; untouched ones are padding)
+    const int P = gridDim.x;
+    for (int i = threadIdx.x; i < M * k; i += kTileBlock) {
+        const Cand c = lists[i];
+        p.part[(size_t)i * P + blockIdx.x] = c;        // i = t*k + entry
+    }
+}
+
+// Gate and selection for the tile path (Eq. 7's W2 projection, then top-g): one workgroup
+// per tile of 16 groups x 16 tokens, the columns split over its 16 waves in steps of 32
+// (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at 8*(l/16));
+// the partial tiles are summed in wave order.  The workgroup that finishes last ranks
+// every token's scores by counting and writes the selection, the token mask of every
+// group and the ascending list of activated groups.
+struct GateSelParams {
+    const uint4* hidden;                    // [M, n_vec]
+    const uint4* gate_W;                    // [G, n_vec]
+    const float* bias;                      // [G] or null
+    float* s;                               // [M, G] scores (workspace)
+    int32_t* sel;                           // [M, g]
+    unsigned long long* group_mask;         // [G]
+    int32_t* union_list;                    // [G]
+    int32_t* n_union;                       // [1]
+    unsigned int* counter;                  // arrival counter, zero between calls
+    int M, G, g, n_vec;
+};
+
+__device__ __forceinline__ float load_score(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
+    __shared__ float part[kFusedWaves][256];
+    __shared__ unsigned long long mask[kMaxG];
+    __shared__ int is_last;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r16 = lane & 15, q4 = lane >> 4;
+    const int n_tt = (p.M + 15) / 16;
+    const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
+    const int n_ks = (p.n_vec + 3) / 4;
+    const int n = gt * 16 + r16, m = tt * 16 + r16;
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int ks0 = wave; ks0 < n_ks; ks0 += kFusedWaves * 8) {      // wave-uniform
+        uint4 a[8], b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int ks = ks0 + kFusedWaves * i;
+            const int vec = ks * 4 + q4;
+            a[i] = make_uint4(0, 0, 0, 0);
+            b[i] = make_uint4(0, 0, 0, 0);
+            if (ks < n_ks && vec < p.n_vec) {
+                if (n < p.G) a[i] = p.gate_W[(size_t)n * p.n_vec + vec];
+                if (m < p.M) b[i] = p.hidden[(size_t)m * p.n_vec + vec];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[i]),
+                                                          __builtin_bit_cast(bf16x8_t, b[i]), acc, 0, 0, 0);
+    }
+    *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        const int e = threadIdx.x, l = e >> 2, i = e & 3;
+        const int gn = gt * 16 + (l >> 4) * 4 + i;
+        const int tm = tt * 16 + (l & 15);
+        float sum = 0.f;
+        for (int w = 0; w < kFusedWaves; ++w) sum += part[w][e];
+        if (gn < p.G && tm < p.M)
+            __hip_atomic_store(p.s + (size_t)tm * p.G + gn, sum + (p.bias ? p.bias[gn] : 0.f),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the scores are out
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        is_last = old == gridDim.x - 1 ? 1 : 0;
+    }
+    __syncthreads();
+    if (!uni(is_last)) return;                         // block-uniform
+
+    for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) mask[g0] = 0ull;
+    __syncthreads();
+    if (p.G <= kWave) {
+        for (int tm = wave; tm < p.M; tm += kFusedWaves) {  // one wave per token, group in lane
+            float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
+            if (!(v == v)) v = -INFINITY;
+            const int rank = wave_rank(v, lane, p.G);
+            if (lane < p.G && rank < p.g) {
+                atomicOr(&mask[lane], 1ull << tm);
+                p.sel[tm * p.g + rank] = lane;
+            }
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < p.M * p.G; idx += kFusedBlock) {
+            const int tm = idx / p.G;
+            const int gn = idx - tm * p.G;
+            const float* row = p.s + (size_t)tm * p.G;
+            float v = load_score(row + gn);
+            if (!(v == v)) v = -INFINITY;
+            int rank = 0;
+            for (int o = 0; o < p.G; ++o) {
+                float ov = load_score(row + o);
+                if (!(ov == ov)) ov = -INFINITY;
+                rank += better(ov, o, v, gn) ? 1 : 0;
+            }
+            if (rank < p.g) {
+                atomicOr(&mask[gn], 1ull << tm);
+                p.sel[tm * p.g + rank] = gn;
+            }
+        }
+    }
+    __syncthreads();
+    for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) p.group_mask[g0] = mask[g0];
+    if (wave == 0) {
+        int count = 0;
+        for (int base = 0; base < p.G; base += kWave) {
+            const int g0 = base + lane;
+            const bool on = g0 < p.G && mask[g0] != 0ull;
+            const unsigned long long b = __ballot(on);
+            if (on) p.union_list[count + __popcll(b & ((1ull << lane) - 1ull))] = g0;
+            count += __popcll(b);
+        }
+        if (lane == 0) {
+            *p.n_union = count;
+            __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// Per token, merges the P published lists part[(t*k + i)*P + w] into the result.
+__global__ __launch_bounds__(256) void k_merge_published(const Cand* __restrict__ part, int P, int M,
+                                                         int k, int32_t* __restrict__ topk_ids,
+                                                         float* __restrict__ topk_logits) {
+    __shared__ Cand scratch_all[4 * kWave];
+    __shared__ int tags_all[4 * kWave];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int t = blockIdx.x * 4 + wave;
+    if (t >= M) return;                                // wave-uniform, no barriers below
+    const Cand* src = part + (size_t)t * k * P;
+    wave_merge_topk(
+        P, k, lane, scratch_all + wave * kWave, tags_all + wave * kWave,
+        [&](int l, int i) { return src[(size_t)i * P + l]; },
+        [&](int r, Cand c) {
+            topk_ids[(size_t)t * k + r] = c.id;
+            topk_logits[(size_t)t * k + r] = c.v;
+        });
+}
+
+}  // namespace

@@ -58,6 +58,19 @@ def test_group_index_validate():
     assert v(ragged, rows, 2, 6) == OK
 
 
+def test_path_selection_covers_the_three_paths():
+    path = coral.coral_lmhead_path
+    assert path(False, 1, 4096, 128256, 32, 4, 10, BF16) == 1      # Llama3 shape, one token
+    assert path(False, 16, 4096, 128256, 32, 4, 10, BF16) == 1
+    assert path(False, 64, 4096, 128256, 64, 8, 16, BF16) == 2     # wide tree: hidden exceeds LDS
+    assert path(True, 16, 4096, 128256, 0, 0, 10, BF16) == 2       # dense, many tokens
+    assert path(True, 1, 4096, 128256, 0, 0, 10, BF16) == 1
+    assert path(False, 64, 512, 1040, 8, 1, 64, BF16) == 0         # k = 64: general path
+    assert path(False, 4, 256, 8192, 16, 2, 8, F32) == 1
+    assert path(True, 64, 8192, 8192, 0, 0, 8, F32) == 0           # fp32 rows longer than 8 KB
+    assert path(False, 65, 256, 8192, 16, 2, 8, F32) == -1
+
+
 def test_workspace_init_rejects_bad_arguments():
     L = coral._L
     assert L.coral_lmhead_workspace_init(None, 4096, None) == WORKSPACE

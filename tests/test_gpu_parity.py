@@ -105,13 +105,30 @@ def test_extreme_m_g_k(coral, M, g, k):
     check_dense(dh, hidden, k, run_dense(coral, dh, hidden, k))
 
 
-def test_all_groups_active_equals_dense_on_device(coral):
-    cfg = HeadConfig("gG", "bf16", 1024, 6 * 111, 6, 6, (9,), 12, 78, True)
+@pytest.mark.parametrize("M", [4, 9])
+def test_all_groups_active_equals_dense_on_device(coral, M):
+    cfg = HeadConfig("gG", "bf16", 1024, 6 * 111, 6, 6, (M,), 12, 78, True)
     dh = DeviceHead(coral, make_head(cfg))
-    hidden = make_hidden(cfg, 9)
+    hidden = make_hidden(cfg, M)
     gi, gz, _ = run_grouped(coral, dh, hidden, 6, 12)
     di, dz = run_dense(coral, dh, hidden, 12)
-    assert np.array_equal(gi, di) and np.array_equal(gz, dz)      # same kernels, same order
+    same_kernels = (coral.coral_lmhead_path(False, M, cfg.H, cfg.V, 6, 6, 12, coral.CORAL_BF16)
+                    == coral.coral_lmhead_path(True, M, cfg.H, cfg.V, 0, 0, 12, coral.CORAL_BF16))
+    assert np.array_equal(gi, di)
+    if same_kernels:                      # same kernels, same summation order: same bits
+        assert np.array_equal(gz, dz)
+    else:                                 # vector units vs matrix cores: fp32 rounding differs
+        assert M == 9 and np.max(np.abs(gz - dz)) < 1e-5
+
+
+def test_every_path_is_exercised(coral):
+    """The scaled and full-size cases above cover all three kernel paths."""
+    P = coral.coral_lmhead_path
+    B = coral.CORAL_BF16
+    assert P(False, 16, 4096, 32 * 203, 32, 4, 10, B) == 1          # scaled Llama3: single launch
+    assert P(False, 64, 4096, 64 * 126, 64, 8, 16, B) == 2          # scaled wide tree: tiles
+    assert P(True, 16, 4096, 32 * 203, 0, 0, 10, B) == 2            # dense, 16 tokens: tiles
+    assert P(False, 64, 512, 8 * 130, 8, 1, 64, B) == 0             # extreme k: staged
 
 
 def test_ragged_and_empty_groups(coral):
