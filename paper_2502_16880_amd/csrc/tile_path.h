@@ -28,7 +28,7 @@ constexpr int kTileRows = 64;                    // weight rows per block (4 row
 constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-column chunk
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
-constexpr int kTileMaxK = 32;                    // two lists must fit the 64 lanes of a wave
+constexpr int kTileMaxK = 64;                    // a list occupies the lanes of one wave
 
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
@@ -61,7 +61,7 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
     L.o_lists = take((size_t)M * k * sizeof(Cand));
     L.o_rowid = take(kTileRows * sizeof(int));
     L.o_tokslot = take(64 * sizeof(int));
-    L.o_scratch = take((size_t)kTileWaves * kWave * sizeof(Cand));
+    L.o_scratch = take(16);
     L.o_ugroup = take((size_t)u_max * sizeof(int));
     L.o_ustart = take((size_t)u_max * sizeof(int));
     L.o_uend = take((size_t)u_max * sizeof(int));
@@ -73,33 +73,38 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
 }
 
 // Merges the block's 64 logits of one token (one per lane, padding = sentinel) into the
-// token's sorted list in LDS.  Only candidates that beat the list's k-th entry take part;
-// at most k of them can matter, so they are first cut to their own k best, then ranked
-// together with the list's entries (2k <= 64 lanes).
-__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c, Cand* scratch) {
+// token's sorted list in LDS.  Only candidates that beat the list's k-th entry take part.
+// Every participant's new rank is counted directly: a candidate's rank is the number of
+// list entries and of other candidates that beat it, a list entry moves down by the number
+// of candidates that beat it.  Ranks are distinct, so all writes go to distinct slots.
+__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c) {
     Cand e = sentinel();
     if (lane < k) e = list[lane];
     const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e.v), k - 1));
     const int ti = __builtin_amdgcn_readlane(e.id, k - 1);
-    bool keep = is_real(c) && better(c.v, c.id, tv, ti);
-    unsigned long long b = __ballot(keep);
+    const bool pass = is_real(c) && better(c.v, c.id, tv, ti);
+    unsigned long long b = __ballot(pass);
     if (b == 0ull) return;                             // wave-uniform
-    if (__popcll(b) > k) {                             // cut to the k best among themselves
-        Cand s = keep ? c : sentinel();
-        const int r = wave_rank(s.v, s.id, kWave);
-        keep = keep && r < k;
-        b = __ballot(keep);
+    const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
+    const unsigned long long ckey = cand_key(c.v, c.id), ekey = cand_key(e.v, e.id);
+    const int clo = (int)(unsigned)ckey, chi = (int)(unsigned)(ckey >> 32);
+    const int elo = (int)(unsigned)ekey, ehi = (int)(unsigned)(ekey >> 32);
+    int rc = 0, re = lane;
+    for (int j = 0; j < kr; ++j) {                     // wave-uniform
+        const unsigned long long o = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(ehi, j) << 32) |
+                                     (unsigned)__builtin_amdgcn_readlane(elo, j);
+        rc += o > ckey ? 1 : 0;
     }
-    const int ns = __popcll(b);
-    if (keep) scratch[__popcll(b & ((1ull << lane) - 1ull))] = c;
-    const unsigned long long lb = __ballot(lane < k && is_real(e));
-    const int kr = __popcll(lb);                       // real entries are a prefix of the list
-    if (lane < kr) scratch[ns + lane] = e;
-    const int n = ns + kr;                             // <= 2k <= 64
-    Cand s = sentinel();
-    if (lane < n) s = scratch[lane];
-    const int r = wave_rank(s.v, s.id, n);
-    if (lane < n && r < k) list[r] = s;
+    while (b) {                                        // wave-uniform
+        const int src = __ffsll(b) - 1;
+        b &= b - 1ull;
+        const unsigned long long o = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(chi, src) << 32) |
+                                     (unsigned)__builtin_amdgcn_readlane(clo, src);
+        rc += o > ckey ? 1 : 0;
+        re += o > ekey ? 1 : 0;
+    }
+    if (pass && rc < k) list[rc] = c;
+    if (lane < kr && re < k) list[re] = e;
 }
 
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
@@ -122,7 +127,6 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     const int r16 = lane & 15, q4 = lane >> 4;
     const int rt = wave / kTileSplit, kq = wave % kTileSplit;
     const int M = p.M, k = p.k;
-    Cand* scratch = reinterpret_cast<Cand*>(lds + lay.o_scratch) + (size_t)wave * kWave;
 
     for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
     int total_blocks;
@@ -297,7 +301,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             c.v = z;
             c.id = rowid[lane];
             if (c.id < 0) c = sentinel();
-            tile_merge_token(lists + (size_t)t * k, k, lane, c, scratch);
+            tile_merge_token(lists + (size_t)t * k, k, lane, c);
         }
         __syncthreads();
         b = nb;

@@ -224,6 +224,86 @@ def test_caller_buffers_and_streams(coral):
     assert e.value.status == 5
 
 
+def test_many_calls_on_one_workspace_stay_consistent(coral):
+    """The single-launch path hands partial lists between workgroups through memory and
+    re-arms its counters itself: 300 back-to-back calls on one workspace, alternating two
+    inputs, must reproduce the first results bit for bit."""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 1003)
+    dh = DeviceHead(coral, make_head(cfg))
+    for M in (1, 8):
+        hs = [coral.device_tensor(make_hidden(cfg, M, b), cfg.dtype) for b in (0, 1)]
+        ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16)
+        first = []
+        for h in hs:
+            r = coral.coral_lmhead_grouped(h, dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k, workspace=ws)
+            torch.cuda.synchronize()
+            first.append([x.clone() for x in r])
+        outs = []
+        for i in range(300):
+            ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+            z = torch.empty((M, cfg.k), device="cuda")
+            sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+            coral.coral_lmhead_grouped(hs[i % 2], dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                       topk_ids=ids, topk_logits=z, sel_groups=sel, workspace=ws)
+            outs.append((ids, z, sel))
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            for got, want in zip(o, first[i % 2]):
+                assert torch.equal(got, want), f"call {i} (M={M}) differs from the first result"
+
+
+def test_hip_graph_replays_match_eager(coral):
+    """Captured once, replayed several times with eager work in between: every replay must
+    give the eager result (the library records kernels only, no memset nodes)."""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 501)
+    dh = DeviceHead(coral, make_head(cfg))
+    M = 4
+    hidden = make_hidden(cfg, M)
+    d_hidden = coral.device_tensor(hidden, cfg.dtype)
+    ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16)
+    ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+    z = torch.empty((M, cfg.k), device="cuda")
+    sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+
+    def call():
+        coral.coral_lmhead_grouped(d_hidden, dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                   topk_ids=ids, topk_logits=z, sel_groups=sel, workspace=ws)
+        coral.coral_lmhead_dense(d_hidden, dh.lm_W, cfg.k, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    want = (ids.clone(), z.clone(), sel.clone())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for rep in range(4):
+        ids.fill_(-1), z.zero_(), sel.fill_(-1)             # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want[0]) and torch.equal(z, want[1]) and torch.equal(sel, want[2]), rep
+    check_grouped(dh, hidden, cfg.g, cfg.k, (ids.cpu().numpy(), z.cpu().numpy(), sel.cpu().numpy()))
+
+
+def test_nan_inputs_do_not_fault(coral):
+    """Results are unspecified for NaN inputs, but every path must finish and stay in range."""
+    for cfg, M in ((CONFIGS["tiny_f32"], 4), (CONFIGS["llama2_7b"].scaled(V=16 * 250), 12),
+                   (CONFIGS["wide_tree"].scaled(V=64 * 126), 64)):
+        head = make_head(cfg)
+        hidden = make_hidden(cfg, M)
+        if cfg.dtype == "f32":
+            hidden[0, 3] = np.nan
+            head.gate_W[1, 5] = np.nan
+        else:
+            hidden[0, 3] = 0x7FC0
+            head.gate_W[1, 5] = 0x7FC0
+        dh = DeviceHead(coral, head)
+        ids, z, sel = run_grouped(coral, dh, hidden, cfg.g, cfg.k)
+        assert np.all((sel >= 0) & (sel < cfg.G))
+        assert np.all(ids[1:] >= 0) and np.all(ids[1:] < cfg.V)   # tokens without NaN are intact
+        run_dense(coral, dh, hidden, cfg.k)
+
+
 # ------------------------------------------------------------------ full-size workloads
 FULL = [("llama2_7b", (1, 8)), ("llama3_8b", (1, 16)), ("qwen25_7b", (1, 16)), ("wide_tree", (64,))]
 
