@@ -5,7 +5,9 @@ A step is one call of coral_lmhead_grouped (gate projection, per-token top-g, lo
 over the activated groups' rows, fused top-k) on one batch of M synthetic draft hidden
 states at the Llama3-8B draft-head shape (H=4096, V=128256, 32 groups of 4008 rows,
 4 active groups per token, k=10, bf16 weights, fp32 accumulation).  All inputs are
-resident in HBM before the timed region.
+resident in HBM before the timed region.  The headline line is M=8 (a level of the draft
+tree; the paper's tree expands the top 10 candidates per level); M=1,4,16 and the dense
+head are timed beside it and reported under "cases".
 
 Protocol: a cycle of R distinct hidden batches is captured once into a HIP graph and
 replayed; consecutive batches of a cycle select disjoint groups whenever the active set
@@ -39,12 +41,17 @@ def parse():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", default="llama3_8b")
-    ap.add_argument("--M", type=int, default=1, help="draft tokens per step of the headline line")
+    ap.add_argument("--M", type=int, default=8,
+                    help="draft tokens per step of the headline line (the paper expands the top "
+                         "10 candidates per tree level; 8 is the nearest configured value)")
     ap.add_argument("--cases", default="default",
                     help="'default': also time the config's other M values and the dense head with "
                          "fewer steps; 'none': headline only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="no HIP graph: one host call per step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run five 1 GiB device-to-device copies (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
 
 
@@ -235,6 +242,9 @@ def parity_spot_check(bench, res):
     return {"tokens": rep.tokens, "exact_tokens": rep.exact_tokens, "max_abs_err": rep.max_abs_err}
 
 
+KERNEL_OF_PATH = {0: "k_logits", 1: "k_fused", 2: "k_tiles"}
+
+
 def read_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
@@ -259,11 +269,21 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     cfg = CONFIGS[a.config]
+    if a.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     bench = Bench(cfg)
     res = bench.time_grouped(a.M, a.steps, a.warmup, eager=a.eager)
     gbps_step = res["bytes"] / (res["us_per_step"] * 1e-6) / 1e9
     gbps_kernel = res["bytes"] / (res["kernel_us"] * 1e-6) / 1e9
     workload = f"{cfg.name}_M{a.M}"
+    import paper_2502_16880_amd as coral
+    path = coral.coral_lmhead_path(False, a.M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, bench.dt)
+    kernel = KERNEL_OF_PATH[path]
     out = {
         "metric": "us per grouped LM-head draft step (Llama3-8B shape)" if a.config == "llama3_8b"
                   else f"us per grouped LM-head draft step ({cfg.name})",
@@ -274,11 +294,11 @@ def main():
                                f"M={a.M} k={cfg.k}, rotating cycle of {res['batches']} hidden batches",
                    "avg_activated_groups": res["U"], "graph": not a.eager},
         "achieved_GBps_whole_step": gbps_step,
-        "roofline": {"bound": "hbm", "kernel": "k_logits (weight-row streaming + fused top-k)",
+        "roofline": {"bound": "hbm", "kernel": f"{kernel} ({coral.PATH_NAMES[path]} path)",
                      "achieved": gbps_kernel, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps_kernel / HBM_PEAK_GBPS, "kernel_us": res["kernel_us"],
                      "algorithmic_bytes": res["bytes"],
-                     "traffic": read_traffic("k_logits", workload)},
+                     "traffic": read_traffic(kernel, workload)},
         "parity": parity_spot_check(bench, res),
     }
     if not a.no_cpu_baseline:

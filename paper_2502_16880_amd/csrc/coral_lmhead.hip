@@ -126,8 +126,8 @@ bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* 
     const int n_vec = H / (bf16 ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     if (jp > kFusedSegs) return false;
-    // more than two tokens: the gate goes through the matrix cores (bf16 only)
-    const bool mfma_gate = !dense && bf16 && M > 2;
+    // many tokens: the gate goes through the matrix cores (bf16 only)
+    const bool mfma_gate = !dense && bf16 && M > 4;
     const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, mfma_gate);
     if (F.total > kLdsLimit) return false;
     int P = compute_units();
@@ -275,7 +275,7 @@ extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, i
     int um = 0, lds = 0;
     const bool tiles = tiles_fit(M, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
     if (dense && M >= 8 && tiles) return 2;
-    const bool mfma_gate = !dense && bf16 && M > 2;
+    const bool mfma_gate = !dense && bf16 && M > 4;
     if (jp <= kFusedSegs &&
         fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense != 0, mfma_gate).total <= kLdsLimit)
         return 1;

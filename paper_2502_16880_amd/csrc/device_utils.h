@@ -75,6 +75,40 @@ __device__ __forceinline__ float wave_sum(float x) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
 }
 
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_add_i32(int x) {
+    return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes (lane 63 holds the total).
+__device__ __forceinline__ int wave_scan_inclusive(int x) {
+    x = dpp_add_i32<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_add_i32<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_add_i32<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_add_i32<0x118, 0xf>(x);   // row_shr:8  -> scan inside each row of 16
+    x = dpp_add_i32<0x142, 0xa>(x);   // row_bcast:15: rows 1 and 3 add the row before
+    x = dpp_add_i32<0x143, 0xc>(x);   // row_bcast:31: rows 2 and 3 add the first half
+    return x;
+}
+
+// MFMA operand loads.  v_mfma_f32_16x16x32_bf16 wants lane l to hold row l%16, 16-byte
+// chunk l/16 of a 64-byte step; loading it that way makes neighbouring lanes touch
+// different rows, which the texture addresser handles at a quarter of its rate.  So lane p
+// loads row p/4, chunk p%4 (four neighbouring lanes cover 64 contiguous bytes) and the
+// registers are then moved to the layout the instruction wants: lane l takes lane
+// 4*(l%16) + l/16.
+__device__ __forceinline__ int mfma_load_row(int lane) { return lane >> 2; }
+__device__ __forceinline__ int mfma_load_chunk(int lane) { return lane & 3; }
+// The move goes through a wave-private LDS slice of kQuadSlots 16-byte slots: one
+// ds_write_b128 and one ds_read_b128 per operand (a slot of padding after every 16 keeps
+// both conflict-free); LDS operations of a wave execute in order, so no barrier is needed.
+constexpr int kQuadSlots = 68;
+__device__ __forceinline__ uint4 mfma_operand_from_quads(uint4 v, int lane, uint4* slice) {
+    slice[lane + (lane >> 4)] = v;
+    const int src = ((lane & 15) << 2) | (lane >> 4);
+    return slice[src + (src >> 4)];
+}
+
 // Value of the lane below (lane 0 keeps its own): one DPP move, no LDS round trip.
 __device__ __forceinline__ int lane_below(int x) {
     return __builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);

@@ -27,6 +27,7 @@ constexpr int kFusedSegs = 8;          // 1 KB segments of a row held in registe
 constexpr int kLdsLimit = 160 * 1024;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 constexpr int kMergeAreaBytes = kWave * 8 + kWave * 4;   // merge scratch per wave
 
 struct FusedParams {
@@ -70,7 +71,7 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
     // the MFMA gate parks its per-wave partial tiles here before the lists are initialised
     const size_t gate_part_bytes =
-        (!dense && mfma_gate) ? (size_t)kFusedWaves * ((M + 15) / 16) * 256 * sizeof(float) : 0;
+        (!dense && mfma_gate) ? (size_t)kFusedWaves * ((M + 15) / 16) * kGateSlice * sizeof(float) : 0;
     if (lists_bytes < gate_part_bytes) lists_bytes = gate_part_bytes;
     L.o_lists = take(lists_bytes);
     L.o_s = take(dense ? 16 : (size_t)M * G * sizeof(float));
@@ -187,20 +188,50 @@ __device__ __forceinline__ int wave_rank(float v, int id, int n) {
 
 __device__ __forceinline__ bool is_real(Cand c) { return c.id != INT_MAX; }
 
-// k-th best of the candidates in lanes [0, n); (tv, ti) is wave-uniform.  Padding entries
-// all compare equal, so with fewer than k real candidates the result is the padding value
-// (a bound that everything reaches).
-__device__ __forceinline__ void wave_kth(float v, int id, int n, int k, int lane, float& tv,
-                                         int& ti) {
-    const int r = wave_rank(v, id, n);
-    const unsigned long long b = __ballot(lane < n && r == k - 1 && id != INT_MAX);
-    tv = -INFINITY;
-    ti = INT_MAX;
-    if (b) {
-        const int src = __ffsll(b) - 1;
-        tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
-        ti = __builtin_amdgcn_readlane(id, src);
+// Order-preserving 32-bit key of a logit (0 is below every logit, used for padding).
+__device__ __forceinline__ unsigned ord32(float v) {
+    const unsigned u = __float_as_uint(v + 0.0f);
+    return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+__device__ __forceinline__ unsigned cand_ord(Cand c) { return is_real(c) ? ord32(c.v) : 0u; }
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ unsigned dpp_max(unsigned x) {
+    const unsigned moved = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, false);
+    return x > moved ? x : moved;
+}
+__device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
+    x = dpp_max<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_max<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_max<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_max<0x118, 0xf>(x);   // row_shr:8
+    x = dpp_max<0x142, 0xa>(x);   // row_bcast:15
+    x = dpp_max<0x143, 0xc>(x);   // row_bcast:31
+    return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+// k-th largest of the keys in lanes [0, n) (by repeated removal of the maximum), or 0 if
+// there are fewer than k non-zero keys.  Wave-uniform.  Used as a bound only: candidates
+// are kept if their key reaches it, ties included.
+__device__ __forceinline__ unsigned wave_kth_key(unsigned key, int n, int k, int lane) {
+    if (lane >= n) key = 0u;
+    if (n <= 24) {                                     // few keys: count ranks instead
+        int r = 0;
+        for (int j = 0; j < n; ++j) {                  // wave-uniform
+            const unsigned o = (unsigned)__builtin_amdgcn_readlane((int)key, j);
+            r += (o > key || (o == key && j < lane)) ? 1 : 0;
+        }
+        const unsigned long long b = __ballot(lane < n && r == k - 1);
+        return b ? (unsigned)__builtin_amdgcn_readlane((int)key, __ffsll(b) - 1) : 0u;
     }
+    unsigned m = 0u;
+    for (int r = 0; r < k; ++r) {                      // wave-uniform
+        m = wave_max_u32(key);
+        if (m == 0u) break;
+        const unsigned long long b = __ballot(key == m);
+        if (lane == __ffsll(b) - 1) key = 0u;
+    }
+    return m;
 }
 
 // e / k for 0 <= e < 4096 and 1 <= k <= 64 without an integer division.
@@ -224,9 +255,9 @@ __device__ __forceinline__ int wave_append(Cand* scratch, int* tag_scratch, int 
 
 // One wave merges n_lists sorted lists of k candidates (get(list, i), padding entries are
 // sentinels) into the k best, put(rank, candidate) for every rank < k.
-// Fast path: the k-th largest of the lists' first entries is a lower bound of the result's
-// k-th entry, so only lists whose first entry reaches it can contribute, and of those only
-// entries that reach it; the few survivors are ranked by counting.  If a bound does not
+// Fast path: the k-th largest value among the lists' first entries is a lower bound of the
+// result's k-th value, so only lists whose first entry reaches it can contribute, and of
+// those only entries that reach it (ties kept); the few survivors are ranked by counting.  If a bound does not
 // exist (fewer than k lists, more than 256 lists) or too many survive (64), the lists are
 // streamed through a sorted register list instead.
 template <class Get, class Put>
@@ -236,8 +267,7 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
     const int inv_k = inv_small(k);
     bool fast = n_lists >= k && n_lists <= 4 * kWave;
     int n_s = 0;
-    float tv = -INFINITY;
-    int ti = INT_MAX;
+    unsigned tau = 0u;
     if (fast) {
         Cand mx[4];
 #pragma unroll
@@ -248,21 +278,21 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
         }
         // bound from a sample of first entries (the first 64 lists); if more than 64 lists
         // reach it, the 64 kept so far are the next, tighter sample
-        Cand sample = mx[0];
+        unsigned sample = cand_ord(mx[0]);
         int n_sample = n_lists < kWave ? n_lists : kWave;
         int cnt = 0;
 #pragma unroll
         for (int round = 0; round < 3; ++round) {              // wave-uniform
-            wave_kth(sample.v, sample.id, n_sample, k, lane, tv, ti);
+            tau = wave_kth_key(sample, n_sample, k, lane);
             cnt = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 if (c * kWave < n_lists)
                     cnt = wave_append(scratch, tags, cnt, kCap,
-                                      is_real(mx[c]) && !better(tv, ti, mx[c].v, mx[c].id), mx[c],
+                                      is_real(mx[c]) && ord32(mx[c].v) >= tau, mx[c],
                                       c * kWave + lane, lane);
             if (cnt <= kCap) break;
-            sample = scratch[lane];
+            sample = cand_ord(scratch[lane]);
             n_sample = kCap;
         }
         if (cnt > kCap) {
@@ -274,9 +304,9 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
                 s = scratch[lane];
                 tag = tags[lane];
             }
-            if (n_lists > kWave || cnt > kWave)                // else the sample was everything
-                wave_kth(s.v, s.id, cnt, k, lane, tv, ti);     // exact k-th largest first entry
-            const bool live = lane < cnt && !better(tv, ti, s.v, s.id);
+            if (n_lists > kWave)                               // else the sample was everything
+                tau = wave_kth_key(cand_ord(s), cnt, k, lane); // k-th largest first entry
+            const bool live = lane < cnt && ord32(s.v) >= tau;
             const unsigned long long b = __ballot(live);
             n_s = __popcll(b);
             if (live) tags[__popcll(b & ((1ull << lane) - 1ull))] = tag;   // compact list ids
@@ -299,7 +329,7 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
 #pragma unroll
             for (int u = 0; u < 2; ++u)
                 cnt = wave_append(scratch, nullptr, cnt, kCap,
-                                  is_real(c2[u]) && !better(tv, ti, c2[u].v, c2[u].id), c2[u], 0, lane);
+                                  is_real(c2[u]) && ord32(c2[u].v) >= tau, c2[u], 0, lane);
         }
         if (cnt <= kCap) {
             Cand s = sentinel();
@@ -436,7 +466,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             const int r16 = lane & 15, q4 = lane >> 4;
             const int n_ks = (p.n_vec + 3) / 4;            // <= 128 because jp <= 8
             const int n_gt = (p.G + 15) / 16, n_tt = (M + 15) / 16;
-            float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][256]
+            float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][kGateSlice]
+            uint4* my_slice = reinterpret_cast<uint4*>(gpart + (size_t)wave * n_tt * kGateSlice);
             // waves 0-7 work on the even tile of a pair of group tiles, waves 8-15 on the odd
             // one; each takes two adjacent 32-column steps at a time (one 128-byte line per
             // gate row) out of every 16
@@ -448,11 +479,11 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             // they do not all queue on one L2 channel
             const int rot = (int)((blockIdx.x >> 3) & 7u);
             auto step_of = [&](int i) { return 16 * (((i >> 1) + rot) & 7) + 2 * kw + (i & 1); };
-            auto load_gate_tile = [&](int gt) {
-                const int n = gt * 16 + r16;
+            auto load_gate_tile = [&](int gt) {                // quad-coalesced, see device_utils.h
+                const int n = gt * 16 + mfma_load_row(lane);
 #pragma unroll
                 for (int i = 0; i < kSteps; ++i) {
-                    const int vec = step_of(i) * 4 + q4;
+                    const int vec = step_of(i) * 4 + mfma_load_chunk(lane);
                     ga[i] = make_uint4(0, 0, 0, 0);
                     if (vec < p.n_vec && n < p.G) ga[i] = p.gate_W[(size_t)n * p.n_vec + vec];
                 }
@@ -461,6 +492,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             __syncthreads();
             for (int pair = 0; pair * 2 < n_gt; ++pair) {
                 if (pair) load_gate_tile(pair * 2 + half);
+#pragma unroll
+                for (int i = 0; i < kSteps; ++i)               // to the MFMA operand layout
+                    ga[i] = mfma_operand_from_quads(ga[i], lane, my_slice);
                 for (int tt = 0; tt < n_tt; ++tt) {            // uniform
                     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
                     const int m = tt * 16 + r16;
@@ -481,7 +515,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                                 __builtin_bit_cast(bf16x8_t, ga[i0 + u]),
                                 __builtin_bit_cast(bf16x8_t, hb[u]), acc, 0, 0, 0);
                     }
-                    *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * 256 + lane * 4) = acc;
+                    *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * kGateSlice + lane * 4) = acc;
                 }
                 __syncthreads();
                 for (int idx = threadIdx.x; idx < 2 * n_tt * 256; idx += kFusedBlock) {
@@ -493,7 +527,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     const int m = tt * 16 + (l & 15);
                     float sum = 0.f;
                     for (int w = hh * 8; w < hh * 8 + 8; ++w)
-                        sum += gpart[((size_t)w * n_tt + tt) * 256 + e];
+                        sum += gpart[((size_t)w * n_tt + tt) * kGateSlice + e];
                     if (n < p.G && m < M) s_lds[m * p.G + n] = sum + (p.bias ? p.bias[n] : 0.f);
                 }
                 __syncthreads();
@@ -601,13 +635,16 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 }
                 count += __popcll(b);
             }
+            int carry = 0;                             // row pairs before each activated group
+            for (int base = 0; base < count; base += kWave) {
+                const int u = base + lane;
+                const int nb = u < count ? (uend[u] - ustart[u] + kFusedRows - 1) / kFusedRows : 0;
+                const int incl = wave_scan_inclusive(nb);
+                if (u < count) uprefix[u] = carry + incl - nb;
+                carry += __builtin_amdgcn_readlane(incl, 63);
+            }
             if (lane == 0) {
-                int acc = 0;
-                for (int u = 0; u < count; ++u) {
-                    uprefix[u] = acc;
-                    acc += (uend[u] - ustart[u] + kFusedRows - 1) / kFusedRows;
-                }
-                uprefix[count] = acc;
+                uprefix[count] = carry;
                 flags[0] = count;
             }
         }

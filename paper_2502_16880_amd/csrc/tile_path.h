@@ -4,8 +4,8 @@
 //
 // One persistent workgroup of 8 waves per compute unit; wave = (row tile rt = wave/2,
 // half kq = wave%2 of every 512-column chunk).  Per block of 64 rows of one group:
-//   - the weight rows go from HBM straight into the MFMA A operand (lane l: row l%16 of
-//     the tile, 8 columns at 8*(l/16)): four 1 KB wave loads per chunk, a ring of 16 in
+//   - the weight rows go from HBM into registers with four neighbouring lanes on 64
+//     contiguous bytes of a row, then by lane permutation into the MFMA A operand: four 1 KB wave loads per chunk, a ring of 16 in
 //     flight, the next block's first 16 issued before this block's epilogue;
 //   - the hidden vectors of the tokens that selected the group are staged chunk by chunk
 //     (512 columns, double buffered) in LDS and read as B operands;
@@ -61,7 +61,7 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
     L.o_lists = take((size_t)M * k * sizeof(Cand));
     L.o_rowid = take(kTileRows * sizeof(int));
     L.o_tokslot = take(64 * sizeof(int));
-    L.o_scratch = take(16);
+    L.o_scratch = take((size_t)kTileWaves * kQuadSlots * sizeof(uint4));
     L.o_ugroup = take((size_t)u_max * sizeof(int));
     L.o_ustart = take((size_t)u_max * sizeof(int));
     L.o_uend = take((size_t)u_max * sizeof(int));
@@ -127,6 +127,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     const int r16 = lane & 15, q4 = lane >> 4;
     const int rt = wave / kTileSplit, kq = wave % kTileSplit;
     const int M = p.M, k = p.k;
+    uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kQuadSlots;
 
     for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
     int total_blocks;
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     // this lane's weight row: row r16 of tile rt (clamped inside the group; the duplicates
     // are dropped when the candidates are formed)
     auto my_row = [&](int first, int end) {
-        int idx = first + rt * 16 + r16;
+        int idx = first + rt * 16 + mfma_load_row(lane);
         if (idx >= end) idx = end - 1;
         return dense ? idx : p.rows[idx];
     };
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     auto load_a = [&](const uint4* row_ptr, int c, int slot4) {
 #pragma unroll
         for (int j = 0; j < kTileSteps; ++j) {
-            const int vec = c * kChunkVecs + (kq * kTileSteps + j) * 4 + q4;
+            const int vec = c * kChunkVecs + (kq * kTileSteps + j) * 4 + mfma_load_chunk(lane);
             a[slot4 * kTileSteps + j] = make_uint4(0, 0, 0, 0);
             if (c < p.n_chunks && vec < p.n_vec) a[slot4 * kTileSteps + j] = load_stream(row_ptr + vec);
         }
@@ -252,12 +253,13 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 #pragma unroll
                     for (int j = 0; j < kTileSteps; ++j) {
                         const int off = (kq * kTileSteps + j) * 4 + q4;
+                        const uint4 am = mfma_operand_from_quads(a[cc * kTileSteps + j], lane, my_slice);
 #pragma unroll
                         for (int ct = 0; ct < 4; ++ct) {
                             if (ct < n_ct) {           // block-uniform
                                 const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
                                 acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, a[cc * kTileSteps + j]),
+                                    __builtin_bit_cast(bf16x8_t, am),
                                     __builtin_bit_cast(bf16x8_t, hv), acc[ct], 0, 0, 0);
                             }
                         }
@@ -343,7 +345,7 @@ __device__ __forceinline__ float load_score(const float* p) {
 }
 
 __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
-    __shared__ float part[kFusedWaves][256];
+    __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
     __shared__ unsigned long long mask[kMaxG];
     __shared__ int is_last;
     const int lane = threadIdx.x & (kWave - 1);
@@ -352,14 +354,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     const int n_tt = (p.M + 15) / 16;
     const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
     const int n_ks = (p.n_vec + 3) / 4;
-    const int n = gt * 16 + r16, m = tt * 16 + r16;
+    const int n = gt * 16 + mfma_load_row(lane), m = tt * 16 + mfma_load_row(lane);
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     for (int ks0 = wave; ks0 < n_ks; ks0 += kFusedWaves * 8) {      // wave-uniform
         uint4 a[8], b[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int ks = ks0 + kFusedWaves * i;
-            const int vec = ks * 4 + q4;
+            const int vec = ks * 4 + mfma_load_chunk(lane);
             a[i] = make_uint4(0, 0, 0, 0);
             b[i] = make_uint4(0, 0, 0, 0);
             if (ks < n_ks && vec < p.n_vec) {
@@ -369,8 +371,12 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[i]),
-                                                          __builtin_bit_cast(bf16x8_t, b[i]), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8_t,
+                                   mfma_operand_from_quads(a[i], lane, reinterpret_cast<uint4*>(part[wave]))),
+                __builtin_bit_cast(bf16x8_t,
+                                   mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave]))),
+                acc, 0, 0, 0);
     }
     *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
     __syncthreads();
