@@ -28,7 +28,14 @@ constexpr int kLdsLimit = 160 * 1024;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
-constexpr int kMergeAreaBytes = kWave * 8 + kWave * 4;   // merge scratch per wave
+// Wave-private LDS scratch of the merges: ranking keys, gathered candidates, list tags.
+struct WaveScratch {
+    unsigned long long keys[kWave];
+    unsigned keys32[kWave];
+    Cand cand[kWave];
+    int tags[kWave];
+};
+constexpr int kMergeAreaBytes = sizeof(WaveScratch);
 
 struct FusedParams {
     const uint4* hidden;        // [M, n_vec]
@@ -48,8 +55,13 @@ struct FusedParams {
 
 struct FusedLds {
     int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags;
+    int o_keys, o_offsets, o_bias;
     int total;
 };
+
+// 16-byte vectors between consecutive hidden vectors in LDS: the row length plus one, so
+// that the matrix-core gate, which reads a column of 16 rows at a time, meets no bank conflicts.
+__host__ __device__ inline int hidden_lds_stride(int jp) { return jp * kWave + 1; }
 
 // Byte offsets of the kernel's regions in dynamic LDS (the host sizes the launch with the
 // same function the kernel lays its pointers out with).
@@ -64,7 +76,7 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     };
     long long um = (long long)M * g < G ? (long long)M * g : G;   // activated groups at most
     if (dense || um < 1) um = 1;
-    size_t hidden_bytes = (size_t)M * jp * kWave * sizeof(uint4);
+    size_t hidden_bytes = (size_t)M * hidden_lds_stride(jp) * sizeof(uint4);
     const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes;
     if (hidden_bytes < scratch_bytes) hidden_bytes = scratch_bytes;   // reused by the merges
     L.o_hidden = take(hidden_bytes);
@@ -82,6 +94,9 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     L.o_uprefix = take((size_t)(um + 1) * sizeof(int));
     L.o_umask = take((size_t)um * sizeof(unsigned long long));
     L.o_flags = take(16);
+    L.o_keys = take(dense ? 16 : (size_t)kFusedWaves * kWave * sizeof(unsigned long long));
+    L.o_offsets = take(dense ? 16 : (size_t)(G + 1) * sizeof(int));
+    L.o_bias = take(dense ? 16 : (size_t)G * sizeof(float));
     L.total = off;
     return L;
 }
@@ -172,18 +187,21 @@ __device__ __forceinline__ unsigned long long cand_key(float v, int id) {
     return ((unsigned long long)u << 32) | (unsigned)(~id);
 }
 
-// Rank of this lane's candidate among the candidates of lanes [0, n): the number of
-// those that beat it.  Candidates are distinct under the total order (distinct ids).
-__device__ __forceinline__ int wave_rank(float v, int id, int n) {
-    const unsigned long long key = cand_key(v, id);
-    const int klo = (int)(unsigned)key, khi = (int)(unsigned)(key >> 32);
+// Number of keys[0, n) above `key`.  keys is LDS that this wave wrote itself (a wave's LDS
+// accesses complete in order); every lane reads the same address, which LDS broadcasts.
+__device__ __forceinline__ int count_above(const unsigned long long* keys, int n, unsigned long long key) {
     int r = 0;
-    for (int j = 0; j < n; ++j) {                      // wave-uniform
-        const unsigned lo = (unsigned)__builtin_amdgcn_readlane(klo, j);
-        const unsigned hi = (unsigned)__builtin_amdgcn_readlane(khi, j);
-        r += (((unsigned long long)hi << 32) | lo) > key ? 1 : 0;
-    }
+#pragma unroll 8
+    for (int j = 0; j < n; ++j) r += keys[j] > key ? 1 : 0;    // wave-uniform trip count
     return r;
+}
+
+// Rank of this lane's candidate among the candidates of lanes [0, n), n <= 64: the number
+// of those that beat it.  Candidates are distinct under the total order (distinct ids).
+__device__ __forceinline__ int wave_rank(unsigned long long* keys, float v, int id, int n, int lane) {
+    const unsigned long long key = cand_key(v, id);
+    keys[lane] = key;
+    return count_above(keys, n, key);
 }
 
 __device__ __forceinline__ bool is_real(Cand c) { return c.id != INT_MAX; }
@@ -196,42 +214,32 @@ __device__ __forceinline__ unsigned ord32(float v) {
 __device__ __forceinline__ unsigned cand_ord(Cand c) { return is_real(c) ? ord32(c.v) : 0u; }
 
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ unsigned dpp_max(unsigned x) {
-    const unsigned moved = (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, false);
-    return x > moved ? x : moved;
+__device__ __forceinline__ unsigned dpp_min(unsigned x) {
+    const unsigned moved = (unsigned)__builtin_amdgcn_update_dpp((int)x, (int)x, CTRL, ROW_MASK, 0xf, false);
+    return x < moved ? x : moved;
 }
-__device__ __forceinline__ unsigned wave_max_u32(unsigned x) {
-    x = dpp_max<0x111, 0xf>(x);   // row_shr:1
-    x = dpp_max<0x112, 0xf>(x);   // row_shr:2
-    x = dpp_max<0x114, 0xf>(x);   // row_shr:4
-    x = dpp_max<0x118, 0xf>(x);   // row_shr:8
-    x = dpp_max<0x142, 0xa>(x);   // row_bcast:15
-    x = dpp_max<0x143, 0xc>(x);   // row_bcast:31
+__device__ __forceinline__ unsigned wave_min_u32(unsigned x) {
+    x = dpp_min<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_min<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_min<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_min<0x118, 0xf>(x);   // row_shr:8
+    x = dpp_min<0x142, 0xa>(x);   // row_bcast:15
+    x = dpp_min<0x143, 0xc>(x);   // row_bcast:31
     return (unsigned)__builtin_amdgcn_readlane((int)x, 63);
 }
 
-// k-th largest of the keys in lanes [0, n) (by repeated removal of the maximum), or 0 if
-// there are fewer than k non-zero keys.  Wave-uniform.  Used as a bound only: candidates
-// are kept if their key reaches it, ties included.
-__device__ __forceinline__ unsigned wave_kth_key(unsigned key, int n, int k, int lane) {
+// k-th largest of the keys in lanes [0, n), or 0 if there are fewer than k keys.
+// Wave-uniform.  Used as a bound only: candidates are kept if their key reaches it, ties
+// included.  A key is among the k largest values exactly when fewer than k keys exceed it;
+// the smallest such key is the k-th largest.  keys32: 64 wave-private LDS words.
+__device__ __forceinline__ unsigned wave_kth_key(unsigned* keys32, unsigned key, int n, int k, int lane) {
+    if (n < k) return 0u;
     if (lane >= n) key = 0u;
-    if (n <= 24) {                                     // few keys: count ranks instead
-        int r = 0;
-        for (int j = 0; j < n; ++j) {                  // wave-uniform
-            const unsigned o = (unsigned)__builtin_amdgcn_readlane((int)key, j);
-            r += (o > key || (o == key && j < lane)) ? 1 : 0;
-        }
-        const unsigned long long b = __ballot(lane < n && r == k - 1);
-        return b ? (unsigned)__builtin_amdgcn_readlane((int)key, __ffsll(b) - 1) : 0u;
-    }
-    unsigned m = 0u;
-    for (int r = 0; r < k; ++r) {                      // wave-uniform
-        m = wave_max_u32(key);
-        if (m == 0u) break;
-        const unsigned long long b = __ballot(key == m);
-        if (lane == __ffsll(b) - 1) key = 0u;
-    }
-    return m;
+    keys32[lane] = key;
+    int above = 0;
+#pragma unroll 16
+    for (int j = 0; j < n; ++j) above += keys32[j] > key ? 1 : 0;   // wave-uniform trip count
+    return wave_min_u32(lane < n && above < k ? key : 0xffffffffu);
 }
 
 // e / k for 0 <= e < 4096 and 1 <= k <= 64 without an integer division.
@@ -255,15 +263,17 @@ __device__ __forceinline__ int wave_append(Cand* scratch, int* tag_scratch, int 
 
 // One wave merges n_lists sorted lists of k candidates (get(list, i), padding entries are
 // sentinels) into the k best, put(rank, candidate) for every rank < k.
-// Fast path: the k-th largest value among the lists' first entries is a lower bound of the
-// result's k-th value, so only lists whose first entry reaches it can contribute, and of
-// those only entries that reach it (ties kept); the few survivors are ranked by counting.  If a bound does not
-// exist (fewer than k lists, more than 256 lists) or too many survive (64), the lists are
-// streamed through a sorted register list instead.
+// Fast path: a value that k lists' first entries reach is a lower bound of the result's
+// k-th value, so only lists whose first entry reaches it can contribute, and of those only
+// entries that reach it (ties kept); the few survivors are ranked by counting.  If a bound
+// does not exist (fewer than k lists, more than 256 lists) or too many survive (64), the
+// lists are streamed through a sorted register list instead.
 template <class Get, class Put>
-__device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Cand* scratch,
-                                                int* tags, Get get, Put put) {
+__device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, WaveScratch* ws,
+                                                Get get, Put put) {
     constexpr int kCap = kWave;
+    Cand* scratch = ws->cand;
+    int* tags = ws->tags;
     const int inv_k = inv_small(k);
     bool fast = n_lists >= k && n_lists <= 4 * kWave;
     int n_s = 0;
@@ -276,14 +286,20 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
             mx[c] = sentinel();
             if (c * kWave < n_lists && l < n_lists) mx[c] = get(l, 0);
         }
-        // bound from a sample of first entries (the first 64 lists); if more than 64 lists
-        // reach it, the 64 kept so far are the next, tighter sample
+        // bound: the k-th largest of the lanes' best first entries (k lanes reach it, so k
+        // lists do); if more than 64 lists reach it, the 64 kept so far are the next,
+        // tighter sample
         unsigned sample = cand_ord(mx[0]);
+#pragma unroll
+        for (int c = 1; c < 4; ++c) {
+            const unsigned o = cand_ord(mx[c]);
+            sample = o > sample ? o : sample;
+        }
         int n_sample = n_lists < kWave ? n_lists : kWave;
         int cnt = 0;
 #pragma unroll
         for (int round = 0; round < 3; ++round) {              // wave-uniform
-            tau = wave_kth_key(sample, n_sample, k, lane);
+            tau = wave_kth_key(ws->keys32, sample, n_sample, k, lane);
             cnt = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -298,18 +314,7 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
         if (cnt > kCap) {
             fast = false;                                      // no usable bound (ties)
         } else {
-            Cand s = sentinel();
-            int tag = 0;
-            if (lane < cnt) {
-                s = scratch[lane];
-                tag = tags[lane];
-            }
-            if (n_lists > kWave)                               // else the sample was everything
-                tau = wave_kth_key(cand_ord(s), cnt, k, lane); // k-th largest first entry
-            const bool live = lane < cnt && ord32(s.v) >= tau;
-            const unsigned long long b = __ballot(live);
-            n_s = __popcll(b);
-            if (live) tags[__popcll(b & ((1ull << lane) - 1ull))] = tag;   // compact list ids
+            n_s = cnt;                                         // the lists that reach the bound
         }
     }
     if (fast) {
@@ -334,7 +339,7 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Ca
         if (cnt <= kCap) {
             Cand s = sentinel();
             if (lane < cnt) s = scratch[lane];
-            const int r = wave_rank(s.v, s.id, cnt);
+            const int r = wave_rank(ws->keys, s.v, s.id, cnt, lane);
             if (lane < cnt && r < k) put(r, s);
             if (lane >= cnt && lane < k) put(lane, sentinel());
             return;
@@ -370,7 +375,7 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
                                              unsigned long long& rem, int rid0, int rid1, bool has1,
                                              float& thr_v, int& thr_i) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int hs_stride = p.jp * kWave;
+    const int hs_stride = hidden_lds_stride(p.jp);
     int tok[NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
@@ -417,41 +422,69 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     int* uprefix = reinterpret_cast<int*>(lds + lay.o_uprefix);
     unsigned long long* umask = reinterpret_cast<unsigned long long*>(lds + lay.o_umask);
     int* flags = reinterpret_cast<int*>(lds + lay.o_flags);
+    int* off_lds = reinterpret_cast<int*>(lds + lay.o_offsets);
+    float* bias_lds = reinterpret_cast<float*>(lds + lay.o_bias);
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int hs_stride = p.jp * kWave;
+    const int hs_stride = hidden_lds_stride(p.jp);
     const int M = p.M, k = p.k;
 
     if (threadIdx.x == 0) flags[2] = 0;                // row-pair counter, see step 3
-    // ---- 1. hidden vectors
-    {
-        const int mm = threadIdx.x / hs_stride;            // hs_stride <= 512: at least 2 rows a pass
-        const int vec = threadIdx.x - mm * hs_stride;
-        const int rows_per_pass = kFusedBlock / hs_stride;
-        constexpr int kU = 8;
-        for (int m0 = 0; m0 < M; m0 += rows_per_pass * kU) {
-            uint4 tmp[kU];
+    // ---- 1. hidden vectors: requested first, written to LDS only after the grouped
+    // variants have requested their first gate rows as well (loads return in order, so the
+    // wait for the hidden vectors does not wait for the gate rows behind them)
+    constexpr int kHU = 4;
+    const int row_vecs = p.jp * kWave;                     // <= 512: at least 2 rows a pass
+    const int h_mm = threadIdx.x / row_vecs;
+    const int h_vec = threadIdx.x - h_mm * row_vecs;
+    const int rows_per_pass = kFusedBlock / row_vecs;
+    uint4 htmp[kHU];
+    auto hidden_request = [&](int m0) {
 #pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                const int m = m0 + u * rows_per_pass + mm;
-                tmp[u] = make_uint4(0, 0, 0, 0);
-                if (mm < rows_per_pass && m < M && vec < p.n_vec)
-                    tmp[u] = p.hidden[(size_t)m * p.n_vec + vec];
-            }
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                const int m = m0 + u * rows_per_pass + mm;
-                if (mm < rows_per_pass && m < M) hs[m * hs_stride + vec] = tmp[u];
-            }
+        for (int u = 0; u < kHU; ++u) {
+            const int m = m0 + u * rows_per_pass + h_mm;
+            htmp[u] = make_uint4(0, 0, 0, 0);
+            if (h_mm < rows_per_pass && m < M && h_vec < p.n_vec)
+                htmp[u] = p.hidden[(size_t)m * p.n_vec + h_vec];
         }
+    };
+    auto hidden_commit = [&](int m0) {                     // then the passes that remain
+#pragma unroll
+        for (int u = 0; u < kHU; ++u) {
+            const int m = m0 + u * rows_per_pass + h_mm;
+            if (h_mm < rows_per_pass && m < M) hs[m * hs_stride + h_vec] = htmp[u];
+        }
+    };
+    auto hidden_rest = [&]() {
+        for (int m0 = rows_per_pass * kHU; m0 < M; m0 += rows_per_pass * kHU) {
+            hidden_request(m0);
+            hidden_commit(m0);
+        }
+    };
+    hidden_request(0);
+    // group offsets and bias travel with them (G <= 1024 = the workgroup's size), so that
+    // no later step waits for memory
+    int off_r0 = 0, off_r1 = 0;
+    float bias_r = 0.f;
+    if (!DENSE) {
+        if ((int)threadIdx.x <= p.G) off_r0 = p.offsets[threadIdx.x];
+        if ((int)threadIdx.x + kFusedBlock <= p.G) off_r1 = p.offsets[threadIdx.x + kFusedBlock];
+        if ((int)threadIdx.x < p.G && p.bias) bias_r = p.bias[threadIdx.x];
     }
+    auto small_commit = [&]() {
+        if ((int)threadIdx.x <= p.G) off_lds[threadIdx.x] = off_r0;
+        if ((int)threadIdx.x + kFusedBlock <= p.G) off_lds[threadIdx.x + kFusedBlock] = off_r1;
+        if ((int)threadIdx.x < p.G) bias_lds[threadIdx.x] = bias_r;
+    };
     Cand* my_lists = lists + (size_t)wave * M * k;
     float thr_v = -INFINITY;
     int thr_i = INT_MAX;
 
     int total_batches;
     if (DENSE) {
+        hidden_commit(0);
+        hidden_rest();
         total_batches = (p.V + kFusedRows - 1) / kFusedRows;
         __syncthreads();
     } else {
@@ -461,8 +494,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             // columns split over the 16 waves in steps of 32 (v_mfma_f32_16x16x32_bf16:
             // lane l feeds row l%16, columns 8*(l/16)..+8 of both operands and receives
             // rows 4*(l/16)..+4, column l%16 of the tile); the waves' partial tiles are
-            // summed in wave order.  The first tile's gate rows are requested before the
-            // barrier that completes the hidden vectors.
+            // summed in wave order.
             const int r16 = lane & 15, q4 = lane >> 4;
             const int n_ks = (p.n_vec + 3) / 4;            // <= 128 because jp <= 8
             const int n_gt = (p.G + 15) / 16, n_tt = (M + 15) / 16;
@@ -489,6 +521,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 }
             };
             load_gate_tile(half);
+            hidden_commit(0);
+            small_commit();
+            hidden_rest();
             __syncthreads();
             for (int pair = 0; pair * 2 < n_gt; ++pair) {
                 if (pair) load_gate_tile(pair * 2 + half);
@@ -528,14 +563,13 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     float sum = 0.f;
                     for (int w = hh * 8; w < hh * 8 + 8; ++w)
                         sum += gpart[((size_t)w * n_tt + tt) * kGateSlice + e];
-                    if (n < p.G && m < M) s_lds[m * p.G + n] = sum + (p.bias ? p.bias[n] : 0.f);
+                    if (n < p.G && m < M) s_lds[m * p.G + n] = sum + bias_lds[n];
                 }
                 __syncthreads();
             }
         } else {
-            // ---- 2a. gate on the vector units (fp32 storage, or one or two tokens): each wave takes rows n0 and n0 + 16 per pass; the
-            // loads of the first pass are issued before the barrier that completes the
-            // hidden vectors
+            // ---- 2a. gate on the vector units (fp32 storage, or few tokens): each wave takes
+            // rows n0 and n0 + 16 per pass
             uint4 ga[kFusedSegs], gb[kFusedSegs];
             auto load_gate_rows = [&](int n0) {
                 const int n1 = n0 + kFusedWaves;
@@ -551,6 +585,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 }
             };
             load_gate_rows(wave);
+            hidden_commit(0);
+            small_commit();
+            hidden_rest();
             __syncthreads();
             for (int n0 = wave; n0 < p.G; n0 += 2 * kFusedWaves) {
                 if (n0 != wave) load_gate_rows(n0);
@@ -573,8 +610,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     a1 = wave_sum(a1);
                     b1 = wave_sum(b1);
                     if (lane == 0) {
-                        const float bias0 = p.bias ? p.bias[n0] : 0.f;
-                        const float bias1 = (p.bias && n1 < p.G) ? p.bias[n1] : 0.f;
+                        const float bias0 = bias_lds[n0];
+                        const float bias1 = n1 < p.G ? bias_lds[n1] : 0.f;
                         s_lds[m * p.G + n0] = a0 + bias0;
                         s_lds[m1 * p.G + n0] = a1 + bias0;
                         if (n1 < p.G) {
@@ -590,10 +627,12 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         // fewer than g groups beat it (larger score first, then lower group id); its rank
         // is its position in the selection
         if (p.G <= kWave) {
+            unsigned long long* sel_keys =
+                reinterpret_cast<unsigned long long*>(lds + lay.o_keys) + (size_t)wave * kWave;
             for (int m = wave; m < M; m += kFusedWaves) {  // one wave per token, group n in lane n
                 float v = lane < p.G ? s_lds[m * p.G + lane] : -INFINITY;
                 if (!(v == v)) v = -INFINITY;              // NaN: unspecified, but keep a total order
-                const int rank = wave_rank(v, lane, p.G);
+                const int rank = wave_rank(sel_keys, v, lane, p.G, lane);
                 if (lane < p.G && rank < p.g) {
                     atomicOr(&mask_lds[lane], 1ull << m);
                     if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = lane;
@@ -630,8 +669,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     const int u = count + __popcll(b & ((1ull << lane) - 1ull));
                     ugroup[u] = n;
                     umask[u] = gm;
-                    ustart[u] = p.offsets[n];
-                    uend[u] = p.offsets[n + 1];
+                    ustart[u] = off_lds[n];
+                    uend[u] = off_lds[n + 1];
                 }
                 count += __popcll(b);
             }
@@ -729,17 +768,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     // ---- 5. merge the waves' lists, publish, last workgroup merges all
     __syncthreads();
     // the hidden vectors are no longer needed: their LDS is the merge scratch
-    char* wave_area = lds + lay.o_hidden + (size_t)wave * kMergeAreaBytes;
-    Cand* scratch = reinterpret_cast<Cand*>(wave_area);                     // [64]
-    int* tags = reinterpret_cast<int*>(scratch + kWave);                    // [64]
-    const int inv_k = inv_small(k);
+    WaveScratch* ws = reinterpret_cast<WaveScratch*>(lds + lay.o_hidden) + wave;
     const int P = gridDim.x;
     // published lists are entry-major, part[(t*k + i)*P + workgroup]: the first entries of
     // all workgroups, which bound the result, are contiguous
     for (int t = wave; t < M; t += kFusedWaves) {
         Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
         wave_merge_topk(
-            kFusedWaves, k, lane, scratch, tags,
+            kFusedWaves, k, lane, ws,
             [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
             [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
     }
@@ -757,7 +793,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     for (int t = wave; t < M; t += kFusedWaves) {
         const Cand* src = p.part + (size_t)t * k * P;
         wave_merge_topk(
-            P, k, lane, scratch, tags,
+            P, k, lane, ws,
             [&](int l, int i) { return fetch_cand(src + (size_t)i * P + l); },
             [&](int r, Cand c) {
                 p.topk_ids[(size_t)t * k + r] = c.id;

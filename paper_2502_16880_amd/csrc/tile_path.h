@@ -77,29 +77,27 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
 // Every participant's new rank is counted directly: a candidate's rank is the number of
 // list entries and of other candidates that beat it, a list entry moves down by the number
 // of candidates that beat it.  Ranks are distinct, so all writes go to distinct slots.
-__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c) {
+// keys: 128 wave-private LDS words (ordering keys of the passing candidates, then of the list).
+__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c,
+                                                 unsigned long long* keys) {
     Cand e = sentinel();
     if (lane < k) e = list[lane];
     const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e.v), k - 1));
     const int ti = __builtin_amdgcn_readlane(e.id, k - 1);
     const bool pass = is_real(c) && better(c.v, c.id, tv, ti);
-    unsigned long long b = __ballot(pass);
+    const unsigned long long b = __ballot(pass);
     if (b == 0ull) return;                             // wave-uniform
+    const int np = __popcll(b);
     const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
     const unsigned long long ckey = cand_key(c.v, c.id), ekey = cand_key(e.v, e.id);
-    const int clo = (int)(unsigned)ckey, chi = (int)(unsigned)(ckey >> 32);
-    const int elo = (int)(unsigned)ekey, ehi = (int)(unsigned)(ekey >> 32);
-    int rc = 0, re = lane;
-    for (int j = 0; j < kr; ++j) {                     // wave-uniform
-        const unsigned long long o = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(ehi, j) << 32) |
-                                     (unsigned)__builtin_amdgcn_readlane(elo, j);
-        rc += o > ckey ? 1 : 0;
-    }
-    while (b) {                                        // wave-uniform
-        const int src = __ffsll(b) - 1;
-        b &= b - 1ull;
-        const unsigned long long o = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(chi, src) << 32) |
-                                     (unsigned)__builtin_amdgcn_readlane(clo, src);
+    unsigned long long* ckeys = keys;
+    unsigned long long* lkeys = keys + kWave;
+    if (pass) ckeys[__popcll(b & ((1ull << lane) - 1ull))] = ckey;
+    if (lane < kr) lkeys[lane] = ekey;
+    int rc = count_above(lkeys, kr, ckey), re = lane;
+#pragma unroll 4
+    for (int j = 0; j < np; ++j) {                     // wave-uniform
+        const unsigned long long o = ckeys[j];
         rc += o > ckey ? 1 : 0;
         re += o > ekey ? 1 : 0;
     }
@@ -303,7 +301,8 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             c.v = z;
             c.id = rowid[lane];
             if (c.id < 0) c = sentinel();
-            tile_merge_token(lists + (size_t)t * k, k, lane, c);
+            tile_merge_token(lists + (size_t)t * k, k, lane, c,
+                             reinterpret_cast<unsigned long long*>(my_slice));
         }
         __syncthreads();
         b = nb;
@@ -347,6 +346,7 @@ __device__ __forceinline__ float load_score(const float* p) {
 __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
     __shared__ unsigned long long mask[kMaxG];
+    __shared__ unsigned long long sel_keys[kFusedWaves][kWave];
     __shared__ int is_last;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -406,7 +406,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         for (int tm = wave; tm < p.M; tm += kFusedWaves) {  // one wave per token, group in lane
             float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
             if (!(v == v)) v = -INFINITY;
-            const int rank = wave_rank(v, lane, p.G);
+            const int rank = wave_rank(sel_keys[wave], v, lane, p.G, lane);
             if (lane < p.G && rank < p.g) {
                 atomicOr(&mask[lane], 1ull << tm);
                 p.sel[tm * p.g + rank] = lane;
@@ -453,15 +453,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
 __global__ __launch_bounds__(256) void k_merge_published(const Cand* __restrict__ part, int P, int M,
                                                          int k, int32_t* __restrict__ topk_ids,
                                                          float* __restrict__ topk_logits) {
-    __shared__ Cand scratch_all[4 * kWave];
-    __shared__ int tags_all[4 * kWave];
+    __shared__ WaveScratch scratch_all[4];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int t = blockIdx.x * 4 + wave;
     if (t >= M) return;                                // wave-uniform, no barriers below
     const Cand* src = part + (size_t)t * k * P;
     wave_merge_topk(
-        P, k, lane, scratch_all + wave * kWave, tags_all + wave * kWave,
+        P, k, lane, scratch_all + wave,
         [&](int l, int i) { return src[(size_t)i * P + l]; },
         [&](int r, Cand c) {
             topk_ids[(size_t)t * k + r] = c.id;
