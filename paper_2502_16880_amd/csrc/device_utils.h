@@ -109,6 +109,26 @@ __device__ __forceinline__ uint4 mfma_operand_from_quads(uint4 v, int lane, uint
     return slice[src + (src >> 4)];
 }
 
+// Whole-line variant for streams that would otherwise fetch every 128-byte line in two
+// halves: a wave load covers 8 rows x 128 bytes (lane p: row p/8, chunk p%8 of the line,
+// i.e. both 32-column steps of a step pair), and the two registers that hold rows 0-7 and
+// 8-15 of a tile go through a slice of kLinePairSlots slots together, which yields the
+// operands of both steps (a slot of padding after every 8 keeps writes and reads
+// conflict-free).
+__device__ __forceinline__ int line_load_row(int lane) { return lane >> 3; }
+__device__ __forceinline__ int line_load_chunk(int lane) { return lane & 7; }
+constexpr int kLinePairSlots = 144;
+__device__ __forceinline__ void mfma_operands_from_lines(uint4 rows_lo, uint4 rows_hi, int lane,
+                                                         uint4* slice, uint4& step0, uint4& step1) {
+    const int w = lane + (lane >> 3);
+    slice[w] = rows_lo;
+    slice[72 + w] = rows_hi;
+    const int r = lane & 15, q = lane >> 4;
+    const int src = (r >> 3) * 72 + (r & 7) * 9 + q;
+    step0 = slice[src];
+    step1 = slice[src + 4];
+}
+
 // Value of the lane below (lane 0 keeps its own): one DPP move, no LDS round trip.
 __device__ __forceinline__ int lane_below(int x) {
     return __builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);

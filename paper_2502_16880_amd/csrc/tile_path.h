@@ -1,16 +1,19 @@
 // Matrix-core path for groups that many tokens selected (wide draft-tree steps) and for
-// the dense head with many tokens: the logits of a block of 64 weight rows for up to 64
+// the dense head with many tokens: the logits of a block of 128 weight rows for up to 64
 // tokens are 16x16 tiles of v_mfma_f32_16x16x32_bf16.
 //
-// One persistent workgroup of 8 waves per compute unit; wave = (row tile rt = wave/2,
-// half kq = wave%2 of every 512-column chunk).  Per block of 64 rows of one group:
-//   - the weight rows go from HBM into registers with four neighbouring lanes on 64
-//     contiguous bytes of a row, then by lane permutation into the MFMA A operand: four 1 KB wave loads per chunk, a ring of 16 in
-//     flight, the next block's first 16 issued before this block's epilogue;
+// One persistent workgroup of 8 waves per compute unit; wave = (row group rg = wave/2: 32
+// rows = two row tiles, half kq = wave%2 of every 512-column chunk).  Per block of 128
+// rows of one group:
+//   - the weight rows go from HBM into registers in whole 128-byte lines (a wave load
+//     covers 8 rows x 128 B), and pairs of such registers go through a wave-private LDS
+//     slice into the MFMA A operands of two 32-column steps; 16 KB per wave in flight,
+//     the next block's first 16 loads issued before this block's epilogue;
 //   - the hidden vectors of the tokens that selected the group are staged chunk by chunk
-//     (512 columns, double buffered) in LDS and read as B operands;
+//     (512 columns, double buffered) in LDS and read as B operands, each fragment used for
+//     both row tiles of the wave;
 //   - the two half sums of each tile are added in a fixed order through LDS, which
-//     leaves, per token, the block's 64 logits one per lane of a wave; those that beat the
+//     leaves, per token, the block's 128 logits two per lane of a wave; those that beat the
 //     token's current k-th are merged into the workgroup's running list by rank counting.
 // Each workgroup publishes its lists; a second small kernel merges them per token.
 // The logits row is never written to memory.
@@ -21,14 +24,14 @@
 namespace {
 
 constexpr int kTileWaves = 8;
-constexpr int kTileSplit = 2;                    // waves that share a row tile (split of a chunk)
-constexpr int kTileSteps = 16 / kTileSplit;      // 32-column steps of a chunk per wave
+constexpr int kTileSplit = 2;                    // waves that share a row group (split of a chunk)
 constexpr int kTileBlock = kTileWaves * kWave;
-constexpr int kTileRows = 64;                    // weight rows per block (4 row tiles)
+constexpr int kTileRows = 128;                   // weight rows per block (4 row groups of 32)
 constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-column chunk
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kTileMaxK = 64;                    // a list occupies the lanes of one wave
+constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
 
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
@@ -61,7 +64,7 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
     L.o_lists = take((size_t)M * k * sizeof(Cand));
     L.o_rowid = take(kTileRows * sizeof(int));
     L.o_tokslot = take(64 * sizeof(int));
-    L.o_scratch = take((size_t)kTileWaves * kQuadSlots * sizeof(uint4));
+    L.o_scratch = take((size_t)kTileWaves * kLinePairSlots * sizeof(uint4));
     L.o_ugroup = take((size_t)u_max * sizeof(int));
     L.o_ustart = take((size_t)u_max * sizeof(int));
     L.o_uend = take((size_t)u_max * sizeof(int));
@@ -72,7 +75,7 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
     return L;
 }
 
-// Merges the block's 64 logits of one token (one per lane, padding = sentinel) into the
+// Merges a block's logits of one token (one per lane, padding = sentinel) into the
 // token's sorted list in LDS.  Only candidates that beat the list's k-th entry take part.
 // Every participant's new rank is counted directly: a candidate's rank is the number of
 // list entries and of other candidates that beat it, a list entry moves down by the number
@@ -123,9 +126,9 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int r16 = lane & 15, q4 = lane >> 4;
-    const int rt = wave / kTileSplit, kq = wave % kTileSplit;
+    const int rg = wave / kTileSplit, kq = wave % kTileSplit;
     const int M = p.M, k = p.k;
-    uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kQuadSlots;
+    uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kLinePairSlots;
 
     for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
     int total_blocks;
@@ -171,33 +174,38 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             bm = uni64(umask[u]);
         }
     };
-    // this lane's weight row: row r16 of tile rt (clamped inside the group; the duplicates
-    // are dropped when the candidates are formed)
-    auto my_row = [&](int first, int end) {
-        int idx = first + rt * 16 + mfma_load_row(lane);
-        if (idx >= end) idx = end - 1;
-        return dense ? idx : p.rows[idx];
-    };
-    uint4 a[2 * kTileSteps];                           // ring: 2 chunks x 8 steps of 32 columns
-    auto load_a = [&](const uint4* row_ptr, int c, int slot4) {
+    // This lane's four weight rows: row (lane / 8) of each 8-row octet o of the wave's 32
+    // rows (clamped inside the group; the duplicates are dropped when the candidates are
+    // formed).
+    auto my_rows = [&](int first, int end, int (&rid)[4]) {
 #pragma unroll
-        for (int j = 0; j < kTileSteps; ++j) {
-            const int vec = c * kChunkVecs + (kq * kTileSteps + j) * 4 + mfma_load_chunk(lane);
-            a[slot4 * kTileSteps + j] = make_uint4(0, 0, 0, 0);
-            if (c < p.n_chunks && vec < p.n_vec) a[slot4 * kTileSteps + j] = load_stream(row_ptr + vec);
+        for (int o = 0; o < 4; ++o) {
+            int idx = first + rg * 32 + o * 8 + line_load_row(lane);
+            if (idx >= end) idx = end - 1;
+            rid[o] = dense ? idx : p.rows[idx];
         }
+    };
+    // Ring slot sp * 4 + o holds, of chunk c, octet o's 128-byte line of the step pair sp
+    // (steps kq * 8 + 2 sp and + 1 of the chunk).
+    uint4 a[kRing];
+    auto load_a = [&](const int (&rid)[4], int c, int sp, int o) {
+        const int vec = c * kChunkVecs + (kq * 8 + 2 * sp) * 4 + line_load_chunk(lane);
+        a[sp * 4 + o] = make_uint4(0, 0, 0, 0);
+        if (c < p.n_chunks && vec < p.n_vec)
+            a[sp * 4 + o] = load_stream(p.lm_W + (size_t)rid[o] * p.n_vec + vec);
     };
 
     int b = blockIdx.x;
     int first = 0, end = 0;
     unsigned long long bm = 0ull;
-    int rid = 0;
+    int rid[4] = {0, 0, 0, 0};
     if (b < total_blocks) {
         locate(b, first, end, bm);
-        rid = my_row(first, end);
-        const uint4* rp = p.lm_W + (size_t)rid * p.n_vec;
+        my_rows(first, end, rid);
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) load_a(rp, cc, cc);
+        for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+            for (int o = 0; o < 4; ++o) load_a(rid, 0, sp, o);
     }
     while (b < total_blocks) {                         // block-uniform
         const int n_t = __popcll(bm);
@@ -207,14 +215,14 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             const bool on = (bm >> lane) & 1ull;
             if (on) tokslot[__popcll(bm & ((1ull << lane) - 1ull))] = lane;
         }
-        if (wave == 1) {
-            const int idx = first + lane;
-            rowid[lane] = idx < end ? (dense ? idx : p.rows[idx]) : -1;
+        if (wave == 1 || wave == 2) {
+            const int j = (wave - 1) * kWave + lane;
+            const int idx = first + j;
+            rowid[j] = idx < end ? (dense ? idx : p.rows[idx]) : -1;
         }
         __syncthreads();
-        const uint4* rp = p.lm_W + (size_t)rid * p.n_vec;
 
-        // hidden chunk staging: slots wave, wave+16, ... ; lane = vector inside the chunk
+        // hidden chunk staging: slots wave, wave+8, ... ; lane = vector inside the chunk
         constexpr int kSlotsPerWave = 64 / kTileWaves;
         uint4 hst[kSlotsPerWave];
         auto fetch_hidden = [&](int c) {
@@ -238,78 +246,94 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         store_hidden(0);
         __syncthreads();
 
-        f32x4_t acc[4];
+        f32x4_t acc[2][4];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        for (int c0 = 0; c0 < p.n_chunks; c0 += 2) {
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int cc = 0; cc < 2; ++cc) {
-                const int c = c0 + cc;
-                if (c < p.n_chunks) {                  // block-uniform
-                    if (c + 1 < p.n_chunks) fetch_hidden(c + 1);
-                    const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
+            for (int ct = 0; ct < 4; ++ct) acc[t][ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < p.n_chunks; ++c) {
+            if (c + 1 < p.n_chunks) fetch_hidden(c + 1);
+            const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
 #pragma unroll
-                    for (int j = 0; j < kTileSteps; ++j) {
-                        const int off = (kq * kTileSteps + j) * 4 + q4;
-                        const uint4 am = mfma_operand_from_quads(a[cc * kTileSteps + j], lane, my_slice);
+            for (int sp = 0; sp < 4; ++sp) {
+                uint4 op[2][2];                            // [row tile][step of the pair]
 #pragma unroll
-                        for (int ct = 0; ct < 4; ++ct) {
-                            if (ct < n_ct) {           // block-uniform
-                                const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
-                                acc[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, am),
-                                    __builtin_bit_cast(bf16x8_t, hv), acc[ct], 0, 0, 0);
-                            }
+                for (int t = 0; t < 2; ++t) {
+                    mfma_operands_from_lines(a[sp * 4 + 2 * t], a[sp * 4 + 2 * t + 1], lane, my_slice,
+                                             op[t][0], op[t][1]);
+                    load_a(rid, c + 1, sp, 2 * t);         // refill the two slots just consumed
+                    load_a(rid, c + 1, sp, 2 * t + 1);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const int off = (kq * 8 + 2 * sp + s2) * 4 + q4;
+#pragma unroll
+                    for (int ct = 0; ct < 4; ++ct) {
+                        if (ct < n_ct) {                   // block-uniform
+                            const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
+#pragma unroll
+                            for (int t = 0; t < 2; ++t)
+                                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8_t, op[t][s2]),
+                                    __builtin_bit_cast(bf16x8_t, hv), acc[t][ct], 0, 0, 0);
                         }
                     }
-                    load_a(rp, c + 2, cc);             // refill the ring slot just consumed
-                    if (c + 1 < p.n_chunks) store_hidden(c + 1);
-                    __syncthreads();
                 }
             }
+            if (c + 1 < p.n_chunks) store_hidden(c + 1);
+            __syncthreads();
         }
 
         // next block: locate it and start its first 16 weight loads before the epilogue
+        // (the refills of the last chunk asked for chunk n_chunks: nothing was loaded)
         const int nb = b + gridDim.x;
-        int nfirst = 0, nend = 0, nrid = 0;
+        int nfirst = 0, nend = 0;
         unsigned long long nbm = 0ull;
         if (nb < total_blocks) {
             locate(nb, nfirst, nend, nbm);
-            nrid = my_row(nfirst, nend);
-            const uint4* nrp = p.lm_W + (size_t)nrid * p.n_vec;
+            my_rows(nfirst, nend, rid);
 #pragma unroll
-            for (int cc = 0; cc < 2; ++cc) load_a(nrp, cc, cc);
+            for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+                for (int o = 0; o < 4; ++o) load_a(rid, 0, sp, o);
         }
 
         // half sums -> LDS (over the staging buffers, free after the last barrier)
-        float* red = reinterpret_cast<float*>(hbuf);   // [wave][ct][256]
+        float* red = reinterpret_cast<float*>(hbuf);   // [wave][row tile][ct][256]
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
-            if (ct < n_ct)
-                *reinterpret_cast<f32x4_t*>(red + ((size_t)wave * 4 + ct) * 256 + lane * 4) = acc[ct];
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct)
+                if (ct < n_ct)
+                    *reinterpret_cast<f32x4_t*>(red + (((size_t)wave * 2 + t) * 4 + ct) * 256 + lane * 4) =
+                        acc[t][ct];
         __syncthreads();
-        // one wave per token slot: lane = (row tile, row) -> the block's 64 logits of the token
+        // one wave per token slot, the block's rows in two halves of 64: lane = (row tile,
+        // row) -> 64 logits of the token
         for (int s = wave; s < n_t; s += kTileWaves) {
-            const int t = tokslot[s];
-            const int crt = lane >> 4, row = lane & 15;
-            const int e = (((row >> 2) * 16 + (s & 15)) << 2) + (row & 3);
-            float z = 0.f;
+            const int tok = tokslot[s];
 #pragma unroll
-            for (int q = 0; q < kTileSplit; ++q)
-                z += red[((size_t)(crt * kTileSplit + q) * 4 + (s >> 4)) * 256 + e];
-            Cand c;
-            c.v = z;
-            c.id = rowid[lane];
-            if (c.id < 0) c = sentinel();
-            tile_merge_token(lists + (size_t)t * k, k, lane, c,
-                             reinterpret_cast<unsigned long long*>(my_slice));
+            for (int hf = 0; hf < 2; ++hf) {
+                const int tile = hf * 4 + (lane >> 4), row = lane & 15;   // row tile 0..7 of the block
+                const int e = (((row >> 2) * 16 + (s & 15)) << 2) + (row & 3);
+                const int w0 = (tile >> 1) * kTileSplit;                  // the row group's first wave
+                float z = 0.f;
+#pragma unroll
+                for (int q = 0; q < kTileSplit; ++q)
+                    z += red[(((size_t)(w0 + q) * 2 + (tile & 1)) * 4 + (s >> 4)) * 256 + e];
+                Cand c;
+                c.v = z;
+                c.id = rowid[hf * kWave + lane];
+                if (c.id < 0) c = sentinel();
+                tile_merge_token(lists + (size_t)tok * k, k, lane, c,
+                                 reinterpret_cast<unsigned long long*>(my_slice));
+            }
         }
         __syncthreads();
         b = nb;
         first = nfirst;
         end = nend;
         bm = nbm;
-        rid = nrid;
     }
 
     // publish the workgroup's lists (all tokens; untouched ones are padding)
