@@ -20,6 +20,7 @@
 #pragma once
 #include "device_utils.h"
 #include "fused_path.h"
+#include <type_traits>
 
 namespace {
 
@@ -42,6 +43,7 @@ struct TileParams {
     const int32_t* union_list;              // [G]     (grouped)
     const int32_t* n_union;                 // [1]     (grouped)
     Cand* part;                             // [M, k, gridDim.x] published lists, entry-major
+    unsigned int* next_block;               // block queue: zero before the launch
     int M, V, G, k;
     int n_vec, n_chunks;
     int u_max;                              // capacity of the activated-group arrays
@@ -108,6 +110,97 @@ __device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Ca
     if (lane < kr && re < k) list[re] = e;
 }
 
+// One 512-column chunk of a block's K loop for NCT token tiles (a compile-time count: no
+// branch inside a chunk, so that LDS reads, matrix instructions and loads of neighbouring
+// steps interleave).  REFILL: a next chunk exists; its weight lines refill the ring slots as
+// they are consumed, and its hidden vectors are requested before those refills and written
+// to the other staging buffer after them.  Loads complete in order, so the wait for the
+// hidden vectors then covers only loads that this chunk has consumed anyway, never the
+// refills that should stay in flight.
+template <int NCT>
+struct TileHidden {
+    int tok[2 * NCT];                                  // wave-uniform token of slot wave + 8 i
+    uint4 regs[2 * NCT];
+};
+
+template <int NCT>
+__device__ __forceinline__ void tile_fetch_hidden(const TileParams& p, TileHidden<NCT>& h, int c, int lane) {
+#pragma unroll
+    for (int i = 0; i < 2 * NCT; ++i)
+        h.regs[i] = p.hidden[(size_t)h.tok[i] * p.n_vec + c * kChunkVecs + lane];
+}
+template <int NCT>
+__device__ __forceinline__ void tile_store_hidden(const TileHidden<NCT>& h, uint4* hbuf, int c, int lane,
+                                                  int wave) {
+    uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs;
+#pragma unroll
+    for (int i = 0; i < 2 * NCT; ++i) dst[(wave + i * kTileWaves) * kHbStride + lane] = h.regs[i];
+}
+
+template <int NCT, bool REFILL>
+__device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a)[kRing],
+                                           f32x4_t (&acc)[2][4], const uint4* const (&wrow)[4],
+                                           uint4* hbuf, TileHidden<NCT>& h, uint4* my_slice) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r16 = lane & 15, q4 = lane >> 4;
+    const int kq = wave % kTileSplit;
+    if (REFILL) tile_fetch_hidden<NCT>(p, h, c + 1, lane);
+    const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+        // the other buffer is free since the last barrier; only this chunk's own (older)
+        // weight loads are waited for along with the hidden vectors
+        if (REFILL && sp == 1) tile_store_hidden<NCT>(h, hbuf, c + 1, lane, wave);
+        uint4 op[2][2];                                // [row tile][step of the pair]
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            mfma_operands_from_lines(a[sp * 4 + 2 * t], a[sp * 4 + 2 * t + 1], lane, my_slice,
+                                     op[t][0], op[t][1]);
+            if (REFILL) {                              // refill the two slots just consumed
+                a[sp * 4 + 2 * t] = load_stream(wrow[2 * t] + (c + 1) * kChunkVecs + sp * 8);
+                a[sp * 4 + 2 * t + 1] = load_stream(wrow[2 * t + 1] + (c + 1) * kChunkVecs + sp * 8);
+            }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const int off = (kq * 8 + 2 * sp + s2) * 4 + q4;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                        __builtin_bit_cast(bf16x8_t, op[t][s2]), __builtin_bit_cast(bf16x8_t, hv),
+                        acc[t][ct], 0, 0, 0);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// The K loop of one block.  Hidden chunk staging: slots wave, wave + 8, ... below 16 NCT;
+// lane = vector inside the chunk; slots past the group's tokens repeat its last token
+// (their columns of the tiles are never read back).
+template <int NCT>
+__device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRing], f32x4_t (&acc)[2][4],
+                                            const uint4* const (&wrow)[4], uint4* hbuf,
+                                            const int* tokslot, uint4* my_slice, int n_t) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    TileHidden<NCT> h;
+#pragma unroll
+    for (int i = 0; i < 2 * NCT; ++i) {
+        const int s = wave + i * kTileWaves;
+        h.tok[i] = uni(tokslot[s < n_t ? s : n_t - 1]);
+    }
+    tile_fetch_hidden<NCT>(p, h, 0, lane);
+    tile_store_hidden<NCT>(h, hbuf, 0, lane, wave);
+    __syncthreads();
+    for (int c = 0; c + 1 < p.n_chunks; ++c) tile_chunk<NCT, true>(p, c, a, acc, wrow, hbuf, h, my_slice);
+    tile_chunk<NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, h, my_slice);
+}
+
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
@@ -130,10 +223,16 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     const int M = p.M, k = p.k;
     uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kLinePairSlots;
 
+    // Blocks cost very different amounts (one to four token tiles), so they are handed
+    // out from a queue, most expensive groups first, rather than dealt round robin.
+    unsigned int drawn = 0u;
+    if (threadIdx.x == 0)
+        drawn = __hip_atomic_fetch_add(p.next_block, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
     int total_blocks;
     if (dense) {
         total_blocks = (p.V + kTileRows - 1) / kTileRows;
+        if (threadIdx.x == 0) flags[1] = (int)drawn;
         __syncthreads();
     } else {
         if (wave == 0) {
@@ -153,6 +252,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                 }
                 uprefix[count] = acc;
                 flags[0] = count;
+                flags[1] = (int)drawn;
             }
         }
         __syncthreads();
@@ -185,29 +285,36 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             rid[o] = dense ? idx : p.rows[idx];
         }
     };
-    // Ring slot sp * 4 + o holds, of chunk c, octet o's 128-byte line of the step pair sp
-    // (steps kq * 8 + 2 sp and + 1 of the chunk).
+    // Ring slot sp * 4 + o holds, of the current chunk, octet o's 128-byte line of the step
+    // pair sp (steps kq * 8 + 2 sp and + 1 of the chunk).  H is a multiple of 512 on this
+    // path, so every chunk is whole and the loads need no guards.
     uint4 a[kRing];
-    auto load_a = [&](const int (&rid)[4], int c, int sp, int o) {
-        const int vec = c * kChunkVecs + (kq * 8 + 2 * sp) * 4 + line_load_chunk(lane);
-        a[sp * 4 + o] = make_uint4(0, 0, 0, 0);
-        if (c < p.n_chunks && vec < p.n_vec)
-            a[sp * 4 + o] = load_stream(p.lm_W + (size_t)rid[o] * p.n_vec + vec);
+    const uint4* wrow[4];                              // this lane's rows at its place in a chunk
+    auto set_rows = [&](const int (&rid)[4]) {
+#pragma unroll
+        for (int o = 0; o < 4; ++o)
+            wrow[o] = p.lm_W + (size_t)rid[o] * p.n_vec + kq * 32 + line_load_chunk(lane);
+    };
+    auto load_a = [&](int c, int sp, int o) {
+        a[sp * 4 + o] = load_stream(wrow[o] + c * kChunkVecs + sp * 8);
     };
 
-    int b = blockIdx.x;
+    int b = uni(flags[1]);
     int first = 0, end = 0;
     unsigned long long bm = 0ull;
     int rid[4] = {0, 0, 0, 0};
     if (b < total_blocks) {
         locate(b, first, end, bm);
         my_rows(first, end, rid);
+        set_rows(rid);
 #pragma unroll
         for (int sp = 0; sp < 4; ++sp)
 #pragma unroll
-            for (int o = 0; o < 4; ++o) load_a(rid, 0, sp, o);
+            for (int o = 0; o < 4; ++o) load_a(0, sp, o);
     }
     while (b < total_blocks) {                         // block-uniform
+        if (threadIdx.x == 0)                          // the draw returns long before the K loop ends
+            drawn = __hip_atomic_fetch_add(p.next_block, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int n_t = __popcll(bm);
         const int n_ct = (n_t + 15) >> 4;
         // token of every slot, and the vocabulary id of every row of the block
@@ -222,80 +329,34 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         }
         __syncthreads();
 
-        // hidden chunk staging: slots wave, wave+8, ... ; lane = vector inside the chunk
-        constexpr int kSlotsPerWave = 64 / kTileWaves;
-        uint4 hst[kSlotsPerWave];
-        auto fetch_hidden = [&](int c) {
-#pragma unroll
-            for (int i = 0; i < kSlotsPerWave; ++i) {
-                const int s = wave + i * kTileWaves;
-                const int vec = c * kChunkVecs + lane;
-                hst[i] = make_uint4(0, 0, 0, 0);
-                if (s < n_t && vec < p.n_vec) hst[i] = p.hidden[(size_t)tokslot[s] * p.n_vec + vec];
-            }
-        };
-        auto store_hidden = [&](int c) {
-            uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs;
-#pragma unroll
-            for (int i = 0; i < kSlotsPerWave; ++i) {
-                const int s = wave + i * kTileWaves;
-                if (s < n_ct * 16) dst[s * kHbStride + lane] = hst[i];   // zero rows pad the tile
-            }
-        };
-        fetch_hidden(0);
-        store_hidden(0);
-        __syncthreads();
-
         f32x4_t acc[2][4];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct) acc[t][ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < p.n_chunks; ++c) {
-            if (c + 1 < p.n_chunks) fetch_hidden(c + 1);
-            const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
-#pragma unroll
-            for (int sp = 0; sp < 4; ++sp) {
-                uint4 op[2][2];                            // [row tile][step of the pair]
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    mfma_operands_from_lines(a[sp * 4 + 2 * t], a[sp * 4 + 2 * t + 1], lane, my_slice,
-                                             op[t][0], op[t][1]);
-                    load_a(rid, c + 1, sp, 2 * t);         // refill the two slots just consumed
-                    load_a(rid, c + 1, sp, 2 * t + 1);
-                }
-#pragma unroll
-                for (int s2 = 0; s2 < 2; ++s2) {
-                    const int off = (kq * 8 + 2 * sp + s2) * 4 + q4;
-#pragma unroll
-                    for (int ct = 0; ct < 4; ++ct) {
-                        if (ct < n_ct) {                   // block-uniform
-                            const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
-#pragma unroll
-                            for (int t = 0; t < 2; ++t)
-                                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                    __builtin_bit_cast(bf16x8_t, op[t][s2]),
-                                    __builtin_bit_cast(bf16x8_t, hv), acc[t][ct], 0, 0, 0);
-                        }
-                    }
-                }
-            }
-            if (c + 1 < p.n_chunks) store_hidden(c + 1);
-            __syncthreads();
+
+        switch (n_ct) {                                    // block-uniform
+            case 1: tile_k_loop<1>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            case 2: tile_k_loop<2>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            case 3: tile_k_loop<3>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            default: tile_k_loop<4>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
         }
 
         // next block: locate it and start its first 16 weight loads before the epilogue
-        // (the refills of the last chunk asked for chunk n_chunks: nothing was loaded)
-        const int nb = b + gridDim.x;
+        // (flags[1] was last read before this block's barriers)
+        if (threadIdx.x == 0) flags[1] = (int)drawn;
+        __syncthreads();
+        const int nb = uni(flags[1]);
         int nfirst = 0, nend = 0;
         unsigned long long nbm = 0ull;
         if (nb < total_blocks) {
             locate(nb, nfirst, nend, nbm);
             my_rows(nfirst, nend, rid);
+            set_rows(rid);
 #pragma unroll
             for (int sp = 0; sp < 4; ++sp)
 #pragma unroll
-                for (int o = 0; o < 4; ++o) load_a(rid, 0, sp, o);
+                for (int o = 0; o < 4; ++o) load_a(0, sp, o);
         }
 
         // half sums -> LDS (over the staging buffers, free after the last barrier)
@@ -371,7 +432,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
     __shared__ unsigned long long mask[kMaxG];
     __shared__ unsigned long long sel_keys[kFusedWaves][kWave];
-    __shared__ int is_last;
+    __shared__ int ulist[kMaxG];
+    __shared__ int is_last, ucount;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int r16 = lane & 15, q4 = lane >> 4;
@@ -463,20 +525,38 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             const int g0 = base + lane;
             const bool on = g0 < p.G && mask[g0] != 0ull;
             const unsigned long long b = __ballot(on);
-            if (on) p.union_list[count + __popcll(b & ((1ull << lane) - 1ull))] = g0;
+            if (on) ulist[count + __popcll(b & ((1ull << lane) - 1ull))] = g0;
             count += __popcll(b);
         }
         if (lane == 0) {
+            ucount = count;
             *p.n_union = count;
             __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+    __syncthreads();
+    // The activated groups in the order the tile kernel works through them: most token
+    // tiles (16 tokens each) first, then ascending group id; placed by rank counting.
+    const int count = uni(ucount);
+    for (int u0 = threadIdx.x; u0 < count; u0 += kFusedBlock) {
+        const int g0 = ulist[u0];
+        const int w0 = (__popcll(mask[g0]) + 15) >> 4;
+        int rank = 0;
+        for (int v = 0; v < count; ++v) {
+            const int wv = (__popcll(mask[ulist[v]]) + 15) >> 4;
+            rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
+        }
+        p.union_list[rank] = g0;
     }
 }
 
 // Per token, merges the P published lists part[(t*k + i)*P + w] into the result.
 __global__ __launch_bounds__(256) void k_merge_published(const Cand* __restrict__ part, int P, int M,
                                                          int k, int32_t* __restrict__ topk_ids,
-                                                         float* __restrict__ topk_logits) {
+                                                         float* __restrict__ topk_logits,
+                                                         unsigned int* next_block) {
+    if (blockIdx.x == 0 && threadIdx.x == 0)           // the tile kernel's queue, for the next call
+        __hip_atomic_store(next_block, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __shared__ WaveScratch scratch_all[4];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
