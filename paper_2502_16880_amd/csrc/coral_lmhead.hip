@@ -168,9 +168,10 @@ bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* 
     return true;
 }
 
-// Matrix-core path: bf16, whole 512-column chunks, LDS plan within the limit.
-bool tiles_fit(int M, int H, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
+// Matrix-core path: bf16, whole 512-column chunks, weights below 4 GiB, LDS plan within the limit.
+bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
     if (dt != CORAL_BF16 || k > kTileMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
+    if ((unsigned long long)V * H * 2ull >= (1ull << 32)) return false;   // 32-bit weight offsets
     long long um = (long long)M * g < G ? (long long)M * g : G;
     if (um < 1) um = 1;
     const TileLds T = tile_lds_layout(M, k, (int)um);
@@ -274,7 +275,7 @@ extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, i
     const int n_vec = H / (bf16 ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     int um = 0, lds = 0;
-    const bool tiles = tiles_fit(M, H, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
+    const bool tiles = tiles_fit(M, H, V, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
     if (dense && M >= 8 && tiles) return 2;
     const bool mfma_gate = !dense && bf16 && M > 4;
     if (jp <= kFusedSegs &&
@@ -353,7 +354,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     const uint4* hid = static_cast<const uint4*>(hidden);
     const uint4* gw = static_cast<const uint4*>(gate_W);
     int tile_umax = 0, tile_lds = 0;
-    if (tiles_fit(M, H, G, g, k, dt, &tile_umax, &tile_lds)) {
+    if (tiles_fit(M, H, V, G, g, k, dt, &tile_umax, &tile_lds)) {
         GateSelParams q = {};
         q.hidden = hid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
         q.group_mask = mask; q.union_list = union_list; q.n_union = n_union;
@@ -433,7 +434,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     char* ws = static_cast<char*>(workspace);
     int tile_umax = 0, tile_lds = 0;
     // many tokens per row: the contraction is no longer cheap on the vector units
-    if (M >= 8 && tiles_fit(M, H, 0, 0, k, dt, &tile_umax, &tile_lds))
+    if (M >= 8 && tiles_fit(M, H, V, 0, 0, k, dt, &tile_umax, &tile_lds))
         return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k,
                             tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                             ev_after);

@@ -36,6 +36,21 @@ __device__ __forceinline__ uint4 load_stream(const uint4* p) {
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// 16-byte accesses as native vectors (a struct copy is a memcpy to the compiler, which it
+// cannot always turn back into registers).
+__device__ __forceinline__ uint4 load_vec(const uint4* p) {
+    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(p);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_vec(uint4* p, uint4 v) {
+    u32x4_t o;
+    o.x = v.x;
+    o.y = v.y;
+    o.z = v.z;
+    o.w = v.w;
+    *reinterpret_cast<u32x4_t*>(p) = o;
+}
+
 template <bool BF16>
 __device__ __forceinline__ float dot_vec(uint4 w, uint4 h, float acc) {
     if (BF16) {

@@ -33,6 +33,14 @@ constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (p
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kTileMaxK = 64;                    // a list occupies the lanes of one wave
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
+// Strides (floats) of the accumulator tiles parked in LDS for the epilogue: token tile,
+// row tile of a wave, wave.  Modulo the 64 banks they are 16, 16 and 48.
+constexpr int kRedCt = 272, kRedTile = 4 * kRedCt + 16, kRedWave = 2 * kRedTile + 16;
+static_assert(kTileWaves * kRedWave * 4 <= 2 * kHbBufVecs * 16, "the parked tiles fit the staging buffers");
+// Compiler-only barrier: no memory access is moved across it.  Keeps global loads at the
+// place in the instruction stream where the source puts them (the compiler would otherwise
+// sink them to their first use, which defeats prefetching).
+__device__ __forceinline__ void keep_memory_order() { asm volatile("" ::: "memory"); }
 
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
@@ -85,13 +93,12 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
 // keys: 128 wave-private LDS words (ordering keys of the passing candidates, then of the list).
 __device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c,
                                                  unsigned long long* keys) {
+    const Cand tail = list[k - 1];                     // one address for all lanes: a broadcast
+    const bool pass = is_real(c) && better(c.v, c.id, tail.v, tail.id);
+    const unsigned long long b = __ballot(pass);
+    if (b == 0ull) return;                             // wave-uniform, the common case
     Cand e = sentinel();
     if (lane < k) e = list[lane];
-    const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(e.v), k - 1));
-    const int ti = __builtin_amdgcn_readlane(e.id, k - 1);
-    const bool pass = is_real(c) && better(c.v, c.id, tv, ti);
-    const unsigned long long b = __ballot(pass);
-    if (b == 0ull) return;                             // wave-uniform
     const int np = __popcll(b);
     const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
     const unsigned long long ckey = cand_key(c.v, c.id), ekey = cand_key(e.v, e.id);
@@ -117,65 +124,113 @@ __device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Ca
 // to the other staging buffer after them.  Loads complete in order, so the wait for the
 // hidden vectors then covers only loads that this chunk has consumed anyway, never the
 // refills that should stay in flight.
+// With three or four token tiles the staging registers would not fit beside the ring, so
+// the slots then go in two rounds (the second requested after the first step pair's refills,
+// whose completion its wait then includes).
 template <int NCT>
 struct TileHidden {
-    int tok[2 * NCT];                                  // wave-uniform token of slot wave + 8 i
-    uint4 regs[2 * NCT];
+    static constexpr int kRounds = NCT > 2 ? 2 : 1;
+    static constexpr int kPerRound = 2 * NCT / kRounds;
+};
+struct TileStage {                                     // staging registers, kPerRound in use
+    uint4 r0, r1, r2, r3;
 };
 
-template <int NCT>
-__device__ __forceinline__ void tile_fetch_hidden(const TileParams& p, TileHidden<NCT>& h, int c, int lane) {
-#pragma unroll
-    for (int i = 0; i < 2 * NCT; ++i)
-        h.regs[i] = p.hidden[(size_t)h.tok[i] * p.n_vec + c * kChunkVecs + lane];
+template <int NCT, int ROUND>
+__device__ __forceinline__ void tile_fetch_hidden(const TileParams& p, const int* tokslot, int n_t,
+                                                  TileStage& hst, int c, int lane, int wave) {
+    constexpr int kN = TileHidden<NCT>::kPerRound;
+    const uint4* src = p.hidden + c * kChunkVecs + lane;
+    // token of slot wave + 8 i (wave-uniform); slots past the group's tokens repeat its last
+    auto tok = [&](int i) {
+        const int s = wave + (ROUND * kN + i) * kTileWaves;
+        return (size_t)uni(tokslot[s < n_t ? s : n_t - 1]);
+    };
+    if (kN > 0) hst.r0 = load_vec(src + tok(0) * p.n_vec);
+    if (kN > 1) hst.r1 = load_vec(src + tok(1) * p.n_vec);
+    if (kN > 2) hst.r2 = load_vec(src + tok(2) * p.n_vec);
+    if (kN > 3) hst.r3 = load_vec(src + tok(3) * p.n_vec);
 }
-template <int NCT>
-__device__ __forceinline__ void tile_store_hidden(const TileHidden<NCT>& h, uint4* hbuf, int c, int lane,
+template <int NCT, int ROUND>
+__device__ __forceinline__ void tile_store_hidden(const TileStage& hst, uint4* hbuf, int c, int lane,
                                                   int wave) {
-    uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs;
-#pragma unroll
-    for (int i = 0; i < 2 * NCT; ++i) dst[(wave + i * kTileWaves) * kHbStride + lane] = h.regs[i];
+    constexpr int kN = TileHidden<NCT>::kPerRound;
+    uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs + (size_t)(wave + ROUND * kN * kTileWaves) * kHbStride + lane;
+    if (kN > 0) store_vec(dst + 0 * kTileWaves * kHbStride, hst.r0);
+    if (kN > 1) store_vec(dst + 1 * kTileWaves * kHbStride, hst.r1);
+    if (kN > 2) store_vec(dst + 2 * kTileWaves * kHbStride, hst.r2);
+    if (kN > 3) store_vec(dst + 3 * kTileWaves * kHbStride, hst.r3);
 }
 
-template <int NCT, bool REFILL>
-__device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a)[kRing],
-                                           f32x4_t (&acc)[2][4], const uint4* const (&wrow)[4],
-                                           uint4* hbuf, TileHidden<NCT>& h, uint4* my_slice) {
+// The 128-byte line of step pair sp of chunk c in the lane's row at byte offset `row` of
+// the weight matrix (offsets are 32-bit: the path takes matrices below 4 GiB).
+__device__ __forceinline__ uint4 tile_load_w(const TileParams& p, unsigned row, int c, int sp) {
+    const unsigned off = row + (unsigned)(c * kChunkVecs + sp * 8) * 16u;
+    return load_stream(reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.lm_W) + off));
+}
+
+// Step pair SP of a chunk: the two 32-column steps whose weight lines sit in ring slots
+// 4 SP .. 4 SP + 3.
+template <int NCT, bool REFILL, int SP>
+__device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4 (&a)[kRing],
+                                               f32x4_t (&acc)[2][4], const unsigned (&wrow)[4],
+                                               uint4* hbuf, const int* tokslot, int n_t, TileStage& hst,
+                                               uint4* my_slice) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int r16 = lane & 15, q4 = lane >> 4;
     const int kq = wave % kTileSplit;
-    if (REFILL) tile_fetch_hidden<NCT>(p, h, c + 1, lane);
     const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
+    // the other buffer is free since the last barrier; only this chunk's own (older) weight
+    // loads are waited for along with the hidden vectors
+    if (REFILL && SP >= 1 && SP <= TileHidden<NCT>::kRounds) {
+        keep_memory_order();
+        tile_store_hidden<NCT, SP - 1>(hst, hbuf, c + 1, lane, wave);
+        if (SP < TileHidden<NCT>::kRounds) tile_fetch_hidden<NCT, SP < 2 ? SP : 0>(p, tokslot, n_t, hst, c + 1, lane, wave);
+        keep_memory_order();
+    }
+    uint4 op[2][2];                                    // [row tile][step of the pair]
 #pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
-        // the other buffer is free since the last barrier; only this chunk's own (older)
-        // weight loads are waited for along with the hidden vectors
-        if (REFILL && sp == 1) tile_store_hidden<NCT>(h, hbuf, c + 1, lane, wave);
-        uint4 op[2][2];                                // [row tile][step of the pair]
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            mfma_operands_from_lines(a[sp * 4 + 2 * t], a[sp * 4 + 2 * t + 1], lane, my_slice,
-                                     op[t][0], op[t][1]);
-            if (REFILL) {                              // refill the two slots just consumed
-                a[sp * 4 + 2 * t] = load_stream(wrow[2 * t] + (c + 1) * kChunkVecs + sp * 8);
-                a[sp * 4 + 2 * t + 1] = load_stream(wrow[2 * t + 1] + (c + 1) * kChunkVecs + sp * 8);
-            }
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const int off = (kq * 8 + 2 * sp + s2) * 4 + q4;
-#pragma unroll
-            for (int ct = 0; ct < NCT; ++ct) {
-                const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-                    acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                        __builtin_bit_cast(bf16x8_t, op[t][s2]), __builtin_bit_cast(bf16x8_t, hv),
-                        acc[t][ct], 0, 0, 0);
-            }
+    for (int t = 0; t < 2; ++t) {
+        mfma_operands_from_lines(a[SP * 4 + 2 * t], a[SP * 4 + 2 * t + 1], lane, my_slice, op[t][0],
+                                 op[t][1]);
+        if (REFILL) {                                  // refill the two slots just consumed
+            a[SP * 4 + 2 * t] = tile_load_w(p, wrow[2 * t], c + 1, SP);
+            a[SP * 4 + 2 * t + 1] = tile_load_w(p, wrow[2 * t + 1], c + 1, SP);
         }
     }
+    if (REFILL) keep_memory_order();
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        const int off = (kq * 8 + 2 * SP + s2) * 4 + q4;
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) {
+            const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                    __builtin_bit_cast(bf16x8_t, op[t][s2]), __builtin_bit_cast(bf16x8_t, hv), acc[t][ct],
+                    0, 0, 0);
+        }
+    }
+}
+
+template <int NCT, bool REFILL>
+__device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a)[kRing],
+                                           f32x4_t (&acc)[2][4], const unsigned (&wrow)[4],
+                                           uint4* hbuf, const int* tokslot, int n_t, uint4* my_slice) {
+    TileStage hst;
+    // (the scheduling barriers keep the compiler from sinking the loads to where their
+    // registers are first needed, which would undo the ordering)
+    if (REFILL) {
+        tile_fetch_hidden<NCT, 0>(p, tokslot, n_t, hst, c + 1, threadIdx.x & (kWave - 1),
+                                  __builtin_amdgcn_readfirstlane(threadIdx.x / kWave));
+        keep_memory_order();
+    }
+    tile_step_pair<NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<NCT, REFILL, 1>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<NCT, REFILL, 2>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<NCT, REFILL, 3>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
     __syncthreads();
 }
 
@@ -184,21 +239,23 @@ __device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a
 // (their columns of the tiles are never read back).
 template <int NCT>
 __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRing], f32x4_t (&acc)[2][4],
-                                            const uint4* const (&wrow)[4], uint4* hbuf,
+                                            const unsigned (&wrow)[4], uint4* hbuf,
                                             const int* tokslot, uint4* my_slice, int n_t) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    TileHidden<NCT> h;
-#pragma unroll
-    for (int i = 0; i < 2 * NCT; ++i) {
-        const int s = wave + i * kTileWaves;
-        h.tok[i] = uni(tokslot[s < n_t ? s : n_t - 1]);
+    {
+        TileStage hst;
+        tile_fetch_hidden<NCT, 0>(p, tokslot, n_t, hst, 0, lane, wave);
+        tile_store_hidden<NCT, 0>(hst, hbuf, 0, lane, wave);
+        if (TileHidden<NCT>::kRounds > 1) {
+            tile_fetch_hidden<NCT, TileHidden<NCT>::kRounds - 1>(p, tokslot, n_t, hst, 0, lane, wave);
+            tile_store_hidden<NCT, TileHidden<NCT>::kRounds - 1>(hst, hbuf, 0, lane, wave);
+        }
     }
-    tile_fetch_hidden<NCT>(p, h, 0, lane);
-    tile_store_hidden<NCT>(h, hbuf, 0, lane, wave);
     __syncthreads();
-    for (int c = 0; c + 1 < p.n_chunks; ++c) tile_chunk<NCT, true>(p, c, a, acc, wrow, hbuf, h, my_slice);
-    tile_chunk<NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, h, my_slice);
+    for (int c = 0; c + 1 < p.n_chunks; ++c)
+        tile_chunk<NCT, true>(p, c, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
+    tile_chunk<NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
 }
 
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
@@ -289,15 +346,13 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     // pair sp (steps kq * 8 + 2 sp and + 1 of the chunk).  H is a multiple of 512 on this
     // path, so every chunk is whole and the loads need no guards.
     uint4 a[kRing];
-    const uint4* wrow[4];                              // this lane's rows at its place in a chunk
+    unsigned wrow[4];                                  // byte offsets of this lane's rows at its place in a chunk
     auto set_rows = [&](const int (&rid)[4]) {
 #pragma unroll
         for (int o = 0; o < 4; ++o)
-            wrow[o] = p.lm_W + (size_t)rid[o] * p.n_vec + kq * 32 + line_load_chunk(lane);
+            wrow[o] = ((unsigned)rid[o] * (unsigned)p.n_vec + kq * 32 + line_load_chunk(lane)) * 16u;
     };
-    auto load_a = [&](int c, int sp, int o) {
-        a[sp * 4 + o] = load_stream(wrow[o] + c * kChunkVecs + sp * 8);
-    };
+    auto load_a = [&](int c, int sp, int o) { a[sp * 4 + o] = tile_load_w(p, wrow[o], c, sp); };
 
     int b = uni(flags[1]);
     int first = 0, end = 0;
@@ -359,36 +414,42 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                 for (int o = 0; o < 4; ++o) load_a(0, sp, o);
         }
 
-        // half sums -> LDS (over the staging buffers, free after the last barrier)
-        float* red = reinterpret_cast<float*>(hbuf);   // [wave][row tile][ct][256]
+        // half sums -> LDS (over the staging buffers, free after the last barrier).  A
+        // tile's accumulators sit at lane * 4 plus 4 floats of padding per 16 lanes, and the
+        // strides between tiles are chosen so that the reads below, whose 64 lanes want one
+        // column of four different tiles, fall on 64 different banks.
+        float* red = reinterpret_cast<float*>(hbuf);
+        const int red_lane = lane * 4 + (lane >> 4) * 4;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct)
                 if (ct < n_ct)
-                    *reinterpret_cast<f32x4_t*>(red + (((size_t)wave * 2 + t) * 4 + ct) * 256 + lane * 4) =
+                    *reinterpret_cast<f32x4_t*>(red + wave * kRedWave + t * kRedTile + ct * kRedCt + red_lane) =
                         acc[t][ct];
         __syncthreads();
         // one wave per token slot, the block's rows in two halves of 64: lane = (row tile,
         // row) -> 64 logits of the token
         for (int s = wave; s < n_t; s += kTileWaves) {
             const int tok = tokslot[s];
+            Cand cand[2];
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int tile = hf * 4 + (lane >> 4), row = lane & 15;   // row tile 0..7 of the block
-                const int e = (((row >> 2) * 16 + (s & 15)) << 2) + (row & 3);
+                const int e = (row >> 2) * 68 + (s & 15) * 4 + (row & 3);
                 const int w0 = (tile >> 1) * kTileSplit;                  // the row group's first wave
                 float z = 0.f;
 #pragma unroll
                 for (int q = 0; q < kTileSplit; ++q)
-                    z += red[(((size_t)(w0 + q) * 2 + (tile & 1)) * 4 + (s >> 4)) * 256 + e];
-                Cand c;
-                c.v = z;
-                c.id = rowid[hf * kWave + lane];
-                if (c.id < 0) c = sentinel();
-                tile_merge_token(lists + (size_t)tok * k, k, lane, c,
-                                 reinterpret_cast<unsigned long long*>(my_slice));
+                    z += red[(w0 + q) * kRedWave + (tile & 1) * kRedTile + (s >> 4) * kRedCt + e];
+                cand[hf].v = z;
+                cand[hf].id = rowid[hf * kWave + lane];
+                if (cand[hf].id < 0) cand[hf] = sentinel();
             }
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf)
+                tile_merge_token(lists + (size_t)tok * k, k, lane, cand[hf],
+                                 reinterpret_cast<unsigned long long*>(my_slice));
         }
         __syncthreads();
         b = nb;
