@@ -168,6 +168,11 @@ bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* 
     return true;
 }
 
+// The dense head goes to the matrix-core path from 8 tokens on, if the vocabulary gives every
+// workgroup at least two 128-row blocks (below that its per-block set-up and epilogue
+// dominate and the vector path is faster).
+bool dense_prefers_tiles(int M, int V) { return M >= 8 && V >= 2 * kMaxWorkgroups * kTileRows; }
+
 // Matrix-core path: bf16, whole 512-column chunks, weights below 4 GiB, LDS plan within the limit.
 bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
     if (dt != CORAL_BF16 || k > kTileMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
@@ -276,7 +281,7 @@ extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, i
     const int jp = (n_vec + kWave - 1) / kWave;
     int um = 0, lds = 0;
     const bool tiles = tiles_fit(M, H, V, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
-    if (dense && M >= 8 && tiles) return 2;
+    if (dense && dense_prefers_tiles(M, V) && tiles) return 2;
     const bool mfma_gate = !dense && bf16 && M > 4;
     if (jp <= kFusedSegs &&
         fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense != 0, mfma_gate).total <= kLdsLimit)
@@ -434,7 +439,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     char* ws = static_cast<char*>(workspace);
     int tile_umax = 0, tile_lds = 0;
     // many tokens per row: the contraction is no longer cheap on the vector units
-    if (M >= 8 && tiles_fit(M, H, V, 0, 0, k, dt, &tile_umax, &tile_lds))
+    if (dense_prefers_tiles(M, V) && tiles_fit(M, H, V, 0, 0, k, dt, &tile_umax, &tile_lds))
         return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k,
                             tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                             ev_after);

@@ -127,8 +127,28 @@ def test_every_path_is_exercised(coral):
     B = coral.CORAL_BF16
     assert P(False, 16, 4096, 32 * 203, 32, 4, 10, B) == 1          # scaled Llama3: single launch
     assert P(False, 64, 4096, 64 * 126, 64, 8, 16, B) == 2          # scaled wide tree: tiles
-    assert P(True, 16, 4096, 32 * 203, 0, 0, 10, B) == 2            # dense, 16 tokens: tiles
+    assert P(True, 16, 4096, 32 * 203, 0, 0, 10, B) == 1            # dense, small vocabulary
+    assert P(True, 16, 4096, 128256, 0, 0, 10, B) == 2              # dense, full size: tiles
+    assert P(False, 64, 2048, 16 * 300, 16, 6, 20, B) == 2          # test_tile_path_shapes
+    assert P(False, 64, 512, 16 * 300, 16, 6, 16, B) == 2
     assert P(False, 64, 512, 8 * 130, 8, 1, 64, B) == 0             # extreme k: staged
+
+
+@pytest.mark.parametrize("H,k", [(2048, 20), (512, 16), (1024, 21)])
+def test_tile_path_shapes(coral, H, k):
+    """Matrix-core path away from the benchmark shapes: one, two and four 512-column chunks,
+    groups of 300 rows (two whole 128-row blocks and a ragged one), popular groups with
+    one to four token tiles (gate bias)."""
+    cfg = HeadConfig("tiles", "bf16", H, 16 * 300, 16, 6, (64,), k, 90 + k, True, bias_std=1.5)
+    assert coral.coral_lmhead_path(False, 64, H, cfg.V, 16, 6, k, coral.CORAL_BF16) == 2
+    dh = DeviceHead(coral, make_head(cfg))
+    for batch in range(2):
+        hidden = make_hidden(cfg, 64, batch)
+        check_grouped(dh, hidden, 6, k, run_grouped(coral, dh, hidden, 6, k))
+    for M in (17, 40, 64):                                # two, three and four token tiles
+        hidden = make_hidden(cfg, M, 7)
+        if coral.coral_lmhead_path(False, M, H, cfg.V, 16, 16, k, coral.CORAL_BF16) == 2:
+            check_grouped(dh, hidden, 16, k, run_grouped(coral, dh, hidden, 16, k))
 
 
 def test_ragged_and_empty_groups(coral):
