@@ -115,26 +115,20 @@ int compute_units() {
     return cached[dev];
 }
 
-// Launches the single-launch path if the shape fits it.  Returns true if it was used
-// (status in *st), false if the caller must take the general path.
-bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* gate_bias,
+// Enqueues the single-launch path (the caller has checked with plan_path that it fits).
+coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, const float* gate_bias,
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
-               char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after,
-               coral_status* st) {
+               char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after) {
     const bool bf16 = dt == CORAL_BF16;
     const int n_vec = H / (bf16 ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
-    if (jp > kFusedSegs) return false;
     // many tokens: the gate goes through the matrix cores (bf16 only)
     const bool mfma_gate = !dense && bf16 && M > 4;
     const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, mfma_gate);
-    if (F.total > kLdsLimit) return false;
+    if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     int P = compute_units();
-    if (P < 1) {
-        *st = CORAL_ERR_HIP;
-        return true;
-    }
+    if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
     FusedParams p = {};
     p.hidden = static_cast<const uint4*>(hidden);
@@ -157,15 +151,13 @@ bool try_fused(bool dense, const void* hidden, const void* gate_W, const float* 
                       : k_fused<false, false, false>);
     if (F.total > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess) {
-        *st = CORAL_ERR_HIP;
-        return true;
-    }
-    if ((*st = record(ev_before, stream)) != CORAL_OK) return true;
+                            hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess)
+        return CORAL_ERR_HIP;
+    coral_status st;
+    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(fn, dim3(P), dim3(kFusedBlock), F.total, stream, p);
-    if ((*st = launch_status()) != CORAL_OK) return true;
-    *st = record(ev_after, stream);
-    return true;
+    if ((st = launch_status()) != CORAL_OK) return st;
+    return record(ev_after, stream);
 }
 
 // The dense head goes to the matrix-core path from 8 tokens on, if the vocabulary gives every
@@ -184,6 +176,34 @@ bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_
     *u_max_out = (int)um;
     *lds_out = T.total;
     return true;
+}
+
+// Which path a call takes, decided in one place for the entry points and the path query.
+struct PathPlan {
+    int path;            // 0 staged, 1 single launch, 2 tiles
+    int tile_umax, tile_lds;
+};
+
+PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_dtype dt) {
+    PathPlan pl = {};
+    const bool bf16 = dt == CORAL_BF16;
+    const int n_vec = H / (bf16 ? 8 : 4);
+    const int jp = (n_vec + kWave - 1) / kWave;
+    const bool mfma_gate = !dense && bf16 && M > 4;
+    const bool fused_ok =
+        jp <= kFusedSegs &&
+        fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense, mfma_gate).total <= kLdsLimit;
+    const bool tiles_ok =
+        tiles_fit(M, H, V, dense ? 0 : G, dense ? 0 : g, k, dt, &pl.tile_umax, &pl.tile_lds);
+    if (dense && dense_prefers_tiles(M, V) && tiles_ok)
+        pl.path = 2;
+    else if (fused_ok)
+        pl.path = 1;
+    else if (tiles_ok)
+        pl.path = 2;
+    else
+        pl.path = 0;
+    return pl;
 }
 
 // Enqueues k_tiles and the merge of its published lists.  For the grouped head the masks
@@ -271,23 +291,12 @@ extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g
 
 extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k,
                                  coral_dtype dt) {
-    (void)V;
     if (dt != CORAL_F32 && dt != CORAL_BF16) return -1;
-    if (M < 1 || H < 1 || k < 1 || M > kMaxM || k > kMaxK) return -1;
+    if (M < 1 || H < 1 || V < 1 || k < 1 || M > kMaxM || k > kMaxK) return -1;
     const bool bf16 = dt == CORAL_BF16;
     if (H % (bf16 ? 8 : 4) != 0) return -1;
     if (!dense && (G < 1 || g < 1 || g > G || G > kMaxG)) return -1;
-    const int n_vec = H / (bf16 ? 8 : 4);
-    const int jp = (n_vec + kWave - 1) / kWave;
-    int um = 0, lds = 0;
-    const bool tiles = tiles_fit(M, H, V, dense ? 0 : G, dense ? 0 : g, k, dt, &um, &lds);
-    if (dense && dense_prefers_tiles(M, V) && tiles) return 2;
-    const bool mfma_gate = !dense && bf16 && M > 4;
-    if (jp <= kFusedSegs &&
-        fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense != 0, mfma_gate).total <= kLdsLimit)
-        return 1;
-    if (!dense && tiles) return 2;
-    return 0;
+    return plan_path(dense != 0, M, H, V, G, g, k, dt).path;
 }
 
 extern "C" coral_status coral_lmhead_workspace_init(void* workspace, size_t workspace_bytes,
@@ -343,9 +352,10 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    if (try_fused(false, hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
-                  topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, &st))
-        return st;
+    const PathPlan plan = plan_path(false, M, H, V, G, g, k, dt);
+    if (plan.path == 1)
+        return launch_fused(false, hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
+                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after);
     float* s = reinterpret_cast<float*>(ws + L.s);
     int32_t* sel = sel_groups ? sel_groups : reinterpret_cast<int32_t*>(ws + L.sel);
     unsigned long long* mask = reinterpret_cast<unsigned long long*>(ws + L.mask);
@@ -358,8 +368,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     const int n_vec = H / (bf16 ? 8 : 4);
     const uint4* hid = static_cast<const uint4*>(hidden);
     const uint4* gw = static_cast<const uint4*>(gate_W);
-    int tile_umax = 0, tile_lds = 0;
-    if (tiles_fit(M, H, V, G, g, k, dt, &tile_umax, &tile_lds)) {
+    if (plan.path == 2) {
         GateSelParams q = {};
         q.hidden = hid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
         q.group_mask = mask; q.union_list = union_list; q.n_union = n_union;
@@ -369,7 +378,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
         hipLaunchKernelGGL(k_gate_select, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
         return launch_tiles(false, hidden, lm_W, gi, mask, union_list, n_union, M, H, V, G, k,
-                            tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
+                            plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                             ev_after);
     }
     if (bf16)
@@ -437,15 +446,15 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    int tile_umax = 0, tile_lds = 0;
+    const PathPlan plan = plan_path(true, M, H, V, 0, 0, k, dt);
     // many tokens per row: the contraction is no longer cheap on the vector units
-    if (dense_prefers_tiles(M, V) && tiles_fit(M, H, V, 0, 0, k, dt, &tile_umax, &tile_lds))
+    if (plan.path == 2)
         return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k,
-                            tile_umax, tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
-                            ev_after);
-    if (try_fused(true, hidden, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
-                  topk_logits, nullptr, ws, L, stream, ev_before, ev_after, &st))
-        return st;
+                            plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream,
+                            ev_before, ev_after);
+    if (plan.path == 1)
+        return launch_fused(true, hidden, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
+                            topk_logits, nullptr, ws, L, stream, ev_before, ev_after);
     const bool bf16 = dt == CORAL_BF16;
     LogitsParams p = {};
     p.hidden = static_cast<const uint4*>(hidden);
