@@ -93,9 +93,10 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
  * Which kernels a call with these sizes will use (dense != 0: coral_lmhead_dense):
  * 0 = staged general path (one launch per stage), 1 = single-launch path (gate,
  * selection, row streaming and top-k of section 3.3 in one persistent kernel),
- * 2 = matrix-core tile path (groups shared by many tokens, the appendix's tree-decoding
- * case; dense head with 8 or more tokens), -1 = sizes not supported.  Host-only, no
- * device work; for tests and benchmark reports.
+ * 2 = matrix-core tile path (bf16, H a multiple of 512, weights below 4 GiB: groups
+ * shared by many tokens, the appendix's tree-decoding case, when the hidden vectors do
+ * not fit on chip; dense head with 8 or more tokens and at least 65536 rows),
+ * -1 = sizes not supported.  Host-only, no device work; for tests and benchmark reports.
  */
 int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral_dtype dt);
 
@@ -106,7 +107,9 @@ int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral
  * workspace; every completed call leaves the control words ready for the next one.
  * The control words count the workgroups that have published their partial top-k
  * lists, so that the last one can merge them (the per-token top-k of the appendix's
- * "Tree decoding" paragraph) without a further launch.
+ * "Tree decoding" paragraph) without a further launch, and hand out blocks of weight
+ * rows to the workgroups of the tile path.  A call that fails with CORAL_ERR_HIP may
+ * leave them non-zero: prepare the workspace again before reusing it.
  *   workspace [device], 256-byte aligned, at least 256 bytes.
  */
 coral_status coral_lmhead_workspace_init(void *workspace, size_t workspace_bytes,
