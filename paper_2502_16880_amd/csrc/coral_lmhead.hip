@@ -115,6 +115,14 @@ int compute_units() {
     return cached[dev];
 }
 
+// Gate of the single-launch path: more than four tokens go through the matrix cores (bf16
+// only), with whole-line loads if their larger LDS slices still fit.
+int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype dt) {
+    if (dense || dt != CORAL_BF16 || M <= 4) return kGateVector;
+    if (fused_lds_layout(M, G, g, k, jp, false, kGateMfmaLines).total <= kLdsLimit) return kGateMfmaLines;
+    return kGateMfmaQuads;
+}
+
 // Enqueues the single-launch path (the caller has checked with plan_path that it fits).
 coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, const float* gate_bias,
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
@@ -123,9 +131,8 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, co
     const bool bf16 = dt == CORAL_BF16;
     const int n_vec = H / (bf16 ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
-    // many tokens: the gate goes through the matrix cores (bf16 only)
-    const bool mfma_gate = !dense && bf16 && M > 4;
-    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, mfma_gate);
+    const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt);
+    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate);
     if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
@@ -146,9 +153,11 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, co
     p.n_vec = n_vec; p.jp = jp;
     typedef void (*fused_fn)(FusedParams);
     const fused_fn fn =
-        dense ? (bf16 ? k_fused<true, true, false> : k_fused<false, true, false>)
-              : (bf16 ? (mfma_gate ? k_fused<true, false, true> : k_fused<true, false, false>)
-                      : k_fused<false, false, false>);
+        dense ? (bf16 ? k_fused<true, true, kGateVector> : k_fused<false, true, kGateVector>)
+              : (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines>
+                         : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads>
+                                                  : k_fused<true, false, kGateVector>)
+                      : k_fused<false, false, kGateVector>);
     if (F.total > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess)
@@ -189,10 +198,10 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
     const bool bf16 = dt == CORAL_BF16;
     const int n_vec = H / (bf16 ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
-    const bool mfma_gate = !dense && bf16 && M > 4;
     const bool fused_ok =
         jp <= kFusedSegs &&
-        fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense, mfma_gate).total <= kLdsLimit;
+        fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense,
+                         fused_gate_mode(dense, M, dense ? 0 : G, dense ? 0 : g, k, jp, dt)).total <= kLdsLimit;
     const bool tiles_ok =
         tiles_fit(M, H, V, dense ? 0 : G, dense ? 0 : g, k, dt, &pl.tile_umax, &pl.tile_lds);
     if (dense && dense_prefers_tiles(M, V) && tiles_ok)

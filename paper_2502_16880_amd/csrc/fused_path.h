@@ -28,6 +28,13 @@ constexpr int kLdsLimit = 160 * 1024;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
+// How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
+// gate rows loaded as 64-byte pieces (16 rows per wave load) or as whole 128-byte lines
+// (8 rows per wave load, twice the LDS slice per wave, used when it fits).
+enum GateMode { kGateVector = 0, kGateMfmaQuads = 1, kGateMfmaLines = 2 };
+__host__ __device__ inline int gate_slice_floats(int mode) {
+    return mode == kGateMfmaLines ? kLinePairSlots * 4 : kGateSlice;
+}
 // Wave-private LDS scratch of the merges: ranking keys, gathered candidates, list tags.
 struct WaveScratch {
     unsigned long long keys[kWave];
@@ -66,7 +73,7 @@ __host__ __device__ inline int hidden_lds_stride(int jp) { return jp * kWave + 1
 // Byte offsets of the kernel's regions in dynamic LDS (the host sizes the launch with the
 // same function the kernel lays its pointers out with).
 __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k, int jp, bool dense,
-                                                     bool mfma_gate) {
+                                                     int gate_mode) {
     FusedLds L;
     int off = 0;
     auto take = [&](size_t bytes) {
@@ -83,7 +90,9 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
     // the MFMA gate parks its per-wave partial tiles here before the lists are initialised
     const size_t gate_part_bytes =
-        (!dense && mfma_gate) ? (size_t)kFusedWaves * ((M + 15) / 16) * kGateSlice * sizeof(float) : 0;
+        (!dense && gate_mode != kGateVector)
+            ? (size_t)kFusedWaves * ((M + 15) / 16) * gate_slice_floats(gate_mode) * sizeof(float)
+            : 0;
     if (lists_bytes < gate_part_bytes) lists_bytes = gate_part_bytes;
     L.o_lists = take(lists_bytes);
     L.o_s = take(dense ? 16 : (size_t)M * G * sizeof(float));
@@ -407,11 +416,11 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
     }
 }
 
-template <bool BF16, bool DENSE, bool MFMA_GATE>
+template <bool BF16, bool DENSE, int GATE>
 __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
-    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, MFMA_GATE);
+    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, GATE);
     uint4* hs = reinterpret_cast<uint4*>(lds + lay.o_hidden);
     Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
     float* s_lds = reinterpret_cast<float*>(lds + lay.o_s);
@@ -489,7 +498,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         __syncthreads();
     } else {
         for (int n = threadIdx.x; n < p.G; n += kFusedBlock) mask_lds[n] = 0ull;
-        if (MFMA_GATE) {
+        if (GATE != kGateVector) {
             // ---- 2a. gate on the matrix cores: s[16 groups x 16 tokens] tiles, the H
             // columns split over the 16 waves in steps of 32 (v_mfma_f32_16x16x32_bf16:
             // lane l feeds row l%16, columns 8*(l/16)..+8 of both operands and receives
@@ -498,8 +507,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             const int r16 = lane & 15, q4 = lane >> 4;
             const int n_ks = (p.n_vec + 3) / 4;            // <= 128 because jp <= 8
             const int n_gt = (p.G + 15) / 16, n_tt = (M + 15) / 16;
-            float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][kGateSlice]
-            uint4* my_slice = reinterpret_cast<uint4*>(gpart + (size_t)wave * n_tt * kGateSlice);
+            constexpr int kSlice = GATE == kGateMfmaLines ? kLinePairSlots * 4 : kGateSlice;
+            float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][kSlice]
+            uint4* my_slice = reinterpret_cast<uint4*>(gpart + (size_t)wave * n_tt * kSlice);
             // waves 0-7 work on the even tile of a pair of group tiles, waves 8-15 on the odd
             // one; each takes two adjacent 32-column steps at a time (one 128-byte line per
             // gate row) out of every 16
@@ -511,11 +521,19 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             // they do not all queue on one L2 channel
             const int rot = (int)((blockIdx.x >> 3) & 7u);
             auto step_of = [&](int i) { return 16 * (((i >> 1) + rot) & 7) + 2 * kw + (i & 1); };
-            auto load_gate_tile = [&](int gt) {                // quad-coalesced, see device_utils.h
-                const int n = gt * 16 + mfma_load_row(lane);
+            // (see device_utils.h for the two load shapes; with whole lines register 2 L + h
+            // holds rows 8 h .. 8 h + 7 of the tile for both steps of line L)
+            auto load_gate_tile = [&](int gt) {
 #pragma unroll
                 for (int i = 0; i < kSteps; ++i) {
-                    const int vec = step_of(i) * 4 + mfma_load_chunk(lane);
+                    int n, vec;
+                    if (GATE == kGateMfmaLines) {
+                        n = gt * 16 + (i & 1) * 8 + line_load_row(lane);
+                        vec = step_of(i & ~1) * 4 + line_load_chunk(lane);
+                    } else {
+                        n = gt * 16 + mfma_load_row(lane);
+                        vec = step_of(i) * 4 + mfma_load_chunk(lane);
+                    }
                     ga[i] = make_uint4(0, 0, 0, 0);
                     if (vec < p.n_vec && n < p.G) ga[i] = p.gate_W[(size_t)n * p.n_vec + vec];
                 }
@@ -527,9 +545,18 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             __syncthreads();
             for (int pair = 0; pair * 2 < n_gt; ++pair) {
                 if (pair) load_gate_tile(pair * 2 + half);
+                if (GATE == kGateMfmaLines) {                  // to the MFMA operand layout
 #pragma unroll
-                for (int i = 0; i < kSteps; ++i)               // to the MFMA operand layout
-                    ga[i] = mfma_operand_from_quads(ga[i], lane, my_slice);
+                    for (int i = 0; i < kSteps; i += 2) {
+                        uint4 s0, s1;
+                        mfma_operands_from_lines(ga[i], ga[i + 1], lane, my_slice, s0, s1);
+                        ga[i] = s0;
+                        ga[i + 1] = s1;
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < kSteps; ++i) ga[i] = mfma_operand_from_quads(ga[i], lane, my_slice);
+                }
                 for (int tt = 0; tt < n_tt; ++tt) {            // uniform
                     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
                     const int m = tt * 16 + r16;
@@ -550,7 +577,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                                 __builtin_bit_cast(bf16x8_t, ga[i0 + u]),
                                 __builtin_bit_cast(bf16x8_t, hb[u]), acc, 0, 0, 0);
                     }
-                    *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * kGateSlice + lane * 4) = acc;
+                    *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * kSlice + lane * 4) = acc;
                 }
                 __syncthreads();
                 for (int idx = threadIdx.x; idx < 2 * n_tt * 256; idx += kFusedBlock) {
@@ -562,7 +589,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     const int m = tt * 16 + (l & 15);
                     float sum = 0.f;
                     for (int w = hh * 8; w < hh * 8 + 8; ++w)
-                        sum += gpart[((size_t)w * n_tt + tt) * kGateSlice + e];
+                        sum += gpart[((size_t)w * n_tt + tt) * kSlice + e];
                     if (n < p.G && m < M) s_lds[m * p.G + n] = sum + bias_lds[n];
                 }
                 __syncthreads();
