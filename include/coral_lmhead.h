@@ -152,6 +152,29 @@ coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
                                   void *hip_stream);
 
 /*
+ * Grouped LM head with the paper's probability composition (section 3.3, Eq. 7 and
+ * Eq. 8).  Selection and logits as in coral_lmhead_grouped; then for each token m and
+ * each row x of a selected group n
+ *   log p(x) = log p_router(n) + z[m,x] - lse(m,n)
+ *   log p_router(n) = s[m,n] - log sum_{n'=0..G-1} exp(s[m,n'])     (softmax over all groups)
+ *   lse(m,n)        = log sum_{r in group n} exp(z[m,r])            (softmax inside the group)
+ * and the output is the k rows with the largest log p(x) among the token's g groups,
+ * best first (equal values: lower vocabulary id first).  The order can differ from
+ * coral_lmhead_grouped's, which ranks the raw logits across groups.  Rows outside the
+ * selected groups have probability zero (Eq. 8) and are never returned.
+ *   topk_logprob [device] out [M,k] fp32 log-probabilities (natural logarithm)
+ * All other arguments, limits and errors as for coral_lmhead_grouped.  Runs the
+ * multi-kernel path for every shape.
+ */
+coral_status coral_lmhead_grouped_logprob(const void *hidden, const void *gate_W,
+                                          const float *gate_bias, const void *lm_W,
+                                          const coral_group_index *gi, int M, int H,
+                                          int V, int g, int k, coral_dtype dt,
+                                          int32_t *topk_ids, float *topk_logprob,
+                                          int32_t *sel_groups, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream);
+
+/*
  * Dense LM head: z[m,r] for every r = 0..V-1, then the k best per token with the
  * same ordering rules (the no-router baseline of Table 4; the head whose latency
  * the appendix paragraph "Backends" measures).  Arguments as above; k <= V.
@@ -162,8 +185,8 @@ coral_status coral_lmhead_dense(const void *hidden, const void *lm_W, int M, int
                                 size_t workspace_bytes, void *hip_stream);
 
 /*
- * Measurement variants: identical to coral_lmhead_grouped / coral_lmhead_dense
- * (same operation of section 3.3, same arguments, same results), and in addition
+ * Measurement variants: identical to coral_lmhead_grouped / coral_lmhead_grouped_logprob /
+ * coral_lmhead_dense (same operation of section 3.3, same arguments, same results), and in addition
  * record two caller-created HIP events (hipEvent_t passed as void*, created with
  * timing enabled) on hip_stream: ev_before immediately before and ev_after
  * immediately after the launch of the kernel that streams the LM-head weight rows,
@@ -179,6 +202,12 @@ coral_status coral_lmhead_grouped_profiled(const void *hidden, const void *gate_
                                            int32_t *sel_groups, void *workspace,
                                            size_t workspace_bytes, void *hip_stream,
                                            void *ev_before, void *ev_after);
+
+coral_status coral_lmhead_grouped_logprob_profiled(
+    const void *hidden, const void *gate_W, const float *gate_bias, const void *lm_W,
+    const coral_group_index *gi, int M, int H, int V, int g, int k, coral_dtype dt,
+    int32_t *topk_ids, float *topk_logprob, int32_t *sel_groups, void *workspace,
+    size_t workspace_bytes, void *hip_stream, void *ev_before, void *ev_after);
 
 coral_status coral_lmhead_dense_profiled(const void *hidden, const void *lm_W, int M,
                                          int H, int V, int k, coral_dtype dt,

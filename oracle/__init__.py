@@ -199,3 +199,41 @@ def dense(hidden, lm_W, k: int, dtype: str) -> DenseResult:
                                     _DT[dtype], r.topk_ids.ctypes.data, r.topk_z.ctypes.data,
                                     r.next_z.ctypes.data), "dense")
     return r
+
+
+@dataclass
+class LogprobResult:
+    sel: np.ndarray          # [M,g] selected groups, rank order
+    topk_ids: np.ndarray     # [M,k]
+    topk_logp: np.ndarray    # [M,k] fp64 log p(x), descending
+    next_logp: np.ndarray    # [M] log p ranked k+1 (-inf if none)
+    s: np.ndarray            # [M,G] gate scores
+    lse: np.ndarray          # [M,g] log-sum-exp of the logits inside each selected group
+    logp_router: np.ndarray  # [M,G]
+
+
+def grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g: int, k: int, dtype: str,
+                    forced_sel=None) -> LogprobResult:
+    """Eq. 8 as written: for every row x of a selected group n of token m,
+    log p(x) = log p_router(n) + z[x] - lse_n, p_router the softmax of the gate scores over
+    all G groups (Eq. 7), lse_n the log-sum-exp of the logits of group n's rows; the k largest
+    log p(x) per token, best first, equal values by ascending id.  Gate, selection, logits,
+    lse_n and log p_router come from the C oracle; the composition is the line below."""
+    base = grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype, forced_sel)
+    offsets = np.asarray(offsets)
+    rows = np.asarray(rows)
+    M = np.asarray(hidden).shape[0]
+    ids_out = np.empty((M, k), np.int32)
+    lp_out = np.empty((M, k))
+    nxt = np.empty(M)
+    for m in range(M):
+        all_ids, all_lp = [], []
+        for j in range(g):
+            n = int(base.sel[m, j])
+            r = rows[offsets[n]:offsets[n + 1]]
+            z = logits_rows(np.asarray(hidden)[m], lm_W, r, dtype)
+            all_ids.append(r)
+            all_lp.append(base.logp_router[m, n] + z - base.lse[m, j])
+        ids_out[m], lp_out[m], nxt[m] = top_k(np.concatenate(all_lp), np.concatenate(all_ids), k)
+    return LogprobResult(base.sel, ids_out, lp_out, nxt, base.s, base.lse, base.logp_router)
+

@@ -29,10 +29,15 @@ import numpy as np
 
 from . import dense as oracle_dense
 from . import grouped as oracle_grouped
+from . import grouped_logprob as oracle_grouped_logprob
 from . import logits_rows, rank_groups
 
 TOL = {"bf16": 2e-3, "f32": 1e-5}
 GATE_TOL = {"bf16": 1e-4, "f32": 1e-6}
+# log p(x) = log p_router + z - lse: the logit's tolerance, the same again for lse (a
+# log-sum-exp moves by at most the largest error of its terms) and twice the gate's for the
+# router's log-softmax (score and its log-sum-exp).
+LOGP_TOL = {d: 2 * TOL[d] + 2 * GATE_TOL[d] for d in TOL}
 
 
 @dataclass
@@ -152,3 +157,56 @@ def check_dense(hidden, lm_W, k, dtype, dev_ids, dev_logits, tol=None, tokens=No
         _check_topk_token(m, ids, dev_logits[m], ref.topk_ids[i], ref.topk_z[i],
                           ref.next_z[i], oz, tol, rep)
     return rep
+
+
+def check_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                          dev_ids, dev_logp, dev_sel, tol=None, gate_tol=None) -> Report:
+    """Rules (i)-(v) and the exactness rule on log p(x) of Eq. 8 instead of the raw logit."""
+    tol = LOGP_TOL[dtype] if tol is None else tol
+    gate_tol = GATE_TOL[dtype] if gate_tol is None else gate_tol
+    rep = Report()
+    dev_ids = np.asarray(dev_ids)
+    dev_logp = np.asarray(dev_logp)
+    dev_sel = np.asarray(dev_sel)
+    M = hidden.shape[0]
+    G = gate_W.shape[0]
+    V = lm_W.shape[0]
+    assert dev_ids.shape == (M, k) and dev_logp.shape == (M, k) and dev_sel.shape == (M, g)
+    assert dev_ids.dtype == np.int32 and dev_sel.dtype == np.int32 and dev_logp.dtype == np.float32
+
+    ref = oracle_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype)
+    order = rank_groups(ref.s)
+    need_forced = False
+    for m in range(M):
+        sel = dev_sel[m]
+        assert np.all((sel >= 0) & (sel < G)), f"token {m}: group id out of range {sel}"
+        assert len(set(sel.tolist())) == g, f"token {m}: duplicate groups {sel}"
+        if np.array_equal(sel, ref.sel[m]):
+            continue
+        best = ref.s[m, order[m, :g]]
+        got = ref.s[m, sel]
+        assert np.all(np.abs(got - best) < gate_tol), \
+            f"token {m}: groups {sel} differ from {ref.sel[m]} beyond the gate tolerance"
+        rep.forced_tokens += 1
+        need_forced = True
+    if need_forced:
+        rep.notes.append("oracle re-run with the device's groups forced")
+        ref = oracle_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                                     forced_sel=dev_sel)
+
+    group_of = np.empty(V, dtype=np.int32)
+    for n in range(G):
+        group_of[rows[offsets[n]:offsets[n + 1]]] = n
+    for m in range(M):
+        ids = dev_ids[m]
+        assert np.all((ids >= 0) & (ids < V)), f"token {m}: id out of range {ids}"
+        sel_m = dev_sel[m]
+        assert np.isin(group_of[ids], sel_m).all(), f"token {m}: id outside the selected groups"
+        slot = {int(n): j for j, n in enumerate(ref.sel[m])}
+        z = logits_rows(hidden[m], lm_W, ids, dtype)
+        olp = np.array([ref.logp_router[m, group_of[x]] + z[i] - ref.lse[m, slot[int(group_of[x])]]
+                        for i, x in enumerate(ids)])
+        _check_topk_token(m, ids, dev_logp[m], ref.topk_ids[m], ref.topk_logp[m],
+                          ref.next_logp[m], olp, tol, rep)
+    return rep
+

@@ -63,6 +63,10 @@ def _load():
                                     [c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.coral_lmhead_grouped_profiled.restype = c.c_int
     L.coral_lmhead_grouped_profiled.argtypes = L.coral_lmhead_grouped.argtypes + [c.c_void_p] * 2
+    L.coral_lmhead_grouped_logprob.restype = c.c_int
+    L.coral_lmhead_grouped_logprob.argtypes = L.coral_lmhead_grouped.argtypes
+    L.coral_lmhead_grouped_logprob_profiled.restype = c.c_int
+    L.coral_lmhead_grouped_logprob_profiled.argtypes = L.coral_lmhead_grouped_profiled.argtypes
     L.coral_lmhead_dense_profiled.restype = c.c_int
     L.coral_lmhead_dense_profiled.argtypes = L.coral_lmhead_dense.argtypes + [c.c_void_p] * 2
     return L
@@ -180,9 +184,11 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
                          g: int, k: int, topk_ids: Optional[torch.Tensor] = None,
                          topk_logits: Optional[torch.Tensor] = None,
                          sel_groups: Optional[torch.Tensor] = None,
-                         workspace: Optional[torch.Tensor] = None, stream=None, events=None
+                         workspace: Optional[torch.Tensor] = None, stream=None, events=None,
+                         logprob: bool = False
                          ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-    """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry."""
+    """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry.
+    logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x))."""
     dt = _dtype_code(hidden)
     if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
         raise TypeError("hidden, gate_W and lm_W must share one dtype")
@@ -212,11 +218,17 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
             _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     if events is None:
-        st = _L.coral_lmhead_grouped(*args)
+        st = (_L.coral_lmhead_grouped_logprob if logprob else _L.coral_lmhead_grouped)(*args)
     else:
-        st = _L.coral_lmhead_grouped_profiled(*args, events[0], events[1])
+        fn = _L.coral_lmhead_grouped_logprob_profiled if logprob else _L.coral_lmhead_grouped_profiled
+        st = fn(*args, events[0], events[1])
     _raise(st)
     return topk_ids, topk_logits, sel_groups
+
+
+def coral_lmhead_grouped_logprob(hidden, gate_W, gate_bias, lm_W, gi, g, k, **kw):
+    """coral_lmhead_grouped_logprob of the C ABI: (ids, log-probabilities, selected groups)."""
+    return coral_lmhead_grouped(hidden, gate_W, gate_bias, lm_W, gi, g, k, logprob=True, **kw)
 
 
 def coral_lmhead_dense(hidden: torch.Tensor, lm_W: torch.Tensor, k: int,

@@ -37,7 +37,7 @@ constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path'
 constexpr size_t kCtrlBytes = 256;     // control words at the start of the workspace
 
 struct Layout {
-    size_t ctrl, fused_part, s, sel, mask, union_list, n_union, chunk_base, part, total;
+    size_t ctrl, fused_part, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, total;
     int part_stride;
 };
 
@@ -65,6 +65,8 @@ Layout make_layout(int M, int V, int G, int g, int k) {
     L.chunk_base = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.part_stride = (V + kChunkRows - 1) / kChunkRows + g;
     L.part = take((size_t)M * L.part_stride * k * sizeof(Cand));
+    L.lse_part = take((size_t)M * L.part_stride * 2 * sizeof(float));     // log-probability mode
+    L.logp_sel = take((size_t)M * (g ? g : 1) * sizeof(float));
     L.total = off;
     return L;
 }
@@ -324,7 +326,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
                           const void* lm_W, const coral_group_index* gi, int M, int H, int V,
                           int g, int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits,
                           int32_t* sel_groups, void* workspace, size_t workspace_bytes,
-                          void* hip_stream, void* ev_before, void* ev_after) {
+                          void* hip_stream, void* ev_before, void* ev_after, bool logprob) {
     if (!gate_W || !gi) return CORAL_ERR_NULL;
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
@@ -361,7 +363,9 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    const PathPlan plan = plan_path(false, M, H, V, G, g, k, dt);
+    // the log-probability mode exists on the staged path only
+    PathPlan plan = plan_path(false, M, H, V, G, g, k, dt);
+    if (logprob) plan.path = 0;
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
                             topk_logits, sel_groups, ws, L, stream, ev_before, ev_after);
@@ -397,8 +401,9 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
         hipLaunchKernelGGL(k_gate<false>, dim3(G), dim3(kBlock), 0, stream, hid, gw, gate_bias, M, G,
                            n_vec, s);
     if ((st = launch_status()) != CORAL_OK) return st;
+    float* logp_sel = logprob ? reinterpret_cast<float*>(ws + L.logp_sel) : nullptr;
     hipLaunchKernelGGL(k_select, dim3(1), dim3(kBlock), 0, stream, s, gi->group_offsets, M, G, g, sel,
-                       mask, union_list, n_union, chunk_base);
+                       mask, union_list, n_union, chunk_base, logp_sel);
     if ((st = launch_status()) != CORAL_OK) return st;
 
     LogitsParams p;
@@ -412,6 +417,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     p.n_union = n_union;
     p.chunk_base = chunk_base;
     p.part = part;
+    p.lse_part = logprob ? reinterpret_cast<float*>(ws + L.lse_part) : nullptr;
     p.M = M; p.V = V; p.G = G; p.g = g; p.k = k;
     p.n_vec = n_vec;
     p.jp = (n_vec + kWave - 1) / kWave;
@@ -424,21 +430,22 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     if (chunks < 1) return CORAL_ERR_SHAPE;
     dim3 grid(chunks, (unsigned)max_union);
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
-    if (bf16) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<true, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return CORAL_ERR_HIP;
-        hipLaunchKernelGGL((k_logits<true, false>), grid, dim3(kBlock), lds, stream, p);
-    } else {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<false, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return CORAL_ERR_HIP;
-        hipLaunchKernelGGL((k_logits<false, false>), grid, dim3(kBlock), lds, stream, p);
-    }
+    typedef void (*logits_fn)(LogitsParams);
+    const logits_fn fn = bf16 ? (logprob ? k_logits<true, false, true> : k_logits<true, false, false>)
+                              : (logprob ? k_logits<false, false, true> : k_logits<false, false, false>);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return CORAL_ERR_HIP;
+    hipLaunchKernelGGL(fn, grid, dim3(kBlock), lds, stream, p);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
-    hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
-                       gi->group_offsets, g, 0, k, topk_ids, topk_logits);
+    if (logprob)
+        hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
+                           L.part_stride, sel, gi->group_offsets, chunk_base, logp_sel, g, k, topk_ids,
+                           topk_logits);
+    else
+        hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
+                           gi->group_offsets, g, 0, k, topk_ids, topk_logits);
     return launch_status();
 }
 
@@ -508,7 +515,28 @@ extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gat
                                              void* hip_stream) {
     return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
-                        nullptr);
+                        nullptr, false);
+}
+
+extern "C" coral_status coral_lmhead_grouped_logprob(
+    const void* hidden, const void* gate_W, const float* gate_bias, const void* lm_W,
+    const coral_group_index* gi, int M, int H, int V, int g, int k, coral_dtype dt,
+    int32_t* topk_ids, float* topk_logprob, int32_t* sel_groups, void* workspace,
+    size_t workspace_bytes, void* hip_stream) {
+    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logprob, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
+                        nullptr, true);
+}
+
+extern "C" coral_status coral_lmhead_grouped_logprob_profiled(
+    const void* hidden, const void* gate_W, const float* gate_bias, const void* lm_W,
+    const coral_group_index* gi, int M, int H, int V, int g, int k, coral_dtype dt,
+    int32_t* topk_ids, float* topk_logprob, int32_t* sel_groups, void* workspace,
+    size_t workspace_bytes, void* hip_stream, void* ev_before, void* ev_after) {
+    if (!ev_before || !ev_after) return CORAL_ERR_NULL;
+    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logprob, sel_groups, workspace, workspace_bytes, hip_stream, ev_before,
+                        ev_after, true);
 }
 
 extern "C" coral_status coral_lmhead_grouped_profiled(
@@ -519,7 +547,7 @@ extern "C" coral_status coral_lmhead_grouped_profiled(
     if (!ev_before || !ev_after) return CORAL_ERR_NULL;
     return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, ev_before,
-                        ev_after);
+                        ev_after, false);
 }
 
 extern "C" coral_status coral_lmhead_dense(const void* hidden, const void* lm_W, int M, int H,

@@ -18,6 +18,7 @@ struct LogitsParams {
     const int32_t* n_union;     // [1]              (grouped)
     const int32_t* chunk_base;  // [M, g] first partial slot of (token, selected group)
     Cand* part;                 // [M, part_stride, k]
+    float* lse_part;            // [M, part_stride, 2] (max, sum of exp) of a slot's logits; log-prob mode
     int M, V, G, g, k;
     int n_vec;                  // 16-byte vectors per row
     int jp;                     // ceil(n_vec / 64)
@@ -27,10 +28,12 @@ struct LogitsParams {
 
 // Streams the rows [row_begin, row_end) of one chunk for the nt tokens staged in
 // LDS and leaves each wave's best candidates per token in (lv, li).
-template <bool BF16, bool DENSE, int TB>
+// LP: also keep, per token, the running maximum and the sum of exp(logit - maximum) over the
+// wave's rows (the pieces of Eq. 8's softmax inside a group).
+template <bool BF16, bool DENSE, int TB, bool LP>
 __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4* hs, int nt,
                                              int row_begin, int row_end, float (&lv)[TB],
-                                             int (&li)[TB]) {
+                                             int (&li)[TB], float (&mx)[TB], float (&sm)[TB]) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int hs_stride = p.jp * kWave;
@@ -40,6 +43,8 @@ __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4*
     for (int t = 0; t < TB; ++t) {
         lv[t] = -INFINITY;
         li[t] = INT_MAX;
+        mx[t] = -INFINITY;
+        sm[t] = 0.f;
     }
     for (int rr = 0; rr < kRowsPerWave; rr += R) {
         const int r0 = row_begin + wave * kRowsPerWave + rr;
@@ -91,6 +96,11 @@ __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4*
             for (int t = 0; t < TB; ++t) {
                 const float z = wave_sum(acc[r][t]);
                 if (t < nt) list_insert(lv[t], li[t], z, row_id[r], lane, p.k);
+                if (LP) {                              // wave-uniform values
+                    const float nm = fmaxf(mx[t], z);
+                    sm[t] = sm[t] * expf(mx[t] - nm) + expf(z - nm);
+                    mx[t] = nm;
+                }
             }
         }
     }
@@ -101,15 +111,16 @@ __device__ __forceinline__ int nth_set_bit(unsigned long long m, int n) {
     return __ffsll(m) - 1;
 }
 
-template <bool BF16, bool DENSE, int TB>
+template <bool BF16, bool DENSE, int TB, bool LP>
 __device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4* hs, Cand* mbuf,
                                              unsigned long long batch, int nt, int group,
                                              int chunk, int row_begin, int row_end) {
+    __shared__ float lse_red[kWavesPerBlock][2];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    float lv[TB];
+    float lv[TB], mx[TB], sm[TB];
     int li[TB];
-    stream_chunk<BF16, DENSE, TB>(p, hs, nt, row_begin, row_end, lv, li);
+    stream_chunk<BF16, DENSE, TB, LP>(p, hs, nt, row_begin, row_end, lv, li, mx, sm);
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
         if (t >= nt) break;                            // block-uniform
@@ -126,13 +137,29 @@ __device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4*
             mbuf[wave * p.k + lane].v = lv[t];
             mbuf[wave * p.k + lane].id = li[t];
         }
+        if (LP && lane == 0) {
+            lse_red[wave][0] = mx[t];
+            lse_red[wave][1] = sm[t];
+        }
         block_rank_merge(mbuf, kWavesPerBlock * p.k, p.k,
                          p.part + ((size_t)m * p.part_stride + slot) * p.k);
+        if (LP && threadIdx.x == 0) {                  // the waves' pieces, combined in wave order
+            float bm = -INFINITY, bs = 0.f;
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                const float nm = fmaxf(bm, lse_red[w][0]);
+                if (nm > -INFINITY) bs = bs * expf(bm - nm) + lse_red[w][1] * expf(lse_red[w][0] - nm);
+                bm = nm;
+            }
+            float* dst = p.lse_part + ((size_t)m * p.part_stride + slot) * 2;
+            dst[0] = bm;
+            dst[1] = bs;
+        }
+        if (LP) __syncthreads();                       // lse_red is rewritten for the next token
     }
 }
 
 // One workgroup per (chunk of kChunkRows rows, activated group).  Dense: per chunk.
-template <bool BF16, bool DENSE>
+template <bool BF16, bool DENSE, bool LP = false>
 __global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
     extern __shared__ uint4 smem[];
     uint4* hs = smem;
@@ -176,13 +203,13 @@ __global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
         }
         __syncthreads();
         if (nt == 1)
-            chunk_tokens<BF16, DENSE, 1>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<BF16, DENSE, 1, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else if (nt == 2)
-            chunk_tokens<BF16, DENSE, 2>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<BF16, DENSE, 2, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else if (nt <= 4)
-            chunk_tokens<BF16, DENSE, 4>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<BF16, DENSE, 4, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else
-            chunk_tokens<BF16, DENSE, kTokBatch>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<BF16, DENSE, kTokBatch, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         // chunk_tokens ends on a barrier, so hs may be overwritten now
     }
 }
@@ -224,7 +251,8 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
                                                    unsigned long long* __restrict__ group_mask,
                                                    int32_t* __restrict__ union_list,
                                                    int32_t* __restrict__ n_union,
-                                                   int32_t* __restrict__ chunk_base) {
+                                                   int32_t* __restrict__ chunk_base,
+                                                   float* __restrict__ logp_sel) {
     __shared__ unsigned long long mask[kMaxG];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -240,6 +268,21 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             sc[i] = n < G ? s[(size_t)m * G + n] : -INFINITY;
             if (!(sc[i] == sc[i])) sc[i] = -INFINITY;       // NaN: keeps every round a winner
             if (n >= G) taken |= 1u << i;
+        }
+        // log of the router's softmax denominator over all G groups (Eq. 7), log-prob mode
+        float lse_s = 0.f;
+        if (logp_sel) {
+            float smax = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < kSelRegs; ++i) smax = fmaxf(smax, sc[i]);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) smax = fmaxf(smax, __shfl_xor(smax, off));
+            float ssum = 0.f;
+#pragma unroll
+            for (int i = 0; i < kSelRegs; ++i)
+                if (i * kWave + lane < G) ssum += expf(sc[i] - smax);
+            ssum = wave_sum(ssum);
+            lse_s = smax + logf(ssum);
         }
         for (int round = 0; round < g; ++round) {
             float bv = -INFINITY;
@@ -265,6 +308,7 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             if ((bi & (kWave - 1)) == lane) taken |= 1u << (bi / kWave);
             if (lane == 0) {
                 sel[m * g + round] = bi;
+                if (logp_sel) logp_sel[m * g + round] = bv - lse_s;
                 atomicOr(&mask[bi], 1ull << m);
             }
         }
@@ -348,5 +392,108 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
     }
 }
 
+
+// Final merge of the log-probability mode (Eq. 8): log p(x) = log p_router(n) + z[x] - lse_n
+// for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
+// group's rows.  One workgroup per token: first the offset log p_router(n) - lse_n of every
+// selected group from its slots' (max, sum) pieces, then the partial lists (sorted by logit,
+// which inside a group is the order of log p as well) are streamed with their group's offset
+// added, and the k best log-probabilities are written, best first (equal values: lower id).
+__global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict__ part,
+                                                          const float* __restrict__ lse_part,
+                                                          int part_stride,
+                                                          const int32_t* __restrict__ sel,
+                                                          const int32_t* __restrict__ offsets,
+                                                          const int32_t* __restrict__ chunk_base,
+                                                          const float* __restrict__ logp_sel, int g,
+                                                          int k, int32_t* __restrict__ topk_ids,
+                                                          float* __restrict__ topk_logprob) {
+    __shared__ Cand mbuf[kWavesPerBlock * kMaxK];
+    __shared__ Cand outbuf[kMaxK];
+    __shared__ float shift[kMaxG];                     // per selected group: log p_router - lse
+    __shared__ int first_slot[kMaxG + 1];
+    __shared__ float red[kWavesPerBlock][2];
+    const int m = blockIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    for (int i = threadIdx.x; i < g; i += kBlock) first_slot[i] = chunk_base[m * g + i];
+    if (threadIdx.x == 0) {
+        const int n = sel[m * g + g - 1];
+        first_slot[g] = chunk_base[m * g + g - 1] + (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
+    }
+    __syncthreads();
+    for (int i = 0; i < g; ++i) {                      // block-uniform
+        const int s0 = first_slot[i], s1 = first_slot[i + 1];
+        float bm = -INFINITY, bs = 0.f;                // this thread's slots, ascending
+        for (int s = s0 + (int)threadIdx.x; s < s1; s += kBlock) {
+            const float pm = lse_part[((size_t)m * part_stride + s) * 2];
+            const float ps = lse_part[((size_t)m * part_stride + s) * 2 + 1];
+            const float nm = fmaxf(bm, pm);
+            if (nm > -INFINITY) bs = bs * expf(bm - nm) + ps * expf(pm - nm);
+            bm = nm;
+        }
+        // lanes, then waves, in a fixed order
+        float wm = bm;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+        float ws = wm > -INFINITY ? bs * expf(bm - wm) : 0.f;
+        ws = wave_sum(ws);
+        if (lane == 0) {
+            red[wave][0] = wm;
+            red[wave][1] = ws;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float tm = -INFINITY, ts = 0.f;
+            for (int w = 0; w < kWavesPerBlock; ++w) {
+                const float nm = fmaxf(tm, red[w][0]);
+                if (nm > -INFINITY) ts = ts * expf(tm - nm) + red[w][1] * expf(red[w][0] - nm);
+                tm = nm;
+            }
+            shift[i] = logp_sel[m * g + i] - (tm + logf(ts));
+        }
+        __syncthreads();
+    }
+    const int lists = first_slot[g];
+    const int n_cand = lists * k;
+    const Cand* src = part + (size_t)m * part_stride * k;
+    float lv = -INFINITY;
+    int li = INT_MAX;
+    for (int base = wave * kWave; base < n_cand; base += kBlock) {   // wave-uniform
+        const int i = base + lane;
+        Cand c;
+        c.v = -INFINITY;
+        c.id = INT_MAX;
+        if (i < n_cand) {
+            c = src[i];
+            const int slot = i / k;
+            int lo = 0, hi = g - 1;                    // the selected group whose slots hold it
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (first_slot[mid] <= slot) lo = mid; else hi = mid - 1;
+            }
+            if (c.id != INT_MAX) c.v += shift[lo];
+        }
+        const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lv), k - 1));
+        const int ti = __builtin_amdgcn_readlane(li, k - 1);
+        unsigned long long pass = __ballot(better(c.v, c.id, tv, ti));
+        while (pass) {
+            const int srcl = __ffsll(pass) - 1;
+            pass &= pass - 1ull;
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), srcl));
+            const int id = __builtin_amdgcn_readlane(c.id, srcl);
+            list_insert(lv, li, v, id, lane, k);
+        }
+    }
+    if (lane < k) {
+        mbuf[wave * k + lane].v = lv;
+        mbuf[wave * k + lane].id = li;
+    }
+    block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
+    if (threadIdx.x < k) {
+        topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
+        topk_logprob[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
+    }
+}
 
 }  // namespace

@@ -123,3 +123,24 @@ def test_group_near_tie_uses_forced_selection():
     assert not np.array_equal(rf.topk_ids, ids)   # the swapped group changes the candidates
     with pytest.raises(AssertionError):           # so the oracle's own candidates do not fit sel2
         check(head, hidden, 2, 4, ids, z, sel2)
+
+
+# ------------------------------------------------------------------ log-probability mode
+def test_logprob_check_accepts_the_oracles_answer_and_rejects_the_logit_ranking():
+    head, hidden = make_head(CFG), make_hidden(CFG, 5)
+    c = head.cfg
+    r = oracle.grouped_logprob(hidden, head.gate_W, head.gate_bias, head.lm_W, head.group_offsets,
+                               head.group_rows, CFG.g, CFG.k, c.dtype)
+    args = (hidden, head.gate_W, head.gate_bias, head.lm_W, head.group_offsets, head.group_rows,
+            CFG.g, CFG.k, c.dtype)
+    rep = compare.check_grouped_logprob(*args, r.topk_ids, r.topk_logp.astype(np.float32), r.sel)
+    assert rep.tokens == 5 and rep.max_abs_err < 1e-6
+    # a device that ranked raw logits (or returned them) must not pass
+    b = oracle.grouped(*args)
+    assert not np.array_equal(b.topk_ids, r.topk_ids)          # the two rankings differ here
+    with pytest.raises(AssertionError):
+        compare.check_grouped_logprob(*args, b.topk_ids, b.topk_z.astype(np.float32), b.sel)
+    # right ids, log-probabilities off by the router term
+    wrong = (r.topk_logp + 0.05).astype(np.float32)
+    with pytest.raises(AssertionError):
+        compare.check_grouped_logprob(*args, r.topk_ids, wrong, r.sel)

@@ -55,6 +55,20 @@ def check_grouped(dh, hidden, g, k, out):
                                  h.group_rows, g, k, h.cfg.dtype, *out)
 
 
+def run_logprob(coral, dh: DeviceHead, hidden, g, k):
+    c = dh.head.cfg
+    d_hidden = coral.device_tensor(hidden, c.dtype)
+    ids, logp, sel = coral.coral_lmhead_grouped_logprob(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, g, k)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), logp.cpu().numpy(), sel.cpu().numpy()
+
+
+def check_logprob(dh, hidden, g, k, out):
+    h = dh.head
+    return compare.check_grouped_logprob(hidden, h.gate_W, h.gate_bias, h.lm_W, h.group_offsets,
+                                         h.group_rows, g, k, h.cfg.dtype, *out)
+
+
 def check_dense(dh, hidden, k, out, tokens=None):
     h = dh.head
     return compare.check_dense(hidden, h.lm_W, k, h.cfg.dtype, *out, tokens=tokens)
@@ -83,6 +97,45 @@ def test_scaled_configs_grouped_and_dense(coral, cfg, Ms):
             assert rep.tokens == M
             rep = check_dense(dh, hidden, cfg.k, run_dense(coral, dh, hidden, cfg.k))
             assert rep.tokens == M
+
+
+@pytest.mark.parametrize("cfg,Ms", SCALED, ids=lambda x: x.name if isinstance(x, HeadConfig) else None)
+def test_scaled_configs_logprob(coral, cfg, Ms):
+    """Eq. 8's probability composition against the oracle, same shapes as above."""
+    dh = DeviceHead(coral, make_head(cfg))
+    for M in Ms:
+        hidden = make_hidden(cfg, M, 2)
+        print(f"case {cfg.name} M={M} log-prob", flush=True)
+        rep = check_logprob(dh, hidden, cfg.g, cfg.k, run_logprob(coral, dh, hidden, cfg.g, cfg.k))
+        assert rep.tokens == M
+
+
+def test_logprob_edge_shapes(coral):
+    """One group (a plain log-softmax), all groups active (probabilities of the whole
+    vocabulary), ragged and single-row groups, two runs bit-identical."""
+    cfg = HeadConfig("lp1", "f32", 64, 300, 1, 1, (3,), 9, 95, False)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 3)
+    check_logprob(dh, hidden, 1, 9, run_logprob(coral, dh, hidden, 1, 9))
+    cfg = HeadConfig("lpG", "bf16", 256, 6 * 111, 6, 6, (5,), 12, 96, True, bias_std=1.0)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, 5)
+    a = run_logprob(coral, dh, hidden, 6, 12)
+    check_logprob(dh, hidden, 6, 12, a)
+    b = run_logprob(coral, dh, hidden, 6, 12)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    sizes = [1, 31, 5, 32, 33, 500, 64, 7]
+    V = sum(sizes)
+    cfg = HeadConfig("lprag", "f32", 128, V, len(sizes), 3, (6,), 4, 97, False)
+    rng = np.random.default_rng(97)
+    perm = rng.permutation(V).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(len(sizes))])
+    lm_W = rng.standard_normal((V, cfg.H)).astype(np.float32) * np.float32(0.05)
+    gate_W = rng.standard_normal((len(sizes), cfg.H)).astype(np.float32) * np.float32(0.05)
+    dh = DeviceHead(coral, Head(cfg, lm_W, gate_W, None, offsets, rows.astype(np.int32)))
+    hidden = make_hidden(cfg, 6)
+    check_logprob(dh, hidden, 3, 4, run_logprob(coral, dh, hidden, 3, 4))
 
 
 @pytest.mark.parametrize("dtype,H", [("bf16", 8), ("bf16", 264), ("bf16", 1032), ("f32", 4),
@@ -347,5 +400,10 @@ def test_full_size_workloads(coral, name, Ms):
         rep = check_dense(dh, hidden, cfg.k, run_dense(coral, dh, hidden, cfg.k), tokens=toks)
         print(f"  dense exact {rep.exact_tokens}/{rep.tokens} max|err| {rep.max_abs_err:.2e}",
               flush=True)
+        if M <= 16:
+            print(f"case {name} M={M} log-prob", flush=True)
+            rep = check_logprob(dh, hidden, cfg.g, cfg.k, run_logprob(coral, dh, hidden, cfg.g, cfg.k))
+            print(f"  log-prob exact {rep.exact_tokens}/{rep.tokens} max|err| {rep.max_abs_err:.2e}",
+                  flush=True)
     del dh
     torch.cuda.empty_cache()

@@ -356,3 +356,88 @@ def test_inputs_follow_the_stated_recipe():
     w = widen(a.lm_W)
     assert abs(w.std() - 0.02) < 2e-4 and abs(w.mean()) < 1e-4
     assert not np.array_equal(make_hidden(cfg, 8, batch=1), make_hidden(cfg, 8, batch=0))
+
+
+# ------------------------------------------------------------------ Eq. 8 composition
+def _np_logprob_reference(hidden, gate_W, bias, lm_W, offsets, rows, g, k):
+    """Independent float64 numpy/scipy version of the log-probability head."""
+    from scipy.special import log_softmax, logsumexp
+    s = hidden @ gate_W.T + (0.0 if bias is None else bias)
+    out_ids, out_lp = [], []
+    for m in range(hidden.shape[0]):
+        sel = np.lexsort((np.arange(s.shape[1]), -s[m]))[:g]
+        lpr = log_softmax(s[m])
+        ids, lp = [], []
+        for n in sel:
+            r = rows[offsets[n]:offsets[n + 1]]
+            z = lm_W[r] @ hidden[m]
+            ids.append(r)
+            lp.append(lpr[n] + z - logsumexp(z))
+        ids, lp = np.concatenate(ids), np.concatenate(lp)
+        o = np.lexsort((ids, -lp))[:k]
+        out_ids.append(ids[o])
+        out_lp.append(lp[o])
+    return np.array(out_ids), np.array(out_lp)
+
+
+@pytest.mark.parametrize("seed,H,V,G,g,M,k", [(0, 16, 96, 6, 2, 3, 7), (1, 24, 120, 4, 4, 2, 12),
+                                               (2, 8, 64, 8, 3, 5, 5)])
+def test_logprob_matches_numpy_scipy(seed, H, V, G, g, M, k):
+    rng = np.random.default_rng(seed)
+    hidden = rng.standard_normal((M, H)).astype(np.float32)
+    gate_W = rng.standard_normal((G, H)).astype(np.float32)
+    lm_W = rng.standard_normal((V, H)).astype(np.float32)
+    bias = rng.standard_normal(G).astype(np.float32)
+    perm = rng.permutation(V).astype(np.int32)
+    v = V // G
+    offsets = (np.arange(G + 1) * v).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[n * v:(n + 1) * v]) for n in range(G)]).astype(np.int32)
+    r = oracle.grouped_logprob(hidden, gate_W, bias, lm_W, offsets, rows, g, k, "f32")
+    ids, lp = _np_logprob_reference(hidden.astype(np.float64), gate_W.astype(np.float64),
+                                    bias.astype(np.float64), lm_W.astype(np.float64), offsets, rows, g, k)
+    assert np.array_equal(r.topk_ids, ids)
+    assert np.max(np.abs(r.topk_logp - lp)) < 1e-11
+
+
+def test_logprob_sums_to_one_over_the_vocabulary_when_all_groups_are_active():
+    rng = np.random.default_rng(5)
+    H, V, G = 12, 60, 5
+    hidden = rng.standard_normal((2, H)).astype(np.float32)
+    gate_W = rng.standard_normal((G, H)).astype(np.float32)
+    lm_W = rng.standard_normal((V, H)).astype(np.float32)
+    offsets = (np.arange(G + 1) * (V // G)).astype(np.int32)
+    rows = np.arange(V, dtype=np.int32)
+    r = oracle.grouped_logprob(hidden, gate_W, None, lm_W, offsets, rows, G, V, "f32")
+    assert np.allclose(np.exp(r.topk_logp).sum(axis=1), 1.0, atol=1e-12)
+    assert np.all(np.diff(r.topk_logp, axis=1) <= 0)
+
+
+def test_logprob_single_group_is_a_log_softmax():
+    from scipy.special import log_softmax
+    rng = np.random.default_rng(6)
+    H, V = 10, 40
+    hidden = rng.standard_normal((3, H)).astype(np.float32)
+    lm_W = rng.standard_normal((V, H)).astype(np.float32)
+    gate_W = rng.standard_normal((1, H)).astype(np.float32)
+    r = oracle.grouped_logprob(hidden, gate_W, None, lm_W, np.array([0, V], np.int32),
+                               np.arange(V, dtype=np.int32), 1, V, "f32")
+    full = log_softmax(hidden.astype(np.float64) @ lm_W.astype(np.float64).T, axis=1)
+    for m in range(3):
+        assert np.allclose(r.topk_logp[m], np.sort(full[m])[::-1], atol=1e-12)
+
+
+def test_logprob_ranking_differs_from_logit_ranking_in_a_hand_worked_case():
+    """Groups A = {0, 1} with logits (2, 2) and B = {2, 3} with (1.5, -10), equal router
+    scores: p(2) = 1/2 * ~1, p(0) = p(1) = 1/2 * 1/2, so row 2 comes first although its logit
+    is the lower one.  Values by hand: log p(0) = -2 ln 2, log p(2) = -ln 2 - ln(1 + e^-11.5)."""
+    hidden = np.array([[1.0, 0.0]], np.float32)
+    lm_W = np.array([[2.0, 0.0], [2.0, 0.0], [1.5, 0.0], [-10.0, 0.0]], np.float32)
+    gate_W = np.zeros((2, 2), np.float32)
+    offsets = np.array([0, 2, 4], np.int32)
+    rows = np.arange(4, dtype=np.int32)
+    r = oracle.grouped_logprob(hidden, gate_W, None, lm_W, offsets, rows, 2, 3, "f32")
+    assert r.topk_ids[0].tolist() == [2, 0, 1]
+    want = [-np.log(2) - np.log1p(np.exp(-11.5)), -2 * np.log(2), -2 * np.log(2)]
+    assert np.allclose(r.topk_logp[0], want, atol=1e-14)
+    b = oracle.grouped(hidden, gate_W, None, lm_W, offsets, rows, 2, 3, "f32")
+    assert b.topk_ids[0].tolist() == [0, 1, 2]
