@@ -131,7 +131,7 @@ class Bench:
         return chosen
 
     # ---------------------------------------------------------------- timing
-    def time_grouped(self, M, steps, warmup, R=24, eager=False, event_steps=240):
+    def time_grouped(self, M, steps, warmup, R=24, eager=False, event_steps=240, logprob=False):
         torch, coral, cfg = self.torch, self.coral, self.cfg
         sched = self.schedule(M, R)
         R = len(sched)
@@ -143,7 +143,7 @@ class Bench:
         def call(i, events=None):
             coral.coral_lmhead_grouped(sched[i % R][2], self.gate_W, self.bias, self.lm_W, self.gi,
                                        cfg.g, cfg.k, topk_ids=ids, topk_logits=z, sel_groups=sel,
-                                       workspace=ws, events=events)
+                                       workspace=ws, events=events, logprob=logprob)
 
         total_ms = self._timed(call, steps, warmup, R, eager)
         spread = self.last_spread
@@ -355,6 +355,12 @@ def main():
                           "kernel_us": r["kernel_us"],
                           "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
                           "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        r = bench.time_grouped(a.M, n, min(a.warmup, 20), eager=a.eager, event_steps=48, logprob=True)
+        cases.append({"path": "grouped, log-probability output (Eq. 8; multi-kernel path, k_logits)",
+                      "M": a.M, "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
+                      "avg_activated_groups": r["U"],
+                      "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
+                      "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
         rep_M = min(cfg.Ms)
         cases.append({"path": "grouped, same input every call (cache-assisted)", "M": rep_M,
                       "us_per_step": bench.time_repeat(rep_M, max(48, n), 8)})

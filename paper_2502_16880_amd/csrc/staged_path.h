@@ -3,6 +3,7 @@
 // when the single-launch path's LDS budget does not fit.
 #pragma once
 #include "device_utils.h"
+#include "fused_path.h"
 
 namespace {
 
@@ -254,11 +255,42 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
                                                    int32_t* __restrict__ chunk_base,
                                                    float* __restrict__ logp_sel) {
     __shared__ unsigned long long mask[kMaxG];
+    __shared__ int off_lds[kMaxG + 1];                 // group offsets: no dependent loads later
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     for (int n = threadIdx.x; n < G; n += kBlock) mask[n] = 0ull;
+    for (int n = threadIdx.x; n <= G; n += kBlock) off_lds[n] = offsets[n];
     __syncthreads();
 
+    __shared__ unsigned long long rank_keys[kWavesPerBlock][kWave];
+    if (G <= kWave) {
+        // one score per lane: rank by counting (larger score first, then lower group id)
+        for (int m = wave; m < M; m += kWavesPerBlock) {
+            float v = lane < G ? s[(size_t)m * G + lane] : -INFINITY;
+            if (!(v == v)) v = -INFINITY;                   // NaN: unspecified, keep a total order
+            float lse_s = 0.f;
+            if (logp_sel) {
+                float smax = v;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) smax = fmaxf(smax, __shfl_xor(smax, off));
+                lse_s = smax + logf(wave_sum(lane < G ? expf(v - smax) : 0.f));
+            }
+            const int rank = wave_rank(rank_keys[wave], v, lane, G, lane);
+            const bool chosen = lane < G && rank < g;
+            const int nch = lane < G ? (off_lds[lane + 1] - off_lds[lane] + kChunkRows - 1) / kChunkRows : 0;
+            if (chosen) {
+                sel[m * g + rank] = lane;
+                if (logp_sel) logp_sel[m * g + rank] = v - lse_s;
+                atomicOr(&mask[lane], 1ull << m);
+            }
+            int slot_base = 0;                              // slots in rank order
+            for (int r = 0; r < g; ++r) {                   // wave-uniform
+                const int src = __ffsll(__ballot(chosen && rank == r)) - 1;
+                if (lane == src) chunk_base[m * g + r] = slot_base;
+                slot_base += __builtin_amdgcn_readlane(nch, src);
+            }
+        }
+    } else
     for (int m = wave; m < M; m += kWavesPerBlock) {
         float sc[kSelRegs];
         unsigned taken = 0;
@@ -284,6 +316,7 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             ssum = wave_sum(ssum);
             lse_s = smax + logf(ssum);
         }
+        int slot_base = 0;                             // first partial-list slot of the next group
         for (int round = 0; round < g; ++round) {
             float bv = -INFINITY;
             int bi = INT_MAX;
@@ -308,9 +341,11 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             if ((bi & (kWave - 1)) == lane) taken |= 1u << (bi / kWave);
             if (lane == 0) {
                 sel[m * g + round] = bi;
+                chunk_base[m * g + round] = slot_base;
                 if (logp_sel) logp_sel[m * g + round] = bv - lse_s;
                 atomicOr(&mask[bi], 1ull << m);
             }
+            slot_base += (off_lds[bi + 1] - off_lds[bi] + kChunkRows - 1) / kChunkRows;
         }
     }
     __syncthreads();
@@ -325,15 +360,6 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             count += __popcll(b);
         }
         if (lane == 0) *n_union = count;
-    }
-    for (int m = threadIdx.x; m < M; m += kBlock) {
-        int base = 0;
-        for (int i = 0; i < g; ++i) {
-            chunk_base[m * g + i] = base;
-            // sel was written by lane 0 of this block's waves before the barrier above
-            const int n = sel[m * g + i];
-            base += (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
-        }
     }
 }
 
@@ -395,10 +421,11 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 
 // Final merge of the log-probability mode (Eq. 8): log p(x) = log p_router(n) + z[x] - lse_n
 // for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
-// group's rows.  One workgroup per token: first the offset log p_router(n) - lse_n of every
-// selected group from its slots' (max, sum) pieces, then the partial lists (sorted by logit,
-// which inside a group is the order of log p as well) are streamed with their group's offset
-// added, and the k best log-probabilities are written, best first (equal values: lower id).
+// group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + 4,
+// ...: it combines the (max, sum) pieces of the group's slots into lse_n, merges the group's
+// partial lists (sorted by logit, which inside a group is the order of log p as well) into
+// the group's k best, adds the offset log p_router(n) - lse_n and merges that list into its
+// running list.  The four running lists are merged at the end; equal values: lower id first.
 __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict__ part,
                                                           const float* __restrict__ lse_part,
                                                           int part_stride,
@@ -408,86 +435,62 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
                                                           const float* __restrict__ logp_sel, int g,
                                                           int k, int32_t* __restrict__ topk_ids,
                                                           float* __restrict__ topk_logprob) {
-    __shared__ Cand mbuf[kWavesPerBlock * kMaxK];
+    __shared__ Cand mbuf[kWavesPerBlock * kMaxK];      // the waves' running lists
+    __shared__ Cand fresh[kWavesPerBlock * kMaxK];     // a group's k best, then the merged list
     __shared__ Cand outbuf[kMaxK];
-    __shared__ float shift[kMaxG];                     // per selected group: log p_router - lse
-    __shared__ int first_slot[kMaxG + 1];
-    __shared__ float red[kWavesPerBlock][2];
+    __shared__ WaveScratch scratch[kWavesPerBlock];
     const int m = blockIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
-    for (int i = threadIdx.x; i < g; i += kBlock) first_slot[i] = chunk_base[m * g + i];
-    if (threadIdx.x == 0) {
-        const int n = sel[m * g + g - 1];
-        first_slot[g] = chunk_base[m * g + g - 1] + (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
-    }
-    __syncthreads();
-    for (int i = 0; i < g; ++i) {                      // block-uniform
-        const int s0 = first_slot[i], s1 = first_slot[i + 1];
-        float bm = -INFINITY, bs = 0.f;                // this thread's slots, ascending
-        for (int s = s0 + (int)threadIdx.x; s < s1; s += kBlock) {
-            const float pm = lse_part[((size_t)m * part_stride + s) * 2];
-            const float ps = lse_part[((size_t)m * part_stride + s) * 2 + 1];
+    Cand* mine = mbuf + wave * k;
+    Cand* grp = fresh + wave * k;
+    if (lane < k) mine[lane] = sentinel();
+    const Cand* src = part + (size_t)m * part_stride * k;
+    for (int i = wave; i < g; i += kWavesPerBlock) {   // wave-uniform
+        const int n = sel[m * g + i];
+        const int s0 = chunk_base[m * g + i];
+        const int n_slots = (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
+        // lse_n from the slots' pieces: per lane in ascending slot order, then across lanes
+        float bm = -INFINITY, bs = 0.f;
+        for (int s = lane; s < n_slots; s += kWave) {
+            const float pm = lse_part[((size_t)m * part_stride + s0 + s) * 2];
+            const float ps = lse_part[((size_t)m * part_stride + s0 + s) * 2 + 1];
             const float nm = fmaxf(bm, pm);
             if (nm > -INFINITY) bs = bs * expf(bm - nm) + ps * expf(pm - nm);
             bm = nm;
         }
-        // lanes, then waves, in a fixed order
         float wm = bm;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
-        float ws = wm > -INFINITY ? bs * expf(bm - wm) : 0.f;
-        ws = wave_sum(ws);
-        if (lane == 0) {
-            red[wave][0] = wm;
-            red[wave][1] = ws;
+        const float ws = wave_sum(wm > -INFINITY ? bs * expf(bm - wm) : 0.f);
+        const float shift = logp_sel[m * g + i] - (wm + logf(ws));
+        // the group's k best by logit, offset added
+        wave_merge_topk(
+            n_slots, k, lane, &scratch[wave],
+            [&](int l, int e) { return src[(size_t)(s0 + l) * k + e]; },
+            [&](int r, Cand c) {
+                if (is_real(c)) c.v += shift;
+                grp[r] = c;
+            });
+        // merge with the running list (two sorted lists of k): ranks by counting
+        Cand a = sentinel(), b = sentinel();
+        if (lane < k) {
+            a = mine[lane];
+            b = grp[lane];
         }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            float tm = -INFINITY, ts = 0.f;
-            for (int w = 0; w < kWavesPerBlock; ++w) {
-                const float nm = fmaxf(tm, red[w][0]);
-                if (nm > -INFINITY) ts = ts * expf(tm - nm) + red[w][1] * expf(red[w][0] - nm);
-                tm = nm;
-            }
-            shift[i] = logp_sel[m * g + i] - (tm + logf(ts));
-        }
-        __syncthreads();
-    }
-    const int lists = first_slot[g];
-    const int n_cand = lists * k;
-    const Cand* src = part + (size_t)m * part_stride * k;
-    float lv = -INFINITY;
-    int li = INT_MAX;
-    for (int base = wave * kWave; base < n_cand; base += kBlock) {   // wave-uniform
-        const int i = base + lane;
-        Cand c;
-        c.v = -INFINITY;
-        c.id = INT_MAX;
-        if (i < n_cand) {
-            c = src[i];
-            const int slot = i / k;
-            int lo = 0, hi = g - 1;                    // the selected group whose slots hold it
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (first_slot[mid] <= slot) lo = mid; else hi = mid - 1;
-            }
-            if (c.id != INT_MAX) c.v += shift[lo];
-        }
-        const float tv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(lv), k - 1));
-        const int ti = __builtin_amdgcn_readlane(li, k - 1);
-        unsigned long long pass = __ballot(better(c.v, c.id, tv, ti));
-        while (pass) {
-            const int srcl = __ffsll(pass) - 1;
-            pass &= pass - 1ull;
-            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c.v), srcl));
-            const int id = __builtin_amdgcn_readlane(c.id, srcl);
-            list_insert(lv, li, v, id, lane, k);
-        }
-    }
-    if (lane < k) {
-        mbuf[wave * k + lane].v = lv;
-        mbuf[wave * k + lane].id = li;
+        const unsigned long long ka = cand_key(a.v, a.id), kb = cand_key(b.v, b.id);
+        scratch[wave].keys[lane] = lane < k ? ka : 0ull;
+        int ra = lane, rb = lane;                       // rank inside the own list
+        unsigned long long* keys = scratch[wave].keys;
+        rb += count_above(keys, k, kb);
+        // (LDS accesses of a wave complete in order: the reads above precede this write)
+        keys[lane] = lane < k ? kb : 0ull;
+        ra += count_above(keys, k, ka);
+        if (lane < k && is_real(a) && ra < k) grp[ra] = a;     // grp is free: b sits in registers
+        if (lane < k && is_real(b) && rb < k) grp[rb] = b;
+        const int n_real = __popcll(__ballot(lane < k && is_real(a))) + __popcll(__ballot(lane < k && is_real(b)));
+        if (lane < k && lane >= n_real) grp[lane] = sentinel();
+        if (lane < k) mine[lane] = grp[lane];
     }
     block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
     if (threadIdx.x < k) {
