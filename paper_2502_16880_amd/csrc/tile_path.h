@@ -90,7 +90,7 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
 // Every participant's new rank is counted directly: a candidate's rank is the number of
 // list entries and of other candidates that beat it, a list entry moves down by the number
 // of candidates that beat it.  Ranks are distinct, so all writes go to distinct slots.
-// keys: 128 wave-private LDS words (ordering keys of the passing candidates, then of the list).
+// keys: 128 wave-private 64-bit LDS words (ordering keys of the passing candidates, then of the list).
 __device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c,
                                                  unsigned long long* keys) {
     const Cand tail = list[k - 1];                     // one address for all lanes: a broadcast
@@ -117,49 +117,116 @@ __device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Ca
     if (lane < kr && re < k) list[re] = e;
 }
 
+// The candidate an ordering key was made from (cand_key's inverse; -0.0 comes back as +0.0).
+__device__ __forceinline__ Cand cand_from_key(unsigned long long key) {
+    const unsigned o = (unsigned)(key >> 32);
+    Cand c;
+    c.v = __uint_as_float((o >> 31) ? (o ^ 0x80000000u) : ~o);
+    c.id = (int)~(unsigned)key;
+    return c;
+}
+
+// The two halves of a block's logits of one token (two candidates per lane) go into the
+// token's sorted list in LDS.  Candidates that do not beat the list's k-th entry drop out
+// first (the common case: none is left).  While the list is short, or early in the stream,
+// most candidates pass; the k-th largest of the lanes' better candidates then bounds the
+// result from below (k candidates reach it), and only candidates that reach it (ties kept)
+// stay.  The survivors' keys are compacted, one per lane; then one pass over them gives
+// every survivor its final position (list entries above it + survivors above it, two
+// ballots) and moves every list entry down by the number of survivors above it.
+// keys: 128 wave-private 64-bit LDS words, keys32: 64 more 32-bit words.
+__device__ __forceinline__ void tile_merge_pair(Cand* list, int k, int lane, Cand c0, Cand c1,
+                                                unsigned long long* keys, unsigned* keys32) {
+    const Cand tail = list[k - 1];                     // a broadcast
+    bool p0 = is_real(c0) && better(c0.v, c0.id, tail.v, tail.id);
+    bool p1 = is_real(c1) && better(c1.v, c1.id, tail.v, tail.id);
+    unsigned long long b0 = __ballot(p0), b1 = __ballot(p1);
+    if ((b0 | b1) == 0ull) return;                     // wave-uniform, the common case
+    if (__popcll(b0) + __popcll(b1) > k + (k >> 1)) {  // wave-uniform
+        const unsigned o0 = p0 ? ord32(c0.v) : 0u, o1 = p1 ? ord32(c1.v) : 0u;
+        const unsigned tau = wave_kth_key(keys32, o0 > o1 ? o0 : o1, kWave, k, lane);
+        p0 = p0 && o0 >= tau;
+        p1 = p1 && o1 >= tau;
+        b0 = __ballot(p0);
+        b1 = __ballot(p1);
+    }
+    const int n0 = __popcll(b0), np = n0 + __popcll(b1);
+    if (np > kWave) {                                  // ties at the bound: one half at a time
+        if (!p0) c0 = sentinel();
+        if (!p1) c1 = sentinel();
+        tile_merge_token(list, k, lane, c0, keys);
+        tile_merge_token(list, k, lane, c1, keys);
+        return;
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (p0) keys[__popcll(b0 & below)] = cand_key(c0.v, c0.id);
+    if (p1) keys[n0 + __popcll(b1 & below)] = cand_key(c1.v, c1.id);
+    Cand e = sentinel();
+    if (lane < k) e = list[lane];
+    const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
+    const bool is_e = lane < kr;
+    // lanes without an entry (a survivor) hold key 0, which is above nothing
+    const unsigned long long ekey = is_e ? cand_key(e.v, e.id) : 0ull;
+    const unsigned long long ckey = lane < np ? keys[lane] : 0ull;
+    int re = lane;
+    unsigned long long placed = 0ull;
+    for (int j = 0; j < np; ++j) {                     // wave-uniform
+        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)ckey, j);
+        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(ckey >> 32), j);
+        const unsigned long long kj = ((unsigned long long)hi << 32) | lo;
+        const bool e_above = ekey > kj;
+        const int rank = __popcll(__ballot(e_above)) + __popcll(__ballot(ckey > kj));
+        re += (is_e && !e_above) ? 1 : 0;              // keys are distinct
+        if (lane == rank) placed = kj;
+    }
+    if (is_e && re != lane && re < k) list[re] = e;
+    if (placed != 0ull && lane < k) list[lane] = cand_from_key(placed);
+}
+
 // One 512-column chunk of a block's K loop for NCT token tiles (a compile-time count: no
 // branch inside a chunk, so that LDS reads, matrix instructions and loads of neighbouring
 // steps interleave).  REFILL: a next chunk exists; its weight lines refill the ring slots as
-// they are consumed, and its hidden vectors are requested before those refills and written
-// to the other staging buffer after them.  Loads complete in order, so the wait for the
-// hidden vectors then covers only loads that this chunk has consumed anyway, never the
-// refills that should stay in flight.
-// With three or four token tiles the staging registers would not fit beside the ring, so
-// the slots then go in two rounds (the second requested after the first step pair's refills,
-// whose completion its wait then includes).
-template <int NCT>
-struct TileHidden {
-    static constexpr int kRounds = NCT > 2 ? 2 : 1;
-    static constexpr int kPerRound = 2 * NCT / kRounds;
-};
-struct TileStage {                                     // staging registers, kPerRound in use
-    uint4 r0, r1, r2, r3;
+// they are consumed.  Its hidden vectors are requested at the top of the chunk, before those
+// refills, and written to the other staging buffer only in the chunk's last step pair: loads
+// complete in order, and the requests are younger than all 16 weight lines of this chunk, so
+// an earlier write would wait for lines that are not needed yet (and were requested least
+// long ago), while by the last step pair all of them have been consumed anyway.
+struct TileStage {                                     // staging registers, 2 NCT in use
+    uint4 r0, r1, r2, r3, r4, r5, r6, r7;
 };
 
-template <int NCT, int ROUND>
+template <int NCT>
 __device__ __forceinline__ void tile_fetch_hidden(const TileParams& p, const int* tokslot, int n_t,
                                                   TileStage& hst, int c, int lane, int wave) {
-    constexpr int kN = TileHidden<NCT>::kPerRound;
+    constexpr int kN = 2 * NCT;
     const uint4* src = p.hidden + c * kChunkVecs + lane;
     // token of slot wave + 8 i (wave-uniform); slots past the group's tokens repeat its last
     auto tok = [&](int i) {
-        const int s = wave + (ROUND * kN + i) * kTileWaves;
+        const int s = wave + i * kTileWaves;
         return (size_t)uni(tokslot[s < n_t ? s : n_t - 1]);
     };
     if (kN > 0) hst.r0 = load_vec(src + tok(0) * p.n_vec);
     if (kN > 1) hst.r1 = load_vec(src + tok(1) * p.n_vec);
     if (kN > 2) hst.r2 = load_vec(src + tok(2) * p.n_vec);
     if (kN > 3) hst.r3 = load_vec(src + tok(3) * p.n_vec);
+    if (kN > 4) hst.r4 = load_vec(src + tok(4) * p.n_vec);
+    if (kN > 5) hst.r5 = load_vec(src + tok(5) * p.n_vec);
+    if (kN > 6) hst.r6 = load_vec(src + tok(6) * p.n_vec);
+    if (kN > 7) hst.r7 = load_vec(src + tok(7) * p.n_vec);
 }
-template <int NCT, int ROUND>
+template <int NCT>
 __device__ __forceinline__ void tile_store_hidden(const TileStage& hst, uint4* hbuf, int c, int lane,
                                                   int wave) {
-    constexpr int kN = TileHidden<NCT>::kPerRound;
-    uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs + (size_t)(wave + ROUND * kN * kTileWaves) * kHbStride + lane;
+    constexpr int kN = 2 * NCT;
+    uint4* dst = hbuf + (size_t)(c & 1) * kHbBufVecs + (size_t)wave * kHbStride + lane;
     if (kN > 0) store_vec(dst + 0 * kTileWaves * kHbStride, hst.r0);
     if (kN > 1) store_vec(dst + 1 * kTileWaves * kHbStride, hst.r1);
     if (kN > 2) store_vec(dst + 2 * kTileWaves * kHbStride, hst.r2);
     if (kN > 3) store_vec(dst + 3 * kTileWaves * kHbStride, hst.r3);
+    if (kN > 4) store_vec(dst + 4 * kTileWaves * kHbStride, hst.r4);
+    if (kN > 5) store_vec(dst + 5 * kTileWaves * kHbStride, hst.r5);
+    if (kN > 6) store_vec(dst + 6 * kTileWaves * kHbStride, hst.r6);
+    if (kN > 7) store_vec(dst + 7 * kTileWaves * kHbStride, hst.r7);
 }
 
 // The 128-byte line of step pair sp of chunk c in the lane's row at byte offset `row` of
@@ -181,14 +248,6 @@ __device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4
     const int r16 = lane & 15, q4 = lane >> 4;
     const int kq = wave % kTileSplit;
     const uint4* hb = hbuf + (size_t)(c & 1) * kHbBufVecs;
-    // the other buffer is free since the last barrier; only this chunk's own (older) weight
-    // loads are waited for along with the hidden vectors
-    if (REFILL && SP >= 1 && SP <= TileHidden<NCT>::kRounds) {
-        keep_memory_order();
-        tile_store_hidden<NCT, SP - 1>(hst, hbuf, c + 1, lane, wave);
-        if (SP < TileHidden<NCT>::kRounds) tile_fetch_hidden<NCT, SP < 2 ? SP : 0>(p, tokslot, n_t, hst, c + 1, lane, wave);
-        keep_memory_order();
-    }
     uint4 op[2][2];                                    // [row tile][step of the pair]
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -200,6 +259,10 @@ __device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4
         }
     }
     if (REFILL) keep_memory_order();
+    if (REFILL && SP == 3) {                           // the other buffer is free since the last barrier
+        tile_store_hidden<NCT>(hst, hbuf, c + 1, lane, wave);
+        keep_memory_order();
+    }
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
         const int off = (kq * 8 + 2 * SP + s2) * 4 + q4;
@@ -223,8 +286,8 @@ __device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a
     // (the scheduling barriers keep the compiler from sinking the loads to where their
     // registers are first needed, which would undo the ordering)
     if (REFILL) {
-        tile_fetch_hidden<NCT, 0>(p, tokslot, n_t, hst, c + 1, threadIdx.x & (kWave - 1),
-                                  __builtin_amdgcn_readfirstlane(threadIdx.x / kWave));
+        tile_fetch_hidden<NCT>(p, tokslot, n_t, hst, c + 1, threadIdx.x & (kWave - 1),
+                               __builtin_amdgcn_readfirstlane(threadIdx.x / kWave));
         keep_memory_order();
     }
     tile_step_pair<NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
@@ -245,12 +308,8 @@ __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRin
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     {
         TileStage hst;
-        tile_fetch_hidden<NCT, 0>(p, tokslot, n_t, hst, 0, lane, wave);
-        tile_store_hidden<NCT, 0>(hst, hbuf, 0, lane, wave);
-        if (TileHidden<NCT>::kRounds > 1) {
-            tile_fetch_hidden<NCT, TileHidden<NCT>::kRounds - 1>(p, tokslot, n_t, hst, 0, lane, wave);
-            tile_store_hidden<NCT, TileHidden<NCT>::kRounds - 1>(hst, hbuf, 0, lane, wave);
-        }
+        tile_fetch_hidden<NCT>(p, tokslot, n_t, hst, 0, lane, wave);
+        tile_store_hidden<NCT>(hst, hbuf, 0, lane, wave);
     }
     __syncthreads();
     for (int c = 0; c + 1 < p.n_chunks; ++c)
@@ -446,10 +505,9 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                 cand[hf].id = rowid[hf * kWave + lane];
                 if (cand[hf].id < 0) cand[hf] = sentinel();
             }
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf)
-                tile_merge_token(lists + (size_t)tok * k, k, lane, cand[hf],
-                                 reinterpret_cast<unsigned long long*>(my_slice));
+            tile_merge_pair(lists + (size_t)tok * k, k, lane, cand[0], cand[1],
+                            reinterpret_cast<unsigned long long*>(my_slice),
+                            reinterpret_cast<unsigned*>(my_slice) + 4 * kWave);
         }
         __syncthreads();
         b = nb;
