@@ -20,6 +20,8 @@ SeedSequence([seed, stream])):
   stream 3  perm      permutation of 0..V-1; group n owns
                              sorted(perm[n*v:(n+1)*v]) with v = V/G
                              (grouping="contiguous": perm is the identity)
+  stream 4  router_W1 [H,H]  N(0, 0.02^2) (the router's first projection, Eq. 7;
+                             drawn only by make_router_W1)
   stream 16+b  hidden batch b  [M,H]  N(0,1), optionally each row divided by
                              its RMS (float64 mean of squares), then rounded
 bf16 storage = round-to-nearest-even of the float32 value, kept as uint16.
@@ -130,6 +132,12 @@ def make_head(cfg: HeadConfig) -> Head:
                      * np.float32(cfg.bias_std)).astype(np.float32)
     offsets, rows = make_partition(cfg)
     return Head(cfg, lm_W, gate_W, gate_bias, offsets, rows)
+
+
+def make_router_W1(cfg: HeadConfig) -> np.ndarray:
+    """The router's square projection W1 [H,H] (row = output feature) in the config's storage type."""
+    w = _rng(cfg.seed, 4).standard_normal((cfg.H, cfg.H), dtype=np.float32) * np.float32(0.02)
+    return _store(w, cfg.dtype)
 
 
 def make_hidden(cfg: HeadConfig, M: int, batch: int = 0) -> np.ndarray:

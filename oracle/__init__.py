@@ -154,8 +154,63 @@ class GroupedResult:
     logp_router: np.ndarray  # [M,G]
 
 
+ACTIVATIONS = ("silu", "relu", "identity")
+
+
+def widen(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Stored values as float64 (bf16 = the upper 16 bits of a float32)."""
+    a = _storage(a, dtype)
+    if dtype == "f32":
+        return a.astype(np.float64)
+    return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """float64 -> float32 (nearest even) and, for bf16, on to the nearest bf16 (ties to
+    even) of that float32, which is the order in which a kernel that accumulates in
+    float32 rounds its result."""
+    f = np.ascontiguousarray(x, dtype=np.float64).astype(np.float32)
+    if dtype == "f32":
+        return f
+    b = f.view(np.uint32)
+    r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    r = np.where(np.isnan(f), np.uint32(0x7FC0), r)
+    return r.astype(np.uint16)
+
+
+def premix(hidden, W1, dtype: str, act: str = "silu"):
+    """The router's inner term of Eq. 7: u = act(W1 h) + h per token, W1 [d,d] with one
+    row per output feature.  The paper does not name act; "silu" is this build's reading.
+    Returns (u as float64, u rounded to the storage type)."""
+    if act not in ACTIVATIONS:
+        raise ValueError(f"unknown activation {act!r}")
+    h = widen(hidden, dtype)
+    w = widen(W1, dtype)
+    M, H = h.shape
+    assert w.shape == (H, H)
+    y = h @ w.T                                   # y[m,i] = sum_j W1[i,j] h[m,j]
+    if act == "silu":
+        a = y / (1.0 + np.exp(-y))
+    elif act == "relu":
+        a = np.maximum(y, 0.0)
+    else:
+        a = y
+    u = a + h
+    return u, round_to_storage(u, dtype)
+
+
 def grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g: int, k: int, dtype: str,
-            forced_sel=None) -> GroupedResult:
+            forced_sel=None, gate_hidden=None) -> GroupedResult:
+    """gate_hidden: the vector the router's W2 projection sees (Eq. 7: u = act(W1 h) + h)
+    when it differs from the vector the LM head sees; scores, selection and log p_router
+    then come from gate_hidden, logits from hidden."""
+    if gate_hidden is not None:
+        s = gate(gate_hidden, gate_W, gate_bias, dtype)
+        sel = rank_groups(s)[:, :g] if forced_sel is None else forced_sel
+        r = grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype, forced_sel=sel)
+        mx = s.max(axis=1, keepdims=True)
+        lse_s = mx + np.log(np.exp(s - mx).sum(axis=1, keepdims=True))
+        return GroupedResult(s, r.sel, r.topk_ids, r.topk_z, r.next_z, r.lse, s - lse_s)
     hidden = _storage(hidden, dtype)
     gate_W = _storage(gate_W, dtype)
     lm_W = _storage(lm_W, dtype)
@@ -213,13 +268,14 @@ class LogprobResult:
 
 
 def grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g: int, k: int, dtype: str,
-                    forced_sel=None) -> LogprobResult:
+                    forced_sel=None, gate_hidden=None) -> LogprobResult:
     """Eq. 8 as written: for every row x of a selected group n of token m,
     log p(x) = log p_router(n) + z[x] - lse_n, p_router the softmax of the gate scores over
     all G groups (Eq. 7), lse_n the log-sum-exp of the logits of group n's rows; the k largest
     log p(x) per token, best first, equal values by ascending id.  Gate, selection, logits,
     lse_n and log p_router come from the C oracle; the composition is the line below."""
-    base = grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype, forced_sel)
+    base = grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype, forced_sel,
+                   gate_hidden)
     offsets = np.asarray(offsets)
     rows = np.asarray(rows)
     M = np.asarray(hidden).shape[0]

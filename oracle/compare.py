@@ -31,6 +31,8 @@ from . import dense as oracle_dense
 from . import grouped as oracle_grouped
 from . import grouped_logprob as oracle_grouped_logprob
 from . import logits_rows, rank_groups
+from . import premix as oracle_premix
+from . import widen
 
 TOL = {"bf16": 2e-3, "f32": 1e-5}
 GATE_TOL = {"bf16": 1e-4, "f32": 1e-6}
@@ -38,6 +40,12 @@ GATE_TOL = {"bf16": 1e-4, "f32": 1e-6}
 # log-sum-exp moves by at most the largest error of its terms) and twice the gate's for the
 # router's log-softmax (score and its log-sum-exp).
 LOGP_TOL = {d: 2 * TOL[d] + 2 * GATE_TOL[d] for d in TOL}
+
+
+# The pre-mix u = act(W1 h) + h is stored in the head's storage type.  A kernel that
+# accumulates in float32 lands within PREMIX_ABS of the exact value before it rounds, and
+# rounding to storage moves it by at most half a unit in the last place of the result.
+PREMIX_ABS = {"bf16": 2e-5, "f32": 1e-5}
 
 
 @dataclass
@@ -89,7 +97,8 @@ def _check_topk_token(m, dev_ids, dev_z, ref_ids, ref_z, next_z, oz_dev, tol, re
 
 
 def check_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
-                  dev_ids, dev_logits, dev_sel, tol=None, gate_tol=None) -> Report:
+                  dev_ids, dev_logits, dev_sel, tol=None, gate_tol=None, gate_hidden=None) -> Report:
+    """gate_hidden: the router's input where it differs from the LM head's (Eq. 7)."""
     tol = TOL[dtype] if tol is None else tol
     gate_tol = GATE_TOL[dtype] if gate_tol is None else gate_tol
     rep = Report()
@@ -103,7 +112,8 @@ def check_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
     assert dev_ids.dtype == np.int32 and dev_sel.dtype == np.int32
     assert dev_logits.dtype == np.float32
 
-    ref = oracle_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype)
+    ref = oracle_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                         gate_hidden=gate_hidden)
     order = rank_groups(ref.s)
     need_forced = False
     for m in range(M):
@@ -121,7 +131,7 @@ def check_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
     if need_forced:
         rep.notes.append("oracle re-run with the device's groups forced")
         ref = oracle_grouped(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
-                             forced_sel=dev_sel)
+                             forced_sel=dev_sel, gate_hidden=gate_hidden)
 
     group_of = np.empty(V, dtype=np.int32)
     for n in range(G):
@@ -160,7 +170,8 @@ def check_dense(hidden, lm_W, k, dtype, dev_ids, dev_logits, tol=None, tokens=No
 
 
 def check_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
-                          dev_ids, dev_logp, dev_sel, tol=None, gate_tol=None) -> Report:
+                          dev_ids, dev_logp, dev_sel, tol=None, gate_tol=None,
+                          gate_hidden=None) -> Report:
     """Rules (i)-(v) and the exactness rule on log p(x) of Eq. 8 instead of the raw logit."""
     tol = LOGP_TOL[dtype] if tol is None else tol
     gate_tol = GATE_TOL[dtype] if gate_tol is None else gate_tol
@@ -174,7 +185,8 @@ def check_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, 
     assert dev_ids.shape == (M, k) and dev_logp.shape == (M, k) and dev_sel.shape == (M, g)
     assert dev_ids.dtype == np.int32 and dev_sel.dtype == np.int32 and dev_logp.dtype == np.float32
 
-    ref = oracle_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype)
+    ref = oracle_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
+                                 gate_hidden=gate_hidden)
     order = rank_groups(ref.s)
     need_forced = False
     for m in range(M):
@@ -192,7 +204,7 @@ def check_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, 
     if need_forced:
         rep.notes.append("oracle re-run with the device's groups forced")
         ref = oracle_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, dtype,
-                                     forced_sel=dev_sel)
+                                     forced_sel=dev_sel, gate_hidden=gate_hidden)
 
     group_of = np.empty(V, dtype=np.int32)
     for n in range(G):
@@ -210,3 +222,24 @@ def check_grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g, k, 
                           ref.next_logp[m], olp, tol, rep)
     return rep
 
+
+
+def check_premix(hidden, W1, dtype, act, dev_u) -> Report:
+    """|device u - oracle u| <= PREMIX_ABS + half a unit in the last place of the storage
+    type at that magnitude (bf16: 8 significand bits; f32: the absolute term only)."""
+    rep = Report()
+    u, _ = oracle_premix(hidden, W1, dtype, act)
+    dev = widen(np.asarray(dev_u), dtype)
+    assert dev.shape == u.shape
+    assert np.all(np.isfinite(dev)), "non-finite pre-mix output"
+    tol = np.full(u.shape, PREMIX_ABS[dtype])
+    if dtype == "bf16":
+        mag = np.maximum(np.abs(u), np.abs(dev))
+        exp = np.floor(np.log2(np.maximum(mag, 2.0 ** -126)))
+        tol = tol + 0.5 * 2.0 ** (exp - 7)
+    err = np.abs(dev - u)
+    bad = np.argwhere(err > tol)
+    assert bad.size == 0, f"pre-mix: {len(bad)} elements off, first {bad[0]}: {dev[tuple(bad[0])]} vs {u[tuple(bad[0])]}"
+    rep.tokens = u.shape[0]
+    rep.max_abs_err = float(err.max())
+    return rep

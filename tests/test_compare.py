@@ -144,3 +144,40 @@ def test_logprob_check_accepts_the_oracles_answer_and_rejects_the_logit_ranking(
     wrong = (r.topk_logp + 0.05).astype(np.float32)
     with pytest.raises(AssertionError):
         compare.check_grouped_logprob(*args, r.topk_ids, wrong, r.sel)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_premix_check_accepts_the_oracles_rounding_and_rejects_planted_mistakes(dtype):
+    from coral_inputs import make_router_W1
+    cfg = HeadConfig("premix_cmp", dtype, 64, 256, 4, 2, (3,), 4, 21, True)
+    h = make_hidden(cfg, 3, 0)
+    W1 = make_router_W1(cfg)
+    u, stored = oracle.premix(h, W1, dtype, "silu")
+    compare.check_premix(h, W1, dtype, "silu", stored)
+    # a different activation, a dropped residual, a transposed projection
+    for wrong in (oracle.premix(h, W1, dtype, "relu")[1],
+                  oracle.round_to_storage(u - oracle.widen(h, dtype), dtype),
+                  oracle.premix(h, np.ascontiguousarray(W1.T), dtype, "silu")[1]):
+        with pytest.raises(AssertionError):
+            compare.check_premix(h, W1, dtype, "silu", wrong)
+    if dtype == "bf16":                            # one unit in the last place is too much
+        off = stored.copy()
+        off[1, 5] += 1
+        with pytest.raises(AssertionError):
+            compare.check_premix(h, W1, dtype, "silu", off)
+
+
+def test_routed_check_follows_gate_hidden():
+    cfg = HeadConfig("routed_cmp", "f32", 64, 512, 8, 2, (3,), 4, 22, False)
+    head = make_head(cfg)
+    h = make_hidden(cfg, 3, 0)
+    gh = make_hidden(cfg, 3, 1)
+    args = (head.gate_W, None, head.lm_W, head.group_offsets, head.group_rows, cfg.g, cfg.k, cfg.dtype)
+    r = oracle.grouped(h, *args, gate_hidden=gh)
+    ok = (r.topk_ids, r.topk_z.astype(np.float32), r.sel)
+    compare.check_grouped(h, *args, *ok, gate_hidden=gh)
+    plain = oracle.grouped(h, *args)
+    assert not np.array_equal(plain.sel, r.sel)
+    with pytest.raises(AssertionError):            # the unrouted answer is not the routed one
+        compare.check_grouped(h, *args, plain.topk_ids, plain.topk_z.astype(np.float32), plain.sel,
+                              gate_hidden=gh)

@@ -441,3 +441,106 @@ def test_logprob_ranking_differs_from_logit_ranking_in_a_hand_worked_case():
     assert np.allclose(r.topk_logp[0], want, atol=1e-14)
     b = oracle.grouped(hidden, gate_W, None, lm_W, offsets, rows, 2, 3, "f32")
     assert b.topk_ids[0].tolist() == [0, 1, 2]
+
+
+# ---------------------------------------------------------------- router pre-mix (Eq. 7)
+def _f32(x):
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+@pytest.mark.parametrize("act", oracle.ACTIVATIONS)
+def test_premix_with_zero_projection_is_the_residual(act):
+    rng = np.random.default_rng(5)
+    h = _f32(rng.standard_normal((3, 16)))
+    u, stored = oracle.premix(h, _f32(np.zeros((16, 16))), "f32", act)
+    assert np.array_equal(u, h.astype(np.float64))          # act(0) = 0 for all three
+    assert np.array_equal(stored, h)
+
+
+def test_premix_single_weight_pins_orientation_and_residual():
+    # W1[i0, j0] = c only: output feature i0 reads input feature j0 (y = W1 h, not W1^T h)
+    H, i0, j0, c = 8, 2, 5, 0.5
+    W1 = np.zeros((H, H), np.float32)
+    W1[i0, j0] = c
+    h = _f32(np.arange(1, 2 * H + 1).reshape(2, H))
+    u, _ = oracle.premix(h, W1, "f32", "identity")
+    want = h.astype(np.float64).copy()
+    want[:, i0] += c * h[:, j0]
+    assert np.array_equal(u, want)
+
+
+def test_premix_activations_closed_forms():
+    # H = 1: u = act(w h) + h
+    one = _f32([[1.0]])
+    for w, h, act, want in [
+        (1.0, 1.0, "silu", 1.0 / (1.0 + np.exp(-1.0)) + 1.0),        # silu(1) = 0.73105857863...
+        (-1.0, 1.0, "silu", -1.0 / (1.0 + np.exp(1.0)) + 1.0),       # silu(-1) = -0.26894142137...
+        (2.0, -1.5, "relu", -1.5),                                   # relu(-3) = 0
+        (2.0, 1.5, "relu", 4.5),
+        (-3.0, 2.0, "identity", -4.0),
+    ]:
+        u, _ = oracle.premix(_f32([[h]]), _f32([[w]]), "f32", act)
+        assert abs(u[0, 0] - want) < 1e-15, (w, h, act)
+    assert abs(oracle.premix(one, one, "f32", "silu")[0][0, 0] - 1.7310585786300049) < 1e-15
+
+
+def test_premix_matches_an_independent_formulation():
+    from scipy.special import expit
+    rng = np.random.default_rng(11)
+    H, M = 48, 5
+    h = to_bits(rng.standard_normal((M, H)))
+    W1 = to_bits(rng.standard_normal((H, H)) * 0.2)
+    hf = oracle.widen(h, "bf16")
+    wf = oracle.widen(W1, "bf16")
+    u, stored = oracle.premix(h, W1, "bf16", "silu")
+    want = np.empty((M, H))
+    for m in range(M):
+        for i in range(H):
+            y = float(np.dot(wf[i], hf[m]))
+            want[m, i] = y * expit(y) + hf[m, i]
+    assert np.allclose(u, want, rtol=0, atol=1e-13)
+    # storage rounding: nearest bf16 of the float32 value, checked against torch
+    import torch
+    t = torch.from_numpy(u.astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(stored, t)
+
+
+def to_bits(x):
+    from coral_inputs import to_bf16_bits
+    return to_bf16_bits(np.asarray(x, dtype=np.float32))
+
+
+def test_routed_head_selects_by_gate_hidden_and_scores_by_hidden():
+    # two groups of two rows; W2 reads feature 0 for group 0 and feature 1 for group 1
+    lm_W = _f32([[1, 0, 0], [0, 1, 0], [0, 0, 1], [1, 1, 1]])
+    offsets = np.array([0, 2, 4], np.int32)
+    rows = np.array([0, 1, 2, 3], np.int32)
+    gate_W = _f32([[1, 0, 0], [0, 1, 0]])
+    hidden = _f32([[3, 1, 2]])          # by itself: group 0 (3 > 1)
+    gate_hidden = _f32([[0, 5, 0]])     # the router sees this: group 1
+    plain = oracle.grouped(hidden, gate_W, None, lm_W, offsets, rows, 1, 2, "f32")
+    assert plain.sel.tolist() == [[0]] and plain.topk_ids.tolist() == [[0, 1]]
+    routed = oracle.grouped(hidden, gate_W, None, lm_W, offsets, rows, 1, 2, "f32",
+                            gate_hidden=gate_hidden)
+    assert routed.sel.tolist() == [[1]]
+    assert routed.topk_ids.tolist() == [[3, 2]]                  # rows of group 1 only
+    assert routed.topk_z.tolist() == [[6.0, 2.0]]                # logits from hidden
+    assert routed.s.tolist() == [[0.0, 5.0]]                     # scores from gate_hidden
+    lp = oracle.grouped_logprob(hidden, gate_W, None, lm_W, offsets, rows, 1, 2, "f32",
+                                gate_hidden=gate_hidden)
+    log_router = 5.0 - np.log(np.exp(0.0) + np.exp(5.0))
+    lse = np.log(np.exp(6.0) + np.exp(2.0))
+    assert np.allclose(lp.topk_logp, [[log_router + 6.0 - lse, log_router + 2.0 - lse]], atol=1e-14)
+
+
+def test_routed_head_with_the_same_vector_is_the_plain_head():
+    cfg = CONFIGS["tiny_f32"]
+    head = make_head(cfg)
+    h = make_hidden(cfg, 3, 1)
+    a = oracle.grouped(h, head.gate_W, None, head.lm_W, head.group_offsets, head.group_rows,
+                       cfg.g, cfg.k, cfg.dtype)
+    b = oracle.grouped(h, head.gate_W, None, head.lm_W, head.group_offsets, head.group_rows,
+                       cfg.g, cfg.k, cfg.dtype, gate_hidden=h)
+    assert np.array_equal(a.sel, b.sel) and np.array_equal(a.topk_ids, b.topk_ids)
+    assert np.array_equal(a.topk_z, b.topk_z) and np.array_equal(a.s, b.s)
+    assert np.allclose(a.logp_router, b.logp_router, atol=1e-14)
