@@ -170,6 +170,38 @@ class Bench:
         total_ms = self._timed(call, steps, warmup, 8, False)
         return total_ms * 1e3 / steps
 
+    def time_routed(self, M, steps, warmup, R=24):
+        """The paper's full router in front of the head (Eq. 7): one step = the pre-mix
+        u = act(W1 h) + h, then the grouped head with the router reading u.  Also times the
+        pre-mix alone over a cycle of W1 copies larger than the last-level cache."""
+        torch, coral, cfg = self.torch, self.coral, self.cfg
+        from coral_inputs import make_hidden, make_router_W1
+        W1 = coral.device_tensor(make_router_W1(cfg), cfg.dtype)
+        hs = [coral.device_tensor(make_hidden(cfg, M, b), cfg.dtype) for b in range(R)]
+        us = [torch.empty_like(h) for h in hs]
+        ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt)
+        ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+        z = torch.empty((M, cfg.k), dtype=torch.float32, device="cuda")
+        sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+
+        def step(i, events=None):
+            coral.coral_router_premix(hs[i % R], W1, "silu", out=us[i % R])
+            coral.coral_lmhead_grouped(hs[i % R], self.gate_W, self.bias, self.lm_W, self.gi, cfg.g,
+                                       cfg.k, topk_ids=ids, topk_logits=z, sel_groups=sel,
+                                       workspace=ws, gate_hidden=us[i % R])
+
+        step_us = self._timed(step, steps, warmup, R, False) * 1e3 / steps
+        w1_bytes = W1.numel() * W1.element_size()
+        copies = [W1] + [W1.clone() for _ in range(int(1.5 * LLC_BYTES // w1_bytes))]
+
+        def premix(i, events=None):
+            coral.coral_router_premix(hs[i % R], copies[i % len(copies)], "silu", out=us[i % R])
+
+        R2 = len(copies) * (R // len(copies) + 1)
+        premix_us = self._timed(premix, max(steps, R2), warmup, R2, False) * 1e3 / max(steps, R2)
+        bytes_premix = w1_bytes + 2 * M * cfg.H * weight_bytes_per_elt(cfg.dtype)
+        return dict(step_us=step_us, premix_us=premix_us, premix_bytes=bytes_premix)
+
     def time_dense(self, M, steps, warmup, eager=False, event_steps=60):
         torch, coral, cfg = self.torch, self.coral, self.cfg
         from coral_inputs import make_hidden
@@ -361,6 +393,14 @@ def main():
                       "avg_activated_groups": r["U"],
                       "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
                       "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        r = bench.time_routed(a.M, n, min(a.warmup, 20))
+        cases.append({"path": "router pre-mix u = silu(W1 h) + h alone (Eq. 7; k_premix, W1 copies "
+                              "cycled past the last-level cache; launch gap included)",
+                      "M": a.M, "us_per_step": r["premix_us"],
+                      "GBps_whole_step": r["premix_bytes"] / r["premix_us"] / 1e3,
+                      "frac_whole_step": r["premix_bytes"] / r["premix_us"] / 1e3 / HBM_PEAK_GBPS})
+        cases.append({"path": "pre-mix, then grouped head with the router reading u (two calls)",
+                      "M": a.M, "us_per_step": r["step_us"]})
         rep_M = min(cfg.Ms)
         cases.append({"path": "grouped, same input every call (cache-assisted)", "M": rep_M,
                       "us_per_step": bench.time_repeat(rep_M, max(48, n), 8)})

@@ -175,6 +175,43 @@ coral_status coral_lmhead_grouped_logprob(const void *hidden, const void *gate_W
                                           size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The router's inner term (section 3.3, Eq. 7): u[m,:] = act(W1 hidden[m,:]) + hidden[m,:]
+ * for every token, W1 [H,H] row-major with one row per output feature
+ * (y[i] = sum_j W1[i,j] hidden[m,j]).  The paper does not name act; CORAL_ACT_SILU is this
+ * library's default reading, the others are there to compare.  Sums in fp32; u is written in
+ * the storage type dt (bf16: round to nearest even).
+ *   hidden [device] [M,H]; W1 [device] [H,H]; u_out [device] out [M,H], must not overlap
+ *   hidden.  All 16-byte aligned; H a multiple of 8 (bf16) / 4 (fp32), H * element size
+ *   at most 160 KB.  Needs no workspace.
+ */
+typedef enum {
+    CORAL_ACT_SILU = 0,
+    CORAL_ACT_RELU = 1,
+    CORAL_ACT_IDENTITY = 2
+} coral_activation;
+
+coral_status coral_router_premix(const void *hidden, const void *W1, int M, int H,
+                                 coral_dtype dt, coral_activation act, void *u_out,
+                                 void *hip_stream);
+
+/*
+ * Grouped LM head whose router sees another vector than the LM head (section 3.3, Eq. 7:
+ * p_router = Softmax(W2 (act(W1 h) + h)), while the logits of Eq. 8's p_group come from h):
+ *   s[m,n] = sum_j gate_W[n,j] * gate_hidden[m,j] (+ gate_bias[n]),  z from hidden.
+ * gate_hidden [device] [M,H] is typically coral_router_premix's output; NULL means hidden.
+ * logprob = 0: output as coral_lmhead_grouped (k best logits); logprob != 0: output as
+ * coral_lmhead_grouped_logprob (k best log p(x), p_router from the scores above).
+ * All other arguments, limits and errors as for those two calls.
+ */
+coral_status coral_lmhead_grouped_routed(const void *hidden, const void *gate_hidden,
+                                         const void *gate_W, const float *gate_bias,
+                                         const void *lm_W, const coral_group_index *gi,
+                                         int M, int H, int V, int g, int k, coral_dtype dt,
+                                         int logprob, int32_t *topk_ids, float *topk_out,
+                                         int32_t *sel_groups, void *workspace,
+                                         size_t workspace_bytes, void *hip_stream);
+
+/*
  * Dense LM head: z[m,r] for every r = 0..V-1, then the k best per token with the
  * same ordering rules (the no-router baseline of Table 4; the head whose latency
  * the appendix paragraph "Backends" measures).  Arguments as above; k <= V.

@@ -69,6 +69,13 @@ def _load():
     L.coral_lmhead_grouped_logprob_profiled.argtypes = L.coral_lmhead_grouped_profiled.argtypes
     L.coral_lmhead_dense_profiled.restype = c.c_int
     L.coral_lmhead_dense_profiled.argtypes = L.coral_lmhead_dense.argtypes + [c.c_void_p] * 2
+    L.coral_router_premix.restype = c.c_int
+    L.coral_router_premix.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int,
+                                      c.c_void_p, c.c_void_p]
+    L.coral_lmhead_grouped_routed.restype = c.c_int
+    L.coral_lmhead_grouped_routed.argtypes = [c.c_void_p] * 5 + [c.POINTER(_GroupIndexStruct)] + \
+                                             [c.c_int] * 7 + [c.c_void_p] * 4 + \
+                                             [c.c_size_t, c.c_void_p]
     return L
 
 
@@ -185,10 +192,11 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
                          topk_logits: Optional[torch.Tensor] = None,
                          sel_groups: Optional[torch.Tensor] = None,
                          workspace: Optional[torch.Tensor] = None, stream=None, events=None,
-                         logprob: bool = False
+                         logprob: bool = False, gate_hidden: Optional[torch.Tensor] = None
                          ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry.
-    logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x))."""
+    logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x)).
+    gate_hidden: call coral_lmhead_grouped_routed (the router sees this [M,H] tensor)."""
     dt = _dtype_code(hidden)
     if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
         raise TypeError("hidden, gate_W and lm_W must share one dtype")
@@ -217,13 +225,43 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
             _dev_ptr(topk_logits, "topk_logits", torch.float32),
             _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    if events is None:
+    if gate_hidden is not None:
+        if events is not None:
+            raise ValueError("the routed entry point has no measurement variant")
+        if gate_hidden.dtype != hidden.dtype or gate_hidden.shape != hidden.shape:
+            raise ValueError("gate_hidden must match hidden in dtype and shape")
+        st = _L.coral_lmhead_grouped_routed(args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
+                                            1 if logprob else 0, *args[11:])
+    elif events is None:
         st = (_L.coral_lmhead_grouped_logprob if logprob else _L.coral_lmhead_grouped)(*args)
     else:
         fn = _L.coral_lmhead_grouped_logprob_profiled if logprob else _L.coral_lmhead_grouped_profiled
         st = fn(*args, events[0], events[1])
     _raise(st)
     return topk_ids, topk_logits, sel_groups
+
+
+ACTIVATIONS = {"silu": 0, "relu": 1, "identity": 2}
+
+
+def coral_router_premix(hidden: torch.Tensor, W1: torch.Tensor, act: str = "silu",
+                        out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """coral_router_premix of the C ABI: u = act(W1 hidden) + hidden, [M,H] in hidden's dtype."""
+    dt = _dtype_code(hidden)
+    if W1.dtype != hidden.dtype:
+        raise TypeError("hidden and W1 must share one dtype")
+    if hidden.dim() != 2 or W1.shape != (hidden.shape[1], hidden.shape[1]):
+        raise ValueError("W1 must be [H,H]")
+    if act not in ACTIVATIONS:
+        raise ValueError(f"unknown activation {act!r}")
+    M, H = hidden.shape
+    if out is None:
+        out = torch.empty_like(hidden)
+    if out.shape != hidden.shape or out.dtype != hidden.dtype:
+        raise ValueError("out must match hidden")
+    _raise(_L.coral_router_premix(_dev_ptr(hidden, "hidden"), _dev_ptr(W1, "W1"), M, H, dt,
+                                  ACTIVATIONS[act], _dev_ptr(out, "out"), _stream_ptr(stream)))
+    return out
 
 
 def coral_lmhead_grouped_logprob(hidden, gate_W, gate_bias, lm_W, gi, g, k, **kw):

@@ -25,6 +25,7 @@
 #include "coral_lmhead.h"
 #include "device_utils.h"
 #include "fused_path.h"
+#include "router_premix.h"
 #include "staged_path.h"
 #include "tile_path.h"
 
@@ -126,7 +127,8 @@ int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype 
 }
 
 // Enqueues the single-launch path (the caller has checked with plan_path that it fits).
-coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, const float* gate_bias,
+coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidden, const void* gate_W,
+               const float* gate_bias,
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
                char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after) {
@@ -141,6 +143,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, co
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
     FusedParams p = {};
     p.hidden = static_cast<const uint4*>(hidden);
+    p.gate_hidden = static_cast<const uint4*>(gate_hidden);
     p.gate_W = static_cast<const uint4*>(gate_W);
     p.bias = gate_bias;
     p.lm_W = static_cast<const uint4*>(lm_W);
@@ -154,12 +157,17 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_W, co
     p.M = M; p.V = V; p.G = G; p.g = g; p.k = k;
     p.n_vec = n_vec; p.jp = jp;
     typedef void (*fused_fn)(FusedParams);
+    const bool routed = !dense && gate_hidden != hidden;
     const fused_fn fn =
-        dense ? (bf16 ? k_fused<true, true, kGateVector> : k_fused<false, true, kGateVector>)
-              : (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines>
-                         : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads>
-                                                  : k_fused<true, false, kGateVector>)
-                      : k_fused<false, false, kGateVector>);
+        dense    ? (bf16 ? k_fused<true, true, kGateVector> : k_fused<false, true, kGateVector>)
+        : routed ? (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines, true>
+                            : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads, true>
+                                                     : k_fused<true, false, kGateVector, true>)
+                         : k_fused<false, false, kGateVector, true>)
+                 : (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines>
+                            : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads>
+                                                     : k_fused<true, false, kGateVector>)
+                         : k_fused<false, false, kGateVector>);
     if (F.total > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess)
@@ -322,8 +330,8 @@ extern "C" coral_status coral_lmhead_workspace_init(void* workspace, size_t work
 
 namespace {
 
-coral_status grouped_impl(const void* hidden, const void* gate_W, const float* gate_bias,
-                          const void* lm_W, const coral_group_index* gi, int M, int H, int V,
+coral_status grouped_impl(const void* hidden, const void* gate_hidden, const void* gate_W,
+                          const float* gate_bias, const void* lm_W, const coral_group_index* gi, int M, int H, int V,
                           int g, int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits,
                           int32_t* sel_groups, void* workspace, size_t workspace_bytes,
                           void* hip_stream, void* ev_before, void* ev_after, bool logprob) {
@@ -334,7 +342,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     const int G = gi->G;
     if (G < 1 || g < 1 || g > G) return CORAL_ERR_SHAPE;
     if (G > kMaxG) return CORAL_ERR_UNSUPPORTED;
-    if ((uintptr_t)gate_W & 15u) return CORAL_ERR_UNSUPPORTED;
+    if (!gate_hidden) gate_hidden = hidden;      // the router sees what the LM head sees
+    if (((uintptr_t)gate_W | (uintptr_t)gate_hidden) & 15u) return CORAL_ERR_UNSUPPORTED;
     const int32_t* off = gi->group_offsets_host;
     if (off[0] != 0 || off[G] != V) return CORAL_ERR_GROUP_INDEX;
     int max_rows = 0;
@@ -367,7 +376,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     PathPlan plan = plan_path(false, M, H, V, G, g, k, dt);
     if (logprob) plan.path = 0;
     if (plan.path == 1)
-        return launch_fused(false, hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
+        return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
                             topk_logits, sel_groups, ws, L, stream, ev_before, ev_after);
     float* s = reinterpret_cast<float*>(ws + L.s);
     int32_t* sel = sel_groups ? sel_groups : reinterpret_cast<int32_t*>(ws + L.sel);
@@ -380,10 +389,11 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
     const bool bf16 = dt == CORAL_BF16;
     const int n_vec = H / (bf16 ? 8 : 4);
     const uint4* hid = static_cast<const uint4*>(hidden);
+    const uint4* ghid = static_cast<const uint4*>(gate_hidden);
     const uint4* gw = static_cast<const uint4*>(gate_W);
     if (plan.path == 2) {
         GateSelParams q = {};
-        q.hidden = hid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
+        q.hidden = ghid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
         q.group_mask = mask; q.union_list = union_list; q.n_union = n_union;
         q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
@@ -395,10 +405,10 @@ coral_status grouped_impl(const void* hidden, const void* gate_W, const float* g
                             ev_after);
     }
     if (bf16)
-        hipLaunchKernelGGL(k_gate<true>, dim3(G), dim3(kBlock), 0, stream, hid, gw, gate_bias, M, G,
+        hipLaunchKernelGGL(k_gate<true>, dim3(G), dim3(kBlock), 0, stream, ghid, gw, gate_bias, M, G,
                            n_vec, s);
     else
-        hipLaunchKernelGGL(k_gate<false>, dim3(G), dim3(kBlock), 0, stream, hid, gw, gate_bias, M, G,
+        hipLaunchKernelGGL(k_gate<false>, dim3(G), dim3(kBlock), 0, stream, ghid, gw, gate_bias, M, G,
                            n_vec, s);
     if ((st = launch_status()) != CORAL_OK) return st;
     float* logp_sel = logprob ? reinterpret_cast<float*>(ws + L.logp_sel) : nullptr;
@@ -469,7 +479,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream,
                             ev_before, ev_after);
     if (plan.path == 1)
-        return launch_fused(true, hidden, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
+        return launch_fused(true, hidden, nullptr, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
                             topk_logits, nullptr, ws, L, stream, ev_before, ev_after);
     const bool bf16 = dt == CORAL_BF16;
     LogitsParams p = {};
@@ -513,9 +523,77 @@ extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gat
                                              float* topk_logits, int32_t* sel_groups,
                                              void* workspace, size_t workspace_bytes,
                                              void* hip_stream) {
-    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+    return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
                         nullptr, false);
+}
+
+extern "C" coral_status coral_lmhead_grouped_routed(
+    const void* hidden, const void* gate_hidden, const void* gate_W, const float* gate_bias,
+    const void* lm_W, const coral_group_index* gi, int M, int H, int V, int g, int k,
+    coral_dtype dt, int logprob, int32_t* topk_ids, float* topk_out, int32_t* sel_groups,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return grouped_impl(hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_out, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
+                        nullptr, logprob != 0);
+}
+
+extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, int M, int H,
+                                            coral_dtype dt, coral_activation act, void* u_out,
+                                            void* hip_stream) {
+    if (!hidden || !W1 || !u_out) return CORAL_ERR_NULL;
+    if (dt != CORAL_F32 && dt != CORAL_BF16) return CORAL_ERR_SHAPE;
+    if (act != CORAL_ACT_SILU && act != CORAL_ACT_RELU && act != CORAL_ACT_IDENTITY) return CORAL_ERR_SHAPE;
+    if (M < 1 || H < 1) return CORAL_ERR_SHAPE;
+    const bool bf16 = dt == CORAL_BF16;
+    if (H % (bf16 ? 8 : 4) != 0) return CORAL_ERR_UNSUPPORTED;
+    if (((uintptr_t)hidden | (uintptr_t)W1 | (uintptr_t)u_out) & 15u) return CORAL_ERR_UNSUPPORTED;
+    const size_t row_bytes = (size_t)H * (bf16 ? 2 : 4);
+    if (row_bytes > (size_t)kLdsLimit) return CORAL_ERR_UNSUPPORTED;
+    {   // u_out must not overlap hidden: workgroups read hidden rows that others write
+        const uintptr_t a = (uintptr_t)hidden, b = (uintptr_t)u_out;
+        const size_t bytes = (size_t)M * row_bytes;
+        if (a < b + bytes && b < a + bytes) return CORAL_ERR_UNSUPPORTED;
+    }
+    PremixParams p = {};
+    p.hidden = static_cast<const uint4*>(hidden);
+    p.W1 = static_cast<const uint4*>(W1);
+    p.out = u_out;
+    p.M = M; p.H = H; p.act = (int)act;
+    p.n_vec = H / (bf16 ? 8 : 4);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (bf16 && H % 64 == 0 && M >= 4) {                      // matrix cores
+        int tok = M < kPremixTileTok ? M : kPremixTileTok;
+        while (tok > 4 && premix_mfma_lds_bytes(tok, p.n_vec) > (size_t)kLdsLimit) --tok;
+        const size_t lds = premix_mfma_lds_bytes(tok, p.n_vec);
+        if (lds <= (size_t)kLdsLimit) {
+            p.tok_per_wg = tok;
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_premix_mfma),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+                return CORAL_ERR_HIP;
+            hipLaunchKernelGGL(k_premix_mfma, dim3(H / 16, (M + tok - 1) / tok), dim3(kBlock), lds,
+                               stream, p);
+            return launch_status();
+        }
+    }
+    int tok = (int)((size_t)kLdsLimit / 2 / row_bytes);       // two workgroups per compute unit
+    if (tok < 1) tok = 1;
+    if (tok > kPremixTok) tok = kPremixTok;
+    if (tok > M) tok = M;
+    p.tok_per_wg = tok;
+    const int lds = (int)((size_t)tok * row_bytes);
+    const int pairs = (H + 1) / 2;
+    int gx = (pairs + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (gx > 2 * kMaxWorkgroups) gx = 2 * kMaxWorkgroups;
+    const dim3 grid(gx, (M + tok - 1) / tok);
+    typedef void (*premix_fn)(PremixParams);
+    const premix_fn fn = bf16 ? k_premix<true> : k_premix<false>;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return CORAL_ERR_HIP;
+    hipLaunchKernelGGL(fn, grid, dim3(kBlock), lds, stream, p);
+    return launch_status();
 }
 
 extern "C" coral_status coral_lmhead_grouped_logprob(
@@ -523,7 +601,7 @@ extern "C" coral_status coral_lmhead_grouped_logprob(
     const coral_group_index* gi, int M, int H, int V, int g, int k, coral_dtype dt,
     int32_t* topk_ids, float* topk_logprob, int32_t* sel_groups, void* workspace,
     size_t workspace_bytes, void* hip_stream) {
-    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+    return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logprob, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
                         nullptr, true);
 }
@@ -534,7 +612,7 @@ extern "C" coral_status coral_lmhead_grouped_logprob_profiled(
     int32_t* topk_ids, float* topk_logprob, int32_t* sel_groups, void* workspace,
     size_t workspace_bytes, void* hip_stream, void* ev_before, void* ev_after) {
     if (!ev_before || !ev_after) return CORAL_ERR_NULL;
-    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+    return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logprob, sel_groups, workspace, workspace_bytes, hip_stream, ev_before,
                         ev_after, true);
 }
@@ -545,7 +623,7 @@ extern "C" coral_status coral_lmhead_grouped_profiled(
     int32_t* topk_ids, float* topk_logits, int32_t* sel_groups, void* workspace,
     size_t workspace_bytes, void* hip_stream, void* ev_before, void* ev_after) {
     if (!ev_before || !ev_after) return CORAL_ERR_NULL;
-    return grouped_impl(hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+    return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, ev_before,
                         ev_after, false);
 }

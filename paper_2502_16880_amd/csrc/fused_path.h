@@ -45,7 +45,8 @@ struct WaveScratch {
 constexpr int kMergeAreaBytes = sizeof(WaveScratch);
 
 struct FusedParams {
-    const uint4* hidden;        // [M, n_vec]
+    const uint4* hidden;        // [M, n_vec]   what the LM head sees
+    const uint4* gate_hidden;   // [M, n_vec]   what the router sees (grouped; may equal hidden)
     const uint4* gate_W;        // [G, n_vec]   (grouped)
     const float* bias;          // [G] or null  (grouped)
     const uint4* lm_W;          // [V, n_vec]
@@ -416,7 +417,7 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
     }
 }
 
-template <bool BF16, bool DENSE, int GATE>
+template <bool BF16, bool DENSE, int GATE, bool ROUTED = false>
 __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
@@ -445,17 +446,22 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     // wait for the hidden vectors does not wait for the gate rows behind them)
     constexpr int kHU = 4;
     const int row_vecs = p.jp * kWave;                     // <= 512: at least 2 rows a pass
-    const int h_mm = threadIdx.x / row_vecs;
-    const int h_vec = threadIdx.x - h_mm * row_vecs;
+    int h_mm = threadIdx.x / row_vecs;
+    int h_vec = threadIdx.x - h_mm * row_vecs;
     const int rows_per_pass = kFusedBlock / row_vecs;
     uint4 htmp[kHU];
+    // The router may see another vector than the LM head (Eq. 7: W2 is applied to
+    // act(W1 h) + h): then the gate's vectors are staged first and the LM head's replace
+    // them after the gate, their loads in flight during the selection (ROUTED, compiled
+    // apart: the kernel has no registers to spare).
+    const uint4* h_src = ROUTED ? p.gate_hidden : p.hidden;
     auto hidden_request = [&](int m0) {
 #pragma unroll
         for (int u = 0; u < kHU; ++u) {
             const int m = m0 + u * rows_per_pass + h_mm;
             htmp[u] = make_uint4(0, 0, 0, 0);
             if (h_mm < rows_per_pass && m < M && h_vec < p.n_vec)
-                htmp[u] = p.hidden[(size_t)m * p.n_vec + h_vec];
+                htmp[u] = h_src[(size_t)m * p.n_vec + h_vec];
         }
     };
     auto hidden_commit = [&](int m0) {                     // then the passes that remain
@@ -650,6 +656,16 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             }
             __syncthreads();
         }
+        if (ROUTED) {                                  // the gate's last read of hs is behind a barrier
+            h_src = p.hidden;
+            // (recomputed behind a compiler barrier: the first staging's addresses would
+            // otherwise be kept through the gate, where there are no registers to spare)
+            int tid = threadIdx.x;
+            asm volatile("" : "+v"(tid));
+            h_mm = tid / row_vecs;
+            h_vec = tid - h_mm * row_vecs;
+            hidden_request(0);
+        }
         // ---- 2b. per-token top-g by rank counting: group n of token m is selected iff
         // fewer than g groups beat it (larger score first, then lower group id); its rank
         // is its position in the selection
@@ -713,6 +729,10 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 uprefix[count] = carry;
                 flags[0] = count;
             }
+        }
+        if (ROUTED) {
+            hidden_commit(0);
+            hidden_rest();
         }
         __syncthreads();
         total_batches = uni(uprefix[uni(flags[0])]);

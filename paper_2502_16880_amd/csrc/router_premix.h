@@ -1,0 +1,197 @@
+// Router pre-mix (section 3.3, Eq. 7): the router's second projection W2 is applied to
+// u = act(W1 h) + h, with W1 [d,d] one row per output feature.  A d x d matrix read once per
+// step for all tokens: HBM-bound like the LM head itself (33.6 MB at d = 4096 in bf16).
+// One wave computes two output features at a time for up to eight tokens whose hidden
+// vectors sit in LDS: both weight rows are requested whole (non-temporal, 16 KB per wave in
+// flight at d = 4096), dotted with every token's vector (fp32 accumulation), and lane t
+// finishes token t: activation, residual, rounding to the storage type.
+//
+// From four tokens on the vector units would bound the kernel (a bf16 dot instruction per two
+// products of every token), so the contraction goes to the matrix cores: a workgroup owns 16
+// output features, its four waves split their columns, and each wave holds 16 whole 128-byte
+// lines of each of the 16 rows (32 loads, 32 KB) in registers at once.
+#pragma once
+#include "device_utils.h"
+#include "fused_path.h"
+
+namespace {
+
+constexpr int kPremixTok = 8;                    // tokens of a workgroup (LDS residents)
+constexpr int kPremixSegs = 8;                   // 1 KB segments of a row requested together
+
+struct PremixParams {
+    const uint4* hidden;        // [M, n_vec]
+    const uint4* W1;            // [H, n_vec]
+    void* out;                  // [M, H] storage type
+    int M, H, n_vec, act, tok_per_wg;
+};
+
+// float -> bf16 bits, round to nearest, ties to even; NaN stays NaN.
+__device__ __forceinline__ unsigned short bf16_bits_rne(float x) {
+    const unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+__device__ __forceinline__ float premix_act(float y, int act) {
+    if (act == CORAL_ACT_SILU) return y / (1.0f + expf(-y));
+    if (act == CORAL_ACT_RELU) return y > 0.f ? y : 0.f;
+    return y;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
+    extern __shared__ uint4 smem[];                                // [tb][n_vec]
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int m0 = blockIdx.y * p.tok_per_wg;
+    const int tb = p.M - m0 < p.tok_per_wg ? p.M - m0 : p.tok_per_wg;
+    for (int i = threadIdx.x; i < tb * p.n_vec; i += kBlock)      // consecutive rows: one block
+        smem[i] = p.hidden[(size_t)m0 * p.n_vec + i];
+    __syncthreads();
+    const int n_waves = gridDim.x * kWavesPerBlock;
+    for (int r0 = (blockIdx.x * kWavesPerBlock + wave) * 2; r0 < p.H; r0 += n_waves * 2) {   // wave-uniform
+        const int r1 = r0 + 1 < p.H ? r0 + 1 : r0;
+        float a0[kPremixTok], a1[kPremixTok];
+#pragma unroll
+        for (int t = 0; t < kPremixTok; ++t) a0[t] = a1[t] = 0.f;
+        const uint4* w0p = p.W1 + (size_t)r0 * p.n_vec;
+        const uint4* w1p = p.W1 + (size_t)r1 * p.n_vec;
+        for (int base = 0; base < p.n_vec; base += kWave * kPremixSegs) {
+            uint4 w0[kPremixSegs], w1[kPremixSegs];
+#pragma unroll
+            for (int j = 0; j < kPremixSegs; ++j) {
+                const int vec = base + j * kWave + lane;
+                w0[j] = make_uint4(0, 0, 0, 0);
+                w1[j] = make_uint4(0, 0, 0, 0);
+                if (vec < p.n_vec) {
+                    w0[j] = load_stream(w0p + vec);
+                    w1[j] = load_stream(w1p + vec);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kPremixSegs; ++j) {
+                const int vec = base + j * kWave + lane;
+                const int hv = vec < p.n_vec ? vec : 0;            // the weights there are zero
+#pragma unroll
+                for (int t = 0; t < kPremixTok; ++t)
+                    if (t < tb) {                                  // uniform
+                        const uint4 h = smem[t * p.n_vec + hv];
+                        a0[t] = dot_vec<BF16>(w0[j], h, a0[t]);
+                        a1[t] = dot_vec<BF16>(w1[j], h, a1[t]);
+                    }
+            }
+        }
+        float y0 = 0.f, y1 = 0.f;                                  // lane t keeps token t's sums
+#pragma unroll
+        for (int t = 0; t < kPremixTok; ++t)
+            if (t < tb) {
+                const float s0 = wave_sum(a0[t]), s1 = wave_sum(a1[t]);
+                if (lane == t) {
+                    y0 = s0;
+                    y1 = s1;
+                }
+            }
+        if (lane < tb) {
+            const size_t o = (size_t)(m0 + lane) * p.H;
+            if (BF16) {
+                const unsigned short* hs = reinterpret_cast<const unsigned short*>(smem) + (size_t)lane * p.H;
+                unsigned short* out = static_cast<unsigned short*>(p.out);
+                out[o + r0] = bf16_bits_rne(premix_act(y0, p.act) + __uint_as_float((unsigned)hs[r0] << 16));
+                if (r1 != r0)
+                    out[o + r1] = bf16_bits_rne(premix_act(y1, p.act) + __uint_as_float((unsigned)hs[r1] << 16));
+            } else {
+                const float* hs = reinterpret_cast<const float*>(smem) + (size_t)lane * p.H;
+                float* out = static_cast<float*>(p.out);
+                out[o + r0] = premix_act(y0, p.act) + hs[r0];
+                if (r1 != r0) out[o + r1] = premix_act(y1, p.act) + hs[r1];
+            }
+        }
+    }
+}
+
+constexpr int kPremixTileTok = 16;               // tokens of a workgroup on the matrix cores
+constexpr int kPremixLines = 16;                 // 128-byte lines of a row a wave holds at once
+
+__host__ __device__ inline size_t premix_mfma_lds_bytes(int tok, int n_vec) {
+    return ((size_t)tok * (n_vec + 1) + (size_t)kWavesPerBlock * kLinePairSlots) * sizeof(uint4) +
+           (size_t)kWavesPerBlock * 256 * sizeof(float);
+}
+
+// bf16, H a multiple of 64 (whole 128-byte lines).  Tile of 16 output features x 16 tokens:
+// A operand = rows of W1, B operand = hidden vectors from LDS (row stride padded by one
+// vector: conflict-free); lane l of the result holds features 4*(l/16)..+4 of token l%16.
+__global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
+    extern __shared__ uint4 smem[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r16 = lane & 15, q4 = lane >> 4;
+    const int stride = p.n_vec + 1;
+    uint4* hs = smem;                                              // [tok_per_wg][stride]
+    uint4* my_slice = smem + (size_t)p.tok_per_wg * stride + (size_t)wave * kLinePairSlots;
+    float* red = reinterpret_cast<float*>(smem + (size_t)p.tok_per_wg * stride +
+                                          (size_t)kWavesPerBlock * kLinePairSlots);   // [4][256]
+    const int m0 = blockIdx.y * p.tok_per_wg;
+    const int tb = p.M - m0 < p.tok_per_wg ? p.M - m0 : p.tok_per_wg;
+    const int r0 = blockIdx.x * 16;                                // H is a multiple of 16 here
+    const int n_lines = p.n_vec / 8;
+    // line L of the rows belongs to wave L % 4; a wave takes 16 of its lines per batch
+    uint4 lo[kPremixLines], hi[kPremixLines];
+    const uint4* wlo = p.W1 + (size_t)(r0 + line_load_row(lane)) * p.n_vec + line_load_chunk(lane);
+    const uint4* whi = wlo + (size_t)8 * p.n_vec;
+    auto load_batch = [&](int b) {
+#pragma unroll
+        for (int i = 0; i < kPremixLines; ++i) {
+            const int L = (b * kPremixLines + i) * kWavesPerBlock + wave;
+            lo[i] = make_uint4(0, 0, 0, 0);
+            hi[i] = make_uint4(0, 0, 0, 0);
+            if (L < n_lines) {                                     // wave-uniform
+                lo[i] = load_stream(wlo + L * 8);
+                hi[i] = load_stream(whi + L * 8);
+            }
+        }
+    };
+    // The tokens are staged before the weight lines are requested: loads complete in order,
+    // so behind 32 KB of weight lines per wave the staging would wait for the whole stream.
+    for (int i = threadIdx.x; i < tb * p.n_vec; i += kBlock) {
+        const int t = i / p.n_vec, v = i - t * p.n_vec;
+        hs[t * stride + v] = p.hidden[(size_t)(m0 + t) * p.n_vec + v];
+    }
+    asm volatile("" ::: "memory");                                 // (keeps the order)
+    load_batch(0);
+    __syncthreads();
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const uint4* hb = hs + (size_t)(r16 < tb ? r16 : tb - 1) * stride + q4;   // columns past tb are not stored
+    for (int b = 0; b * kPremixLines * kWavesPerBlock < n_lines; ++b) {       // block-uniform
+        if (b) load_batch(b);
+#pragma unroll
+        for (int i = 0; i < kPremixLines; ++i) {
+            const int L = (b * kPremixLines + i) * kWavesPerBlock + wave;
+            if (L < n_lines) {                                     // wave-uniform
+                uint4 s0, s1;
+                mfma_operands_from_lines(lo[i], hi[i], lane, my_slice, s0, s1);
+                const uint4 b0 = hb[L * 8], b1 = hb[L * 8 + 4];
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, s0),
+                                                              __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, s1),
+                                                              __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
+            }
+        }
+    }
+    *reinterpret_cast<f32x4_t*>(red + wave * 256 + lane * 4) = acc;
+    __syncthreads();
+    {
+        const int e = threadIdx.x, l = e >> 2, i = e & 3;
+        const int row = r0 + (l >> 4) * 4 + i, tok = l & 15;
+        float y = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) y += red[w * 256 + e];    // wave order
+        if (tok < tb) {
+            const unsigned short* hrow = reinterpret_cast<const unsigned short*>(hs + (size_t)tok * stride);
+            static_cast<unsigned short*>(p.out)[(size_t)(m0 + tok) * p.H + row] =
+                bf16_bits_rne(premix_act(y, p.act) + __uint_as_float((unsigned)hrow[row] << 16));
+        }
+    }
+}
+
+}  // namespace

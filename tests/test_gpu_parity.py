@@ -12,6 +12,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 from coral_inputs import CONFIGS, Head, HeadConfig, make_head, make_hidden  # noqa: E402
+import oracle  # noqa: E402
 from oracle import compare  # noqa: E402
 
 
@@ -407,3 +408,108 @@ def test_full_size_workloads(coral, name, Ms):
                   flush=True)
     del dh
     torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------ router pre-mix (Eq. 7) and routed head
+PREMIX_SHAPES = [
+    # (dtype, H, M): one pair of rows per wave, several token batches, a ragged last pair,
+    # a row longer than one pass of 8 segments, and the workload's own width
+    ("f32", 256, 4), ("bf16", 512, 1), ("bf16", 1000, 9), ("bf16", 4104, 3), ("f32", 2052, 17),
+    ("bf16", 4096, 16),
+    # matrix-core kernel: fewer tokens than a tile, several ragged token batches, LDS that
+    # only fits part of a tile's tokens, fewer lines than waves, more than one batch of lines
+    ("bf16", 4096, 5), ("bf16", 4096, 40), ("bf16", 8192, 16), ("bf16", 192, 20), ("bf16", 4480, 4),
+]
+
+
+@pytest.mark.parametrize("dtype,H,M", PREMIX_SHAPES)
+def test_router_premix(coral, dtype, H, M):
+    from coral_inputs import make_router_W1
+    cfg = HeadConfig(f"premix_{dtype}_{H}", dtype, H, 64, 2, 1, (M,), 4, 31, True)
+    W1 = make_router_W1(cfg)
+    hidden = make_hidden(cfg, M, 0)
+    d_W1 = coral.device_tensor(W1, dtype)
+    d_h = coral.device_tensor(hidden, dtype)
+    for act in ("silu", "relu", "identity"):
+        print(f"case premix {dtype} H={H} M={M} act={act}", flush=True)
+        u = coral.coral_router_premix(d_h, d_W1, act)
+        torch.cuda.synchronize()
+        raw = u.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else u.cpu().numpy()
+        rep = compare.check_premix(hidden, W1, dtype, act, raw)
+        assert rep.tokens == M
+
+
+def test_router_premix_rejects_bad_arguments(coral):
+    cfg = HeadConfig("premix_bad", "bf16", 256, 64, 2, 1, (2,), 4, 32, True)
+    from coral_inputs import make_router_W1
+    d_W1 = coral.device_tensor(make_router_W1(cfg), "bf16")
+    d_h = coral.device_tensor(make_hidden(cfg, 2, 0), "bf16")
+    with pytest.raises(coral.CoralError):                      # in place: u_out overlaps hidden
+        coral.coral_router_premix(d_h, d_W1, "silu", out=d_h)
+    with pytest.raises(ValueError):
+        coral.coral_router_premix(d_h, d_W1, "tanh")
+
+
+ROUTED = [
+    (CONFIGS["tiny_f32"], (4,)),
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203), (1, 4, 8, 16)),     # single-launch path, all three gates
+    (CONFIGS["wide_tree"].scaled(V=64 * 126), (64,)),             # tile path
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203, H=4160), (8,)),      # multi-kernel path
+]
+
+
+@pytest.mark.parametrize("cfg,Ms", ROUTED, ids=lambda x: x.name if isinstance(x, HeadConfig) else None)
+def test_routed_head_gate_sees_another_vector(coral, cfg, Ms):
+    dh = DeviceHead(coral, make_head(cfg))
+    h = dh.head
+    for M in Ms:
+        hidden = make_hidden(cfg, M, 0)
+        gate_hidden = make_hidden(cfg, M, 7)                   # independent of hidden
+        d_h = coral.device_tensor(hidden, cfg.dtype)
+        d_gh = coral.device_tensor(gate_hidden, cfg.dtype)
+        for logprob in (False, True):
+            print(f"case routed {cfg.name} M={M} logprob={logprob}", flush=True)
+            ids, out, sel = coral.coral_lmhead_grouped(d_h, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g,
+                                                       cfg.k, logprob=logprob, gate_hidden=d_gh)
+            torch.cuda.synchronize()
+            res = (ids.cpu().numpy(), out.cpu().numpy(), sel.cpu().numpy())
+            check = compare.check_grouped_logprob if logprob else compare.check_grouped
+            rep = check(hidden, h.gate_W, h.gate_bias, h.lm_W, h.group_offsets, h.group_rows, cfg.g,
+                        cfg.k, cfg.dtype, *res, gate_hidden=gate_hidden)
+            assert rep.tokens == M
+        # NULL gate_hidden is the plain head
+        a = coral.coral_lmhead_grouped(d_h, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k)
+        b = coral.coral_lmhead_grouped(d_h, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k, gate_hidden=d_h)
+        torch.cuda.synchronize()
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+
+
+def test_premix_then_routed_head_end_to_end(coral):
+    """The paper's router as a chain of two calls: u = act(W1 h) + h, then W2 on u.  The
+    oracle rounds its own u to storage; a device u that differs in the last place of a few
+    elements moves scores by more than the plain gate tolerance, so that tolerance is
+    widened by the measured score difference."""
+    from coral_inputs import make_router_W1
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
+    dh = DeviceHead(coral, make_head(cfg))
+    h = dh.head
+    W1 = make_router_W1(cfg)
+    d_W1 = coral.device_tensor(W1, cfg.dtype)
+    M = 8
+    hidden = make_hidden(cfg, M, 3)
+    d_h = coral.device_tensor(hidden, cfg.dtype)
+    d_u = coral.coral_router_premix(d_h, d_W1, "silu")
+    ids, z, sel = coral.coral_lmhead_grouped(d_h, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                             gate_hidden=d_u)
+    torch.cuda.synchronize()
+    u_dev = d_u.view(torch.int16).cpu().numpy().view(np.uint16)
+    compare.check_premix(hidden, W1, cfg.dtype, "silu", u_dev)
+    _, u_ref = oracle.premix(hidden, W1, cfg.dtype, "silu")
+    drift = np.abs(oracle.gate(u_dev, h.gate_W, h.gate_bias, cfg.dtype)
+                   - oracle.gate(u_ref, h.gate_W, h.gate_bias, cfg.dtype)).max()
+    rep = compare.check_grouped(hidden, h.gate_W, h.gate_bias, h.lm_W, h.group_offsets, h.group_rows,
+                                cfg.g, cfg.k, cfg.dtype, ids.cpu().numpy(), z.cpu().numpy(),
+                                sel.cpu().numpy(), gate_tol=compare.GATE_TOL[cfg.dtype] + 2 * drift,
+                                gate_hidden=u_ref)
+    assert rep.tokens == M
