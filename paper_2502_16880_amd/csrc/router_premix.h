@@ -18,6 +18,7 @@ namespace {
 
 constexpr int kPremixTok = 8;                    // tokens of a workgroup (LDS residents)
 constexpr int kPremixSegs = 8;                   // 1 KB segments of a row requested together
+constexpr int kPremixStage = 8;                  // 16-byte vectors a thread stages through registers
 
 struct PremixParams {
     const uint4* hidden;        // [M, n_vec]
@@ -46,11 +47,32 @@ __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int m0 = blockIdx.y * p.tok_per_wg;
     const int tb = p.M - m0 < p.tok_per_wg ? p.M - m0 : p.tok_per_wg;
-    for (int i = threadIdx.x; i < tb * p.n_vec; i += kBlock)      // consecutive rows: one block
-        smem[i] = p.hidden[(size_t)m0 * p.n_vec + i];
-    __syncthreads();
+    // The tokens' vectors are requested first and written to LDS only after the first weight
+    // rows have been requested too: loads complete in order, so the wait for the tokens does
+    // not wait for the weights behind them (what does not fit the registers goes directly).
+    const int total = tb * p.n_vec;                                // consecutive rows: one block
+    const uint4* hsrc = p.hidden + (size_t)m0 * p.n_vec;
+    uint4 st[kPremixStage];
+#pragma unroll
+    for (int j = 0; j < kPremixStage; ++j) {
+        const int i = threadIdx.x + j * kBlock;
+        if (i < total) st[j] = load_vec(hsrc + i);
+    }
+    for (int i = threadIdx.x + kPremixStage * kBlock; i < total; i += kBlock) smem[i] = hsrc[i];
     const int n_waves = gridDim.x * kWavesPerBlock;
-    for (int r0 = (blockIdx.x * kWavesPerBlock + wave) * 2; r0 < p.H; r0 += n_waves * 2) {   // wave-uniform
+    const int r_first = (blockIdx.x * kWavesPerBlock + wave) * 2;
+    auto commit_tokens = [&]() {                                   // every wave exactly once
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < kPremixStage; ++j) {
+            const int i = threadIdx.x + j * kBlock;
+            if (i < total) store_vec(smem + i, st[j]);
+        }
+        __syncthreads();
+    };
+    bool staged = false;
+    if (r_first >= p.H) commit_tokens();                           // a wave without rows (wave-uniform)
+    for (int r0 = r_first; r0 < p.H; r0 += n_waves * 2) {          // wave-uniform
         const int r1 = r0 + 1 < p.H ? r0 + 1 : r0;
         float a0[kPremixTok], a1[kPremixTok];
 #pragma unroll
@@ -68,6 +90,10 @@ __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
                     w0[j] = load_stream(w0p + vec);
                     w1[j] = load_stream(w1p + vec);
                 }
+            }
+            if (!staged) {                                         // wave-uniform: the wave's first pass
+                commit_tokens();
+                staged = true;
             }
 #pragma unroll
             for (int j = 0; j < kPremixSegs; ++j) {
@@ -112,6 +138,7 @@ __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
 
 constexpr int kPremixTileTok = 16;               // tokens of a workgroup on the matrix cores
 constexpr int kPremixLines = 16;                 // 128-byte lines of a row a wave holds at once
+constexpr int kPremixTileStage = 32;             // 16-byte vectors a thread stages through registers
 
 __host__ __device__ inline size_t premix_mfma_lds_bytes(int tok, int n_vec) {
     return ((size_t)tok * (n_vec + 1) + (size_t)kWavesPerBlock * kLinePairSlots) * sizeof(uint4) +
@@ -151,14 +178,30 @@ __global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
             }
         }
     };
-    // The tokens are staged before the weight lines are requested: loads complete in order,
-    // so behind 32 KB of weight lines per wave the staging would wait for the whole stream.
-    for (int i = threadIdx.x; i < tb * p.n_vec; i += kBlock) {
-        const int t = i / p.n_vec, v = i - t * p.n_vec;
-        hs[t * stride + v] = p.hidden[(size_t)(m0 + t) * p.n_vec + v];
+    // The tokens' vectors are requested before the weight lines and written to LDS after
+    // those have been requested too: loads complete in order, so the tokens do not wait for
+    // the 32 KB of weight lines per wave behind them, and the lines stream meanwhile.
+    const int total = tb * p.n_vec;
+    const uint4* hsrc = p.hidden + (size_t)m0 * p.n_vec;
+    auto hs_slot = [&](int i) {
+        const int t = i / p.n_vec;
+        return hs + (size_t)t * stride + (i - t * p.n_vec);
+    };
+    uint4 st[kPremixTileStage];
+#pragma unroll
+    for (int j = 0; j < kPremixTileStage; ++j) {
+        const int i = threadIdx.x + j * kBlock;
+        if (i < total) st[j] = load_vec(hsrc + i);
     }
+    for (int i = threadIdx.x + kPremixTileStage * kBlock; i < total; i += kBlock) *hs_slot(i) = hsrc[i];
     asm volatile("" ::: "memory");                                 // (keeps the order)
     load_batch(0);
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < kPremixTileStage; ++j) {
+        const int i = threadIdx.x + j * kBlock;
+        if (i < total) store_vec(hs_slot(i), st[j]);
+    }
     __syncthreads();
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const uint4* hb = hs + (size_t)(r16 < tb ? r16 : tb - 1) * stride + q4;   // columns past tb are not stored
