@@ -293,3 +293,31 @@ def grouped_logprob(hidden, gate_W, gate_bias, lm_W, offsets, rows, g: int, k: i
         ids_out[m], lp_out[m], nxt[m] = top_k(np.concatenate(all_lp), np.concatenate(all_ids), k)
     return LogprobResult(base.sel, ids_out, lp_out, nxt, base.s, base.lse, base.logp_router)
 
+
+
+def tree_expand(parent_score, cand_ids, cand_logp, n_next: int):
+    """One level of draft-tree expansion (the dynamic tree the paper drafts with, section 2.1
+    and section 4.1 "Implementation": several candidates per node, a fixed number of nodes
+    kept per level).  Node m of the current level carries the cumulative log-probability
+    parent_score[m]; its k candidates have log-probabilities cand_logp[m,:] and token ids
+    cand_ids[m,:] (id < 0: empty slot).  The score of candidate (m,i) is the float32 sum
+    parent_score[m] + cand_logp[m,i] (both sides of a parity check add in float32, so the
+    ranking is exact integer work); the n_next best scores become the next level, best
+    first, equal scores by lower m, then lower i.  Returns (parent [n_next] int32,
+    token [n_next] int32, score [n_next] float32); slots beyond the number of candidates
+    hold (-1, -1, -inf)."""
+    cand_ids = np.ascontiguousarray(cand_ids, dtype=np.int32)
+    cand_logp = np.ascontiguousarray(cand_logp, dtype=np.float32)
+    M, k = cand_ids.shape
+    assert cand_logp.shape == (M, k)
+    base = np.zeros(M, np.float32) if parent_score is None else np.ascontiguousarray(parent_score, dtype=np.float32)
+    assert base.shape == (M,)
+    score = (base[:, None] + cand_logp).astype(np.float32)
+    items = [(-float(score[m, i]), m, i) for m in range(M) for i in range(k) if cand_ids[m, i] >= 0]
+    items.sort()
+    parent = np.full(n_next, -1, np.int32)
+    token = np.full(n_next, -1, np.int32)
+    out = np.full(n_next, -np.inf, np.float32)
+    for r, (_, m, i) in enumerate(items[:n_next]):
+        parent[r], token[r], out[r] = m, cand_ids[m, i], score[m, i]
+    return parent, token, out

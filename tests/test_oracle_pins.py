@@ -544,3 +544,47 @@ def test_routed_head_with_the_same_vector_is_the_plain_head():
     assert np.array_equal(a.sel, b.sel) and np.array_equal(a.topk_ids, b.topk_ids)
     assert np.array_equal(a.topk_z, b.topk_z) and np.array_equal(a.s, b.s)
     assert np.allclose(a.logp_router, b.logp_router, atol=1e-14)
+
+
+# ---------------------------------------------------------------- draft-tree expansion
+def test_tree_expand_hand_worked_level():
+    # two nodes with cumulative scores -1 and -3; candidates' log-probabilities below
+    parent = np.array([-1.0, -3.0], np.float32)
+    ids = np.array([[11, 12, 13], [21, 22, 23]], np.int32)
+    logp = np.array([[-0.5, -2.0, -4.0], [-0.25, -0.5, -9.0]], np.float32)
+    # scores: node 0: -1.5, -3.0, -5.0; node 1: -3.25, -3.5, -12.0
+    p, t, s = oracle.tree_expand(parent, ids, logp, 4)
+    assert p.tolist() == [0, 0, 1, 1] and t.tolist() == [11, 12, 21, 22]
+    assert s.tolist() == [-1.5, -3.0, -3.25, -3.5]
+
+
+def test_tree_expand_ties_empty_slots_and_padding():
+    ids = np.array([[5, 6], [7, -1]], np.int32)
+    logp = np.array([[-1.0, -2.0], [-1.0, -0.5]], np.float32)      # (1,1) is an empty slot
+    p, t, s = oracle.tree_expand(None, ids, logp, 5)
+    assert p.tolist() == [0, 1, 0, -1, -1]                          # equal scores: lower node first
+    assert t.tolist() == [5, 7, 6, -1, -1]
+    assert s[:3].tolist() == [-1.0, -1.0, -2.0] and np.all(np.isneginf(s[3:]))
+
+
+def test_tree_expand_is_a_prefix_of_the_full_sort_and_adds_in_float32():
+    rng = np.random.default_rng(3)
+    M, k = 7, 9
+    parent = rng.standard_normal(M).astype(np.float32) * 3
+    logp = -np.sort(rng.random((M, k)).astype(np.float32) * 8, axis=1)
+    ids = rng.integers(0, 1000, (M, k)).astype(np.int32)
+    full = oracle.tree_expand(parent, ids, logp, M * k)
+    assert np.all(np.diff(full[2]) <= 0)
+    assert sorted(zip(full[0].tolist(), full[1].tolist())) == sorted(
+        (m, int(ids[m, i])) for m in range(M) for i in range(k))
+    flat = (parent[:, None] + logp).astype(np.float32).reshape(-1)
+    order = np.argsort(-flat.astype(np.float64), kind="stable")
+    assert np.array_equal(full[2], flat[order])
+    assert np.array_equal(full[0], (order // k).astype(np.int32))
+    for n in (1, 10, 20):
+        part = oracle.tree_expand(parent, ids, logp, n)
+        for a, b in zip(part, full):
+            assert np.array_equal(a, b[:n])
+    # one node, no parent score: the node's own candidates in order
+    one = oracle.tree_expand(None, ids[:1], logp[:1], k)
+    assert np.array_equal(one[1], ids[0]) and np.array_equal(one[2], logp[0])
