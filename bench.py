@@ -202,6 +202,19 @@ class Bench:
         bytes_premix = w1_bytes + 2 * M * cfg.H * weight_bytes_per_elt(cfg.dtype)
         return dict(step_us=step_us, premix_us=premix_us, premix_bytes=bytes_premix)
 
+    def time_tree_expand(self, M, k, n_next, steps=240):
+        """One level of draft-tree expansion on synthetic candidate lists (sorted rows)."""
+        torch, coral = self.torch, self.coral
+        g = torch.Generator(device="cuda").manual_seed(7)
+        logp = -torch.sort(torch.rand((M, k), device="cuda", generator=g) * 6, dim=1).values
+        ids = torch.randint(0, self.cfg.V, (M, k), device="cuda", generator=g, dtype=torch.int32)
+        parent = -torch.rand(M, device="cuda", generator=g) * 4
+
+        def call(i, events=None):
+            coral.coral_tree_expand(parent, ids, logp, n_next)
+
+        return self._timed(call, steps, 8, 24, False) * 1e3 / steps
+
     def time_dense(self, M, steps, warmup, eager=False, event_steps=60):
         torch, coral, cfg = self.torch, self.coral, self.cfg
         from coral_inputs import make_hidden
@@ -401,6 +414,10 @@ def main():
                       "frac_whole_step": r["premix_bytes"] / r["premix_us"] / 1e3 / HBM_PEAK_GBPS})
         cases.append({"path": "pre-mix, then grouped head with the router reading u (two calls)",
                       "M": a.M, "us_per_step": r["step_us"]})
+        for (tm, tk, tn) in ((10, 10, 10), (64, 16, 64)):
+            cases.append({"path": f"draft-tree level expansion alone: {tm} nodes x {tk} candidates -> "
+                                  f"{tn} nodes (k_tree_expand; latency-bound, launch gap included)",
+                          "M": tm, "us_per_step": bench.time_tree_expand(tm, tk, tn)})
         rep_M = min(cfg.Ms)
         cases.append({"path": "grouped, same input every call (cache-assisted)", "M": rep_M,
                       "us_per_step": bench.time_repeat(rep_M, max(48, n), 8)})

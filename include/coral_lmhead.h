@@ -212,6 +212,28 @@ coral_status coral_lmhead_grouped_routed(const void *hidden, const void *gate_hi
                                          size_t workspace_bytes, void *hip_stream);
 
 /*
+ * One level of draft-tree expansion (tree drafting of section 2.1 with the per-level node
+ * budget of section 4.1, "Implementation"; the paper takes the rule from the dynamic draft
+ * tree it builds on and does not restate it, so this is a reading): node m of the current
+ * level carries the cumulative log-probability parent_score[m]; candidate i of node m has
+ * score = parent_score[m] + cand_logp[m,i] (one fp32 addition); the n_next best scores of
+ * all M*k candidates form the next level, best first; equal scores: lower m, then lower i.
+ *   parent_score [device] [M] fp32, or NULL for all zero (the root level)
+ *   cand_ids     [device] [M,k] int32 token ids, e.g. coral_lmhead_grouped_logprob's
+ *                topk_ids; a negative id marks an empty slot
+ *   cand_logp    [device] [M,k] fp32, each row non-increasing (as the heads return it)
+ *   next_parent  [device] out [n_next] int32: index m of the parent node
+ *   next_token   [device] out [n_next] int32: the candidate's token id
+ *   next_score   [device] out [n_next] fp32: its cumulative score
+ *   Slots beyond the number of candidates hold (-1, -1, -inf).
+ * Limits: 1 <= M <= 64, 1 <= k <= 64, 1 <= n_next <= M*k.  Needs no workspace.
+ */
+coral_status coral_tree_expand(const float *parent_score, const int32_t *cand_ids,
+                               const float *cand_logp, int M, int k, int n_next,
+                               int32_t *next_parent, int32_t *next_token,
+                               float *next_score, void *hip_stream);
+
+/*
  * Dense LM head: z[m,r] for every r = 0..V-1, then the k best per token with the
  * same ordering rules (the no-router baseline of Table 4; the head whose latency
  * the appendix paragraph "Backends" measures).  Arguments as above; k <= V.

@@ -72,6 +72,8 @@ def _load():
     L.coral_router_premix.restype = c.c_int
     L.coral_router_premix.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int,
                                       c.c_void_p, c.c_void_p]
+    L.coral_tree_expand.restype = c.c_int
+    L.coral_tree_expand.argtypes = [c.c_void_p] * 3 + [c.c_int] * 3 + [c.c_void_p] * 4
     L.coral_lmhead_grouped_routed.restype = c.c_int
     L.coral_lmhead_grouped_routed.argtypes = [c.c_void_p] * 5 + [c.POINTER(_GroupIndexStruct)] + \
                                              [c.c_int] * 7 + [c.c_void_p] * 4 + \
@@ -262,6 +264,27 @@ def coral_router_premix(hidden: torch.Tensor, W1: torch.Tensor, act: str = "silu
     _raise(_L.coral_router_premix(_dev_ptr(hidden, "hidden"), _dev_ptr(W1, "W1"), M, H, dt,
                                   ACTIVATIONS[act], _dev_ptr(out, "out"), _stream_ptr(stream)))
     return out
+
+
+def coral_tree_expand(parent_score: Optional[torch.Tensor], cand_ids: torch.Tensor,
+                      cand_logp: torch.Tensor, n_next: int, stream=None
+                      ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """coral_tree_expand of the C ABI: (parent index, token id, cumulative score), each [n_next]."""
+    if cand_ids.dim() != 2 or cand_logp.shape != cand_ids.shape:
+        raise ValueError("cand_ids and cand_logp must both be [M,k]")
+    M, k = cand_ids.shape
+    if parent_score is not None and parent_score.shape != (M,):
+        raise ValueError("parent_score must be [M]")
+    dev = cand_ids.device
+    parent = torch.empty(n_next, dtype=torch.int32, device=dev)
+    token = torch.empty(n_next, dtype=torch.int32, device=dev)
+    score = torch.empty(n_next, dtype=torch.float32, device=dev)
+    _raise(_L.coral_tree_expand(_dev_ptr(parent_score, "parent_score", torch.float32),
+                                _dev_ptr(cand_ids, "cand_ids", torch.int32),
+                                _dev_ptr(cand_logp, "cand_logp", torch.float32), M, k, int(n_next),
+                                _dev_ptr(parent, "next_parent"), _dev_ptr(token, "next_token"),
+                                _dev_ptr(score, "next_score"), _stream_ptr(stream)))
+    return parent, token, score
 
 
 def coral_lmhead_grouped_logprob(hidden, gate_W, gate_bias, lm_W, gi, g, k, **kw):

@@ -28,6 +28,7 @@
 #include "router_premix.h"
 #include "staged_path.h"
 #include "tile_path.h"
+#include "tree_expand.h"
 
 namespace {
 
@@ -536,6 +537,21 @@ extern "C" coral_status coral_lmhead_grouped_routed(
     return grouped_impl(hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_out, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
                         nullptr, logprob != 0);
+}
+
+extern "C" coral_status coral_tree_expand(const float* parent_score, const int32_t* cand_ids,
+                                          const float* cand_logp, int M, int k, int n_next,
+                                          int32_t* next_parent, int32_t* next_token,
+                                          float* next_score, void* hip_stream) {
+    if (!cand_ids || !cand_logp || !next_parent || !next_token || !next_score) return CORAL_ERR_NULL;
+    if (M < 1 || k < 1 || n_next < 1) return CORAL_ERR_SHAPE;
+    if (M > kMaxM || k > kMaxK) return CORAL_ERR_UNSUPPORTED;
+    if (n_next > M * k) return CORAL_ERR_SHAPE;
+    hipLaunchKernelGGL(k_tree_expand, dim3(M), dim3(kWave), (size_t)M * k * sizeof(unsigned long long),
+                       static_cast<hipStream_t>(hip_stream),
+                       parent_score, cand_ids, cand_logp, M, k, n_next, next_parent, next_token,
+                       next_score);
+    return launch_status();
 }
 
 extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, int M, int H,

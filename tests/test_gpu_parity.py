@@ -513,3 +513,59 @@ def test_premix_then_routed_head_end_to_end(coral):
                                 sel.cpu().numpy(), gate_tol=compare.GATE_TOL[cfg.dtype] + 2 * drift,
                                 gate_hidden=u_ref)
     assert rep.tokens == M
+
+
+# ------------------------------------------------------------------ draft-tree expansion
+TREE_SHAPES = [
+    # (M, k, n_next): the root level, the paper's operating point (10 candidates per node, 60
+    # nodes in the tree), a full sort, the largest level, lists longer than n_next
+    (1, 10, 10), (10, 10, 10), (10, 10, 60), (8, 10, 80), (64, 64, 64), (64, 64, 4096), (60, 16, 7),
+]
+
+
+@pytest.mark.parametrize("M,k,n_next", TREE_SHAPES)
+def test_tree_expand_is_bit_exact(coral, M, k, n_next):
+    rng = np.random.default_rng(1000 * M + k)
+    for case in range(3):
+        print(f"case tree M={M} k={k} n_next={n_next} #{case}", flush=True)
+        parent = (rng.standard_normal(M) * 2 - 3).astype(np.float32)
+        logp = -np.sort(rng.random((M, k)).astype(np.float32) * 6, axis=1)
+        ids = rng.integers(0, 128256, (M, k)).astype(np.int32)
+        if case == 1:                       # ties across nodes and empty slots at list ends
+            logp = np.round(logp * 2) / 2
+            parent = np.round(parent)
+            ids[rng.random((M, k)) < 0.1] = -1
+            ids = np.where(np.cumsum(ids < 0, axis=1) > 0, -1, ids).astype(np.int32)
+        use_parent = case != 2 or M == 1
+        out = coral.coral_tree_expand(torch.from_numpy(parent).cuda() if use_parent else None,
+                                      torch.from_numpy(ids).cuda(), torch.from_numpy(logp).cuda(), n_next)
+        torch.cuda.synchronize()
+        ref = oracle.tree_expand(parent if use_parent else None, ids, logp, n_next)
+        for name, a, b in zip(("parent", "token", "score"), out, ref):
+            assert np.array_equal(a.cpu().numpy(), b), f"{name}: {a.cpu().numpy()} vs {b}"
+
+
+def test_tree_expand_after_the_logprob_head(coral):
+    """Two calls chained on the device.  The expansion's inputs here are the device head's
+    outputs, which are not oracle inputs, so this checks properties that hold for any input:
+    scores non-increasing, every kept node is a candidate of its parent with the parent's
+    score added, nothing better was left out.  (Exactness of the expansion itself is the test
+    above; of the head, the log-probability parity tests.)"""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
+    dh = DeviceHead(coral, make_head(cfg))
+    M, n_next = 8, 10
+    hidden = make_hidden(cfg, M, 5)
+    ids, logp, _ = coral.coral_lmhead_grouped_logprob(coral.device_tensor(hidden, cfg.dtype), dh.gate_W,
+                                                      dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k)
+    parent = torch.linspace(-2.0, -0.25, M, device="cuda")
+    p, t, s = (x.cpu().numpy() for x in coral.coral_tree_expand(parent, ids, logp, n_next))
+    torch.cuda.synchronize()
+    ids_h, logp_h, parent_h = ids.cpu().numpy(), logp.cpu().numpy(), parent.cpu().numpy()
+    assert np.all(np.diff(s) <= 0)
+    all_scores = (parent_h[:, None] + logp_h).astype(np.float32)
+    for r in range(n_next):
+        pos = np.where(ids_h[p[r]] == t[r])[0]
+        assert len(pos) == 1 and all_scores[p[r], pos[0]] == s[r]
+    assert np.sum(all_scores > s[-1]) <= n_next - 1
+    with pytest.raises(coral.CoralError):
+        coral.coral_tree_expand(parent, ids, logp, M * cfg.k + 1)
