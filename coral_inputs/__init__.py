@@ -67,6 +67,13 @@ CONFIGS = {
     "qwen25_7b": HeadConfig("qwen25_7b", "bf16", 3584, 152064, 32, 4, (1, 8, 16), 10, 3, True),
     "wide_tree": HeadConfig("wide_tree", "bf16", 4096, 128256, 64, 8, (64,), 16, 4, True,
                             bias_std=2.0),
+    # The paper's own best router setting at the Llama3 shape (Table 4: 16 groups, top 2) with
+    # its equal contiguous split of the vocabulary and the appendix's 10 candidates per step,
+    # and the same with permuted groups (gathered rows against contiguous rows).
+    "paper_point": HeadConfig("paper_point", "bf16", 4096, 128256, 16, 2, (1, 10), 10, 5, True,
+                              grouping="contiguous"),
+    "paper_point_permuted": HeadConfig("paper_point_permuted", "bf16", 4096, 128256, 16, 2, (1, 10),
+                                       10, 5, True),
 }
 
 

@@ -84,6 +84,7 @@ SCALED = [
     (CONFIGS["llama3_8b"].scaled(V=32 * 203), (1, 4, 8, 16)),
     (CONFIGS["qwen25_7b"].scaled(V=32 * 297), (1, 8, 16)),
     (CONFIGS["wide_tree"].scaled(V=64 * 126), (64,)),
+    (CONFIGS["paper_point"].scaled(V=16 * 375), (1, 10)),          # contiguous groups
 ]
 
 
@@ -379,7 +380,8 @@ def test_nan_inputs_do_not_fault(coral):
 
 
 # ------------------------------------------------------------------ full-size workloads
-FULL = [("llama2_7b", (1, 8)), ("llama3_8b", (1, 16)), ("qwen25_7b", (1, 16)), ("wide_tree", (64,))]
+FULL = [("llama2_7b", (1, 8)), ("llama3_8b", (1, 16)), ("qwen25_7b", (1, 16)), ("wide_tree", (64,)),
+        ("paper_point", (10,))]
 
 
 @pytest.mark.parametrize("name,Ms", FULL)
