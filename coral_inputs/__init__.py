@@ -24,7 +24,8 @@ SeedSequence([seed, stream])):
                              drawn only by make_router_W1)
   stream 16+b  hidden batch b  [M,H]  N(0,1), optionally each row divided by
                              its RMS (float64 mean of squares), then rounded
-bf16 storage = round-to-nearest-even of the float32 value, kept as uint16.
+bf16 storage = round-to-nearest-even of the float32 value, kept as uint16; f16 storage =
+IEEE binary16 of the float32 value (nearest even), kept as uint16 as well.
 """
 from __future__ import annotations
 
@@ -74,6 +75,9 @@ CONFIGS = {
                               grouping="contiguous"),
     "paper_point_permuted": HeadConfig("paper_point_permuted", "bf16", 4096, 128256, 16, 2, (1, 10),
                                        10, 5, True),
+    # ... and in the paper's storage type (appendix "Backends": FP16)
+    "paper_point_f16": HeadConfig("paper_point_f16", "f16", 4096, 128256, 16, 2, (1, 10), 10, 5, True,
+                                  grouping="contiguous"),
 }
 
 
@@ -103,6 +107,8 @@ def _store(x: np.ndarray, dtype: str) -> np.ndarray:
         return np.ascontiguousarray(x, dtype=np.float32)
     if dtype == "bf16":
         return to_bf16_bits(x)
+    if dtype == "f16":                             # IEEE binary16 bits, round to nearest even
+        return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
     raise ValueError(f"unknown dtype {dtype!r}")
 
 

@@ -19,7 +19,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "coral_oracle.c")
 _LIB = os.path.join(_HERE, "libcoral_oracle.so")
 
-_DT = {"f32": 0, "bf16": 1}
+_DT = {"f32": 0, "bf16": 1, "f16": 2}
 
 
 def build(force: bool = False) -> str:
@@ -162,6 +162,8 @@ def widen(a: np.ndarray, dtype: str) -> np.ndarray:
     a = _storage(a, dtype)
     if dtype == "f32":
         return a.astype(np.float64)
+    if dtype == "f16":
+        return a.view(np.float16).astype(np.float64)
     return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
@@ -172,6 +174,8 @@ def round_to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
     f = np.ascontiguousarray(x, dtype=np.float64).astype(np.float32)
     if dtype == "f32":
         return f
+    if dtype == "f16":
+        return f.astype(np.float16).view(np.uint16)
     b = f.view(np.uint32)
     r = (b + np.uint32(0x7FFF) + ((b >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
     r = np.where(np.isnan(f), np.uint32(0x7FC0), r)

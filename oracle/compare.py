@@ -34,8 +34,10 @@ from . import logits_rows, rank_groups
 from . import premix as oracle_premix
 from . import widen
 
-TOL = {"bf16": 2e-3, "f32": 1e-5}
-GATE_TOL = {"bf16": 1e-4, "f32": 1e-6}
+# f16 (the paper's storage type): products of two 11-bit significands are exact in float32
+# as bf16's are, and the sums are the same float32 sums, so it takes bf16's tolerances.
+TOL = {"bf16": 2e-3, "f16": 2e-3, "f32": 1e-5}
+GATE_TOL = {"bf16": 1e-4, "f16": 1e-4, "f32": 1e-6}
 # log p(x) = log p_router + z - lse: the logit's tolerance, the same again for lse (a
 # log-sum-exp moves by at most the largest error of its terms) and twice the gate's for the
 # router's log-softmax (score and its log-sum-exp).
@@ -45,7 +47,7 @@ LOGP_TOL = {d: 2 * TOL[d] + 2 * GATE_TOL[d] for d in TOL}
 # The pre-mix u = act(W1 h) + h is stored in the head's storage type.  A kernel that
 # accumulates in float32 lands within PREMIX_ABS of the exact value before it rounds, and
 # rounding to storage moves it by at most half a unit in the last place of the result.
-PREMIX_ABS = {"bf16": 2e-5, "f32": 1e-5}
+PREMIX_ABS = {"bf16": 2e-5, "f16": 2e-5, "f32": 1e-5}
 
 
 @dataclass
@@ -233,10 +235,12 @@ def check_premix(hidden, W1, dtype, act, dev_u) -> Report:
     assert dev.shape == u.shape
     assert np.all(np.isfinite(dev)), "non-finite pre-mix output"
     tol = np.full(u.shape, PREMIX_ABS[dtype])
-    if dtype == "bf16":
+    if dtype in ("bf16", "f16"):                   # 8 and 11 significand bits
         mag = np.maximum(np.abs(u), np.abs(dev))
         exp = np.floor(np.log2(np.maximum(mag, 2.0 ** -126)))
-        tol = tol + 0.5 * 2.0 ** (exp - 7)
+        if dtype == "f16":
+            exp = np.maximum(exp, -14)             # below 2^-14 the spacing stays 2^-24
+        tol = tol + 0.5 * 2.0 ** (exp - (7 if dtype == "bf16" else 10))
     err = np.abs(dev - u)
     bad = np.argwhere(err > tol)
     assert bad.size == 0, f"pre-mix: {len(bad)} elements off, first {bad[0]}: {dev[tuple(bad[0])]} vs {u[tuple(bad[0])]}"

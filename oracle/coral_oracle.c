@@ -43,7 +43,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 enum {
     ORACLE_OK = 0,
@@ -56,7 +56,19 @@ static inline double widen(const void *base, size_t idx, int dtype)
 {
     if (dtype == ORACLE_F32)
         return (double)((const float *)base)[idx];
-    uint32_t u = ((uint32_t)((const uint16_t *)base)[idx]) << 16;
+    const uint16_t h = ((const uint16_t *)base)[idx];
+    if (dtype == ORACLE_F16) {      /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+        const int sign = h >> 15, ex = (h >> 10) & 31, fr = h & 1023;
+        double v;
+        if (ex == 0)
+            v = ldexp((double)fr, -24);                    /* zero and subnormals */
+        else if (ex == 31)
+            v = fr ? NAN : INFINITY;
+        else
+            v = ldexp((double)(1024 + fr), ex - 25);
+        return sign ? -v : v;
+    }
+    uint32_t u = ((uint32_t)h) << 16;                      /* bf16: the upper half of a float */
     float f;
     memcpy(&f, &u, sizeof f);
     return (double)f;

@@ -39,7 +39,7 @@ __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4*
     const int wave = threadIdx.x / kWave;
     const int hs_stride = p.jp * kWave;
     constexpr int R = kRowsInFlight;
-    constexpr int JU = 4;
+    constexpr int JU = 8;
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
         lv[t] = -INFINITY;

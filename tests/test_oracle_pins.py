@@ -588,3 +588,50 @@ def test_tree_expand_is_a_prefix_of_the_full_sort_and_adds_in_float32():
     # one node, no parent score: the node's own candidates in order
     one = oracle.tree_expand(None, ids[:1], logp[:1], k)
     assert np.array_equal(one[1], ids[0]) and np.array_equal(one[2], logp[0])
+
+
+# ---------------------------------------------------------------- fp16 storage
+def test_f16_widening_on_known_bit_patterns_and_against_numpy():
+    # 1.0, -2.0, smallest subnormal 2^-24, largest subnormal, smallest normal 2^-14, 65504, 0.1 rounded
+    bits = np.array([[0x3C00, 0xC000, 0x0001, 0x03FF, 0x0400, 0x7BFF, 0x2E66]], np.uint16)
+    one = np.array([[0x3C00] * 7], np.uint16)
+    # gate(hidden=bits, gate_W=one-hot rows) reads the widened values back one by one
+    eye = np.zeros((7, 7), np.uint16)
+    np.fill_diagonal(eye, 0x3C00)
+    s = oracle.gate(bits, eye, None, "f16")
+    want = [1.0, -2.0, 2.0 ** -24, 1023 * 2.0 ** -24, 2.0 ** -14, 65504.0, 0.0999755859375]
+    assert s[0].tolist() == want
+    rng = np.random.default_rng(0)
+    anyb = rng.integers(0, 0x7C00, (1, 512)).astype(np.uint16)      # all finite non-negative patterns
+    anyb[0, ::2] |= 0x8000
+    ref = anyb.view(np.float16).astype(np.float64)
+    assert np.array_equal(oracle.widen(anyb, "f16"), ref)
+    ones = np.full((1, 512), 0x3C00, np.uint16)
+    assert oracle.gate(anyb, ones, None, "f16")[0, 0] == pytest.approx(float(ref.sum()), rel=1e-15)
+    # rounding to storage: nearest even, checked against torch
+    import torch
+    x = rng.standard_normal(4096) * 3
+    got = oracle.round_to_storage(x, "f16")
+    t = torch.from_numpy(x.astype(np.float32)).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, t)
+
+
+def test_f16_head_matches_numpy_brute_force():
+    cfg = HeadConfig("small_f16", "f16", 64, 480, 6, 2, (3,), 5, 41, True)
+    head = make_head(cfg)
+    h = make_hidden(cfg, 3, 0)
+    r = oracle.grouped(h, head.gate_W, None, head.lm_W, head.group_offsets, head.group_rows,
+                       cfg.g, cfg.k, "f16")
+    hf = h.view(np.float16).astype(np.float64)
+    gw = head.gate_W.view(np.float16).astype(np.float64)
+    lw = head.lm_W.view(np.float16).astype(np.float64)
+    s = hf @ gw.T
+    assert np.allclose(r.s, s, rtol=0, atol=1e-12)
+    for m in range(3):
+        sel = np.lexsort((np.arange(cfg.G), -s[m]))[:cfg.g]
+        assert r.sel[m].tolist() == sel.tolist()
+        rows = np.concatenate([head.group_rows[head.group_offsets[n]:head.group_offsets[n + 1]] for n in sel])
+        z = lw[rows] @ hf[m]
+        order = np.lexsort((rows, -z))[:cfg.k]
+        assert r.topk_ids[m].tolist() == rows[order].tolist()
+        assert np.allclose(r.topk_z[m], z[order], rtol=0, atol=1e-12)
