@@ -56,7 +56,7 @@ def parse():
 
 
 def weight_bytes_per_elt(dtype):
-    return 2 if dtype == "bf16" else 4
+    return 4 if dtype == "f32" else 2
 
 
 def algorithmic_bytes(cfg, M, U):
@@ -84,7 +84,7 @@ class Bench:
         self.lm_W = coral.device_tensor(self.head.lm_W, cfg.dtype)
         self.bias = None if self.head.gate_bias is None else torch.from_numpy(self.head.gate_bias).cuda()
         self.gi = coral.GroupIndex(self.head.group_offsets, self.head.group_rows)
-        self.dt = coral.CORAL_BF16 if cfg.dtype == "bf16" else coral.CORAL_F32
+        self.dt = {"f32": coral.CORAL_F32, "bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[cfg.dtype]
         self.setup_s = time.time() - t0
 
     # ---------------------------------------------------------------- inputs

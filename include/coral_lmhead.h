@@ -46,11 +46,13 @@ typedef enum {
     CORAL_ERR_HIP = 6            /* the HIP runtime refused a launch                 */
 } coral_status;
 
-/* Storage type of hidden, gate_W and lm_W (all three share it).  Products are
- * accumulated in fp32 for both; outputs are always fp32 logits and int32 ids. */
+/* Storage type of hidden, gate_W and lm_W (all three share it): fp32, bf16, or IEEE
+ * fp16 (the type the appendix paragraph "Backends" measures).  Products are accumulated
+ * in fp32 for all; outputs are always fp32 logits and int32 ids. */
 typedef enum {
     CORAL_F32 = 0,
-    CORAL_BF16 = 1
+    CORAL_BF16 = 1,
+    CORAL_F16 = 2
 } coral_dtype;
 
 /*
@@ -181,7 +183,7 @@ coral_status coral_lmhead_grouped_logprob(const void *hidden, const void *gate_W
  * library's default reading, the others are there to compare.  Sums in fp32; u is written in
  * the storage type dt (bf16: round to nearest even).
  *   hidden [device] [M,H]; W1 [device] [H,H]; u_out [device] out [M,H], must not overlap
- *   hidden.  All 16-byte aligned; H a multiple of 8 (bf16) / 4 (fp32), H * element size
+ *   hidden.  All 16-byte aligned; H a multiple of 8 (bf16, fp16) / 4 (fp32), H * element size
  *   at most 160 KB.  Needs no workspace.
  */
 typedef enum {

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libcoral_lmhead.so")
 CORAL_OK = 0
 CORAL_F32 = 0
 CORAL_BF16 = 1
+CORAL_F16 = 2
 
 
 class CoralError(RuntimeError):
@@ -96,9 +97,11 @@ def _raise(status: int):
 def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.bfloat16:
         return CORAL_BF16
+    if t.dtype == torch.float16:
+        return CORAL_F16
     if t.dtype == torch.float32:
         return CORAL_F32
-    raise TypeError(f"hidden/gate_W/lm_W must be bfloat16 or float32, got {t.dtype}")
+    raise TypeError(f"hidden/gate_W/lm_W must be bfloat16, float16 or float32, got {t.dtype}")
 
 
 def _dev_ptr(t: Optional[torch.Tensor], name: str, dtype=None) -> Optional[int]:
@@ -120,11 +123,12 @@ def _stream_ptr(stream) -> int:
 
 
 def device_tensor(a: np.ndarray, storage: str, device="cuda") -> torch.Tensor:
-    """Upload a host array; storage 'bf16' takes uint16 bit patterns, 'f32' float32."""
-    if storage == "bf16":
+    """Upload a host array; storage 'bf16' and 'f16' take uint16 bit patterns, 'f32' float32."""
+    if storage in ("bf16", "f16"):
         if a.dtype != np.uint16:
-            raise TypeError("bf16 storage expects uint16 bit patterns")
-        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+            raise TypeError(f"{storage} storage expects uint16 bit patterns")
+        return torch.from_numpy(a.view(np.int16)).to(device).view(
+            torch.bfloat16 if storage == "bf16" else torch.float16)
     if storage == "f32":
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
     raise ValueError(f"unknown storage {storage!r}")

@@ -35,6 +35,11 @@ namespace {
 // ---------------------------------------------------------------- host side
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+inline bool dtype_ok(coral_dtype dt) { return dt == CORAL_F32 || dt == CORAL_BF16 || dt == CORAL_F16; }
+inline bool is_16bit(coral_dtype dt) { return dt != CORAL_F32; }
+// One of three instantiations by storage type (kernels without an fp32 form pass nullptr).
+#define CORAL_PICK_DT(dt, f32, bf16, f16) ((dt) == CORAL_F32 ? (f32) : (dt) == CORAL_BF16 ? (bf16) : (f16))
+
 constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path's grid
 constexpr size_t kCtrlBytes = 256;     // control words at the start of the workspace
 
@@ -76,10 +81,10 @@ Layout make_layout(int M, int V, int G, int g, int k) {
 coral_status check_common(const void* hidden, const void* lm_W, int M, int H, int V, int k,
                           coral_dtype dt, const int32_t* topk_ids, const float* topk_logits) {
     if (!hidden || !lm_W || !topk_ids || !topk_logits) return CORAL_ERR_NULL;
-    if (dt != CORAL_F32 && dt != CORAL_BF16) return CORAL_ERR_SHAPE;
+    if (!dtype_ok(dt)) return CORAL_ERR_SHAPE;
     if (M < 1 || H < 1 || V < 1 || k < 1) return CORAL_ERR_SHAPE;
     if (M > kMaxM || k > kMaxK) return CORAL_ERR_UNSUPPORTED;
-    if (H % (dt == CORAL_BF16 ? 8 : 4) != 0) return CORAL_ERR_UNSUPPORTED;
+    if (H % (is_16bit(dt) ? 8 : 4) != 0) return CORAL_ERR_UNSUPPORTED;
     if (((uintptr_t)hidden | (uintptr_t)lm_W) & 15u) return CORAL_ERR_UNSUPPORTED;
     return CORAL_OK;
 }
@@ -119,10 +124,10 @@ int compute_units() {
     return cached[dev];
 }
 
-// Gate of the single-launch path: more than four tokens go through the matrix cores (bf16
-// only), with whole-line loads if their larger LDS slices still fit.
+// Gate of the single-launch path: more than four tokens go through the matrix cores (16-bit
+// storage only), with whole-line loads if their larger LDS slices still fit.
 int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype dt) {
-    if (dense || dt != CORAL_BF16 || M <= 4) return kGateVector;
+    if (dense || !is_16bit(dt) || M <= 4) return kGateVector;
     if (fused_lds_layout(M, G, g, k, jp, false, kGateMfmaLines).total <= kLdsLimit) return kGateMfmaLines;
     return kGateMfmaQuads;
 }
@@ -133,8 +138,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
                char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after) {
-    const bool bf16 = dt == CORAL_BF16;
-    const int n_vec = H / (bf16 ? 8 : 4);
+    const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt);
     const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate);
@@ -159,16 +163,21 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     p.n_vec = n_vec; p.jp = jp;
     typedef void (*fused_fn)(FusedParams);
     const bool routed = !dense && gate_hidden != hidden;
-    const fused_fn fn =
-        dense    ? (bf16 ? k_fused<true, true, kGateVector> : k_fused<false, true, kGateVector>)
-        : routed ? (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines, true>
-                            : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads, true>
-                                                     : k_fused<true, false, kGateVector, true>)
-                         : k_fused<false, false, kGateVector, true>)
-                 : (bf16 ? (gate == kGateMfmaLines   ? k_fused<true, false, kGateMfmaLines>
-                            : gate == kGateMfmaQuads ? k_fused<true, false, kGateMfmaQuads>
-                                                     : k_fused<true, false, kGateVector>)
-                         : k_fused<false, false, kGateVector>);
+    fused_fn fn;
+#define CORAL_FUSED_GATES(DT, R)                                                                 \
+    (gate == kGateMfmaLines   ? k_fused<DT, false, kGateMfmaLines, R>                            \
+     : gate == kGateMfmaQuads ? k_fused<DT, false, kGateMfmaQuads, R>                            \
+                              : k_fused<DT, false, kGateVector, R>)
+    if (dense)
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, true, kGateVector>), (k_fused<kBF16, true, kGateVector>),
+                           (k_fused<kF16, true, kGateVector>));
+    else if (routed)
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, true>), CORAL_FUSED_GATES(kBF16, true),
+                           CORAL_FUSED_GATES(kF16, true));
+    else
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, false>), CORAL_FUSED_GATES(kBF16, false),
+                           CORAL_FUSED_GATES(kF16, false));
+#undef CORAL_FUSED_GATES
     if (F.total > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess)
@@ -185,9 +194,9 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
 // dominate and the vector path is faster).
 bool dense_prefers_tiles(int M, int V) { return M >= 8 && V >= 2 * kMaxWorkgroups * kTileRows; }
 
-// Matrix-core path: bf16, whole 512-column chunks, weights below 4 GiB, LDS plan within the limit.
+// Matrix-core path: 16-bit storage, whole 512-column chunks, weights below 4 GiB, LDS plan within the limit.
 bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
-    if (dt != CORAL_BF16 || k > kTileMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
+    if (!is_16bit(dt) || k > kTileMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
     if ((unsigned long long)V * H * 2ull >= (1ull << 32)) return false;   // 32-bit weight offsets
     long long um = (long long)M * g < G ? (long long)M * g : G;
     if (um < 1) um = 1;
@@ -206,8 +215,7 @@ struct PathPlan {
 
 PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_dtype dt) {
     PathPlan pl = {};
-    const bool bf16 = dt == CORAL_BF16;
-    const int n_vec = H / (bf16 ? 8 : 4);
+    const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     const bool fused_ok =
         jp <= kFusedSegs &&
@@ -231,9 +239,9 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
 coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
                           const coral_group_index* gi, const unsigned long long* mask,
                           const int32_t* union_list, const int32_t* n_union, int M, int H, int V,
-                          int G, int k, int u_max, int lds, int32_t* topk_ids, float* topk_logits,
-                          char* ws, const Layout& L, hipStream_t stream, void* ev_before,
-                          void* ev_after) {
+                          int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
+                          float* topk_logits, char* ws, const Layout& L, hipStream_t stream,
+                          void* ev_before, void* ev_after) {
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
@@ -251,12 +259,14 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.n_vec = H / 8;
     p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
     p.u_max = u_max;
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_tiles),
+    typedef void (*tiles_fn)(TileParams, int);
+    const tiles_fn fn = dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>;
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return CORAL_ERR_HIP;
     coral_status st;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
-    hipLaunchKernelGGL(k_tiles, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
+    hipLaunchKernelGGL(fn, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(k_merge_published, dim3((M + 3) / 4), dim3(256), 0, stream,
@@ -311,10 +321,9 @@ extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g
 
 extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k,
                                  coral_dtype dt) {
-    if (dt != CORAL_F32 && dt != CORAL_BF16) return -1;
+    if (!dtype_ok(dt)) return -1;
     if (M < 1 || H < 1 || V < 1 || k < 1 || M > kMaxM || k > kMaxK) return -1;
-    const bool bf16 = dt == CORAL_BF16;
-    if (H % (bf16 ? 8 : 4) != 0) return -1;
+    if (H % (is_16bit(dt) ? 8 : 4) != 0) return -1;
     if (!dense && (G < 1 || g < 1 || g > G || G > kMaxG)) return -1;
     return plan_path(dense != 0, M, H, V, G, g, k, dt).path;
 }
@@ -387,8 +396,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     int32_t* chunk_base = reinterpret_cast<int32_t*>(ws + L.chunk_base);
     Cand* part = reinterpret_cast<Cand*>(ws + L.part);
 
-    const bool bf16 = dt == CORAL_BF16;
-    const int n_vec = H / (bf16 ? 8 : 4);
+    const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const uint4* hid = static_cast<const uint4*>(hidden);
     const uint4* ghid = static_cast<const uint4*>(gate_hidden);
     const uint4* gw = static_cast<const uint4*>(gate_W);
@@ -399,18 +407,17 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
-        hipLaunchKernelGGL(k_gate_select, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
+        typedef void (*gate_select_fn)(GateSelParams);
+        const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
+        hipLaunchKernelGGL(gs, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
-        return launch_tiles(false, hidden, lm_W, gi, mask, union_list, n_union, M, H, V, G, k,
+        return launch_tiles(false, hidden, lm_W, gi, mask, union_list, n_union, M, H, V, G, k, dt,
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                             ev_after);
     }
-    if (bf16)
-        hipLaunchKernelGGL(k_gate<true>, dim3(G), dim3(kBlock), 0, stream, ghid, gw, gate_bias, M, G,
-                           n_vec, s);
-    else
-        hipLaunchKernelGGL(k_gate<false>, dim3(G), dim3(kBlock), 0, stream, ghid, gw, gate_bias, M, G,
-                           n_vec, s);
+    typedef void (*gate_fn)(const uint4*, const uint4*, const float*, int, int, int, float*);
+    const gate_fn gate_kernel = CORAL_PICK_DT(dt, k_gate<kF32>, k_gate<kBF16>, k_gate<kF16>);
+    hipLaunchKernelGGL(gate_kernel, dim3(G), dim3(kBlock), 0, stream, ghid, gw, gate_bias, M, G, n_vec, s);
     if ((st = launch_status()) != CORAL_OK) return st;
     float* logp_sel = logprob ? reinterpret_cast<float*>(ws + L.logp_sel) : nullptr;
     hipLaunchKernelGGL(k_select, dim3(1), dim3(kBlock), 0, stream, s, gi->group_offsets, M, G, g, sel,
@@ -442,8 +449,11 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     dim3 grid(chunks, (unsigned)max_union);
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     typedef void (*logits_fn)(LogitsParams);
-    const logits_fn fn = bf16 ? (logprob ? k_logits<true, false, true> : k_logits<true, false, false>)
-                              : (logprob ? k_logits<false, false, true> : k_logits<false, false, false>);
+    const logits_fn fn =
+        logprob ? CORAL_PICK_DT(dt, (k_logits<kF32, false, true>), (k_logits<kBF16, false, true>),
+                                (k_logits<kF16, false, true>))
+                : CORAL_PICK_DT(dt, (k_logits<kF32, false, false>), (k_logits<kBF16, false, false>),
+                                (k_logits<kF16, false, false>));
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
         return CORAL_ERR_HIP;
@@ -476,19 +486,18 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     const PathPlan plan = plan_path(true, M, H, V, 0, 0, k, dt);
     // many tokens per row: the contraction is no longer cheap on the vector units
     if (plan.path == 2)
-        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k,
+        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k, dt,
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream,
                             ev_before, ev_after);
     if (plan.path == 1)
         return launch_fused(true, hidden, nullptr, nullptr, nullptr, lm_W, nullptr, M, H, V, 0, 0, k, dt, topk_ids,
                             topk_logits, nullptr, ws, L, stream, ev_before, ev_after);
-    const bool bf16 = dt == CORAL_BF16;
     LogitsParams p = {};
     p.hidden = static_cast<const uint4*>(hidden);
     p.lm_W = static_cast<const uint4*>(lm_W);
     p.part = reinterpret_cast<Cand*>(ws + L.part);
     p.M = M; p.V = V; p.G = 0; p.g = 0; p.k = k;
-    p.n_vec = H / (bf16 ? 8 : 4);
+    p.n_vec = H / (is_16bit(dt) ? 8 : 4);
     p.jp = (p.n_vec + kWave - 1) / kWave;
     p.tb_max = M < kTokBatch ? M : kTokBatch;
     p.part_stride = L.part_stride;
@@ -496,17 +505,12 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     if (lds > 160 * 1024) return CORAL_ERR_UNSUPPORTED;
     const int chunks = (V + kChunkRows - 1) / kChunkRows;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
-    if (bf16) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<true, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return CORAL_ERR_HIP;
-        hipLaunchKernelGGL((k_logits<true, true>), dim3(chunks), dim3(kBlock), lds, stream, p);
-    } else {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_logits<false, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return CORAL_ERR_HIP;
-        hipLaunchKernelGGL((k_logits<false, true>), dim3(chunks), dim3(kBlock), lds, stream, p);
-    }
+    typedef void (*logits_fn)(LogitsParams);
+    const logits_fn fn = CORAL_PICK_DT(dt, (k_logits<kF32, true>), (k_logits<kBF16, true>), (k_logits<kF16, true>));
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return CORAL_ERR_HIP;
+    hipLaunchKernelGGL(fn, dim3(chunks), dim3(kBlock), lds, stream, p);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, p.part, L.part_stride,
@@ -558,13 +562,13 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
                                             coral_dtype dt, coral_activation act, void* u_out,
                                             void* hip_stream) {
     if (!hidden || !W1 || !u_out) return CORAL_ERR_NULL;
-    if (dt != CORAL_F32 && dt != CORAL_BF16) return CORAL_ERR_SHAPE;
+    if (!dtype_ok(dt)) return CORAL_ERR_SHAPE;
     if (act != CORAL_ACT_SILU && act != CORAL_ACT_RELU && act != CORAL_ACT_IDENTITY) return CORAL_ERR_SHAPE;
     if (M < 1 || H < 1) return CORAL_ERR_SHAPE;
-    const bool bf16 = dt == CORAL_BF16;
-    if (H % (bf16 ? 8 : 4) != 0) return CORAL_ERR_UNSUPPORTED;
+    const bool w16 = is_16bit(dt);
+    if (H % (w16 ? 8 : 4) != 0) return CORAL_ERR_UNSUPPORTED;
     if (((uintptr_t)hidden | (uintptr_t)W1 | (uintptr_t)u_out) & 15u) return CORAL_ERR_UNSUPPORTED;
-    const size_t row_bytes = (size_t)H * (bf16 ? 2 : 4);
+    const size_t row_bytes = (size_t)H * (w16 ? 2 : 4);
     if (row_bytes > (size_t)kLdsLimit) return CORAL_ERR_UNSUPPORTED;
     {   // u_out must not overlap hidden: workgroups read hidden rows that others write
         const uintptr_t a = (uintptr_t)hidden, b = (uintptr_t)u_out;
@@ -576,19 +580,20 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
     p.W1 = static_cast<const uint4*>(W1);
     p.out = u_out;
     p.M = M; p.H = H; p.act = (int)act;
-    p.n_vec = H / (bf16 ? 8 : 4);
+    p.n_vec = H / (w16 ? 8 : 4);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    if (bf16 && H % 64 == 0 && M >= 4) {                      // matrix cores
+    typedef void (*premix_fn)(PremixParams);
+    if (w16 && H % 64 == 0 && M >= 4) {                       // matrix cores
         int tok = M < kPremixTileTok ? M : kPremixTileTok;
         while (tok > 4 && premix_mfma_lds_bytes(tok, p.n_vec) > (size_t)kLdsLimit) --tok;
         const size_t lds = premix_mfma_lds_bytes(tok, p.n_vec);
         if (lds <= (size_t)kLdsLimit) {
             p.tok_per_wg = tok;
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_premix_mfma),
+            const premix_fn mf = dt == CORAL_F16 ? k_premix_mfma<kF16> : k_premix_mfma<kBF16>;
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(mf),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
                 return CORAL_ERR_HIP;
-            hipLaunchKernelGGL(k_premix_mfma, dim3(H / 16, (M + tok - 1) / tok), dim3(kBlock), lds,
-                               stream, p);
+            hipLaunchKernelGGL(mf, dim3(H / 16, (M + tok - 1) / tok), dim3(kBlock), lds, stream, p);
             return launch_status();
         }
     }
@@ -602,8 +607,7 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
     int gx = (pairs + kWavesPerBlock - 1) / kWavesPerBlock;
     if (gx > 2 * kMaxWorkgroups) gx = 2 * kMaxWorkgroups;
     const dim3 grid(gx, (M + tok - 1) / tok);
-    typedef void (*premix_fn)(PremixParams);
-    const premix_fn fn = bf16 ? k_premix<true> : k_premix<false>;
+    const premix_fn fn = CORAL_PICK_DT(dt, k_premix<kF32>, k_premix<kBF16>, k_premix<kF16>);
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)

@@ -19,7 +19,15 @@ constexpr int kMaxG = 1024;
 constexpr int kSelRegs = kMaxG / kWave;
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+// Storage type of hidden vectors and weights (the template parameter DT of the kernels):
+// fp32, bf16, or IEEE fp16; sums are fp32 in all three.  Values match coral_dtype.
+enum StorageType { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
 struct Cand {
     float v;
@@ -51,9 +59,14 @@ __device__ __forceinline__ void store_vec(uint4* p, uint4 v) {
     *reinterpret_cast<u32x4_t*>(p) = o;
 }
 
-template <bool BF16>
+template <int DT>
 __device__ __forceinline__ float dot_vec(uint4 w, uint4 h, float acc) {
-    if (BF16) {
+    if (DT == kF16) {
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w.x), __builtin_bit_cast(f16x2_t, h.x), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w.y), __builtin_bit_cast(f16x2_t, h.y), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w.z), __builtin_bit_cast(f16x2_t, h.z), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, w.w), __builtin_bit_cast(f16x2_t, h.w), acc, false);
+    } else if (DT == kBF16) {
         acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x),
                                               __builtin_bit_cast(bf16x2_t, h.x), acc, false);
         acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y),
@@ -69,6 +82,32 @@ __device__ __forceinline__ float dot_vec(uint4 w, uint4 h, float acc) {
         acc = fmaf(__uint_as_float(w.w), __uint_as_float(h.w), acc);
     }
     return acc;
+}
+
+// One 16x16 tile step of 32 columns on the matrix cores: lane l feeds row l%16, columns
+// 8*(l/16)..+8 of both operands (eight 16-bit values each) and holds rows 4*(l/16)..+4,
+// column l%16 of the result.
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_tile(uint4 a, uint4 b, f32x4_t acc) {
+    if (DT == kF16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), acc, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                   __builtin_bit_cast(bf16x8_t, b), acc, 0, 0, 0);
+}
+
+// A 16-bit storage value as fp32, and fp32 rounded to the storage type (nearest even).
+template <int DT>
+__device__ __forceinline__ float widen16(unsigned short bits) {
+    if (DT == kF16) return (float)__builtin_bit_cast(_Float16, bits);
+    return __uint_as_float((unsigned)bits << 16);
+}
+template <int DT>
+__device__ __forceinline__ unsigned short narrow16(float x) {
+    if (DT == kF16) return __builtin_bit_cast(unsigned short, (_Float16)x);
+    const unsigned u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;    // NaN stays NaN
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
 // ---------------------------------------------------------------- wave helpers

@@ -25,8 +25,6 @@ constexpr int kFusedBlock = kFusedWaves * kWave;
 constexpr int kFusedRows = 2;          // rows a wave loads together
 constexpr int kFusedSegs = 8;          // 1 KB segments of a row held in registers
 constexpr int kLdsLimit = 160 * 1024;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
 // gate rows loaded as 64-byte pieces (16 rows per wave load) or as whole 128-byte lines
@@ -378,7 +376,7 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
     }
 }
 
-template <bool BF16, int NT>
+template <int DT, int NT>
 __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* hs, Cand* my_lists,
                                              const uint4 (&w0)[kFusedSegs],
                                              const uint4 (&w1)[kFusedSegs],
@@ -401,8 +399,8 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
 #pragma unroll
             for (int i = 0; i < NT; ++i) {
                 const uint4 h = hs[tok[i] * hs_stride + j * kWave + lane];
-                a0[i] = dot_vec<BF16>(w0[j], h, a0[i]);
-                a1[i] = dot_vec<BF16>(w1[j], h, a1[i]);
+                a0[i] = dot_vec<DT>(w0[j], h, a0[i]);
+                a1[i] = dot_vec<DT>(w1[j], h, a1[i]);
             }
         }
     }
@@ -417,7 +415,7 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
     }
 }
 
-template <bool BF16, bool DENSE, int GATE, bool ROUTED = false>
+template <int DT, bool DENSE, int GATE, bool ROUTED = false>
 __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
@@ -579,9 +577,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                         }
 #pragma unroll
                         for (int u = 0; u < 2; ++u)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                                __builtin_bit_cast(bf16x8_t, ga[i0 + u]),
-                                __builtin_bit_cast(bf16x8_t, hb[u]), acc, 0, 0, 0);
+                            acc = mfma_tile<DT>(ga[i0 + u], hb[u], acc);
                     }
                     *reinterpret_cast<f32x4_t*>(gpart + ((size_t)wave * n_tt + tt) * kSlice + lane * 4) = acc;
                 }
@@ -633,10 +629,10 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                         if (j < p.jp) {
                             const uint4 h0 = hs[m * hs_stride + j * kWave + lane];
                             const uint4 h1 = hs[m1 * hs_stride + j * kWave + lane];
-                            a0 = dot_vec<BF16>(ga[j], h0, a0);
-                            b0 = dot_vec<BF16>(gb[j], h0, b0);
-                            a1 = dot_vec<BF16>(ga[j], h1, a1);
-                            b1 = dot_vec<BF16>(gb[j], h1, b1);
+                            a0 = dot_vec<DT>(ga[j], h0, a0);
+                            b0 = dot_vec<DT>(gb[j], h0, b0);
+                            a1 = dot_vec<DT>(ga[j], h1, a1);
+                            b1 = dot_vec<DT>(gb[j], h1, b1);
                         }
                     a0 = wave_sum(a0);
                     b0 = wave_sum(b0);
@@ -799,11 +795,11 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         while (rem) {                                  // wave-uniform
             const int cnt = __popcll(rem);
             if (cnt >= 4)
-                fused_tokens<BF16, 4>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 4>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
             else if (cnt >= 2)
-                fused_tokens<BF16, 2>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 2>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
             else
-                fused_tokens<BF16, 1>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 1>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
         }
         b = nb;
         rid0 = nrid0;

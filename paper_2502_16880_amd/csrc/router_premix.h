@@ -27,20 +27,13 @@ struct PremixParams {
     int M, H, n_vec, act, tok_per_wg;
 };
 
-// float -> bf16 bits, round to nearest, ties to even; NaN stays NaN.
-__device__ __forceinline__ unsigned short bf16_bits_rne(float x) {
-    const unsigned u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
-    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
 __device__ __forceinline__ float premix_act(float y, int act) {
     if (act == CORAL_ACT_SILU) return y / (1.0f + expf(-y));
     if (act == CORAL_ACT_RELU) return y > 0.f ? y : 0.f;
     return y;
 }
 
-template <bool BF16>
+template <int DT>
 __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
     extern __shared__ uint4 smem[];                                // [tb][n_vec]
     const int lane = threadIdx.x & (kWave - 1);
@@ -103,8 +96,8 @@ __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
                 for (int t = 0; t < kPremixTok; ++t)
                     if (t < tb) {                                  // uniform
                         const uint4 h = smem[t * p.n_vec + hv];
-                        a0[t] = dot_vec<BF16>(w0[j], h, a0[t]);
-                        a1[t] = dot_vec<BF16>(w1[j], h, a1[t]);
+                        a0[t] = dot_vec<DT>(w0[j], h, a0[t]);
+                        a1[t] = dot_vec<DT>(w1[j], h, a1[t]);
                     }
             }
         }
@@ -120,12 +113,12 @@ __global__ __launch_bounds__(kBlock) void k_premix(PremixParams p) {
             }
         if (lane < tb) {
             const size_t o = (size_t)(m0 + lane) * p.H;
-            if (BF16) {
+            if (DT != kF32) {
                 const unsigned short* hs = reinterpret_cast<const unsigned short*>(smem) + (size_t)lane * p.H;
                 unsigned short* out = static_cast<unsigned short*>(p.out);
-                out[o + r0] = bf16_bits_rne(premix_act(y0, p.act) + __uint_as_float((unsigned)hs[r0] << 16));
+                out[o + r0] = narrow16<DT>(premix_act(y0, p.act) + widen16<DT>(hs[r0]));
                 if (r1 != r0)
-                    out[o + r1] = bf16_bits_rne(premix_act(y1, p.act) + __uint_as_float((unsigned)hs[r1] << 16));
+                    out[o + r1] = narrow16<DT>(premix_act(y1, p.act) + widen16<DT>(hs[r1]));
             } else {
                 const float* hs = reinterpret_cast<const float*>(smem) + (size_t)lane * p.H;
                 float* out = static_cast<float*>(p.out);
@@ -148,6 +141,7 @@ __host__ __device__ inline size_t premix_mfma_lds_bytes(int tok, int n_vec) {
 // bf16, H a multiple of 64 (whole 128-byte lines).  Tile of 16 output features x 16 tokens:
 // A operand = rows of W1, B operand = hidden vectors from LDS (row stride padded by one
 // vector: conflict-free); lane l of the result holds features 4*(l/16)..+4 of token l%16.
+template <int DT>
 __global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
     extern __shared__ uint4 smem[];
     const int lane = threadIdx.x & (kWave - 1);
@@ -214,10 +208,8 @@ __global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
                 uint4 s0, s1;
                 mfma_operands_from_lines(lo[i], hi[i], lane, my_slice, s0, s1);
                 const uint4 b0 = hb[L * 8], b1 = hb[L * 8 + 4];
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, s0),
-                                                              __builtin_bit_cast(bf16x8_t, b0), acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, s1),
-                                                              __builtin_bit_cast(bf16x8_t, b1), acc, 0, 0, 0);
+                acc = mfma_tile<DT>(s0, b0, acc);
+                acc = mfma_tile<DT>(s1, b1, acc);
             }
         }
     }
@@ -232,7 +224,7 @@ __global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
         if (tok < tb) {
             const unsigned short* hrow = reinterpret_cast<const unsigned short*>(hs + (size_t)tok * stride);
             static_cast<unsigned short*>(p.out)[(size_t)(m0 + tok) * p.H + row] =
-                bf16_bits_rne(premix_act(y, p.act) + __uint_as_float((unsigned)hrow[row] << 16));
+                narrow16<DT>(premix_act(y, p.act) + widen16<DT>(hrow[row]));
         }
     }
 }

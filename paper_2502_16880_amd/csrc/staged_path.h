@@ -31,7 +31,7 @@ struct LogitsParams {
 // LDS and leaves each wave's best candidates per token in (lv, li).
 // LP: also keep, per token, the running maximum and the sum of exp(logit - maximum) over the
 // wave's rows (the pieces of Eq. 8's softmax inside a group).
-template <bool BF16, bool DENSE, int TB, bool LP>
+template <int DT, bool DENSE, int TB, bool LP>
 __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4* hs, int nt,
                                              int row_begin, int row_end, float (&lv)[TB],
                                              int (&li)[TB], float (&mx)[TB], float (&sm)[TB]) {
@@ -85,7 +85,7 @@ __device__ __forceinline__ void stream_chunk(const LogitsParams& p, const uint4*
                         const int tt = t < nt ? t : nt - 1;
                         const uint4 h = hs[tt * hs_stride + vec];
 #pragma unroll
-                        for (int r = 0; r < R; ++r) acc[r][t] = dot_vec<BF16>(w[ju][r], h, acc[r][t]);
+                        for (int r = 0; r < R; ++r) acc[r][t] = dot_vec<DT>(w[ju][r], h, acc[r][t]);
                     }
                 }
             }
@@ -112,7 +112,7 @@ __device__ __forceinline__ int nth_set_bit(unsigned long long m, int n) {
     return __ffsll(m) - 1;
 }
 
-template <bool BF16, bool DENSE, int TB, bool LP>
+template <int DT, bool DENSE, int TB, bool LP>
 __device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4* hs, Cand* mbuf,
                                              unsigned long long batch, int nt, int group,
                                              int chunk, int row_begin, int row_end) {
@@ -121,7 +121,7 @@ __device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4*
     const int wave = threadIdx.x / kWave;
     float lv[TB], mx[TB], sm[TB];
     int li[TB];
-    stream_chunk<BF16, DENSE, TB, LP>(p, hs, nt, row_begin, row_end, lv, li, mx, sm);
+    stream_chunk<DT, DENSE, TB, LP>(p, hs, nt, row_begin, row_end, lv, li, mx, sm);
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
         if (t >= nt) break;                            // block-uniform
@@ -160,7 +160,7 @@ __device__ __forceinline__ void chunk_tokens(const LogitsParams& p, const uint4*
 }
 
 // One workgroup per (chunk of kChunkRows rows, activated group).  Dense: per chunk.
-template <bool BF16, bool DENSE, bool LP = false>
+template <int DT, bool DENSE, bool LP = false>
 __global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
     extern __shared__ uint4 smem[];
     uint4* hs = smem;
@@ -204,13 +204,13 @@ __global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
         }
         __syncthreads();
         if (nt == 1)
-            chunk_tokens<BF16, DENSE, 1, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<DT, DENSE, 1, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else if (nt == 2)
-            chunk_tokens<BF16, DENSE, 2, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<DT, DENSE, 2, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else if (nt <= 4)
-            chunk_tokens<BF16, DENSE, 4, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<DT, DENSE, 4, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         else
-            chunk_tokens<BF16, DENSE, kTokBatch, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
+            chunk_tokens<DT, DENSE, kTokBatch, LP>(p, hs, mbuf, batch, nt, group, chunk, row_begin, row_end);
         // chunk_tokens ends on a barrier, so hs may be overwritten now
     }
 }
@@ -218,7 +218,7 @@ __global__ __launch_bounds__(kBlock) void k_logits(LogitsParams p) {
 // ---------------------------------------------------------------- gate
 // s[m,n] = sum_j gate_W[n,j] hidden[m,j] + bias[n]   (Eq. 7, W2 projection).
 // One workgroup per group n.
-template <bool BF16>
+template <int DT>
 __global__ __launch_bounds__(kBlock) void k_gate(const uint4* __restrict__ hidden,
                                                  const uint4* __restrict__ gate_W,
                                                  const float* __restrict__ bias, int M, int G,
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kBlock) void k_gate(const uint4* __restrict__ hidde
     for (int m = 0; m < M; ++m) {
         float acc = 0.f;
         for (int vec = threadIdx.x; vec < n_vec; vec += kBlock)
-            acc = dot_vec<BF16>(gate_W[(size_t)n * n_vec + vec], hidden[(size_t)m * n_vec + vec], acc);
+            acc = dot_vec<DT>(gate_W[(size_t)n * n_vec + vec], hidden[(size_t)m * n_vec + vec], acc);
         acc = wave_sum(acc);
         __syncthreads();
         if (lane == 0) red[wave] = acc;

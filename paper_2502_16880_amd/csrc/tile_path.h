@@ -238,7 +238,7 @@ __device__ __forceinline__ uint4 tile_load_w(const TileParams& p, unsigned row, 
 
 // Step pair SP of a chunk: the two 32-column steps whose weight lines sit in ring slots
 // 4 SP .. 4 SP + 3.
-template <int NCT, bool REFILL, int SP>
+template <int DT, int NCT, bool REFILL, int SP>
 __device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4 (&a)[kRing],
                                                f32x4_t (&acc)[2][4], const unsigned (&wrow)[4],
                                                uint4* hbuf, const int* tokslot, int n_t, TileStage& hst,
@@ -271,14 +271,12 @@ __device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4
             const uint4 hv = hb[(ct * 16 + r16) * kHbStride + off];
 #pragma unroll
             for (int t = 0; t < 2; ++t)
-                acc[t][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                    __builtin_bit_cast(bf16x8_t, op[t][s2]), __builtin_bit_cast(bf16x8_t, hv), acc[t][ct],
-                    0, 0, 0);
+                acc[t][ct] = mfma_tile<DT>(op[t][s2], hv, acc[t][ct]);
         }
     }
 }
 
-template <int NCT, bool REFILL>
+template <int DT, int NCT, bool REFILL>
 __device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a)[kRing],
                                            f32x4_t (&acc)[2][4], const unsigned (&wrow)[4],
                                            uint4* hbuf, const int* tokslot, int n_t, uint4* my_slice) {
@@ -290,17 +288,17 @@ __device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a
                                __builtin_amdgcn_readfirstlane(threadIdx.x / kWave));
         keep_memory_order();
     }
-    tile_step_pair<NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<NCT, REFILL, 1>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<NCT, REFILL, 2>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<NCT, REFILL, 3>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 1>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 2>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 3>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
     __syncthreads();
 }
 
 // The K loop of one block.  Hidden chunk staging: slots wave, wave + 8, ... below 16 NCT;
 // lane = vector inside the chunk; slots past the group's tokens repeat its last token
 // (their columns of the tiles are never read back).
-template <int NCT>
+template <int DT, int NCT>
 __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRing], f32x4_t (&acc)[2][4],
                                             const unsigned (&wrow)[4], uint4* hbuf,
                                             const int* tokslot, uint4* my_slice, int n_t) {
@@ -313,10 +311,11 @@ __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRin
     }
     __syncthreads();
     for (int c = 0; c + 1 < p.n_chunks; ++c)
-        tile_chunk<NCT, true>(p, c, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
-    tile_chunk<NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
+        tile_chunk<DT, NCT, true>(p, c, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
+    tile_chunk<DT, NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
 }
 
+template <int DT>
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
@@ -450,10 +449,10 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             for (int ct = 0; ct < 4; ++ct) acc[t][ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
         switch (n_ct) {                                    // block-uniform
-            case 1: tile_k_loop<1>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
-            case 2: tile_k_loop<2>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
-            case 3: tile_k_loop<3>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
-            default: tile_k_loop<4>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            case 1: tile_k_loop<DT, 1>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            case 2: tile_k_loop<DT, 2>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            case 3: tile_k_loop<DT, 3>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
+            default: tile_k_loop<DT, 4>(p, a, acc, wrow, hbuf, tokslot, my_slice, n_t); break;
         }
 
         // next block: locate it and start its first 16 weight loads before the epilogue
@@ -547,6 +546,7 @@ __device__ __forceinline__ float load_score(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+template <int DT>
 __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
     __shared__ unsigned long long mask[kMaxG];
@@ -576,12 +576,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(bf16x8_t,
-                                   mfma_operand_from_quads(a[i], lane, reinterpret_cast<uint4*>(part[wave]))),
-                __builtin_bit_cast(bf16x8_t,
-                                   mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave]))),
-                acc, 0, 0, 0);
+            acc = mfma_tile<DT>(mfma_operand_from_quads(a[i], lane, reinterpret_cast<uint4*>(part[wave])),
+                                mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave])), acc);
     }
     *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
     __syncthreads();

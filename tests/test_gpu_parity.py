@@ -85,6 +85,11 @@ SCALED = [
     (CONFIGS["qwen25_7b"].scaled(V=32 * 297), (1, 8, 16)),
     (CONFIGS["wide_tree"].scaled(V=64 * 126), (64,)),
     (CONFIGS["paper_point"].scaled(V=16 * 375), (1, 10)),          # contiguous groups
+    # fp16 storage on each of the three paths (single launch with all three gates, tiles,
+    # multi-kernel: H = 4160 does not fit eight wave loads)
+    (CONFIGS["llama3_8b"].scaled(name="llama3_f16", dtype="f16", V=32 * 203), (1, 4, 8, 16)),
+    (CONFIGS["wide_tree"].scaled(name="wide_tree_f16", dtype="f16", V=64 * 126), (64,)),
+    (CONFIGS["llama3_8b"].scaled(name="llama3_f16_h4160", dtype="f16", V=32 * 203, H=4160), (8,)),
 ]
 
 
@@ -381,7 +386,7 @@ def test_nan_inputs_do_not_fault(coral):
 
 # ------------------------------------------------------------------ full-size workloads
 FULL = [("llama2_7b", (1, 8)), ("llama3_8b", (1, 16)), ("qwen25_7b", (1, 16)), ("wide_tree", (64,)),
-        ("paper_point", (10,))]
+        ("paper_point", (10,)), ("paper_point_f16", (10,))]
 
 
 @pytest.mark.parametrize("name,Ms", FULL)
@@ -421,6 +426,7 @@ PREMIX_SHAPES = [
     # matrix-core kernel: fewer tokens than a tile, several ragged token batches, LDS that
     # only fits part of a tile's tokens, fewer lines than waves, more than one batch of lines
     ("bf16", 4096, 5), ("bf16", 4096, 40), ("bf16", 8192, 16), ("bf16", 192, 20), ("bf16", 4480, 4),
+    ("f16", 4096, 16), ("f16", 1000, 3), ("f16", 4096, 1),
 ]
 
 
@@ -436,7 +442,7 @@ def test_router_premix(coral, dtype, H, M):
         print(f"case premix {dtype} H={H} M={M} act={act}", flush=True)
         u = coral.coral_router_premix(d_h, d_W1, act)
         torch.cuda.synchronize()
-        raw = u.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else u.cpu().numpy()
+        raw = u.cpu().numpy() if dtype == "f32" else u.view(torch.int16).cpu().numpy().view(np.uint16)
         rep = compare.check_premix(hidden, W1, dtype, act, raw)
         assert rep.tokens == M
 
@@ -454,6 +460,7 @@ def test_router_premix_rejects_bad_arguments(coral):
 
 ROUTED = [
     (CONFIGS["tiny_f32"], (4,)),
+    (CONFIGS["llama3_8b"].scaled(name="llama3_f16", dtype="f16", V=32 * 203), (8,)),
     (CONFIGS["llama3_8b"].scaled(V=32 * 203), (1, 4, 8, 16)),     # single-launch path, all three gates
     (CONFIGS["wide_tree"].scaled(V=64 * 126), (64,)),             # tile path
     (CONFIGS["llama3_8b"].scaled(V=32 * 203, H=4160), (8,)),      # multi-kernel path
