@@ -621,8 +621,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             for (int n0 = wave; n0 < p.G; n0 += 2 * kFusedWaves) {
                 if (n0 != wave) load_gate_rows(n0);
                 const int n1 = n0 + kFusedWaves;
-                for (int m = 0; m < M; m += 2) {
-                    const int m1 = m + 1 < M ? m + 1 : m;
+                for (int m = 0; m + 1 < M; m += 2) {           // two tokens per pass
+                    const int m1 = m + 1;
                     float a0 = 0.f, b0 = 0.f, a1 = 0.f, b1 = 0.f;
 #pragma unroll
                     for (int j = 0; j < kFusedSegs; ++j)
@@ -647,6 +647,23 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                             s_lds[m * p.G + n1] = b0 + bias1;
                             s_lds[m1 * p.G + n1] = b1 + bias1;
                         }
+                    }
+                }
+                if (M & 1) {                                   // the last of an odd number of tokens
+                    const int m = M - 1;                       // (the dot instructions bound this step)
+                    float a0 = 0.f, b0 = 0.f;
+#pragma unroll
+                    for (int j = 0; j < kFusedSegs; ++j)
+                        if (j < p.jp) {
+                            const uint4 h0 = hs[m * hs_stride + j * kWave + lane];
+                            a0 = dot_vec<DT>(ga[j], h0, a0);
+                            b0 = dot_vec<DT>(gb[j], h0, b0);
+                        }
+                    a0 = wave_sum(a0);
+                    b0 = wave_sum(b0);
+                    if (lane == 0) {
+                        s_lds[m * p.G + n0] = a0 + bias_lds[n0];
+                        if (n1 < p.G) s_lds[m * p.G + n1] = b0 + bias_lds[n1];
                     }
                 }
             }
