@@ -44,7 +44,7 @@ constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path'
 constexpr size_t kCtrlBytes = 256;     // control words at the start of the workspace
 
 struct Layout {
-    size_t ctrl, fused_part, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, total;
+    size_t ctrl, fused_part, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
     int part_stride;
 };
 
@@ -74,6 +74,7 @@ Layout make_layout(int M, int V, int G, int g, int k) {
     L.part = take((size_t)M * L.part_stride * k * sizeof(Cand));
     L.lse_part = take((size_t)M * L.part_stride * 2 * sizeof(float));     // log-probability mode
     L.logp_sel = take((size_t)M * (g ? g : 1) * sizeof(float));
+    L.tile_table = take((size_t)(G ? G : 1) * sizeof(TileGroup));
     L.total = off;
     return L;
 }
@@ -237,8 +238,8 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
 // Enqueues k_tiles and the merge of its published lists.  For the grouped head the masks
 // and the list of activated groups must already be enqueued (k_gate, k_select).
 coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
-                          const coral_group_index* gi, const unsigned long long* mask,
-                          const int32_t* union_list, const int32_t* n_union, int M, int H, int V,
+                          const coral_group_index* gi, const TileGroup* table,
+                          const int32_t* n_union, int M, int H, int V,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
                           float* topk_logits, char* ws, const Layout& L, hipStream_t stream,
                           void* ev_before, void* ev_after) {
@@ -250,8 +251,7 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.lm_W = static_cast<const uint4*>(lm_W);
     p.offsets = gi ? gi->group_offsets : nullptr;
     p.rows = gi ? gi->group_rows : nullptr;
-    p.group_mask = mask;
-    p.union_list = union_list;
+    p.table = table;
     p.n_union = n_union;
     p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
     p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 4;
@@ -403,7 +403,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if (plan.path == 2) {
         GateSelParams q = {};
         q.hidden = ghid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
-        q.group_mask = mask; q.union_list = union_list; q.n_union = n_union;
+        TileGroup* table = reinterpret_cast<TileGroup*>(ws + L.tile_table);
+        q.group_mask = mask; q.offsets = gi->group_offsets; q.table = table; q.n_union = n_union;
         q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
@@ -411,7 +412,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
         hipLaunchKernelGGL(gs, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
-        return launch_tiles(false, hidden, lm_W, gi, mask, union_list, n_union, M, H, V, G, k, dt,
+        return launch_tiles(false, hidden, lm_W, gi, table, n_union, M, H, V, G, k, dt,
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                             ev_after);
     }
@@ -486,7 +487,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     const PathPlan plan = plan_path(true, M, H, V, 0, 0, k, dt);
     // many tokens per row: the contraction is no longer cheap on the vector units
     if (plan.path == 2)
-        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, nullptr, M, H, V, 0, k, dt,
+        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, M, H, V, 0, k, dt,
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream,
                             ev_before, ev_after);
     if (plan.path == 1)

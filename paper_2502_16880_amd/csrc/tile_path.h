@@ -42,14 +42,21 @@ static_assert(kTileWaves * kRedWave * 4 <= 2 * kHbBufVecs * 16, "the parked tile
 // sink them to their first use, which defeats prefetching).
 __device__ __forceinline__ void keep_memory_order() { asm volatile("" ::: "memory"); }
 
+// One activated group as the gate kernel hands it to the tile kernel: a single read per
+// group instead of a chain of dependent ones (list -> masks and offsets -> prefix).
+struct TileGroup {
+    int32_t group, start, end;              // rows group_rows[start, end)
+    int32_t first_block;                    // blocks of the groups before it
+    unsigned long long mask;                // tokens that selected it
+};
+
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* lm_W;                      // [V, n_vec]
     const int32_t* offsets;                 // [G+1]   (grouped)
     const int32_t* rows;                    // [V]     (grouped)
-    const unsigned long long* group_mask;   // [G]     (grouped)
-    const int32_t* union_list;              // [G]     (grouped)
-    const int32_t* n_union;                 // [1]     (grouped)
+    const struct TileGroup* table;          // [G]     (grouped) activated groups in working order
+    const int32_t* n_union;                 // [1]     (grouped) how many
     Cand* part;                             // [M, k, gridDim.x] published lists, entry-major
     unsigned int* next_block;               // block queue: zero before the launch
     int M, V, G, k;
@@ -351,21 +358,23 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         __syncthreads();
     } else {
         if (wave == 0) {
+            // the count and the table rows are requested together (rows past the count are
+            // stale but inside the table, which has u_max rows)
             const int count = *p.n_union;
-            for (int u = lane; u < count; u += kWave) {
-                const int n = p.union_list[u];
-                ugroup[u] = n;
-                umask[u] = p.group_mask[n];
-                ustart[u] = p.offsets[n];
-                uend[u] = p.offsets[n + 1];
+            for (int u = lane; u < p.u_max; u += kWave) {
+                const TileGroup tg = p.table[u];
+                if (u < count) {
+                    ugroup[u] = tg.group;
+                    umask[u] = tg.mask;
+                    ustart[u] = tg.start;
+                    uend[u] = tg.end;
+                    uprefix[u] = tg.first_block;
+                    if (u == count - 1)
+                        uprefix[count] = tg.first_block + (tg.end - tg.start + kTileRows - 1) / kTileRows;
+                }
             }
             if (lane == 0) {                           // LDS is in order within a wave
-                int acc = 0;
-                for (int u = 0; u < count; ++u) {
-                    uprefix[u] = acc;
-                    acc += (uend[u] - ustart[u] + kTileRows - 1) / kTileRows;
-                }
-                uprefix[count] = acc;
+                if (count == 0) uprefix[0] = 0;
                 flags[0] = count;
                 flags[1] = (int)drawn;
             }
@@ -536,7 +545,8 @@ struct GateSelParams {
     float* s;                               // [M, G] scores (workspace)
     int32_t* sel;                           // [M, g]
     unsigned long long* group_mask;         // [G]
-    int32_t* union_list;                    // [G]
+    const int32_t* offsets;                 // [G+1] row ranges of the groups
+    TileGroup* table;                       // [G] out: activated groups in working order
     int32_t* n_union;                       // [1]
     unsigned int* counter;                  // arrival counter, zero between calls
     int M, G, g, n_vec;
@@ -552,6 +562,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ unsigned long long mask[kMaxG];
     __shared__ unsigned long long sel_keys[kFusedWaves][kWave];
     __shared__ int ulist[kMaxG];
+    __shared__ int order[kMaxG], nblk[kMaxG];
     __shared__ int is_last, ucount;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -651,7 +662,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     }
     __syncthreads();
     // The activated groups in the order the tile kernel works through them: most token
-    // tiles (16 tokens each) first, then ascending group id; placed by rank counting.
+    // tiles (16 tokens each) first, then ascending group id; placed by rank counting.  The
+    // table row of each carries its row range, token mask and the number of blocks before it.
     const int count = uni(ucount);
     for (int u0 = threadIdx.x; u0 < count; u0 += kFusedBlock) {
         const int g0 = ulist[u0];
@@ -661,7 +673,28 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             const int wv = (__popcll(mask[ulist[v]]) + 15) >> 4;
             rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
         }
-        p.union_list[rank] = g0;
+        order[rank] = g0;
+        nblk[rank] = (p.offsets[g0 + 1] - p.offsets[g0] + kTileRows - 1) / kTileRows;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        int carry = 0;
+        for (int base = 0; base < count; base += kWave) {  // wave-uniform
+            const int r = base + lane;
+            const int nb = r < count ? nblk[r] : 0;
+            const int incl = wave_scan_inclusive(nb);
+            if (r < count) {
+                const int g0 = order[r];
+                TileGroup tg;
+                tg.group = g0;
+                tg.start = p.offsets[g0];
+                tg.end = p.offsets[g0 + 1];
+                tg.first_block = carry + incl - nb;
+                tg.mask = mask[g0];
+                p.table[r] = tg;
+            }
+            carry += __builtin_amdgcn_readlane(incl, 63);
+        }
     }
 }
 
