@@ -103,6 +103,13 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
 int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral_dtype dt);
 
 /*
+ * The same for coral_lmhead_grouped_logprob (Eq. 8's output): 1 = single-launch kernel
+ * (at most 64 activated groups, min(M*g, G) <= 64, g <= 16, and its LDS plan fits),
+ * 0 = staged path, -1 = sizes not supported.  Host-only.
+ */
+int coral_lmhead_logprob_path(int M, int H, int V, int G, int g, int k, coral_dtype dt);
+
+/*
  * Prepares a freshly allocated workspace: zeroes its control words (a small kernel
  * on hip_stream, no memset node, so it may be captured in a HIP graph).  Required
  * once before the first coral_lmhead_grouped / coral_lmhead_dense call that uses the

@@ -52,6 +52,8 @@ def _load():
     L.coral_lmhead_workspace_bytes.argtypes = [c.c_int] * 7
     L.coral_lmhead_path.restype = c.c_int
     L.coral_lmhead_path.argtypes = [c.c_int] * 8
+    L.coral_lmhead_logprob_path.restype = c.c_int
+    L.coral_lmhead_logprob_path.argtypes = [c.c_int] * 7
     L.coral_lmhead_workspace_init.restype = c.c_int
     L.coral_lmhead_workspace_init.argtypes = [c.c_void_p, c.c_size_t, c.c_void_p]
     L.coral_lmhead_grouped.restype = c.c_int
@@ -174,6 +176,10 @@ PATH_NAMES = {0: "staged", 1: "single-launch", 2: "tiles", -1: "unsupported"}
 
 def coral_lmhead_path(dense: bool, M: int, H: int, V: int, G: int, g: int, k: int, dt: int) -> int:
     return int(_L.coral_lmhead_path(1 if dense else 0, M, H, V, G, g, k, dt))
+
+
+def coral_lmhead_logprob_path(M: int, H: int, V: int, G: int, g: int, k: int, dt: int) -> int:
+    return int(_L.coral_lmhead_logprob_path(M, H, V, G, g, k, dt))
 
 
 def coral_lmhead_workspace_init(workspace: torch.Tensor, stream=None) -> None:

@@ -41,10 +41,11 @@ inline bool is_16bit(coral_dtype dt) { return dt != CORAL_F32; }
 #define CORAL_PICK_DT(dt, f32, bf16, f16) ((dt) == CORAL_F32 ? (f32) : (dt) == CORAL_BF16 ? (bf16) : (f16))
 
 constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path's grid
-constexpr size_t kCtrlBytes = 256;     // control words at the start of the workspace
+constexpr size_t kCtrlBytes = 512;     // control words at the start of the workspace
+static_assert(kCtrlBytes >= (kLpGroupCounters + kWave) * sizeof(unsigned int), "per-group counters");
 
 struct Layout {
-    size_t ctrl, fused_part, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
+    size_t ctrl, fused_part, fused_lse, fused_glist, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
     int part_stride;
 };
 
@@ -64,6 +65,8 @@ Layout make_layout(int M, int V, int G, int g, int k) {
     };
     L.ctrl = take(kCtrlBytes);
     L.fused_part = take((size_t)kMaxWorkgroups * M * k * sizeof(Cand));
+    L.fused_lse = take((size_t)kMaxWorkgroups * M * sizeof(unsigned long long));   // log-probability mode
+    L.fused_glist = take((size_t)M * (g ? g : 1) * k * sizeof(Cand));
     L.s = take((size_t)M * (G ? G : 1) * sizeof(float));
     L.sel = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.mask = take((size_t)(G ? G : 1) * sizeof(unsigned long long));
@@ -127,10 +130,24 @@ int compute_units() {
 
 // Gate of the single-launch path: more than four tokens go through the matrix cores (16-bit
 // storage only), with whole-line loads if their larger LDS slices still fit.
-int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype dt) {
+int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype dt, bool logprob = false) {
     if (dense || !is_16bit(dt) || M <= 4) return kGateVector;
-    if (fused_lds_layout(M, G, g, k, jp, false, kGateMfmaLines).total <= kLdsLimit) return kGateMfmaLines;
+    if (fused_lds_layout(M, G, g, k, jp, false, kGateMfmaLines, logprob).total <= kLdsLimit) return kGateMfmaLines;
     return kGateMfmaQuads;
+}
+
+// Activated groups at most.
+inline long long max_union(int M, int G, int g) { return (long long)M * g < G ? (long long)M * g : G; }
+
+// The single-launch kernel's log-probability mode gives every activated group workgroups of
+// its own and ranks the groups in one wave: at most 64 activated groups, fewer than half the
+// workgroups; a token's g lists share the LDS of one wave's lists.
+bool fused_logprob_fits(int M, int G, int g, int k, int jp, coral_dtype dt, int workgroups) {
+    if (jp > kFusedSegs || g > kFusedWaves) return false;
+    const long long um = max_union(M, G, g);
+    if (um > kWave || 2 * um > workgroups) return false;
+    return fused_lds_layout(M, G, g, k, jp, false, fused_gate_mode(false, M, G, g, k, jp, dt, true), true)
+               .total <= kLdsLimit;
 }
 
 // Enqueues the single-launch path (the caller has checked with plan_path that it fits).
@@ -138,11 +155,12 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
                const float* gate_bias,
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
-               char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after) {
+               char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after,
+               bool logprob = false) {
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
-    const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt);
-    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate);
+    const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt, logprob);
+    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate, logprob);
     if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
@@ -157,6 +175,8 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     p.rows = gi ? gi->group_rows : nullptr;
     p.sel_out = sel_groups;
     p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
+    p.lse_part = reinterpret_cast<unsigned long long*>(ws + L.fused_lse);
+    p.glist = reinterpret_cast<Cand*>(ws + L.fused_glist);
     p.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl);
     p.topk_ids = topk_ids;
     p.topk_logits = topk_logits;
@@ -165,19 +185,26 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     typedef void (*fused_fn)(FusedParams);
     const bool routed = !dense && gate_hidden != hidden;
     fused_fn fn;
-#define CORAL_FUSED_GATES(DT, R)                                                                 \
-    (gate == kGateMfmaLines   ? k_fused<DT, false, kGateMfmaLines, R>                            \
-     : gate == kGateMfmaQuads ? k_fused<DT, false, kGateMfmaQuads, R>                            \
-                              : k_fused<DT, false, kGateVector, R>)
-    if (dense)
+#define CORAL_FUSED_GATES(DT, R, LP)                                                             \
+    (gate == kGateMfmaLines   ? k_fused<DT, false, kGateMfmaLines, R, LP>                        \
+     : gate == kGateMfmaQuads ? k_fused<DT, false, kGateMfmaQuads, R, LP>                        \
+                              : k_fused<DT, false, kGateVector, R, LP>)
+    if (logprob && (dense || 2 * max_union(M, G, g) > P)) return CORAL_ERR_UNSUPPORTED;   // not reached
+    if (logprob && routed)
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, true, true>),
+                           CORAL_FUSED_GATES(kBF16, true, true), CORAL_FUSED_GATES(kF16, true, true));
+    else if (logprob)
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, false, true>),
+                           CORAL_FUSED_GATES(kBF16, false, true), CORAL_FUSED_GATES(kF16, false, true));
+    else if (dense)
         fn = CORAL_PICK_DT(dt, (k_fused<kF32, true, kGateVector>), (k_fused<kBF16, true, kGateVector>),
                            (k_fused<kF16, true, kGateVector>));
     else if (routed)
-        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, true>), CORAL_FUSED_GATES(kBF16, true),
-                           CORAL_FUSED_GATES(kF16, true));
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, true>), CORAL_FUSED_GATES(kBF16, true, false),
+                           CORAL_FUSED_GATES(kF16, true, false));
     else
-        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, false>), CORAL_FUSED_GATES(kBF16, false),
-                           CORAL_FUSED_GATES(kF16, false));
+        fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, false>), CORAL_FUSED_GATES(kBF16, false, false),
+                           CORAL_FUSED_GATES(kF16, false, false));
 #undef CORAL_FUSED_GATES
     if (F.total > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
@@ -214,10 +241,15 @@ struct PathPlan {
     int tile_umax, tile_lds;
 };
 
-PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_dtype dt) {
+PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_dtype dt,
+                   bool logprob = false) {
     PathPlan pl = {};
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
+    if (logprob) {     // the single-launch kernel where it fits, else the multi-kernel path
+        pl.path = !dense && fused_logprob_fits(M, G, g, k, jp, dt, kMaxWorkgroups) ? 1 : 0;
+        return pl;
+    }
     const bool fused_ok =
         jp <= kFusedSegs &&
         fused_lds_layout(M, dense ? 0 : G, dense ? 0 : g, k, jp, dense,
@@ -328,6 +360,11 @@ extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, i
     return plan_path(dense != 0, M, H, V, G, g, k, dt).path;
 }
 
+extern "C" int coral_lmhead_logprob_path(int M, int H, int V, int G, int g, int k, coral_dtype dt) {
+    if (coral_lmhead_path(0, M, H, V, G, g, k, dt) < 0) return -1;
+    return plan_path(false, M, H, V, G, g, k, dt, true).path;
+}
+
 extern "C" coral_status coral_lmhead_workspace_init(void* workspace, size_t workspace_bytes,
                                                     void* hip_stream) {
     coral_status st = check_workspace(workspace, workspace_bytes, kCtrlBytes);
@@ -382,12 +419,14 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
-    // the log-probability mode exists on the staged path only
-    PathPlan plan = plan_path(false, M, H, V, G, g, k, dt);
-    if (logprob) plan.path = 0;
+    PathPlan plan = plan_path(false, M, H, V, G, g, k, dt, logprob);
+    if (logprob && plan.path == 1) {   // a device with few compute units: see fused_logprob_fits
+        const int cu = compute_units();
+        if (2 * max_union(M, G, g) > (cu < kMaxWorkgroups ? cu : kMaxWorkgroups)) plan.path = 0;
+    }
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
-                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after);
+                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob);
     float* s = reinterpret_cast<float*>(ws + L.s);
     int32_t* sel = sel_groups ? sel_groups : reinterpret_cast<int32_t*>(ws + L.sel);
     unsigned long long* mask = reinterpret_cast<unsigned long long*>(ws + L.mask);
@@ -445,9 +484,9 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);
     if (lds > 160 * 1024) return CORAL_ERR_UNSUPPORTED;
     const int chunks = (max_rows + kChunkRows - 1) / kChunkRows;
-    const long long max_union = (long long)M * g < G ? (long long)M * g : G;
+    const long long union_max = max_union(M, G, g);
     if (chunks < 1) return CORAL_ERR_SHAPE;
-    dim3 grid(chunks, (unsigned)max_union);
+    dim3 grid(chunks, (unsigned)union_max);
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     typedef void (*logits_fn)(LogitsParams);
     const logits_fn fn =

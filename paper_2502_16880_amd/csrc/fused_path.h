@@ -25,6 +25,11 @@ constexpr int kFusedBlock = kFusedWaves * kWave;
 constexpr int kFusedRows = 2;          // rows a wave loads together
 constexpr int kFusedSegs = 8;          // 1 KB segments of a row held in registers
 constexpr int kLdsLimit = 160 * 1024;
+// Log-probability mode: a row pair's cost in a workgroup's time is its load latency plus
+// the dot products of every token that selected its group; measured in units of one
+// token's dot products the latency is about this much.
+constexpr int kLpBaseCost = 10;
+constexpr int kLpGroupCounters = 64;   // first of the 64 per-group arrival counters (control words)
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
 // gate rows loaded as 64-byte pieces (16 rows per wave load) or as whole 128-byte lines
@@ -52,7 +57,10 @@ struct FusedParams {
     const int32_t* rows;        // [V]          (grouped)
     int32_t* sel_out;           // [M, g] or null
     Cand* part;                 // [M, k, gridDim.x] per-workgroup lists, entry-major
-    unsigned int* counter;      // arrival counter, zero between calls
+    unsigned long long* lse_part;   // [M, gridDim.x] (max, sum of exp) pairs (log-probability mode)
+    Cand* glist;                // [M, g, k] a token's list per selected group (log-probability mode)
+    unsigned int* counter;      // arrival counter, zero between calls; the log-probability
+                                // mode also uses words kLpGroupCounters .. + 63, zero as well
     int32_t* topk_ids;          // [M, k]
     float* topk_logits;         // [M, k]
     int M, V, G, g, k;
@@ -62,6 +70,7 @@ struct FusedParams {
 struct FusedLds {
     int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags;
     int o_keys, o_offsets, o_bias;
+    int o_sel, o_wgstart;       // log-probability mode only
     int total;
 };
 
@@ -72,7 +81,7 @@ __host__ __device__ inline int hidden_lds_stride(int jp) { return jp * kWave + 1
 // Byte offsets of the kernel's regions in dynamic LDS (the host sizes the launch with the
 // same function the kernel lays its pointers out with).
 __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k, int jp, bool dense,
-                                                     int gate_mode) {
+                                                     int gate_mode, bool logprob = false) {
     FusedLds L;
     int off = 0;
     auto take = [&](size_t bytes) {
@@ -83,7 +92,9 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     long long um = (long long)M * g < G ? (long long)M * g : G;   // activated groups at most
     if (dense || um < 1) um = 1;
     size_t hidden_bytes = (size_t)M * hidden_lds_stride(jp) * sizeof(uint4);
-    const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes;
+    // merge scratch; the log-probability mode parks the waves' (max, sum) pairs behind it
+    const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes +
+                                 (logprob ? (size_t)kFusedWaves * M * 2 * sizeof(float) : 0);
     if (hidden_bytes < scratch_bytes) hidden_bytes = scratch_bytes;   // reused by the merges
     L.o_hidden = take(hidden_bytes);
     size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
@@ -105,6 +116,8 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     L.o_keys = take(dense ? 16 : (size_t)kFusedWaves * kWave * sizeof(unsigned long long));
     L.o_offsets = take(dense ? 16 : (size_t)(G + 1) * sizeof(int));
     L.o_bias = take(dense ? 16 : (size_t)G * sizeof(float));
+    L.o_sel = take(logprob ? (size_t)M * g * sizeof(int) : 0);
+    L.o_wgstart = take(logprob ? (size_t)(um + 1) * sizeof(int) : 0);
     L.total = off;
     return L;
 }
@@ -275,7 +288,8 @@ __device__ __forceinline__ int wave_append(Cand* scratch, int* tag_scratch, int 
 // k-th value, so only lists whose first entry reaches it can contribute, and of those only
 // entries that reach it (ties kept); the few survivors are ranked by counting.  If a bound
 // does not exist (fewer than k lists, more than 256 lists) or too many survive (64), the
-// lists are streamed through a sorted register list instead.
+// lists are streamed through a sorted register list instead.  No more than 64 candidates in
+// all are ranked directly.
 template <class Get, class Put>
 __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, WaveScratch* ws,
                                                 Get get, Put put) {
@@ -283,6 +297,20 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
     Cand* scratch = ws->cand;
     int* tags = ws->tags;
     const int inv_k = inv_small(k);
+    if (n_lists * k <= kWave) {
+        // one candidate per lane: ranked by counting at once
+        const int n_e = n_lists * k;
+        Cand c = sentinel();
+        if (lane < n_e) {
+            const int l = div_small(lane, inv_k);
+            c = get(l, lane - l * k);
+        }
+        const int n_real = __popcll(__ballot(is_real(c)));
+        const int r = wave_rank(ws->keys, c.v, c.id, n_e, lane);   // real ones are distinct
+        if (is_real(c) && r < k) put(r, c);
+        if (lane >= n_real && lane < k) put(lane, sentinel());
+        return;
+    }
     bool fast = n_lists >= k && n_lists <= 4 * kWave;
     int n_s = 0;
     unsigned tau = 0u;
@@ -353,20 +381,34 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
             return;
         }
     }
-    // general path
-    Cand seed = sentinel();
-    if (lane < k) seed = get(0, lane);
-    float lv = seed.v;
-    int li = seed.id;
+    // general path: the candidates stream through a sorted register list (lane i = rank i),
+    // 256 at a time so that their loads are in flight together; the first list, sorted
+    // already, seeds the register list
+    float lv = -INFINITY;
+    int li = INT_MAX;
     const int n_e = n_lists * k;
-    for (int base = k; base < n_e; base += kWave) {
-        const int e = base + lane;
-        Cand c = sentinel();
-        if (e < n_e) {
-            const int l = e / k;                       // n_e may exceed div_small's range here
-            c = get(l, e - l * k);
+    const bool small = n_e <= 4096;                    // div_small's range
+    for (int base = 0; base < n_e; base += 4 * kWave) {    // wave-uniform
+        Cand c4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int e = base + u * kWave + lane;
+            c4[u] = sentinel();
+            if (e < n_e) {
+                const int l = small ? div_small(e, inv_k) : e / k;
+                c4[u] = get(l, e - l * k);
+            }
         }
-        offer_candidates(lv, li, c, k, lane);
+        if (base == 0) {
+            if (lane < k) {
+                lv = c4[0].v;
+                li = c4[0].id;
+                c4[0] = sentinel();
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (base + u * kWave < n_e) offer_candidates(lv, li, c4[u], k, lane);
     }
     if (lane < k) {
         Cand o;
@@ -376,12 +418,32 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
     }
 }
 
-template <int DT, int NT>
+// Running log-sum-exp state (max, sum of exp(z - max)) of the lanes flagged `mine` takes in
+// z0 and z1 (-inf: absent).
+__device__ __forceinline__ void lse_update(float& m, float& s, float z0, float z1, bool mine) {
+    const float nm = fmaxf(m, fmaxf(z0, z1));
+    if (mine && nm > -INFINITY) {
+        s = s * expf(m - nm) + expf(z0 - nm) + expf(z1 - nm);
+        m = nm;
+    }
+}
+
+// Combines the (max, sum) states of all lanes (absent: (-inf, 0)) into log(sum of exp); -inf
+// if there is nothing to sum.
+__device__ __forceinline__ float lse_finish(float m, float s) {
+    float wm = m;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+    const float ws = wave_sum(wm > -INFINITY ? s * expf(m - wm) : 0.f);
+    return wm + logf(ws);
+}
+
+template <int DT, int NT, bool LP>
 __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* hs, Cand* my_lists,
                                              const uint4 (&w0)[kFusedSegs],
                                              const uint4 (&w1)[kFusedSegs],
                                              unsigned long long& rem, int rid0, int rid1, bool has1,
-                                             float& thr_v, int& thr_i) {
+                                             float& thr_v, int& thr_i, float& lse_m, float& lse_s) {
     const int lane = threadIdx.x & (kWave - 1);
     const int hs_stride = hidden_lds_stride(p.jp);
     int tok[NT];
@@ -408,18 +470,21 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
     for (int i = 0; i < NT; ++i) {
         const float z0 = wave_sum(a0[i]);
         lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z0, rid0, thr_v, thr_i, tok[i]);
+        float z1 = -INFINITY;
         if (has1) {                                    // uniform
-            const float z1 = wave_sum(a1[i]);
+            z1 = wave_sum(a1[i]);
             lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z1, rid1, thr_v, thr_i, tok[i]);
         }
+        if (LP) lse_update(lse_m, lse_s, z0, z1, lane == tok[i]);   // lane t: token t's state
     }
 }
 
-template <int DT, bool DENSE, int GATE, bool ROUTED = false>
+template <int DT, bool DENSE, int GATE, bool ROUTED = false, bool LP = false>
 __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
+    static_assert(!(LP && DENSE), "the log-probability mode belongs to the grouped head");
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
-    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, GATE);
+    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, GATE, LP);
     uint4* hs = reinterpret_cast<uint4*>(lds + lay.o_hidden);
     Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
     float* s_lds = reinterpret_cast<float*>(lds + lay.o_s);
@@ -432,6 +497,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     int* flags = reinterpret_cast<int*>(lds + lay.o_flags);
     int* off_lds = reinterpret_cast<int*>(lds + lay.o_offsets);
     float* bias_lds = reinterpret_cast<float*>(lds + lay.o_bias);
+    int* sel_lds = reinterpret_cast<int*>(lds + lay.o_sel);          // LP: [M, g] selections
+    int* wgstart = reinterpret_cast<int*>(lds + lay.o_wgstart);      // LP: first workgroup of a group
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -692,6 +759,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 if (lane < p.G && rank < p.g) {
                     atomicOr(&mask_lds[lane], 1ull << m);
                     if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = lane;
+                    if (LP) sel_lds[m * p.g + rank] = lane;
                 }
             }
         } else {
@@ -710,6 +778,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 if (rank < p.g) {
                     atomicOr(&mask_lds[n], 1ull << m);
                     if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = n;
+                    if (LP) sel_lds[m * p.g + rank] = n;
                 }
             }
         }
@@ -742,6 +811,33 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 uprefix[count] = carry;
                 flags[0] = count;
             }
+            if (LP) {
+                // Log-probability mode: every workgroup streams rows of one group only (it
+                // keeps one list and one log-sum-exp state per token, Eq. 8 normalises per
+                // group), so the workgroups are shared out among the count <= 64 activated
+                // groups in proportion to their cost, row pairs x (kLpBaseCost + tokens that
+                // selected the group): one each, the rest by the groups' shares rounded
+                // down, what is then left one more each to the groups with the highest cost
+                // per workgroup.  The numbers add up to gridDim.x.
+                const int P = gridDim.x;
+                const int nb = lane < count ? uprefix[lane + 1] - uprefix[lane] : 0;
+                // (row pairs scaled to 16 bits so that the products below stay in 31)
+                const int shift = max(0, 16 - __clz(carry));
+                const unsigned cost =
+                    lane < count ? (unsigned)(nb >> shift) * (unsigned)(kLpBaseCost + __popcll(umask[lane])) : 0u;
+                const unsigned total = (unsigned)__builtin_amdgcn_readlane(wave_scan_inclusive((int)cost), 63);
+                int n_wg = lane < count ? 1 + (int)(cost * (unsigned)(P - count) / (total ? total : 1u)) : 0;
+                const int left = P - __builtin_amdgcn_readlane(wave_scan_inclusive(n_wg), 63);
+                if (left > 0) {                        // wave-uniform
+                    unsigned long long* rank_keys = reinterpret_cast<unsigned long long*>(lds + lay.o_keys);
+                    const int rank = wave_rank(rank_keys, lane < count ? (float)cost / (float)n_wg : -INFINITY,
+                                               lane, kWave, lane);
+                    if (lane < count && rank < left) ++n_wg;
+                }
+                const int incl = wave_scan_inclusive(n_wg);
+                if (lane < count) wgstart[lane] = incl - n_wg;
+                if (lane == 0) wgstart[count] = P;
+            }
         }
         if (ROUTED) {
             hidden_commit(0);
@@ -757,15 +853,31 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     // The workgroup's row pairs are b(i) = (i / 16) * 16 * #workgroups + 16 * blockIdx + i % 16
     // for i = 0, 1, ...; its waves draw i from an LDS counter, so a wave that the memory
     // system serves faster takes more of them and all waves finish together.
+    // (Log-probability mode: the workgroup's share is a contiguous range of one group's row
+    // pairs instead, the j-th of the equal parts its group's workgroups cut the group into.)
     const int stride_batches = gridDim.x * kFusedWaves;
+    int u = 0;
+    int lp_lo = 0, lp_nwg = 0;
+    float lse_m = -INFINITY, lse_s = 0.f;              // lane t: token t's running log-sum-exp
+    if (LP) {
+        const int count = uni(flags[0]);
+        const int nxt = lane < count ? wgstart[lane + 1] : INT_MAX;
+        u = __popcll(__ballot(nxt <= (int)blockIdx.x));    // wgstart[u] <= blockIdx.x < wgstart[u + 1]
+        const int j = blockIdx.x - uni(wgstart[u]);
+        lp_nwg = uni(wgstart[u + 1]) - uni(wgstart[u]);
+        const int nb = uni(uprefix[u + 1]) - uni(uprefix[u]);
+        const int per = (nb + lp_nwg - 1) / lp_nwg;
+        lp_lo = uni(uprefix[u]) + min(j * per, nb);
+        total_batches = uni(uprefix[u]) + min((j + 1) * per, nb);  // the end of this workgroup's range
+    }
     auto draw_batch = [&]() {
         int i = 0;
         if (lane == 0) i = atomicAdd(&flags[2], 1);
         i = uni(i);
-        return (i / kFusedWaves) * stride_batches + blockIdx.x * kFusedWaves + (i % kFusedWaves);
+        if (LP) return lp_lo + i;
+        return (int)((i / kFusedWaves) * stride_batches + blockIdx.x * kFusedWaves + (i % kFusedWaves));
     };
     const unsigned long long all_tokens = M >= 64 ? ~0ull : ((1ull << M) - 1ull);
-    int u = 0;
     auto describe = [&](int b, int& rid0, int& rid1, bool& has1, unsigned long long& bm) {
         if (DENSE) {
             rid0 = b * kFusedRows;
@@ -812,11 +924,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         while (rem) {                                  // wave-uniform
             const int cnt = __popcll(rem);
             if (cnt >= 4)
-                fused_tokens<DT, 4>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 4, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                                        lse_m, lse_s);
             else if (cnt >= 2)
-                fused_tokens<DT, 2>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 2, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                                        lse_m, lse_s);
             else
-                fused_tokens<DT, 1>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i);
+                fused_tokens<DT, 1, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                                        lse_m, lse_s);
         }
         b = nb;
         rid0 = nrid0;
@@ -832,15 +947,140 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     const int P = gridDim.x;
     // published lists are entry-major, part[(t*k + i)*P + workgroup]: the first entries of
     // all workgroups, which bound the result, are contiguous
-    for (int t = wave; t < M; t += kFusedWaves) {
-        Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
-        wave_merge_topk(
-            kFusedWaves, k, lane, ws,
-            [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
-            [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
+    if (!LP) {
+        for (int t = wave; t < M; t += kFusedWaves) {
+            Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
+            wave_merge_topk(
+                kFusedWaves, k, lane, ws,
+                [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
+                [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
+        }
+    } else {
+        // the tokens of this workgroup's group only: their lists, ranked by logit (inside
+        // a group that is the order of log p as well), and their log-sum-exp pieces
+        float* lse_w = reinterpret_cast<float*>(lds + lay.o_hidden + kFusedWaves * sizeof(WaveScratch));
+        if (lane < M) {
+            lse_w[(wave * M + lane) * 2] = lse_m;
+            lse_w[(wave * M + lane) * 2 + 1] = lse_s;
+        }
+        __syncthreads();
+        unsigned long long rem = uni64(umask[u]);
+        for (int idx = 0; rem; ++idx, rem &= rem - 1ull) {     // block-uniform
+            if ((idx & (kFusedWaves - 1)) != wave) continue;
+            const int t = __ffsll(rem) - 1;
+            Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
+            wave_merge_topk(
+                kFusedWaves, k, lane, ws,
+                [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
+                [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
+            float pm = -INFINITY, ps = 0.f;
+            if (lane < kFusedWaves) {
+                pm = lse_w[(lane * M + t) * 2];
+                ps = lse_w[(lane * M + t) * 2 + 1];
+            }
+            float wm = pm;
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+            float tot = wm > -INFINITY ? ps * expf(pm - wm) : 0.f;   // summed in wave order
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+            if (lane == 0)
+                __hip_atomic_store(p.lse_part + (size_t)t * P + blockIdx.x,
+                                   ((unsigned long long)__float_as_uint(tot) << 32) | __float_as_uint(wm),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the published lists are out
     __syncthreads();
+    if (LP) {
+        // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n.  The workgroup of a group that
+        // arrives last (a counter per activated group) finishes the group: one wave per token
+        // that selected it combines the log-sum-exp pieces of the group's workgroups, takes
+        // the router's log-softmax over all G scores, merges the group's published lists by
+        // logit and publishes the k best with the offset added.  The group that finishes
+        // last (one more counter) merges every token's g lists.
+        unsigned int* group_counter = p.counter + kLpGroupCounters + u;
+        if (threadIdx.x == 0) {
+            const unsigned int old = __hip_atomic_fetch_add(group_counter, 1u, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+            flags[1] = old == (unsigned)lp_nwg - 1u ? 1 : 0;
+        }
+        __syncthreads();
+        if (!uni(flags[1])) return;                    // block-uniform
+        if (threadIdx.x == 0)                          // ready for the next call
+            __hip_atomic_store(group_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int n = uni(ugroup[u]);
+        const int w0 = uni(wgstart[u]);
+        Cand* mine = lists + (size_t)wave * M * k;     // the waves' lists are merged: free
+        unsigned long long rem = uni64(umask[u]);
+        for (int idx = 0; rem; ++idx, rem &= rem - 1ull) {     // block-uniform
+            if ((idx & (kFusedWaves - 1)) != wave) continue;
+            const int t = __ffsll(rem) - 1;
+            const int i = __ffsll(__ballot(lane < p.g && sel_lds[t * p.g + lane] == n)) - 1;
+            // the pieces are requested first and used after the merge, whose own loads
+            // then share their trip to memory
+            unsigned long long piece[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int l = c * kWave + lane;
+                piece[c] = 0xff800000ull;              // (-inf, 0)
+                if (l < lp_nwg)
+                    piece[c] = __hip_atomic_load(p.lse_part + (size_t)t * P + w0 + l, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const Cand* src = p.part + (size_t)t * k * P + w0;
+            wave_merge_topk(
+                lp_nwg, k, lane, ws, [&](int l, int e) { return fetch_cand(src + (size_t)e * P + l); },
+                [&](int r, Cand c) { mine[r] = c; });
+            float bm = -INFINITY, bs = 0.f;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {              // per lane in ascending workgroup order
+                const float pm = __uint_as_float((unsigned)(piece[c] & 0xffffffffull));
+                const float ps = __uint_as_float((unsigned)(piece[c] >> 32));
+                const float nm = fmaxf(bm, pm);
+                if (nm > -INFINITY) bs = bs * expf(bm - nm) + ps * expf(pm - nm);
+                bm = nm;
+            }
+            const float lse_n = lse_finish(bm, bs);
+            float rm = -INFINITY, rs = 0.f, s_n = 0.f;
+            for (int o = lane; o < p.G; o += kWave) {
+                float v = s_lds[t * p.G + o];
+                if (!(v == v)) v = -INFINITY;
+                if (o == n) s_n = v;
+                const float nm = fmaxf(rm, v);
+                if (nm > -INFINITY) rs = rs * expf(rm - nm) + expf(v - nm);
+                rm = nm;
+            }
+            s_n = wave_sum(s_n);                       // one lane holds it, the others zero
+            const float shift = (s_n - lse_finish(rm, rs)) - lse_n;
+            if (lane < k) {
+                Cand c = mine[lane];
+                if (is_real(c)) c.v += shift;
+                publish_cand(p.glist + ((size_t)t * p.g + i) * k + lane, c.v, c.id);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the group's lists are out
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+            flags[1] = old == (unsigned)uni(flags[0]) - 1u ? 1 : 0;
+        }
+        __syncthreads();
+        if (!uni(flags[1])) return;                    // block-uniform
+        for (int t = wave; t < M; t += kFusedWaves) {
+            const Cand* src = p.glist + (size_t)t * p.g * k;
+            wave_merge_topk(
+                p.g, k, lane, ws, [&](int l, int e) { return fetch_cand(src + l * k + e); },
+                [&](int r, Cand c) {
+                    p.topk_ids[(size_t)t * k + r] = c.id;
+                    p.topk_logits[(size_t)t * k + r] = c.v;
+                });
+        }
+        if (threadIdx.x == 0)
+            __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
     if (threadIdx.x == 0) {
         const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);

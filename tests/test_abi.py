@@ -73,6 +73,17 @@ def test_path_selection_covers_the_three_paths():
     assert path(False, 65, 256, 8192, 16, 2, 8, F32) == -1
 
 
+def test_logprob_path_selection():
+    lp = coral.coral_lmhead_logprob_path
+    assert lp(1, 4096, 128256, 32, 4, 10, BF16) == 1               # Llama3 shape
+    assert lp(16, 4096, 128256, 32, 4, 10, BF16) == 1
+    assert lp(16, 3584, 152064, 32, 4, 10, BF16) == 1              # Qwen shape
+    assert lp(64, 4096, 128256, 64, 8, 16, BF16) == 0              # wide tree: hidden exceeds LDS
+    assert lp(20, 256, 8192, 128, 4, 8, F32) == 0                  # 80 groups may be active
+    assert lp(2, 256, 8192, 64, 17, 8, F32) == 0                   # 17 lists per token
+    assert lp(65, 256, 8192, 16, 2, 8, F32) == -1
+
+
 def test_workspace_init_rejects_bad_arguments():
     L = coral._L
     assert L.coral_lmhead_workspace_init(None, 4096, None) == WORKSPACE

@@ -145,6 +145,53 @@ def test_logprob_edge_shapes(coral):
     check_logprob(dh, hidden, 3, 4, run_logprob(coral, dh, hidden, 3, 4))
 
 
+LOGPROB_PATH_CASES = [
+    # single-launch kernel: up to 64 activated groups with workgroups of their own
+    (HeadConfig("lp64", "bf16", 256, 64 * 37, 64, 2, (32,), 4, 98, True, bias_std=0.5), 1),
+    # ... every group active for every token (the probabilities of the whole vocabulary)
+    (HeadConfig("lpall", "bf16", 512, 16 * 300, 16, 16, (4,), 10, 99, True), 1),
+    # ... fp16 storage, contiguous groups, more candidates than a group's workgroups
+    (HeadConfig("lpf16", "f16", 1024, 8 * 4000, 8, 2, (7,), 33, 102, True, grouping="contiguous"), 1),
+    # multi-kernel path: more than 64 groups can be active; more than 16 groups per token
+    (HeadConfig("lpmany", "f32", 128, 128 * 20, 128, 4, (20,), 8, 100, False), 0),
+    (HeadConfig("lpg17", "f32", 128, 64 * 20, 64, 17, (2,), 8, 101, False), 0),
+]
+
+
+@pytest.mark.parametrize("cfg,path", LOGPROB_PATH_CASES, ids=lambda x: x.name if isinstance(x, HeadConfig) else None)
+def test_logprob_on_both_paths(coral, cfg, path):
+    M = cfg.Ms[0]
+    dt = {"f32": coral.CORAL_F32, "bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[cfg.dtype]
+    assert coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, dt) == path
+    dh = DeviceHead(coral, make_head(cfg))
+    for batch in (0, 1):
+        hidden = make_hidden(cfg, M, batch)
+        print(f"case {cfg.name} M={M} batch={batch} log-prob path {path}", flush=True)
+        rep = check_logprob(dh, hidden, cfg.g, cfg.k, run_logprob(coral, dh, hidden, cfg.g, cfg.k))
+        assert rep.tokens == M
+
+
+def test_logprob_with_empty_and_tiny_groups(coral):
+    """Groups without rows can be selected (their log-sum-exp is -inf and they offer no
+    candidate); a group smaller than its share of workgroups leaves workgroups idle."""
+    sizes = [0, 40, 0, 50, 3, 64, 5, 900]
+    V = sum(sizes)
+    cfg = HeadConfig("lpempty", "f32", 128, V, len(sizes), 3, (6,), 3, 103, False)
+    rng = np.random.default_rng(103)
+    perm = rng.permutation(V).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(len(sizes))])
+    lm_W = rng.standard_normal((V, cfg.H)).astype(np.float32) * np.float32(0.05)
+    gate_W = rng.standard_normal((len(sizes), cfg.H)).astype(np.float32) * np.float32(0.05)
+    bias = np.array([2.0, 0, 1.5, 0, 0.5, 0, 0.5, 0], np.float32)    # the empty groups do get chosen
+    dh = DeviceHead(coral, Head(cfg, lm_W, gate_W, bias, offsets, rows.astype(np.int32)))
+    assert coral.coral_lmhead_logprob_path(6, cfg.H, V, len(sizes), 3, 3, coral.CORAL_F32) == 1
+    hidden = make_hidden(cfg, 6)
+    out = run_logprob(coral, dh, hidden, 3, 3)
+    assert np.isin(out[2], [0, 2]).any()
+    check_logprob(dh, hidden, 3, 3, out)
+
+
 @pytest.mark.parametrize("dtype,H", [("bf16", 8), ("bf16", 264), ("bf16", 1032), ("f32", 4),
                                      ("f32", 260), ("f32", 1028)])
 def test_hidden_sizes_that_do_not_fill_a_wave(coral, dtype, H):
