@@ -148,14 +148,16 @@ class Bench:
         total_ms = self._timed(call, steps, warmup, R, eager)
         spread = self.last_spread
         kernel_us = self._kernel_us(call, min(event_steps, steps))
-        if not logprob and coral.coral_lmhead_path(False, M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt) == 1:
+        path = (coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt) if logprob
+                else coral.coral_lmhead_path(False, M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt))
+        if path == 1:
             # single launch: the events around the timed region time nothing but this kernel
             # (launch gaps included); the pair around one launch adds the dispatch latency
             kernel_us = min(kernel_us, self.last_event_ms * 1e3 / steps)
         U = sum(len(c[3]) for c in sched) / R
         return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms, kernel_us=kernel_us,
                     U=U, bytes=algorithmic_bytes(cfg, M, U), batches=R, sched=sched,
-                    out=(ids, z, sel), call=call, spread=spread)
+                    out=(ids, z, sel), call=call, spread=spread, path=path)
 
     def time_repeat(self, M, steps, warmup):
         """The same input every call: the activated rows may stay in the 256 MB last-level
@@ -413,7 +415,8 @@ def main():
                           "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
                           "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
         r = bench.time_grouped(a.M, n, min(a.warmup, 20), eager=a.eager, event_steps=48, logprob=True)
-        cases.append({"path": "grouped, log-probability output (Eq. 8; multi-kernel path, k_logits)",
+        lp_kernel = "single-launch kernel k_fused" if r["path"] == 1 else "multi-kernel path, k_logits"
+        cases.append({"path": f"grouped, log-probability output (Eq. 8; {lp_kernel})",
                       "M": a.M, "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
                       "avg_activated_groups": r["U"],
                       "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,

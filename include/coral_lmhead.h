@@ -172,8 +172,8 @@ coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
  * coral_lmhead_grouped's, which ranks the raw logits across groups.  Rows outside the
  * selected groups have probability zero (Eq. 8) and are never returned.
  *   topk_logprob [device] out [M,k] fp32 log-probabilities (natural logarithm)
- * All other arguments, limits and errors as for coral_lmhead_grouped.  Runs the
- * multi-kernel path for every shape.
+ * All other arguments, limits and errors as for coral_lmhead_grouped.  Runs in the
+ * single-launch kernel or on the staged path (coral_lmhead_logprob_path tells which).
  */
 coral_status coral_lmhead_grouped_logprob(const void *hidden, const void *gate_W,
                                           const float *gate_bias, const void *lm_W,

@@ -15,6 +15,13 @@
 //   5. merges its waves' lists and publishes one list per token; the workgroup that
 //      arrives last merges all workgroups' lists and writes the result.
 // The logits row never exists in memory.  No workgroup ever waits for another.
+//
+// Log-probability mode (LP, Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n, the softmax
+// taken inside each selected group): a workgroup streams rows of one group only, the
+// workgroups shared out among the activated groups by cost; lane t of every wave carries
+// token t's running log-sum-exp beside the lists; the last workgroup of each group finishes
+// the group (lse_n, offset, the group's k best per token) and the last group merges every
+// token's g lists.
 #pragma once
 #include "device_utils.h"
 
