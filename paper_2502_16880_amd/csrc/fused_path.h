@@ -1035,30 +1035,16 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the published lists are out
     __syncthreads();
     if (LP) {
-        // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n.  The workgroup of a group that
-        // arrives last (a counter per activated group) finishes the group: one wave per token
-        // that selected it combines the log-sum-exp pieces of the group's workgroups, takes
-        // the router's log-softmax over all G scores, merges the group's published lists by
-        // logit and publishes the k best with the offset added.  The group that finishes
-        // last (one more counter) merges every token's g lists.
-        unsigned int* group_counter = p.counter + kLpGroupCounters + u;
-        if (threadIdx.x == 0) {
-            const unsigned int old = __hip_atomic_fetch_add(group_counter, 1u, __ATOMIC_RELAXED,
-                                                            __HIP_MEMORY_SCOPE_AGENT);
-            flags[1] = old == (unsigned)lp_nwg - 1u ? 1 : 0;
-        }
-        __syncthreads();
-        if (!uni(flags[1])) return;                    // block-uniform
-        if (threadIdx.x == 0)                          // ready for the next call
-            __hip_atomic_store(group_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int n = uni(ugroup[u]);
-        const int w0 = uni(wgstart[u]);
+        // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n.  finish(t, gu) is one wave's work
+        // for token t and its selected group ugroup[gu]: it combines the log-sum-exp pieces
+        // of the group's workgroups, takes the router's log-softmax over all G scores, merges
+        // the group's published lists by logit and leaves the k best, offset added, in its
+        // lanes (lane r = rank r).
         Cand* mine = lists + (size_t)wave * M * k;     // the waves' lists are merged: free
-        unsigned long long rem = uni64(umask[u]);
-        for (int idx = 0; rem; ++idx, rem &= rem - 1ull) {     // block-uniform
-            if ((idx & (kFusedWaves - 1)) != wave) continue;
-            const int t = __ffsll(rem) - 1;
-            const int i = __ffsll(__ballot(lane < p.g && sel_lds[t * p.g + lane] == n)) - 1;
+        auto finish = [&](int t, int gu) {
+            const int n = uni(ugroup[gu]);
+            const int w0 = uni(wgstart[gu]);
+            const int n_wg = uni(wgstart[gu + 1]) - w0;
             // the pieces are requested first and used after the merge, whose own loads
             // then share their trip to memory
             unsigned long long piece[4];
@@ -1066,13 +1052,13 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             for (int c = 0; c < 4; ++c) {
                 const int l = c * kWave + lane;
                 piece[c] = 0xff800000ull;              // (-inf, 0)
-                if (l < lp_nwg)
+                if (l < n_wg)
                     piece[c] = __hip_atomic_load(p.lse_part + (size_t)t * P + w0 + l, __ATOMIC_RELAXED,
                                                  __HIP_MEMORY_SCOPE_AGENT);
             }
             const Cand* src = p.part + (size_t)t * k * P + w0;
             wave_merge_topk<true>(
-                lp_nwg, k, lane, ws, [&](int l, int e) { return fetch_cand(src + (size_t)e * P + l); },
+                n_wg, k, lane, ws, [&](int l, int e) { return fetch_cand(src + (size_t)e * P + l); },
                 [&](int r, Cand c) { mine[r] = c; });
             float bm = -INFINITY, bs = 0.f;
 #pragma unroll
@@ -1095,11 +1081,68 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             }
             s_n = wave_sum(s_n);                       // one lane holds it, the others zero
             const float shift = (s_n - lse_finish(rm, rs)) - lse_n;
-            if (lane < k) {
-                Cand c = mine[lane];
-                if (is_real(c)) c.v += shift;
-                publish_cand(p.glist + ((size_t)t * p.g + i) * k + lane, c.v, c.id);
+            Cand c = sentinel();
+            if (lane < k) c = mine[lane];
+            if (is_real(c)) c.v += shift;
+            return c;
+        };
+        auto write_result = [&](int t, int r, Cand c) {
+            p.topk_ids[(size_t)t * k + r] = c.id;
+            p.topk_logits[(size_t)t * k + r] = c.v;
+        };
+        if (2 * M * p.g <= kFusedWaves) {
+            // Few (token, group) pairs: the workgroup that arrives last takes them all, one
+            // wave each, and merges every token's g lists through LDS (two hand-overs through
+            // memory fewer than below; from about 16 pairs on the scheme below is faster).
+            if (threadIdx.x == 0) {
+                const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
+                                                                __HIP_MEMORY_SCOPE_AGENT);
+                flags[1] = old == gridDim.x - 1 ? 1 : 0;
             }
+            __syncthreads();
+            if (!uni(flags[1])) return;                // block-uniform
+            const int count = uni(flags[0]);
+            Cand* glists = reinterpret_cast<Cand*>(lds + lay.o_keys);   // [M * g, k], <= 16 x 64 entries
+            if (wave < M * p.g) {
+                const int n = uni(sel_lds[wave]);
+                const int gu = __ffsll(__ballot(lane < count && ugroup[lane] == n)) - 1;
+                const Cand c = finish(wave / p.g, gu);
+                if (lane < k) glists[wave * k + lane] = c;
+            }
+            __syncthreads();
+            if (wave < M) {
+                const Cand* src = glists + (size_t)wave * p.g * k;
+                wave_merge_topk(
+                    p.g, k, lane, ws, [&](int l, int e) { return src[l * k + e]; },
+                    [&](int r, Cand c) { write_result(wave, r, c); });
+            }
+            if (threadIdx.x == 0)                      // ready for the next call
+                __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        // More pairs than waves: the workgroup of a group that arrives last (a counter per
+        // activated group) finishes the group, one wave per token that selected it, and
+        // publishes the lists; the group that finishes last (one more counter) merges every
+        // token's g lists.  The groups' last workgroups work side by side, most of them
+        // while other groups still stream.
+        unsigned int* group_counter = p.counter + kLpGroupCounters + u;
+        if (threadIdx.x == 0) {
+            const unsigned int old = __hip_atomic_fetch_add(group_counter, 1u, __ATOMIC_RELAXED,
+                                                            __HIP_MEMORY_SCOPE_AGENT);
+            flags[1] = old == (unsigned)lp_nwg - 1u ? 1 : 0;
+        }
+        __syncthreads();
+        if (!uni(flags[1])) return;                    // block-uniform
+        if (threadIdx.x == 0)                          // ready for the next call
+            __hip_atomic_store(group_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int n = uni(ugroup[u]);
+        unsigned long long rem = uni64(umask[u]);
+        for (int idx = 0; rem; ++idx, rem &= rem - 1ull) {     // block-uniform
+            if ((idx & (kFusedWaves - 1)) != wave) continue;
+            const int t = __ffsll(rem) - 1;
+            const int i = __ffsll(__ballot(lane < p.g && sel_lds[t * p.g + lane] == n)) - 1;
+            const Cand c = finish(t, u);
+            if (lane < k) publish_cand(p.glist + ((size_t)t * p.g + i) * k + lane, c.v, c.id);
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the group's lists are out
         __syncthreads();
@@ -1114,10 +1157,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             const Cand* src = p.glist + (size_t)t * p.g * k;
             wave_merge_topk(
                 p.g, k, lane, ws, [&](int l, int e) { return fetch_cand(src + l * k + e); },
-                [&](int r, Cand c) {
-                    p.topk_ids[(size_t)t * k + r] = c.id;
-                    p.topk_logits[(size_t)t * k + r] = c.v;
-                });
+                [&](int r, Cand c) { write_result(t, r, c); });
         }
         if (threadIdx.x == 0)
             __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
