@@ -412,6 +412,45 @@ def test_hip_graph_replays_match_eager(coral):
     check_grouped(dh, hidden, cfg.g, cfg.k, (ids.cpu().numpy(), z.cpu().numpy(), sel.cpu().numpy()))
 
 
+@pytest.mark.parametrize("M", [1, 4])
+def test_hip_graph_replays_of_the_logprob_head(coral, M):
+    """The log-probability mode keeps several counters in the workspace (one per activated
+    group with 4 tokens, one in all with 1 token): every replay, and an eager call after the
+    replays, must find them as the first call did."""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 501)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, M, 3)
+    d_hidden = coral.device_tensor(hidden, cfg.dtype)
+    assert coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16) == 1
+    ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16)
+    ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+    lp = torch.empty((M, cfg.k), device="cuda")
+    sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+
+    def call():
+        coral.coral_lmhead_grouped_logprob(d_hidden, dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                           topk_ids=ids, topk_logits=lp, sel_groups=sel, workspace=ws)
+
+    call()
+    torch.cuda.synchronize()
+    want = (ids.clone(), lp.clone(), sel.clone())
+    check_logprob(dh, hidden, cfg.g, cfg.k, tuple(x.cpu().numpy() for x in want))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+        call()
+    for rep in range(3):
+        ids.fill_(-1), lp.zero_(), sel.fill_(-1)            # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ids, want[0]) and torch.equal(lp, want[1]) and torch.equal(sel, want[2]), rep
+    ids.fill_(-1)
+    call()
+    torch.cuda.synchronize()
+    assert torch.equal(ids, want[0]) and torch.equal(lp, want[1])
+
+
 def test_nan_inputs_do_not_fault(coral):
     """Results are unspecified for NaN inputs, but every path must finish and stay in range."""
     for cfg, M in ((CONFIGS["tiny_f32"], 4), (CONFIGS["llama2_7b"].scaled(V=16 * 250), 12),
@@ -429,6 +468,8 @@ def test_nan_inputs_do_not_fault(coral):
         assert np.all((sel >= 0) & (sel < cfg.G))
         assert np.all(ids[1:] >= 0) and np.all(ids[1:] < cfg.V)   # tokens without NaN are intact
         run_dense(coral, dh, hidden, cfg.k)
+        ids, _, sel = run_logprob(coral, dh, hidden, cfg.g, cfg.k)
+        assert np.all((sel >= 0) & (sel < cfg.G))
 
 
 # ------------------------------------------------------------------ full-size workloads
