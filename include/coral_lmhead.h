@@ -243,6 +243,30 @@ coral_status coral_tree_expand(const float *parent_score, const int32_t *cand_id
                                float *next_score, void *hip_stream);
 
 /*
+ * One level of tree drafting in one call: the log-probability head of section 3.3 (Eq. 7,
+ * Eq. 8; arguments as coral_lmhead_grouped_routed with logprob != 0, gate_hidden may be
+ * NULL) for the M nodes of the current level, then coral_tree_expand on its own output
+ * (cand_ids = topk_ids, cand_logp = topk_logprob).  Where the head runs in the single-launch
+ * kernel (coral_lmhead_logprob_path == 1) the workgroup that writes the head's result also
+ * expands the level, so the call is one launch; otherwise the expansion is one more launch
+ * behind the staged path's.  Results are identical to the two calls made one after the other.
+ *   parent_score [device] [M] fp32 or NULL, n_next, next_parent / next_token / next_score
+ *   [device] out [n_next]: as for coral_tree_expand.  topk_ids, topk_logprob, sel_groups:
+ *   as for coral_lmhead_grouped_logprob (they are written as well).
+ * Errors as for the two calls.
+ */
+coral_status coral_lmhead_draft_level(const void *hidden, const void *gate_hidden,
+                                      const void *gate_W, const float *gate_bias,
+                                      const void *lm_W, const coral_group_index *gi,
+                                      int M, int H, int V, int g, int k, coral_dtype dt,
+                                      const float *parent_score, int n_next,
+                                      int32_t *topk_ids, float *topk_logprob,
+                                      int32_t *sel_groups, int32_t *next_parent,
+                                      int32_t *next_token, float *next_score,
+                                      void *workspace, size_t workspace_bytes,
+                                      void *hip_stream);
+
+/*
  * Dense LM head: z[m,r] for every r = 0..V-1, then the k best per token with the
  * same ordering rules (the no-router baseline of Table 4; the head whose latency
  * the appendix paragraph "Backends" measures).  Arguments as above; k <= V.

@@ -77,6 +77,10 @@ def _load():
                                       c.c_void_p, c.c_void_p]
     L.coral_tree_expand.restype = c.c_int
     L.coral_tree_expand.argtypes = [c.c_void_p] * 3 + [c.c_int] * 3 + [c.c_void_p] * 4
+    L.coral_lmhead_draft_level.restype = c.c_int
+    L.coral_lmhead_draft_level.argtypes = [c.c_void_p] * 5 + [c.POINTER(_GroupIndexStruct)] + \
+                                          [c.c_int] * 6 + [c.c_void_p, c.c_int] + [c.c_void_p] * 7 + \
+                                          [c.c_size_t, c.c_void_p]
     L.coral_lmhead_grouped_routed.restype = c.c_int
     L.coral_lmhead_grouped_routed.argtypes = [c.c_void_p] * 5 + [c.POINTER(_GroupIndexStruct)] + \
                                              [c.c_int] * 7 + [c.c_void_p] * 4 + \
@@ -204,11 +208,13 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
                          topk_logits: Optional[torch.Tensor] = None,
                          sel_groups: Optional[torch.Tensor] = None,
                          workspace: Optional[torch.Tensor] = None, stream=None, events=None,
-                         logprob: bool = False, gate_hidden: Optional[torch.Tensor] = None
-                         ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+                         logprob: bool = False, gate_hidden: Optional[torch.Tensor] = None,
+                         level=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry.
     logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x)).
-    gate_hidden: call coral_lmhead_grouped_routed (the router sees this [M,H] tensor)."""
+    gate_hidden: call coral_lmhead_grouped_routed (the router sees this [M,H] tensor).
+    level: (parent_score or None, n_next, next_parent, next_token, next_score): call
+    coral_lmhead_draft_level (see coral_lmhead_draft_level below)."""
     dt = _dtype_code(hidden)
     if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
         raise TypeError("hidden, gate_W and lm_W must share one dtype")
@@ -237,11 +243,21 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
             _dev_ptr(topk_logits, "topk_logits", torch.float32),
             _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
-    if gate_hidden is not None:
+    if gate_hidden is not None and (gate_hidden.dtype != hidden.dtype or gate_hidden.shape != hidden.shape):
+        raise ValueError("gate_hidden must match hidden in dtype and shape")
+    if level is not None:
+        if events is not None:
+            raise ValueError("the draft-level entry point has no measurement variant")
+        parent_score, n_next, next_parent, next_token, next_score = level
+        st = _L.coral_lmhead_draft_level(
+            args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
+            _dev_ptr(parent_score, "parent_score", torch.float32), int(n_next), *args[11:14],
+            _dev_ptr(next_parent, "next_parent", torch.int32),
+            _dev_ptr(next_token, "next_token", torch.int32),
+            _dev_ptr(next_score, "next_score", torch.float32), *args[14:])
+    elif gate_hidden is not None:
         if events is not None:
             raise ValueError("the routed entry point has no measurement variant")
-        if gate_hidden.dtype != hidden.dtype or gate_hidden.shape != hidden.shape:
-            raise ValueError("gate_hidden must match hidden in dtype and shape")
         st = _L.coral_lmhead_grouped_routed(args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
                                             1 if logprob else 0, *args[11:])
     elif events is None:
@@ -295,6 +311,32 @@ def coral_tree_expand(parent_score: Optional[torch.Tensor], cand_ids: torch.Tens
                                 _dev_ptr(parent, "next_parent"), _dev_ptr(token, "next_token"),
                                 _dev_ptr(score, "next_score"), _stream_ptr(stream)))
     return parent, token, score
+
+
+def coral_lmhead_draft_level(hidden, gate_W, gate_bias, lm_W, gi, g, k, n_next: int,
+                             parent_score: Optional[torch.Tensor] = None,
+                             next_parent: Optional[torch.Tensor] = None,
+                             next_token: Optional[torch.Tensor] = None,
+                             next_score: Optional[torch.Tensor] = None, **kw):
+    """coral_lmhead_draft_level of the C ABI: the log-probability head for the M nodes of a tree
+    level and the level's expansion.  Returns (ids, log-probabilities, selected groups,
+    parent index, token id, cumulative score), the last three [n_next]."""
+    M = hidden.shape[0]
+    dev = hidden.device
+    if parent_score is not None and parent_score.shape != (M,):
+        raise ValueError("parent_score must be [M]")
+    if next_parent is None:
+        next_parent = torch.empty(n_next, dtype=torch.int32, device=dev)
+    if next_token is None:
+        next_token = torch.empty(n_next, dtype=torch.int32, device=dev)
+    if next_score is None:
+        next_score = torch.empty(n_next, dtype=torch.float32, device=dev)
+    if next_parent.shape != (n_next,) or next_token.shape != (n_next,) or next_score.shape != (n_next,):
+        raise ValueError("next_parent, next_token and next_score must be [n_next]")
+    ids, logp, sel = coral_lmhead_grouped(hidden, gate_W, gate_bias, lm_W, gi, g, k, logprob=True,
+                                          level=(parent_score, n_next, next_parent, next_token, next_score),
+                                          **kw)
+    return ids, logp, sel, next_parent, next_token, next_score
 
 
 def coral_lmhead_grouped_logprob(hidden, gate_W, gate_bias, lm_W, gi, g, k, **kw):

@@ -150,13 +150,23 @@ bool fused_logprob_fits(int M, int G, int g, int k, int jp, coral_dtype dt, int 
                .total <= kLdsLimit;
 }
 
+// What a draft-level call adds to the log-probability head: the expansion of the tree level
+// whose nodes are the call's tokens.
+struct LevelExpand {
+    const float* parent_score;
+    int n_next;
+    int32_t* next_parent;
+    int32_t* next_token;
+    float* next_score;
+};
+
 // Enqueues the single-launch path (the caller has checked with plan_path that it fits).
 coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidden, const void* gate_W,
                const float* gate_bias,
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
                char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after,
-               bool logprob = false) {
+               bool logprob = false, const LevelExpand* level = nullptr) {
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt, logprob);
@@ -177,6 +187,13 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
     p.lse_part = reinterpret_cast<unsigned long long*>(ws + L.fused_lse);
     p.glist = reinterpret_cast<Cand*>(ws + L.fused_glist);
+    if (level) {
+        p.parent_score = level->parent_score;
+        p.n_next = level->n_next;
+        p.next_parent = level->next_parent;
+        p.next_token = level->next_token;
+        p.next_score = level->next_score;
+    }
     p.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl);
     p.topk_ids = topk_ids;
     p.topk_logits = topk_logits;
@@ -381,7 +398,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
                           const float* gate_bias, const void* lm_W, const coral_group_index* gi, int M, int H, int V,
                           int g, int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits,
                           int32_t* sel_groups, void* workspace, size_t workspace_bytes,
-                          void* hip_stream, void* ev_before, void* ev_after, bool logprob) {
+                          void* hip_stream, void* ev_before, void* ev_after, bool logprob,
+                          const LevelExpand* level = nullptr) {
     if (!gate_W || !gi) return CORAL_ERR_NULL;
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
@@ -426,7 +444,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     }
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
-                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob);
+                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob, level);
     float* s = reinterpret_cast<float*>(ws + L.s);
     int32_t* sel = sel_groups ? sel_groups : reinterpret_cast<int32_t*>(ws + L.sel);
     unsigned long long* mask = reinterpret_cast<unsigned long long*>(ws + L.mask);
@@ -507,6 +525,11 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     else
         hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
                            gi->group_offsets, g, 0, k, topk_ids, topk_logits);
+    if ((st = launch_status()) != CORAL_OK || !level) return st;
+    // draft-level call on the multi-kernel path: the expansion is one more launch
+    hipLaunchKernelGGL(k_tree_expand, dim3(M), dim3(kWave), (size_t)M * k * sizeof(unsigned long long),
+                       stream, level->parent_score, topk_ids, topk_logits, M, k, level->n_next,
+                       level->next_parent, level->next_token, level->next_score);
     return launch_status();
 }
 
@@ -581,6 +604,22 @@ extern "C" coral_status coral_lmhead_grouped_routed(
     return grouped_impl(hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_out, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
                         nullptr, logprob != 0);
+}
+
+extern "C" coral_status coral_lmhead_draft_level(
+    const void* hidden, const void* gate_hidden, const void* gate_W, const float* gate_bias,
+    const void* lm_W, const coral_group_index* gi, int M, int H, int V, int g, int k,
+    coral_dtype dt, const float* parent_score, int n_next, int32_t* topk_ids, float* topk_logprob,
+    int32_t* sel_groups, int32_t* next_parent, int32_t* next_token, float* next_score,
+    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!next_parent || !next_token || !next_score) return CORAL_ERR_NULL;
+    if (M < 1 || k < 1 || n_next < 1) return CORAL_ERR_SHAPE;
+    if (M > kMaxM || k > kMaxK) return CORAL_ERR_UNSUPPORTED;
+    if (n_next > M * k) return CORAL_ERR_SHAPE;
+    const LevelExpand level = {parent_score, n_next, next_parent, next_token, next_score};
+    return grouped_impl(hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logprob, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
+                        nullptr, true, &level);
 }
 
 extern "C" coral_status coral_tree_expand(const float* parent_score, const int32_t* cand_ids,

@@ -230,4 +230,12 @@ __device__ __forceinline__ void block_rank_merge(const Cand* buf, int n, int k, 
 }
 
 
+// Order-preserving 64-bit key: key(a) > key(b) exactly when a beats b (larger value
+// first, then lower id).  -0.0 counts as +0.0, as it does for the float comparison.
+__device__ __forceinline__ unsigned long long cand_key(float v, int id) {
+    unsigned u = __float_as_uint(v + 0.0f);
+    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+    return ((unsigned long long)u << 32) | (unsigned)(~id);
+}
+
 }  // namespace

@@ -24,6 +24,7 @@
 // token's g lists.
 #pragma once
 #include "device_utils.h"
+#include "tree_expand.h"
 
 namespace {
 
@@ -66,6 +67,13 @@ struct FusedParams {
     Cand* part;                 // [M, k, gridDim.x] per-workgroup lists, entry-major
     unsigned long long* lse_part;   // [M, gridDim.x] (max, sum of exp) pairs (log-probability mode)
     Cand* glist;                // [M, g, k] a token's list per selected group (log-probability mode)
+    // Draft-level call (log-probability mode): the tokens are the nodes of a tree level and
+    // the workgroup that writes the result also expands the level (tree_expand.h).
+    const float* parent_score;  // [M] cumulative log-probabilities of the nodes, or null (zero)
+    int32_t* next_parent;       // [n_next], or null: no expansion
+    int32_t* next_token;        // [n_next]
+    float* next_score;          // [n_next]
+    int n_next;
     unsigned int* counter;      // arrival counter, zero between calls; the log-probability
                                 // mode also uses words kLpGroupCounters .. + 63, zero as well
     int32_t* topk_ids;          // [M, k]
@@ -207,14 +215,6 @@ __device__ __forceinline__ void offer_candidates(float& lv, int& li, Cand c, int
 }
 
 // ---------------------------------------------------------------- merging sorted lists
-// Order-preserving 64-bit key: key(a) > key(b) exactly when a beats b (larger logit
-// first, then lower id).  -0.0 counts as +0.0, as it does for the float comparison.
-__device__ __forceinline__ unsigned long long cand_key(float v, int id) {
-    unsigned u = __float_as_uint(v + 0.0f);
-    u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
-    return ((unsigned long long)u << 32) | (unsigned)(~id);
-}
-
 // Number of keys[0, n) above `key`.  keys is LDS that this wave wrote itself (a wave's LDS
 // accesses complete in order); every lane reads the same address, which LDS broadcasts.
 __device__ __forceinline__ int count_above(const unsigned long long* keys, int n, unsigned long long key) {
@@ -1086,9 +1086,43 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             if (is_real(c)) c.v += shift;
             return c;
         };
+        // Draft-level call: the results also go to a table of tree keys in LDS (the waves'
+        // lists are no longer needed), from which the level is expanded below.
+        const bool expand = p.next_parent != nullptr;  // uniform
+        unsigned long long* tree_keys = reinterpret_cast<unsigned long long*>(lists);   // [M * k]
+        int* tree_ids = reinterpret_cast<int*>(tree_keys + M * k);
+        float* tree_scores = reinterpret_cast<float*>(tree_ids + M * k);
         auto write_result = [&](int t, int r, Cand c) {
             p.topk_ids[(size_t)t * k + r] = c.id;
             p.topk_logits[(size_t)t * k + r] = c.v;
+            if (expand) {
+                const int e = t * k + r;
+                const float parent = p.parent_score ? p.parent_score[t] : 0.f;
+                tree_keys[e] = tree_key(parent, c.v, is_real(c) ? c.id : -1, e);
+                tree_ids[e] = c.id;
+                tree_scores[e] = parent + c.v;
+            }
+        };
+        auto expand_level = [&]() {                    // called by every thread of the workgroup
+            if (!expand) return;
+            __syncthreads();
+            for (int m = wave; m < M; m += kFusedWaves) {
+                int e;
+                bool keep;
+                const int rank = tree_rank_node(tree_keys, M, k, p.n_next, m, lane, e, keep);
+                if (keep) {
+                    p.next_parent[rank] = m;
+                    p.next_token[rank] = tree_ids[e];
+                    p.next_score[rank] = tree_scores[e];
+                }
+            }
+            if (wave == 0) {
+                int n_real = 0;
+                for (int e = lane; e < M * k; e += kWave) n_real += tree_keys[e] != 0ull ? 1 : 0;
+                n_real = wave_scan_inclusive(n_real);
+                n_real = __builtin_amdgcn_readlane(n_real, 63);
+                tree_pad(n_real, p.n_next, lane, p.next_parent, p.next_token, p.next_score);
+            }
         };
         if (2 * M * p.g <= kFusedWaves) {
             // Few (token, group) pairs: the workgroup that arrives last takes them all, one
@@ -1116,6 +1150,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     p.g, k, lane, ws, [&](int l, int e) { return src[l * k + e]; },
                     [&](int r, Cand c) { write_result(wave, r, c); });
             }
+            expand_level();
             if (threadIdx.x == 0)                      // ready for the next call
                 __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
@@ -1159,6 +1194,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 p.g, k, lane, ws, [&](int l, int e) { return fetch_cand(src + l * k + e); },
                 [&](int r, Cand c) { write_result(t, r, c); });
         }
+        expand_level();
         if (threadIdx.x == 0)
             __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;

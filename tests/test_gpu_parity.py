@@ -666,3 +666,55 @@ def test_tree_expand_after_the_logprob_head(coral):
     assert np.sum(all_scores > s[-1]) <= n_next - 1
     with pytest.raises(coral.CoralError):
         coral.coral_tree_expand(parent, ids, logp, M * cfg.k + 1)
+
+
+DRAFT_LEVEL_CASES = [
+    # (config, M, n_next, parent scores?, expected log-probability path)
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203), 8, 10, True, 1),        # a group's last workgroup finishes it
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203), 1, 10, False, 1),       # root level: the last workgroup alone
+    (CONFIGS["llama3_8b"].scaled(V=32 * 203), 16, 7, True, 1),        # fewer nodes kept than candidates per node
+    (CONFIGS["paper_point"].scaled(V=16 * 501), 10, 10, True, 1),
+    (CONFIGS["tiny_f32"], 4, 32, True, 1),                            # every candidate kept (n_next = M k)
+    (CONFIGS["llama2_7b"].scaled(H=1024, V=16 * 250, k=40), 20, 64, True, 1),  # lists of 40, 20 nodes
+    (CONFIGS["wide_tree"].scaled(V=64 * 126), 64, 64, True, 0),       # multi-kernel path: one more launch
+]
+
+
+@pytest.mark.parametrize("cfg,M,n_next,with_parent,path", DRAFT_LEVEL_CASES,
+                         ids=lambda x: x.name if isinstance(x, HeadConfig) else None)
+def test_draft_level_is_the_head_followed_by_the_expansion(coral, cfg, M, n_next, with_parent, path):
+    """coral_lmhead_draft_level against the two calls it stands for, bit for bit (the head
+    against the oracle as well; the expansion kernel has its own exact test above)."""
+    dt = {"f32": coral.CORAL_F32, "bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[cfg.dtype]
+    assert coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, dt) == path
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, M, 4)
+    d_hidden = coral.device_tensor(hidden, cfg.dtype)
+    parent = torch.linspace(-3.0, -0.5, M, device="cuda") if with_parent else None
+    ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, dt)
+    for rep in range(2):                                   # the second call finds the counters reset
+        print(f"case {cfg.name} M={M} n_next={n_next} call {rep}", flush=True)
+        ids, logp, sel, p, t, s = coral.coral_lmhead_draft_level(
+            d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k, n_next, parent_score=parent,
+            workspace=ws)
+        ids2, logp2, sel2 = coral.coral_lmhead_grouped_logprob(d_hidden, dh.gate_W, dh.bias, dh.lm_W,
+                                                               dh.gi, cfg.g, cfg.k, workspace=ws)
+        p2, t2, s2 = coral.coral_tree_expand(parent, ids2, logp2, n_next)
+        torch.cuda.synchronize()
+        for a, b in ((ids, ids2), (logp, logp2), (sel, sel2), (p, p2), (t, t2), (s, s2)):
+            assert torch.equal(a, b)
+    check_logprob(dh, hidden, cfg.g, cfg.k, (ids.cpu().numpy(), logp.cpu().numpy(), sel.cpu().numpy()))
+
+
+def test_draft_level_rejects_bad_arguments(coral):
+    cfg = CONFIGS["tiny_f32"]
+    dh = DeviceHead(coral, make_head(cfg))
+    d_hidden = coral.device_tensor(make_hidden(cfg, 4), cfg.dtype)
+    for n_next in (0, 4 * cfg.k + 1):
+        with pytest.raises(coral.CoralError):
+            coral.coral_lmhead_draft_level(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                           n_next)
+    with pytest.raises(ValueError):
+        coral.coral_lmhead_draft_level(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k, 8,
+                                       parent_score=torch.zeros(3, device="cuda"))
+
