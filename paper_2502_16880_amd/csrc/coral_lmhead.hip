@@ -45,7 +45,7 @@ constexpr size_t kCtrlBytes = 512;     // control words at the start of the work
 static_assert(kCtrlBytes >= (kLpGroupCounters + kWave) * sizeof(unsigned int), "per-group counters");
 
 struct Layout {
-    size_t ctrl, fused_part, fused_lse, fused_glist, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
+    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
     int part_stride;
 };
 
@@ -67,6 +67,9 @@ Layout make_layout(int M, int V, int G, int g, int k) {
     L.fused_part = take((size_t)kMaxWorkgroups * M * k * sizeof(Cand));
     L.fused_lse = take((size_t)kMaxWorkgroups * M * sizeof(unsigned long long));   // log-probability mode
     L.fused_glist = take((size_t)M * (g ? g : 1) * k * sizeof(Cand));
+    // one (max, sum) piece per (row pair of a selected group, token that selected it): a
+    // token's g groups are distinct, so their pairs number V / 2 + g at most
+    L.fused_pairs = take(G ? (size_t)M * ((size_t)V / 2 + g) * sizeof(unsigned long long) : 0);
     L.s = take((size_t)M * (G ? G : 1) * sizeof(float));
     L.sel = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.mask = take((size_t)(G ? G : 1) * sizeof(unsigned long long));
@@ -187,6 +190,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
     p.lse_part = reinterpret_cast<unsigned long long*>(ws + L.fused_lse);
     p.glist = reinterpret_cast<Cand*>(ws + L.fused_glist);
+    p.pair_lse = reinterpret_cast<unsigned long long*>(ws + L.fused_pairs);
     if (level) {
         p.parent_score = level->parent_score;
         p.n_next = level->n_next;

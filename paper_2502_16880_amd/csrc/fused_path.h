@@ -37,6 +37,7 @@ constexpr int kLdsLimit = 160 * 1024;
 // the dot products of every token that selected its group; measured in units of one
 // token's dot products the latency is about this much.
 constexpr int kLpBaseCost = 10;
+constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp pieces, at most
 constexpr int kLpGroupCounters = 64;   // first of the 64 per-group arrival counters (control words)
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
@@ -67,6 +68,7 @@ struct FusedParams {
     Cand* part;                 // [M, k, gridDim.x] per-workgroup lists, entry-major
     unsigned long long* lse_part;   // [M, gridDim.x] (max, sum of exp) pairs (log-probability mode)
     Cand* glist;                // [M, g, k] a token's list per selected group (log-probability mode)
+    unsigned long long* pair_lse;   // (max, sum of exp) of every (row pair, token) (same mode)
     // Draft-level call (log-probability mode): the tokens are the nodes of a tree level and
     // the workgroup that writes the result also expands the level (tree_expand.h).
     const float* parent_score;  // [M] cumulative log-probabilities of the nodes, or null (zero)
@@ -86,6 +88,7 @@ struct FusedLds {
     int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags;
     int o_keys, o_offsets, o_bias;
     int o_sel, o_wgstart;       // log-probability mode only
+    int o_pieces, pieces_bytes; // same mode: the log-sum-exp pieces of a workgroup's pairs, if they fit
     int total;
 };
 
@@ -107,9 +110,7 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     long long um = (long long)M * g < G ? (long long)M * g : G;   // activated groups at most
     if (dense || um < 1) um = 1;
     size_t hidden_bytes = (size_t)M * hidden_lds_stride(jp) * sizeof(uint4);
-    // merge scratch; the log-probability mode parks the waves' (max, sum) pairs behind it
-    const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes +
-                                 (logprob ? (size_t)kFusedWaves * M * 2 * sizeof(float) : 0);
+    const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes;
     if (hidden_bytes < scratch_bytes) hidden_bytes = scratch_bytes;   // reused by the merges
     L.o_hidden = take(hidden_bytes);
     size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
@@ -133,6 +134,13 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     L.o_bias = take(dense ? 16 : (size_t)G * sizeof(float));
     L.o_sel = take(logprob ? (size_t)M * g * sizeof(int) : 0);
     L.o_wgstart = take(logprob ? (size_t)(um + 1) * sizeof(int) : 0);
+    L.o_pieces = off;
+    L.pieces_bytes = 0;
+    if (logprob) {                                     // what is left, up to kLpPiecesMax
+        const int left = (kLdsLimit - off) / 16 * 16;
+        L.pieces_bytes = left < 0 ? 0 : left < kLpPiecesMax ? left : kLpPiecesMax;
+        off += L.pieces_bytes;
+    }
     L.total = off;
     return L;
 }
@@ -460,14 +468,21 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
     }
 }
 
-// Running log-sum-exp state (max, sum of exp(z - max)) of the lanes flagged `mine` takes in
-// z0 and z1 (-inf: absent).
-__device__ __forceinline__ void lse_update(float& m, float& s, float z0, float z1, bool mine) {
-    const float nm = fmaxf(m, fmaxf(z0, z1));
-    if (mine && nm > -INFINITY) {
-        s = s * expf(m - nm) + expf(z0 - nm) + expf(z1 - nm);
-        m = nm;
-    }
+// (max, sum of exp(z - max)) of the one or two logits of a row pair (z1 = -inf: absent).
+__device__ __forceinline__ void pair_lse(float& m, float& s, float z0, float z1) {
+    m = fmaxf(z0, z1);
+    s = m > -INFINITY ? expf(z0 - m) + expf(z1 - m) : 0.f;
+}
+__device__ __forceinline__ unsigned long long pack_lse(float m, float s) {
+    return ((unsigned long long)__float_as_uint(s) << 32) | __float_as_uint(m);
+}
+// Takes a packed (max, sum) piece into the running state (m, s).
+__device__ __forceinline__ void lse_take(float& m, float& s, unsigned long long piece) {
+    const float pm = __uint_as_float((unsigned)(piece & 0xffffffffull));
+    const float ps = __uint_as_float((unsigned)(piece >> 32));
+    const float nm = fmaxf(m, pm);
+    if (nm > -INFINITY) s = s * expf(m - nm) + ps * expf(pm - nm);
+    m = nm;
 }
 
 // Combines the (max, sum) states of all lanes (absent: (-inf, 0)) into log(sum of exp); -inf
@@ -517,7 +532,7 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
             z1 = wave_sum(a1[i]);
             lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z1, rid1, thr_v, thr_i, tok[i]);
         }
-        if (LP) lse_update(lse_m, lse_s, z0, z1, lane == tok[i]);   // lane t: token t's state
+        if (LP && lane == tok[i]) pair_lse(lse_m, lse_s, z0, z1);   // lane t: token t's piece
     }
 }
 
@@ -629,11 +644,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             const int half = wave >> 3, kw = wave & 7;
             constexpr int kSteps = 2 * kFusedSegs;
             uint4 ga[kSteps];
-            // every workgroup reads the same gate matrix at the same time: those that share
-            // an L2 (workgroup b runs on XCD b % 8) start at different column blocks so that
-            // they do not all queue on one L2 channel
-            const int rot = (int)((blockIdx.x >> 3) & 7u);
-            auto step_of = [&](int i) { return 16 * (((i >> 1) + rot) & 7) + 2 * kw + (i & 1); };
+            // (every workgroup sums the columns in the same order: the scores, and with them
+            // the selection, must come out bit-identical in all of them)
+            auto step_of = [&](int i) { return 16 * (i >> 1) + 2 * kw + (i & 1); };
             // (see device_utils.h for the two load shapes; with whole lines register 2 L + h
             // holds rows 8 h .. 8 h + 7 of the tile for both steps of line L)
             auto load_gate_tile = [&](int gt) {
@@ -900,7 +913,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     const int stride_batches = gridDim.x * kFusedWaves;
     int u = 0;
     int lp_lo = 0, lp_nwg = 0;
-    float lse_m = -INFINITY, lse_s = 0.f;              // lane t: token t's running log-sum-exp
+    // lane t: (max, sum of exp) of the current row pair for token t.  The pieces go to memory
+    // per pair and are summed in pair order at the end: a running state per wave would make
+    // the sum depend on which wave drew which pair, and the result would not repeat bit for bit
+    float lse_m = -INFINITY, lse_s = 0.f;
+    unsigned long long* lp_pieces = nullptr;           // piece of (token slot j, pair b) at
+    int lp_stride = 0, lp_origin = 0;                  // lp_pieces[j * lp_stride + b - lp_origin],
+    bool lp_in_lds = false;                            // in memory, or in lds_pieces likewise
+    unsigned long long* lds_pieces = reinterpret_cast<unsigned long long*>(lds + lay.o_pieces);
     if (LP) {
         const int count = uni(flags[0]);
         const int nxt = lane < count ? wgstart[lane + 1] : INT_MAX;
@@ -911,6 +931,19 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         const int per = (nb + lp_nwg - 1) / lp_nwg;
         lp_lo = uni(uprefix[u]) + min(j * per, nb);
         total_batches = uni(uprefix[u]) + min((j + 1) * per, nb);  // the end of this workgroup's range
+        // The pieces stay in LDS if this workgroup's fit there; else they go through memory,
+        // this group's behind those of the activated groups before it.
+        const int n_mine = total_batches - lp_lo;
+        if ((size_t)n_mine * __popcll(uni64(umask[u])) * sizeof(unsigned long long) <= (size_t)lay.pieces_bytes) {
+            lp_in_lds = true;
+            lp_stride = n_mine;
+            lp_origin = lp_lo;
+        } else {
+            const int before = lane < u ? (uprefix[lane + 1] - uprefix[lane]) * __popcll(umask[lane]) : 0;
+            lp_pieces = p.pair_lse + (size_t)__builtin_amdgcn_readlane(wave_scan_inclusive(before), 63);
+            lp_stride = nb;
+            lp_origin = uni(uprefix[u]);
+        }
     }
     auto draw_batch = [&]() {
         int i = 0;
@@ -975,6 +1008,15 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 fused_tokens<DT, 1, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
                                         lse_m, lse_s);
         }
+        if (LP && ((bm >> lane) & 1ull)) {             // token slot j of the group, pair b
+            const int j = __popcll(bm & ((1ull << lane) - 1ull));
+            const int at = j * lp_stride + (b - lp_origin);
+            if (lp_in_lds)                             // uniform
+                lds_pieces[at] = pack_lse(lse_m, lse_s);
+            else
+                __hip_atomic_store(lp_pieces + at, pack_lse(lse_m, lse_s), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
         b = nb;
         rid0 = nrid0;
         rid1 = nrid1;
@@ -1000,36 +1042,49 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     } else {
         // the tokens of this workgroup's group only: their lists, ranked by logit (inside
         // a group that is the order of log p as well), and their log-sum-exp pieces
-        float* lse_w = reinterpret_cast<float*>(lds + lay.o_hidden + kFusedWaves * sizeof(WaveScratch));
-        if (lane < M) {
-            lse_w[(wave * M + lane) * 2] = lse_m;
-            lse_w[(wave * M + lane) * 2 + 1] = lse_s;
-        }
-        __syncthreads();
         unsigned long long rem = uni64(umask[u]);
         for (int idx = 0; rem; ++idx, rem &= rem - 1ull) {     // block-uniform
             if ((idx & (kFusedWaves - 1)) != wave) continue;
             const int t = __ffsll(rem) - 1;
+            // the pieces of this workgroup's pairs for token slot idx, summed in pair order;
+            // the first 256 are requested before the merge, which hides their latency
+            const int q0 = idx * lp_stride + lp_lo - lp_origin + lane;
+            const int q_end = idx * lp_stride + total_batches - lp_origin;
+            auto piece_at = [&](int q) {
+                return lp_in_lds ? lds_pieces[q]
+                                 : __hip_atomic_load(lp_pieces + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            };
+            unsigned long long early[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                early[c] = 0xff800000ull;              // (-inf, 0)
+                if (q0 + c * kWave < q_end) early[c] = piece_at(q0 + c * kWave);
+            }
             Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
             wave_merge_topk(
                 kFusedWaves, k, lane, ws,
                 [&](int l, int i) { return lists[((size_t)l * M + t) * k + i]; },
                 [&](int r, Cand c) { publish_cand(dst + (size_t)r * P, c.v, c.id); });
-            float pm = -INFINITY, ps = 0.f;
-            if (lane < kFusedWaves) {
-                pm = lse_w[(lane * M + t) * 2];
-                ps = lse_w[(lane * M + t) * 2 + 1];
+            // (the maximum first, then every piece scaled to it: independent exponentials)
+            float late_m = -INFINITY, late_s = 0.f;    // pairs beyond the first 256, if any
+            for (int q = q0 + 4 * kWave; q < q_end; q += kWave) lse_take(late_m, late_s, piece_at(q));
+            float wm = late_m;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) wm = fmaxf(wm, __uint_as_float((unsigned)(early[c] & 0xffffffffull)));
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+            float mine_s = 0.f;
+            if (wm > -INFINITY) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)            // ascending pair order
+                    mine_s += __uint_as_float((unsigned)(early[c] >> 32)) *
+                              expf(__uint_as_float((unsigned)(early[c] & 0xffffffffull)) - wm);
+                mine_s += late_s * expf(late_m - wm);
             }
-            float wm = pm;
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
-            float tot = wm > -INFINITY ? ps * expf(pm - wm) : 0.f;   // summed in wave order
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+            const float tot = wave_sum(mine_s);
             if (lane == 0)
                 __hip_atomic_store(p.lse_part + (size_t)t * P + blockIdx.x,
-                                   ((unsigned long long)__float_as_uint(tot) << 32) | __float_as_uint(wm),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                   pack_lse(wm, tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the published lists are out
@@ -1062,13 +1117,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 [&](int r, Cand c) { mine[r] = c; });
             float bm = -INFINITY, bs = 0.f;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {              // per lane in ascending workgroup order
-                const float pm = __uint_as_float((unsigned)(piece[c] & 0xffffffffull));
-                const float ps = __uint_as_float((unsigned)(piece[c] >> 32));
-                const float nm = fmaxf(bm, pm);
-                if (nm > -INFINITY) bs = bs * expf(bm - nm) + ps * expf(pm - nm);
-                bm = nm;
-            }
+            for (int c = 0; c < 4; ++c) lse_take(bm, bs, piece[c]);   // ascending workgroup order
             const float lse_n = lse_finish(bm, bs);
             float rm = -INFINITY, rs = 0.f, s_n = 0.f;
             for (int o = lane; o < p.G; o += kWave) {

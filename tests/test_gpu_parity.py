@@ -325,6 +325,20 @@ def test_two_runs_are_bit_identical(coral):
     assert all(np.array_equal(x, y) for x, y in zip(a, b))
 
 
+@pytest.mark.parametrize("M", [1, 8, 16])
+def test_logprob_runs_are_bit_identical(coral, M):
+    """The log-sum-exp of a group is a sum over thousands of rows taken by waves that draw
+    their work dynamically, and the router's scores are computed by every workgroup for
+    itself: neither may show in the result."""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, M, 4)
+    first = run_logprob(coral, dh, hidden, cfg.g, cfg.k)
+    for rep in range(8):
+        again = run_logprob(coral, dh, hidden, cfg.g, cfg.k)
+        assert all(np.array_equal(x, y) for x, y in zip(first, again)), rep
+
+
 def test_caller_buffers_and_streams(coral):
     """Outputs land in the caller's tensors, on the caller's stream; the workspace is reusable."""
     cfg = CONFIGS["tiny_f32"]
