@@ -208,6 +208,38 @@ class Bench:
         bytes_premix = w1_bytes + 2 * M * cfg.H * weight_bytes_per_elt(cfg.dtype)
         return dict(step_us=step_us, premix_us=premix_us, premix_bytes=bytes_premix)
 
+    def time_draft_level(self, M, n_next, steps, warmup, R=24):
+        """One level of tree drafting: the log-probability head for M nodes and the expansion
+        to n_next nodes, as one call (coral_lmhead_draft_level) and as the two calls it
+        stands for."""
+        torch, coral, cfg = self.torch, self.coral, self.cfg
+        sched = self.schedule(M, R)
+        R = len(sched)
+        ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt)
+        ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
+        lp = torch.empty((M, cfg.k), dtype=torch.float32, device="cuda")
+        sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
+        parent = -torch.rand(M, device="cuda", generator=torch.Generator(device="cuda").manual_seed(9)) * 4
+        nxt = (torch.empty(n_next, dtype=torch.int32, device="cuda"),
+               torch.empty(n_next, dtype=torch.int32, device="cuda"),
+               torch.empty(n_next, dtype=torch.float32, device="cuda"))
+
+        def one_call(i, events=None):
+            coral.coral_lmhead_draft_level(sched[i % R][2], self.gate_W, self.bias, self.lm_W, self.gi,
+                                           cfg.g, cfg.k, n_next, parent_score=parent,
+                                           next_parent=nxt[0], next_token=nxt[1], next_score=nxt[2],
+                                           topk_ids=ids, topk_logits=lp, sel_groups=sel, workspace=ws)
+
+        def two_calls(i, events=None):
+            coral.coral_lmhead_grouped(sched[i % R][2], self.gate_W, self.bias, self.lm_W, self.gi,
+                                       cfg.g, cfg.k, topk_ids=ids, topk_logits=lp, sel_groups=sel,
+                                       workspace=ws, logprob=True)
+            coral.coral_tree_expand(parent, ids, lp, n_next)
+
+        one = self._timed(one_call, steps, warmup, R, False) * 1e3 / steps
+        two = self._timed(two_calls, steps, warmup, R, False) * 1e3 / steps
+        return dict(one_call_us=one, two_calls_us=two)
+
     def time_tree_expand(self, M, k, n_next, steps=240):
         """One level of draft-tree expansion on synthetic candidate lists (sorted rows)."""
         torch, coral = self.torch, self.coral
@@ -421,6 +453,11 @@ def main():
                       "avg_activated_groups": r["U"],
                       "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
                       "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        r = bench.time_draft_level(a.M, a.M, n, min(a.warmup, 20))
+        cases.append({"path": f"draft level in one call: log-probability head for {a.M} nodes + expansion to "
+                              f"{a.M} nodes (coral_lmhead_draft_level)",
+                      "M": a.M, "us_per_step": r["one_call_us"],
+                      "us_per_step_as_two_calls": r["two_calls_us"]})
         r = bench.time_routed(a.M, n, min(a.warmup, 20))
         cases.append({"path": "router pre-mix u = silu(W1 h) + h alone (Eq. 7; k_premix, W1 copies "
                               "cycled past the last-level cache; launch gap included)",
