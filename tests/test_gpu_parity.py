@@ -512,9 +512,12 @@ def test_full_size_workloads(coral, name, Ms):
               flush=True)
         if M <= 16:
             print(f"case {name} M={M} log-prob", flush=True)
-            rep = check_logprob(dh, hidden, cfg.g, cfg.k, run_logprob(coral, dh, hidden, cfg.g, cfg.k))
+            out = run_logprob(coral, dh, hidden, cfg.g, cfg.k)
+            rep = check_logprob(dh, hidden, cfg.g, cfg.k, out)
             print(f"  log-prob exact {rep.exact_tokens}/{rep.tokens} max|err| {rep.max_abs_err:.2e}",
                   flush=True)
+            again = run_logprob(coral, dh, hidden, cfg.g, cfg.k)    # (pieces through memory at M=16)
+            assert all(np.array_equal(x, y) for x, y in zip(out, again))
     del dh
     torch.cuda.empty_cache()
 
