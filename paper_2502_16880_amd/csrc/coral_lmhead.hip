@@ -55,7 +55,9 @@ bool sizes_ok(int M, int H, int V, int G, int g, int k) {
     return true;
 }
 
-Layout make_layout(int M, int V, int G, int g, int k) {
+// pair_pieces: the shape can take the single-launch kernel's log-probability mode (the table
+// of its per-pair pieces is the largest item and is left out otherwise).
+Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces) {
     Layout L;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -69,7 +71,7 @@ Layout make_layout(int M, int V, int G, int g, int k) {
     L.fused_glist = take((size_t)M * (g ? g : 1) * k * sizeof(Cand));
     // one (max, sum) piece per (row pair of a selected group, token that selected it): a
     // token's g groups are distinct, so their pairs number V / 2 + g at most
-    L.fused_pairs = take(G ? (size_t)M * ((size_t)V / 2 + g) * sizeof(unsigned long long) : 0);
+    L.fused_pairs = take(pair_pieces ? (size_t)M * ((size_t)V / 2 + g) * sizeof(unsigned long long) : 0);
     L.s = take((size_t)M * (G ? G : 1) * sizeof(float));
     L.sel = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.mask = take((size_t)(G ? G : 1) * sizeof(unsigned long long));
@@ -162,6 +164,12 @@ struct LevelExpand {
     int32_t* next_token;
     float* next_score;
 };
+
+bool layout_has_pair_pieces(int M, int H, int G, int g, int k, coral_dtype dt) {
+    if (G < 1 || !dtype_ok(dt)) return false;
+    const int n_vec = H / (is_16bit(dt) ? 8 : 4);
+    return fused_logprob_fits(M, G, g, k, (n_vec + kWave - 1) / kWave, dt, kMaxWorkgroups);
+}
 
 // Enqueues the single-launch path (the caller has checked with plan_path that it fits).
 coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidden, const void* gate_W,
@@ -367,9 +375,8 @@ extern "C" coral_status coral_group_index_validate(const int32_t* host_offsets,
 
 extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
                                                coral_dtype dt) {
-    (void)dt;
     if (!sizes_ok(M, H, V, G, g, k)) return 0;
-    return make_layout(M, V, G, g, k).total;
+    return make_layout(M, V, G, g, k, layout_has_pair_pieces(M, H, G, g, k, dt)).total;
 }
 
 extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k,
@@ -435,7 +442,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         min_cand += smallest[i];
     }
     if ((long long)k > min_cand) return CORAL_ERR_SHAPE;
-    const Layout L = make_layout(M, V, G, g, k);
+    const Layout L = make_layout(M, V, G, g, k, layout_has_pair_pieces(M, H, G, g, k, dt));
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != CORAL_OK) return st;
 
@@ -544,7 +551,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
     if (k > V) return CORAL_ERR_SHAPE;
-    const Layout L = make_layout(M, V, 0, 0, k);
+    const Layout L = make_layout(M, V, 0, 0, k, false);
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != CORAL_OK) return st;
 
