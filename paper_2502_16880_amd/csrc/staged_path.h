@@ -412,7 +412,7 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
         mbuf[wave * k + lane].id = li;
     }
     block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
-    if (threadIdx.x < k) {
+    if ((int)threadIdx.x < k) {
         topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
         topk_logits[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
     }
@@ -493,7 +493,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
         if (lane < k) mine[lane] = grp[lane];
     }
     block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
-    if (threadIdx.x < k) {
+    if ((int)threadIdx.x < k) {
         topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
         topk_logprob[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
     }

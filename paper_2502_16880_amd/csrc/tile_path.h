@@ -149,7 +149,7 @@ __device__ __forceinline__ void tile_merge_pair(Cand* list, int k, int lane, Can
     bool p1 = is_real(c1) && better(c1.v, c1.id, tail.v, tail.id);
     unsigned long long b0 = __ballot(p0), b1 = __ballot(p1);
     if ((b0 | b1) == 0ull) return;                     // wave-uniform, the common case
-    if (__popcll(b0) + __popcll(b1) > k + (k >> 1)) {  // wave-uniform
+    if ((int)(__popcll(b0) + __popcll(b1)) > k + (k >> 1)) {  // wave-uniform
         const unsigned o0 = p0 ? ord32(c0.v) : 0u, o1 = p1 ? ord32(c1.v) : 0u;
         const unsigned tau = wave_kth_key(keys32, o0 > o1 ? o0 : o1, kWave, k, lane);
         p0 = p0 && o0 >= tau;
@@ -248,8 +248,7 @@ __device__ __forceinline__ uint4 tile_load_w(const TileParams& p, unsigned row, 
 template <int DT, int NCT, bool REFILL, int SP>
 __device__ __forceinline__ void tile_step_pair(const TileParams& p, int c, uint4 (&a)[kRing],
                                                f32x4_t (&acc)[2][4], const unsigned (&wrow)[4],
-                                               uint4* hbuf, const int* tokslot, int n_t, TileStage& hst,
-                                               uint4* my_slice) {
+                                               uint4* hbuf, TileStage& hst, uint4* my_slice) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int r16 = lane & 15, q4 = lane >> 4;
@@ -295,10 +294,10 @@ __device__ __forceinline__ void tile_chunk(const TileParams& p, int c, uint4 (&a
                                __builtin_amdgcn_readfirstlane(threadIdx.x / kWave));
         keep_memory_order();
     }
-    tile_step_pair<DT, NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<DT, NCT, REFILL, 1>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<DT, NCT, REFILL, 2>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
-    tile_step_pair<DT, NCT, REFILL, 3>(p, c, a, acc, wrow, hbuf, tokslot, n_t, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 0>(p, c, a, acc, wrow, hbuf, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 1>(p, c, a, acc, wrow, hbuf, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 2>(p, c, a, acc, wrow, hbuf, hst, my_slice);
+    tile_step_pair<DT, NCT, REFILL, 3>(p, c, a, acc, wrow, hbuf, hst, my_slice);
     __syncthreads();
 }
 
@@ -340,7 +339,6 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int r16 = lane & 15, q4 = lane >> 4;
     const int rg = wave / kTileSplit, kq = wave % kTileSplit;
     const int M = p.M, k = p.k;
     uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kLinePairSlots;
@@ -566,7 +564,6 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ int is_last, ucount;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int r16 = lane & 15, q4 = lane >> 4;
     const int n_tt = (p.M + 15) / 16;
     const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
     const int n_ks = (p.n_vec + 3) / 4;
