@@ -562,8 +562,15 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ int ulist[kMaxG];
     __shared__ int order[kMaxG], nblk[kMaxG];
     __shared__ int is_last, ucount;
+    __shared__ int off_lds[kMaxG + 1];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    // the groups' row ranges travel with the first operand loads (requested here, put into LDS
+    // after the contraction): the workgroup that ends up building the table then has them
+    // without two more dependent trips to memory
+    int off_r0 = 0, off_r1 = 0;
+    if ((int)threadIdx.x <= p.G) off_r0 = p.offsets[threadIdx.x];
+    if ((int)threadIdx.x + kFusedBlock <= p.G) off_r1 = p.offsets[threadIdx.x + kFusedBlock];
     const int n_tt = (p.M + 15) / 16;
     const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
     const int n_ks = (p.n_vec + 3) / 4;
@@ -588,6 +595,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                                 mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave])), acc);
     }
     *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
+    if ((int)threadIdx.x <= p.G) off_lds[threadIdx.x] = off_r0;
+    if ((int)threadIdx.x + kFusedBlock <= p.G) off_lds[threadIdx.x + kFusedBlock] = off_r1;
     __syncthreads();
     if (threadIdx.x < 256) {
         const int e = threadIdx.x, l = e >> 2, i = e & 3;
@@ -671,7 +680,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
         }
         order[rank] = g0;
-        nblk[rank] = (p.offsets[g0 + 1] - p.offsets[g0] + kTileRows - 1) / kTileRows;
+        nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
     }
     __syncthreads();
     if (wave == 0) {
@@ -684,8 +693,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                 const int g0 = order[r];
                 TileGroup tg;
                 tg.group = g0;
-                tg.start = p.offsets[g0];
-                tg.end = p.offsets[g0 + 1];
+                tg.start = off_lds[g0];
+                tg.end = off_lds[g0 + 1];
                 tg.first_block = carry + incl - nb;
                 tg.mask = mask[g0];
                 p.table[r] = tg;
