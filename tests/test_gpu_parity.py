@@ -279,6 +279,45 @@ def test_ragged_and_empty_groups(coral):
         run_grouped(coral, dh, make_hidden(cfg, 6), 2, 4)
 
 
+@pytest.mark.parametrize("seed", range(200, 264))
+def test_random_small_heads(coral, seed):
+    """Seeded random shapes with ragged groups (some empty, some of one row): token counts,
+    group counts, g and k drawn freely within the limits, fp32 heads so that the oracle is
+    fast.  Logit ranking, log-probabilities (twice: they must repeat) and the dense head."""
+    rng = np.random.default_rng(seed)
+    G = int(rng.integers(1, 65))
+    g = int(rng.integers(1, min(G, 16) + 1))
+    M = int(rng.integers(1, 25))
+    H = int(rng.choice([32, 64, 100, 256, 516]))
+    sizes = rng.integers(0, 120, G)
+    sizes[rng.integers(0, G)] += int(rng.integers(100, 2000))     # one large group
+    if G > 3:
+        sizes[rng.integers(0, G, 2)] = (0, 1)
+    min_cand = int(np.sort(sizes)[:g].sum())
+    while min_cand < 1:                                           # the g smallest must hold a row
+        sizes[np.argsort(sizes)[0]] += 1
+        min_cand = int(np.sort(sizes)[:g].sum())
+    k = int(rng.integers(1, min(min_cand, 20) + 1))
+    V = int(sizes.sum())
+    cfg = HeadConfig(f"rand{seed}", "f32", H, V, G, g, (M,), k, seed, bool(rng.integers(0, 2)))
+    perm = rng.permutation(V).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(G)]).astype(np.int32)
+    lm_W = rng.standard_normal((V, H)).astype(np.float32) * np.float32(0.05)
+    gate_W = rng.standard_normal((G, H)).astype(np.float32) * np.float32(0.05)
+    bias = (rng.standard_normal(G) * 0.3).astype(np.float32) if rng.integers(0, 2) else None
+    dh = DeviceHead(coral, Head(cfg, lm_W, gate_W, bias, offsets, rows))
+    hidden = make_hidden(cfg, M, 1)
+    print(f"case seed={seed} M={M} H={H} V={V} G={G} g={g} k={k} "
+          f"logprob path {coral.coral_lmhead_logprob_path(M, H, V, G, g, k, coral.CORAL_F32)}", flush=True)
+    check_grouped(dh, hidden, g, k, run_grouped(coral, dh, hidden, g, k))
+    out = run_logprob(coral, dh, hidden, g, k)
+    check_logprob(dh, hidden, g, k, out)
+    again = run_logprob(coral, dh, hidden, g, k)
+    assert all(np.array_equal(x, y) for x, y in zip(out, again))
+    check_dense(dh, hidden, k, run_dense(coral, dh, hidden, k))
+
+
 def test_duplicate_rows_tie_break_to_the_lower_id(coral):
     cfg = HeadConfig("dup", "bf16", 256, 4 * 96, 4, 4, (2,), 6, 80, True)
     head = make_head(cfg)
