@@ -102,7 +102,9 @@ def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return r.astype(np.uint16)
 
 
-def _store(x: np.ndarray, dtype: str) -> np.ndarray:
+def to_storage(x: np.ndarray, dtype: str) -> np.ndarray:
+    """float32 values in the storage type's representation (fp32 as is, bf16 / fp16 as their
+    bit patterns in uint16, rounded to nearest even)."""
     if dtype == "f32":
         return np.ascontiguousarray(x, dtype=np.float32)
     if dtype == "bf16":
@@ -136,9 +138,9 @@ def make_head(cfg: HeadConfig) -> Head:
         hi = min(cfg.V, lo + _ROW_BLOCK)
         blk = r0.standard_normal((hi - lo, cfg.H), dtype=np.float32)
         blk *= np.float32(0.02)
-        lm_W[lo:hi] = _store(blk, cfg.dtype)
+        lm_W[lo:hi] = to_storage(blk, cfg.dtype)
     gw = _rng(cfg.seed, 1).standard_normal((cfg.G, cfg.H), dtype=np.float32) * np.float32(0.02)
-    gate_W = _store(gw, cfg.dtype)
+    gate_W = to_storage(gw, cfg.dtype)
     gate_bias = None
     if cfg.bias_std > 0:
         gate_bias = (_rng(cfg.seed, 2).standard_normal(cfg.G, dtype=np.float32)
@@ -150,7 +152,7 @@ def make_head(cfg: HeadConfig) -> Head:
 def make_router_W1(cfg: HeadConfig) -> np.ndarray:
     """The router's square projection W1 [H,H] (row = output feature) in the config's storage type."""
     w = _rng(cfg.seed, 4).standard_normal((cfg.H, cfg.H), dtype=np.float32) * np.float32(0.02)
-    return _store(w, cfg.dtype)
+    return to_storage(w, cfg.dtype)
 
 
 def make_hidden(cfg: HeadConfig, M: int, batch: int = 0) -> np.ndarray:
@@ -159,4 +161,4 @@ def make_hidden(cfg: HeadConfig, M: int, batch: int = 0) -> np.ndarray:
     if cfg.unit_rms:
         rms = np.sqrt(np.mean(x.astype(np.float64) ** 2, axis=1, keepdims=True))
         x = (x / rms).astype(np.float32)
-    return _store(x, cfg.dtype)
+    return to_storage(x, cfg.dtype)

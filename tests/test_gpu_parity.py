@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-from coral_inputs import CONFIGS, Head, HeadConfig, make_head, make_hidden  # noqa: E402
+from coral_inputs import CONFIGS, Head, HeadConfig, make_head, make_hidden, to_storage  # noqa: E402
 import oracle  # noqa: E402
 from oracle import compare  # noqa: E402
 
@@ -279,7 +279,7 @@ def test_ragged_and_empty_groups(coral):
         run_grouped(coral, dh, make_hidden(cfg, 6), 2, 4)
 
 
-@pytest.mark.parametrize("seed", range(200, 264))
+@pytest.mark.parametrize("seed", list(range(200, 264)) + list(range(300, 324)))
 def test_random_small_heads(coral, seed):
     """Seeded random shapes with ragged groups (some empty, some of one row): token counts,
     group counts, g and k drawn freely within the limits, fp32 heads so that the oracle is
@@ -288,7 +288,8 @@ def test_random_small_heads(coral, seed):
     G = int(rng.integers(1, 65))
     g = int(rng.integers(1, min(G, 16) + 1))
     M = int(rng.integers(1, 25))
-    H = int(rng.choice([32, 64, 100, 256, 516]))
+    dtype = "f32" if seed < 300 else ("bf16", "f16")[seed % 2]  # 16-bit: matrix-core gate from 5 tokens on
+    H = int(rng.choice([32, 64, 100, 256, 516] if dtype == "f32" else [64, 104, 256, 512]))
     sizes = rng.integers(0, 120, G)
     sizes[rng.integers(0, G)] += int(rng.integers(100, 2000))     # one large group
     if G > 3:
@@ -299,17 +300,18 @@ def test_random_small_heads(coral, seed):
         min_cand = int(np.sort(sizes)[:g].sum())
     k = int(rng.integers(1, min(min_cand, 20) + 1))
     V = int(sizes.sum())
-    cfg = HeadConfig(f"rand{seed}", "f32", H, V, G, g, (M,), k, seed, bool(rng.integers(0, 2)))
+    cfg = HeadConfig(f"rand{seed}", dtype, H, V, G, g, (M,), k, seed, bool(rng.integers(0, 2)))
     perm = rng.permutation(V).astype(np.int32)
     offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
     rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(G)]).astype(np.int32)
-    lm_W = rng.standard_normal((V, H)).astype(np.float32) * np.float32(0.05)
-    gate_W = rng.standard_normal((G, H)).astype(np.float32) * np.float32(0.05)
+    lm_W = to_storage(rng.standard_normal((V, H)).astype(np.float32) * np.float32(0.05), dtype)
+    gate_W = to_storage(rng.standard_normal((G, H)).astype(np.float32) * np.float32(0.05), dtype)
     bias = (rng.standard_normal(G) * 0.3).astype(np.float32) if rng.integers(0, 2) else None
     dh = DeviceHead(coral, Head(cfg, lm_W, gate_W, bias, offsets, rows))
     hidden = make_hidden(cfg, M, 1)
-    print(f"case seed={seed} M={M} H={H} V={V} G={G} g={g} k={k} "
-          f"logprob path {coral.coral_lmhead_logprob_path(M, H, V, G, g, k, coral.CORAL_F32)}", flush=True)
+    dt = {"f32": coral.CORAL_F32, "bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[dtype]
+    print(f"case seed={seed} {dtype} M={M} H={H} V={V} G={G} g={g} k={k} "
+          f"logprob path {coral.coral_lmhead_logprob_path(M, H, V, G, g, k, dt)}", flush=True)
     check_grouped(dh, hidden, g, k, run_grouped(coral, dh, hidden, g, k))
     out = run_logprob(coral, dh, hidden, g, k)
     check_logprob(dh, hidden, g, k, out)
