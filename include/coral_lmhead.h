@@ -105,6 +105,7 @@ int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral
 /*
  * The same for coral_lmhead_grouped_logprob (Eq. 8's output): 1 = single-launch kernel
  * (at most 64 activated groups, min(M*g, G) <= 64, g <= 16, and its LDS plan fits),
+ * 2 = matrix-core tile path (where that path's conditions hold, G <= 64 and M*g <= 1024),
  * 0 = staged path, -1 = sizes not supported.  Host-only.
  */
 int coral_lmhead_logprob_path(int M, int H, int V, int G, int g, int k, coral_dtype dt);
@@ -173,7 +174,8 @@ coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
  * selected groups have probability zero (Eq. 8) and are never returned.
  *   topk_logprob [device] out [M,k] fp32 log-probabilities (natural logarithm)
  * All other arguments, limits and errors as for coral_lmhead_grouped.  Runs in the
- * single-launch kernel or on the staged path (coral_lmhead_logprob_path tells which).
+ * single-launch kernel, on the tile path or on the staged path (coral_lmhead_logprob_path
+ * tells which).
  */
 coral_status coral_lmhead_grouped_logprob(const void *hidden, const void *gate_W,
                                           const float *gate_bias, const void *lm_W,

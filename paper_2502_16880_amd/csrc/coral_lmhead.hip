@@ -275,8 +275,17 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
     PathPlan pl = {};
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
-    if (logprob) {     // the single-launch kernel where it fits, else the multi-kernel path
-        pl.path = !dense && fused_logprob_fits(M, G, g, k, jp, dt, kMaxWorkgroups) ? 1 : 0;
+    if (logprob) {     // the single-launch kernel where it fits, else the tile path, else the staged path
+        pl.path = 0;
+        if (dense) return pl;
+        if (fused_logprob_fits(M, G, g, k, jp, dt, kMaxWorkgroups)) {
+            pl.path = 1;
+        } else if (tiles_fit(M, H, V, G, g, k, dt, &pl.tile_umax, &pl.tile_lds) && G <= kWave &&
+                   (long long)M * g <= kGateSelMaxPairs &&
+                   // a block per slot of the per-chunk arrays: V / 128 + G blocks at most
+                   (long long)V / kTileRows + G <= (long long)(V + kChunkRows - 1) / kChunkRows + g) {
+            pl.path = 2;
+        }
         return pl;
     }
     const bool fused_ok =
@@ -303,7 +312,9 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
                           const int32_t* n_union, int M, int H, int V,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
                           float* topk_logits, char* ws, const Layout& L, hipStream_t stream,
-                          void* ev_before, void* ev_after) {
+                          void* ev_before, void* ev_after, const int32_t* lp_sel = nullptr, int g = 0) {
+    // lp_sel: log-probability mode (grouped): the selection k_gate_select wrote; its first
+    // blocks and log p_router sit in the workspace's chunk_base and logp_sel arrays
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
@@ -320,8 +331,12 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.n_vec = H / 8;
     p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
     p.u_max = u_max;
+    p.blk_part = reinterpret_cast<Cand*>(ws + L.part);
+    p.blk_lse = reinterpret_cast<float*>(ws + L.lse_part);
+    p.blk_stride = L.part_stride;
     typedef void (*tiles_fn)(TileParams, int);
-    const tiles_fn fn = dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>;
+    const tiles_fn fn = lp_sel ? (dt == CORAL_F16 ? k_tiles<kF16, true> : k_tiles<kBF16, true>)
+                               : (dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>);
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
         return CORAL_ERR_HIP;
@@ -330,6 +345,14 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     hipLaunchKernelGGL(fn, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
+    if (lp_sel) {
+        hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, p.blk_part, p.blk_lse,
+                           L.part_stride, lp_sel, gi->group_offsets,
+                           reinterpret_cast<const int32_t*>(ws + L.chunk_base),
+                           reinterpret_cast<const float*>(ws + L.logp_sel), g, k, topk_ids, topk_logits,
+                           kTileRows, p.next_block);
+        return launch_status();
+    }
     hipLaunchKernelGGL(k_merge_published, dim3((M + 3) / 4), dim3(256), 0, stream,
                        reinterpret_cast<const Cand*>(ws + L.fused_part), P, M, k, topk_ids,
                        topk_logits, p.next_block);
@@ -475,14 +498,23 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         q.group_mask = mask; q.offsets = gi->group_offsets; q.table = table; q.n_union = n_union;
         q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
+        if (logprob) {
+            q.first_block = chunk_base;
+            q.logp_sel = reinterpret_cast<float*>(ws + L.logp_sel);
+        }
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
         typedef void (*gate_select_fn)(GateSelParams);
         const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
         hipLaunchKernelGGL(gs, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
-        return launch_tiles(false, hidden, lm_W, gi, table, n_union, M, H, V, G, k, dt,
-                            plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
-                            ev_after);
+        st = launch_tiles(false, hidden, lm_W, gi, table, n_union, M, H, V, G, k, dt,
+                          plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
+                          ev_after, logprob ? sel : nullptr, g);
+        if (st != CORAL_OK || !level) return st;
+        hipLaunchKernelGGL(k_tree_expand, dim3(M), dim3(kWave), (size_t)M * k * sizeof(unsigned long long),
+                           stream, level->parent_score, topk_ids, topk_logits, M, k, level->n_next,
+                           level->next_parent, level->next_token, level->next_score);
+        return launch_status();
     }
     typedef void (*gate_fn)(const uint4*, const uint4*, const float*, int, int, int, float*);
     const gate_fn gate_kernel = CORAL_PICK_DT(dt, k_gate<kF32>, k_gate<kBF16>, k_gate<kF16>);
@@ -532,7 +564,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if (logprob)
         hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
                            L.part_stride, sel, gi->group_offsets, chunk_base, logp_sel, g, k, topk_ids,
-                           topk_logits);
+                           topk_logits, kChunkRows, nullptr);
     else
         hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
                            gi->group_offsets, g, 0, k, topk_ids, topk_logits);

@@ -419,7 +419,9 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 }
 
 
-// Final merge of the log-probability mode (Eq. 8): log p(x) = log p_router(n) + z[x] - lse_n
+// Final merge of the log-probability mode behind k_logits (a slot = a chunk of kChunkRows
+// rows) and behind k_tiles (a slot = a block of kTileRows rows; rows_per_slot says which).
+// Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n
 // for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
 // group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + 4,
 // ...: it combines the (max, sum) pieces of the group's slots into lse_n, merges the group's
@@ -434,7 +436,9 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
                                                           const int32_t* __restrict__ chunk_base,
                                                           const float* __restrict__ logp_sel, int g,
                                                           int k, int32_t* __restrict__ topk_ids,
-                                                          float* __restrict__ topk_logprob) {
+                                                          float* __restrict__ topk_logprob,
+                                                          int rows_per_slot,
+                                                          unsigned int* __restrict__ reset_word) {
     __shared__ Cand mbuf[kWavesPerBlock * kMaxK];      // the waves' running lists
     __shared__ Cand fresh[kWavesPerBlock * kMaxK];     // a group's k best, then the merged list
     __shared__ Cand outbuf[kMaxK];
@@ -449,7 +453,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
     for (int i = wave; i < g; i += kWavesPerBlock) {   // wave-uniform
         const int n = sel[m * g + i];
         const int s0 = chunk_base[m * g + i];
-        const int n_slots = (offsets[n + 1] - offsets[n] + kChunkRows - 1) / kChunkRows;
+        const int n_slots = (offsets[n + 1] - offsets[n] + rows_per_slot - 1) / rows_per_slot;
         // lse_n from the slots' pieces: per lane in ascending slot order, then across lanes
         float bm = -INFINITY, bs = 0.f;
         for (int s = lane; s < n_slots; s += kWave) {
@@ -465,7 +469,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
         const float ws = wave_sum(wm > -INFINITY ? bs * expf(bm - wm) : 0.f);
         const float shift = logp_sel[m * g + i] - (wm + logf(ws));
         // the group's k best by logit, offset added
-        wave_merge_topk(
+        wave_merge_topk<true>(                          // (few slots: all candidates in one trip)
             n_slots, k, lane, &scratch[wave],
             [&](int l, int e) { return src[(size_t)(s0 + l) * k + e]; },
             [&](int r, Cand c) {
@@ -497,6 +501,8 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
         topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
         topk_logprob[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
     }
+    // (behind the tile kernel this launch also leaves its block queue ready for the next call)
+    if (reset_word && blockIdx.x == 0 && threadIdx.x == 0) *reset_word = 0u;
 }
 
 }  // namespace

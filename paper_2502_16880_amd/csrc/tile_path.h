@@ -62,6 +62,12 @@ struct TileParams {
     int M, V, G, k;
     int n_vec, n_chunks;
     int u_max;                              // capacity of the activated-group arrays
+    // Log-probability mode (Eq. 8 normalises per group, and a block is rows of one group):
+    // every block leaves, per token that selected its group, the k best of its rows by logit
+    // and the (max, sum of exp) of its logits, slot = the block's number in the working order.
+    Cand* blk_part;                         // [M, blk_stride, k]
+    float* blk_lse;                         // [M, blk_stride, 2]
+    int blk_stride;
 };
 
 struct TileLds {
@@ -321,7 +327,7 @@ __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRin
     tile_chunk<DT, NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
 }
 
-template <int DT>
+template <int DT, bool LP = false>
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
@@ -495,9 +501,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         __syncthreads();
         // one wave per token slot, the block's rows in two halves of 64: lane = (row tile,
         // row) -> 64 logits of the token
-        for (int s = wave; s < n_t; s += kTileWaves) {
-            const int tok = tokslot[s];
-            Cand cand[2];
+        auto slot_logits = [&](int s, Cand (&cand)[2]) {
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int tile = hf * 4 + (lane >> 4), row = lane & 15;   // row tile 0..7 of the block
@@ -511,9 +515,34 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                 cand[hf].id = rowid[hf * kWave + lane];
                 if (cand[hf].id < 0) cand[hf] = sentinel();
             }
+        };
+        if (LP) {
+            // this block's share of the group's log-sum-exp for every token (a pass of its own:
+            // the merge below has no registers to spare), and fresh lists: the block's k best
+            // are its own (the tokens' LDS lists are scratch here)
+            for (int s = wave; s < n_t; s += kTileWaves) {
+                const int tok = tokslot[s];
+                Cand cand[2];
+                slot_logits(s, cand);
+                const float z0 = is_real(cand[0]) ? cand[0].v : -INFINITY;
+                const float z1 = is_real(cand[1]) ? cand[1].v : -INFINITY;
+                float wm = fmaxf(z0, z1);
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
+                const float tot = wave_sum(wm > -INFINITY ? expf(z0 - wm) + expf(z1 - wm) : 0.f);
+                if (lane < 2) p.blk_lse[uni(tok * p.blk_stride + b) * 2 + lane] = lane ? tot : wm;
+                if (lane < k) lists[tok * k + lane] = sentinel();
+            }
+        }
+        for (int s = wave; s < n_t; s += kTileWaves) {
+            const int tok = tokslot[s];
+            Cand cand[2];
+            slot_logits(s, cand);
             tile_merge_pair(lists + (size_t)tok * k, k, lane, cand[0], cand[1],
                             reinterpret_cast<unsigned long long*>(my_slice),
                             reinterpret_cast<unsigned*>(my_slice) + 4 * kWave);
+            if (LP && lane < k)
+                p.blk_part[uni(tok * p.blk_stride + b) * k + lane] = lists[tok * k + lane];
         }
         __syncthreads();
         b = nb;
@@ -522,6 +551,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         bm = nbm;
     }
 
+    if (LP) return;                                    // (every block has left its own lists)
     // publish the workgroup's lists (all tokens; untouched ones are padding)
     const int P = gridDim.x;
     for (int i = threadIdx.x; i < M * k; i += kTileBlock) {
@@ -548,7 +578,11 @@ struct GateSelParams {
     int32_t* n_union;                       // [1]
     unsigned int* counter;                  // arrival counter, zero between calls
     int M, G, g, n_vec;
+    // log-probability mode (G <= 64, M * g <= kGateSelMaxPairs), else null:
+    int32_t* first_block;                   // [M, g] out: first block of the selected group
+    float* logp_sel;                        // [M, g] out: log p_router of the selected group
 };
+constexpr int kGateSelMaxPairs = 1024;
 
 __device__ __forceinline__ float load_score(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -563,6 +597,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ int order[kMaxG], nblk[kMaxG];
     __shared__ int is_last, ucount;
     __shared__ int off_lds[kMaxG + 1];
+    __shared__ int rank_of[kMaxG];
+    __shared__ int sel_lds[kGateSelMaxPairs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     // the groups' row ranges travel with the first operand loads (requested here, put into LDS
@@ -625,9 +661,20 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
             if (!(v == v)) v = -INFINITY;
             const int rank = wave_rank(sel_keys[wave], v, lane, p.G, lane);
+            float lse_s = 0.f;
+            if (p.logp_sel) {                               // the router's softmax over all G scores (Eq. 7)
+                float smax = v;
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) smax = fmaxf(smax, __shfl_xor(smax, off));
+                lse_s = smax + logf(wave_sum(lane < p.G ? expf(v - smax) : 0.f));
+            }
             if (lane < p.G && rank < p.g) {
                 atomicOr(&mask[lane], 1ull << tm);
                 p.sel[tm * p.g + rank] = lane;
+                if (p.logp_sel) {
+                    p.logp_sel[tm * p.g + rank] = v - lse_s;
+                    sel_lds[tm * p.g + rank] = lane;
+                }
             }
         }
     } else {
@@ -680,6 +727,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
         }
         order[rank] = g0;
+        rank_of[g0] = rank;
         nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
     }
     __syncthreads();
@@ -699,8 +747,14 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                 tg.mask = mask[g0];
                 p.table[r] = tg;
             }
+            if (p.first_block && r < count) nblk[r] = carry + incl - nb;   // (now: blocks before it)
             carry += __builtin_amdgcn_readlane(incl, 63);
         }
+    }
+    if (p.first_block) {                               // block-uniform
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < p.M * p.g; idx += kFusedBlock)
+            p.first_block[idx] = nblk[rank_of[sel_lds[idx]]];
     }
 }
 

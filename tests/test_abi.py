@@ -78,7 +78,9 @@ def test_logprob_path_selection():
     assert lp(1, 4096, 128256, 32, 4, 10, BF16) == 1               # Llama3 shape
     assert lp(16, 4096, 128256, 32, 4, 10, BF16) == 1
     assert lp(16, 3584, 152064, 32, 4, 10, BF16) == 1              # Qwen shape
-    assert lp(64, 4096, 128256, 64, 8, 16, BF16) == 0              # wide tree: hidden exceeds LDS
+    assert lp(64, 4096, 128256, 64, 8, 16, BF16) == 2              # wide tree: hidden exceeds LDS
+    assert lp(64, 4160, 128256, 64, 8, 16, BF16) == 0              # ... and H not a multiple of 512
+    assert lp(64, 4096, 128256, 128, 8, 16, BF16) == 0             # tile path ranks 64 groups at most
     assert lp(20, 256, 8192, 128, 4, 8, F32) == 0                  # 80 groups may be active
     assert lp(2, 256, 8192, 64, 17, 8, F32) == 0                   # 17 lists per token
     assert lp(65, 256, 8192, 16, 2, 8, F32) == -1

@@ -152,6 +152,11 @@ LOGPROB_PATH_CASES = [
     (HeadConfig("lpall", "bf16", 512, 16 * 300, 16, 16, (4,), 10, 99, True), 1),
     # ... fp16 storage, contiguous groups, more candidates than a group's workgroups
     (HeadConfig("lpf16", "f16", 1024, 8 * 4000, 8, 2, (7,), 33, 102, True, grouping="contiguous"), 1),
+    # tile path: 64 tokens do not fit the single-launch kernel; ragged last blocks, a second
+    # token tile only partly used, fp16
+    (CONFIGS["wide_tree"].scaled(V=64 * 300), 2),
+    (HeadConfig("lptile40", "bf16", 2048, 16 * 777, 16, 5, (40,), 12, 104, True, bias_std=1.0), 2),
+    (HeadConfig("lptilef16", "f16", 2048, 10 * 333, 10, 4, (33,), 16, 105, True), 2),
     # multi-kernel path: more than 64 groups can be active; more than 16 groups per token
     (HeadConfig("lpmany", "f32", 128, 128 * 20, 128, 4, (20,), 8, 100, False), 0),
     (HeadConfig("lpg17", "f32", 128, 64 * 20, 64, 17, (2,), 8, 101, False), 0),
@@ -734,7 +739,8 @@ DRAFT_LEVEL_CASES = [
     (CONFIGS["paper_point"].scaled(V=16 * 501), 10, 10, True, 1),
     (CONFIGS["tiny_f32"], 4, 32, True, 1),                            # every candidate kept (n_next = M k)
     (CONFIGS["llama2_7b"].scaled(H=1024, V=16 * 250, k=40), 20, 64, True, 1),  # lists of 40, 20 nodes
-    (CONFIGS["wide_tree"].scaled(V=64 * 126), 64, 64, True, 0),       # multi-kernel path: one more launch
+    (CONFIGS["wide_tree"].scaled(V=64 * 126), 64, 64, True, 2),       # tile path: one more launch
+    (CONFIGS["wide_tree"].scaled(H=4160, V=64 * 126), 64, 20, True, 0),   # staged path: one more launch
 ]
 
 
