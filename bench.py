@@ -447,7 +447,7 @@ def main():
                           "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
                           "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
         r = bench.time_grouped(a.M, n, min(a.warmup, 20), eager=a.eager, event_steps=48, logprob=True)
-        lp_kernel = "single-launch kernel k_fused" if r["path"] == 1 else "multi-kernel path, k_logits"
+        lp_kernel = {1: "single-launch kernel k_fused", 2: "tile path, k_tiles"}.get(r["path"], "multi-kernel path, k_logits")
         cases.append({"path": f"grouped, log-probability output (Eq. 8; {lp_kernel})",
                       "M": a.M, "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
                       "avg_activated_groups": r["U"],
