@@ -45,7 +45,7 @@ constexpr size_t kCtrlBytes = 512;     // control words at the start of the work
 static_assert(kCtrlBytes >= (kLpGroupCounters + kWave) * sizeof(unsigned int), "per-group counters");
 
 struct Layout {
-    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, part, lse_part, logp_sel, tile_table, total;
+    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_table, total;
     int part_stride;
 };
 
@@ -78,6 +78,7 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces) {
     L.union_list = take((size_t)(G ? G : 1) * sizeof(int32_t));
     L.n_union = take(sizeof(int32_t));
     L.chunk_base = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
+    L.slot_count = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.part_stride = (V + kChunkRows - 1) / kChunkRows + g;
     L.part = take((size_t)M * L.part_stride * k * sizeof(Cand));
     L.lse_part = take((size_t)M * L.part_stride * 2 * sizeof(float));     // log-probability mode
@@ -347,10 +348,10 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     if (lp_sel) {
         hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, p.blk_part, p.blk_lse,
-                           L.part_stride, lp_sel, gi->group_offsets,
+                           L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count),
                            reinterpret_cast<const int32_t*>(ws + L.chunk_base),
                            reinterpret_cast<const float*>(ws + L.logp_sel), g, k, topk_ids, topk_logits,
-                           kTileRows, p.next_block);
+                           p.next_block);
         return launch_status();
     }
     hipLaunchKernelGGL(k_merge_published, dim3((M + 3) / 4), dim3(256), 0, stream,
@@ -500,6 +501,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
         if (logprob) {
             q.first_block = chunk_base;
+            q.block_count = reinterpret_cast<int32_t*>(ws + L.slot_count);
             q.logp_sel = reinterpret_cast<float*>(ws + L.logp_sel);
         }
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
@@ -522,7 +524,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if ((st = launch_status()) != CORAL_OK) return st;
     float* logp_sel = logprob ? reinterpret_cast<float*>(ws + L.logp_sel) : nullptr;
     hipLaunchKernelGGL(k_select, dim3(1), dim3(kBlock), 0, stream, s, gi->group_offsets, M, G, g, sel,
-                       mask, union_list, n_union, chunk_base, logp_sel);
+                       mask, union_list, n_union, chunk_base, logp_sel,
+                       logprob ? reinterpret_cast<int32_t*>(ws + L.slot_count) : nullptr);
     if ((st = launch_status()) != CORAL_OK) return st;
 
     LogitsParams p;
@@ -563,8 +566,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     if (logprob)
         hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
-                           L.part_stride, sel, gi->group_offsets, chunk_base, logp_sel, g, k, topk_ids,
-                           topk_logits, kChunkRows, nullptr);
+                           L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count), chunk_base,
+                           logp_sel, g, k, topk_ids, topk_logits, nullptr);
     else
         hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
                            gi->group_offsets, g, 0, k, topk_ids, topk_logits);

@@ -253,7 +253,8 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
                                                    int32_t* __restrict__ union_list,
                                                    int32_t* __restrict__ n_union,
                                                    int32_t* __restrict__ chunk_base,
-                                                   float* __restrict__ logp_sel) {
+                                                   float* __restrict__ logp_sel,
+                                                   int32_t* __restrict__ slot_count) {
     __shared__ unsigned long long mask[kMaxG];
     __shared__ int off_lds[kMaxG + 1];                 // group offsets: no dependent loads later
     const int lane = threadIdx.x & (kWave - 1);
@@ -286,7 +287,10 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             int slot_base = 0;                              // slots in rank order
             for (int r = 0; r < g; ++r) {                   // wave-uniform
                 const int src = __ffsll(__ballot(chosen && rank == r)) - 1;
-                if (lane == src) chunk_base[m * g + r] = slot_base;
+                if (lane == src) {
+                    chunk_base[m * g + r] = slot_base;
+                    if (slot_count) slot_count[m * g + r] = nch;
+                }
                 slot_base += __builtin_amdgcn_readlane(nch, src);
             }
         }
@@ -342,6 +346,8 @@ __global__ __launch_bounds__(kBlock) void k_select(const float* __restrict__ s,
             if (lane == 0) {
                 sel[m * g + round] = bi;
                 chunk_base[m * g + round] = slot_base;
+                if (slot_count)
+                    slot_count[m * g + round] = (off_lds[bi + 1] - off_lds[bi] + kChunkRows - 1) / kChunkRows;
                 if (logp_sel) logp_sel[m * g + round] = bv - lse_s;
                 atomicOr(&mask[bi], 1ull << m);
             }
@@ -420,7 +426,8 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 
 
 // Final merge of the log-probability mode behind k_logits (a slot = a chunk of kChunkRows
-// rows) and behind k_tiles (a slot = a block of kTileRows rows; rows_per_slot says which).
+// rows) and behind k_tiles (a slot = a block of kTileRows rows): slot_count[m, i] slots from
+// chunk_base[m, i] on belong to token m's i-th selected group.
 // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n
 // for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
 // group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + 4,
@@ -431,13 +438,11 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict__ part,
                                                           const float* __restrict__ lse_part,
                                                           int part_stride,
-                                                          const int32_t* __restrict__ sel,
-                                                          const int32_t* __restrict__ offsets,
+                                                          const int32_t* __restrict__ slot_count,
                                                           const int32_t* __restrict__ chunk_base,
                                                           const float* __restrict__ logp_sel, int g,
                                                           int k, int32_t* __restrict__ topk_ids,
                                                           float* __restrict__ topk_logprob,
-                                                          int rows_per_slot,
                                                           unsigned int* __restrict__ reset_word) {
     __shared__ Cand mbuf[kWavesPerBlock * kMaxK];      // the waves' running lists
     __shared__ Cand fresh[kWavesPerBlock * kMaxK];     // a group's k best, then the merged list
@@ -451,9 +456,8 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
     if (lane < k) mine[lane] = sentinel();
     const Cand* src = part + (size_t)m * part_stride * k;
     for (int i = wave; i < g; i += kWavesPerBlock) {   // wave-uniform
-        const int n = sel[m * g + i];
-        const int s0 = chunk_base[m * g + i];
-        const int n_slots = (offsets[n + 1] - offsets[n] + rows_per_slot - 1) / rows_per_slot;
+        const int s0 = chunk_base[m * g + i];          // (three loads that do not wait for each other)
+        const int n_slots = slot_count[m * g + i];
         // lse_n from the slots' pieces: per lane in ascending slot order, then across lanes
         float bm = -INFINITY, bs = 0.f;
         for (int s = lane; s < n_slots; s += kWave) {

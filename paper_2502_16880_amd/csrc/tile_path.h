@@ -580,6 +580,7 @@ struct GateSelParams {
     int M, G, g, n_vec;
     // log-probability mode (G <= 64, M * g <= kGateSelMaxPairs), else null:
     int32_t* first_block;                   // [M, g] out: first block of the selected group
+    int32_t* block_count;                   // [M, g] out: how many blocks it has
     float* logp_sel;                        // [M, g] out: log p_router of the selected group
 };
 constexpr int kGateSelMaxPairs = 1024;
@@ -747,14 +748,21 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                 tg.mask = mask[g0];
                 p.table[r] = tg;
             }
-            if (p.first_block && r < count) nblk[r] = carry + incl - nb;   // (now: blocks before it)
+            if (p.first_block && r < count) {
+                nblk[r] = carry + incl - nb;            // (now: blocks before it)
+                ulist[r] = nb;                          // (the list of activated groups is spent)
+            }
             carry += __builtin_amdgcn_readlane(incl, 63);
         }
     }
     if (p.first_block) {                               // block-uniform
         __syncthreads();
         for (int idx = threadIdx.x; idx < p.M * p.g; idx += kFusedBlock)
-            p.first_block[idx] = nblk[rank_of[sel_lds[idx]]];
+        {
+            const int r = rank_of[sel_lds[idx]];
+            p.first_block[idx] = nblk[r];
+            p.block_count[idx] = ulist[r];
+        }
     }
 }
 
