@@ -284,7 +284,7 @@ def test_ragged_and_empty_groups(coral):
         run_grouped(coral, dh, make_hidden(cfg, 6), 2, 4)
 
 
-@pytest.mark.parametrize("seed", list(range(200, 264)) + list(range(300, 324)))
+@pytest.mark.parametrize("seed", list(range(200, 264)) + list(range(300, 324)) + list(range(400, 412)))
 def test_random_small_heads(coral, seed):
     """Seeded random shapes with ragged groups (some empty, some of one row): token counts,
     group counts, g and k drawn freely within the limits, fp32 heads so that the oracle is
@@ -295,6 +295,8 @@ def test_random_small_heads(coral, seed):
     M = int(rng.integers(1, 25))
     dtype = "f32" if seed < 300 else ("bf16", "f16")[seed % 2]  # 16-bit: matrix-core gate from 5 tokens on
     H = int(rng.choice([32, 64, 100, 256, 516] if dtype == "f32" else [64, 104, 256, 512]))
+    if seed >= 400:                                             # many tokens x long rows: the tile path
+        M, H = int(rng.integers(41, 65)), 2048
     sizes = rng.integers(0, 120, G)
     sizes[rng.integers(0, G)] += int(rng.integers(100, 2000))     # one large group
     if G > 3:
