@@ -347,7 +347,10 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     if (lp_sel) {
-        hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, p.blk_part, p.blk_lse,
+        typedef void (*merge_fn)(const Cand*, const float*, int, const int32_t*, const int32_t*, const float*,
+                                 int, int, int32_t*, float*, unsigned int*);
+        const merge_fn mf = g > 4 ? k_merge_logprob<8> : k_merge_logprob<4>;
+        hipLaunchKernelGGL(mf, dim3(M), dim3(g > 4 ? 8 * kWave : kBlock), 0, stream, p.blk_part, p.blk_lse,
                            L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count),
                            reinterpret_cast<const int32_t*>(ws + L.chunk_base),
                            reinterpret_cast<const float*>(ws + L.logp_sel), g, k, topk_ids, topk_logits,
@@ -565,7 +568,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
     if (logprob)
-        hipLaunchKernelGGL(k_merge_logprob, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
+        hipLaunchKernelGGL(k_merge_logprob<4>, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
                            L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count), chunk_base,
                            logp_sel, g, k, topk_ids, topk_logits, nullptr);
     else

@@ -430,12 +430,14 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 // chunk_base[m, i] on belong to token m's i-th selected group.
 // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n
 // for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
-// group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + 4,
+// group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + WAVES,
 // ...: it combines the (max, sum) pieces of the group's slots into lse_n, merges the group's
 // partial lists (sorted by logit, which inside a group is the order of log p as well) into
 // the group's k best, adds the offset log p_router(n) - lse_n and merges that list into its
-// running list.  The four running lists are merged at the end; equal values: lower id first.
-__global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict__ part,
+// running list.  The waves' running lists (WAVES = 4, or 8 when a token has more than four
+// groups) are merged at the end; equal values: lower id first.
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * kWave) void k_merge_logprob(const Cand* __restrict__ part,
                                                           const float* __restrict__ lse_part,
                                                           int part_stride,
                                                           const int32_t* __restrict__ slot_count,
@@ -444,10 +446,10 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
                                                           int k, int32_t* __restrict__ topk_ids,
                                                           float* __restrict__ topk_logprob,
                                                           unsigned int* __restrict__ reset_word) {
-    __shared__ Cand mbuf[kWavesPerBlock * kMaxK];      // the waves' running lists
-    __shared__ Cand fresh[kWavesPerBlock * kMaxK];     // a group's k best, then the merged list
+    __shared__ Cand mbuf[WAVES * kMaxK];      // the waves' running lists
+    __shared__ Cand fresh[WAVES * kMaxK];     // a group's k best, then the merged list
     __shared__ Cand outbuf[kMaxK];
-    __shared__ WaveScratch scratch[kWavesPerBlock];
+    __shared__ WaveScratch scratch[WAVES];
     const int m = blockIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
@@ -455,7 +457,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
     Cand* grp = fresh + wave * k;
     if (lane < k) mine[lane] = sentinel();
     const Cand* src = part + (size_t)m * part_stride * k;
-    for (int i = wave; i < g; i += kWavesPerBlock) {   // wave-uniform
+    for (int i = wave; i < g; i += WAVES) {   // wave-uniform
         const int s0 = chunk_base[m * g + i];          // (three loads that do not wait for each other)
         const int n_slots = slot_count[m * g + i];
         // lse_n from the slots' pieces: per lane in ascending slot order, then across lanes
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(kBlock) void k_merge_logprob(const Cand* __restrict
         if (lane < k && lane >= n_real) grp[lane] = sentinel();
         if (lane < k) mine[lane] = grp[lane];
     }
-    block_rank_merge(mbuf, kWavesPerBlock * k, k, outbuf);
+    block_rank_merge(mbuf, WAVES * k, k, outbuf);
     if ((int)threadIdx.x < k) {
         topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
         topk_logprob[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
