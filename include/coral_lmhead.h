@@ -251,7 +251,8 @@ coral_status coral_tree_expand(const float *parent_score, const int32_t *cand_id
  * (cand_ids = topk_ids, cand_logp = topk_logprob).  Where the head runs in the single-launch
  * kernel (coral_lmhead_logprob_path == 1) the workgroup that writes the head's result also
  * expands the level, so the call is one launch; otherwise the expansion is one more launch
- * behind the staged path's.  Results are identical to the two calls made one after the other.
+ * behind those of the tile or staged path.  Results are identical to the two calls made one
+ * after the other.
  *   parent_score [device] [M] fp32 or NULL, n_next, next_parent / next_token / next_score
  *   [device] out [n_next]: as for coral_tree_expand.  topk_ids, topk_logprob, sel_groups:
  *   as for coral_lmhead_grouped_logprob (they are written as well).
