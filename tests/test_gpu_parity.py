@@ -474,23 +474,24 @@ def test_hip_graph_replays_match_eager(coral):
     check_grouped(dh, hidden, cfg.g, cfg.k, (ids.cpu().numpy(), z.cpu().numpy(), sel.cpu().numpy()))
 
 
-@pytest.mark.parametrize("M", [1, 4])
+@pytest.mark.parametrize("M", [1, 4, 64])
 def test_hip_graph_replays_of_the_logprob_head(coral, M):
     """The log-probability mode keeps several counters in the workspace (one per activated
-    group with 4 tokens, one in all with 1 token): every replay, and an eager call after the
-    replays, must find them as the first call did."""
-    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 501)
+    group with 4 tokens, one in all with 1 token; the tile path's block queue with 64): every
+    replay, and an eager call after the replays, must find them as the first call did."""
+    cfg = CONFIGS["llama3_8b"].scaled(V=32 * 501) if M < 64 else CONFIGS["wide_tree"].scaled(V=64 * 300)
     dh = DeviceHead(coral, make_head(cfg))
     hidden = make_hidden(cfg, M, 3)
     d_hidden = coral.device_tensor(hidden, cfg.dtype)
-    assert coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16) == 1
+    assert coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k,
+                                           coral.CORAL_BF16) == (1 if M < 64 else 2)
     ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16)
     ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
     lp = torch.empty((M, cfg.k), device="cuda")
     sel = torch.empty((M, cfg.g), dtype=torch.int32, device="cuda")
 
     def call():
-        coral.coral_lmhead_grouped_logprob(d_hidden, dh.gate_W, None, dh.lm_W, dh.gi, cfg.g, cfg.k,
+        coral.coral_lmhead_grouped_logprob(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k,
                                            topk_ids=ids, topk_logits=lp, sel_groups=sel, workspace=ws)
 
     call()
