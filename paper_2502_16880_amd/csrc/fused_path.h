@@ -18,10 +18,12 @@
 //
 // Log-probability mode (LP, Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n, the softmax
 // taken inside each selected group): a workgroup streams rows of one group only, the
-// workgroups shared out among the activated groups by cost; lane t of every wave carries
-// token t's running log-sum-exp beside the lists; the last workgroup of each group finishes
-// the group (lse_n, offset, the group's k best per token) and the last group merges every
-// token's g lists.
+// workgroups shared out among the activated groups by cost; beside the lists, lane t of
+// every wave notes the (max, sum of exp) of every row pair for token t, and the workgroup
+// sums these pieces in pair order (the result then does not depend on which wave drew
+// which pair); the last workgroup of each group finishes the group (lse_n, offset, the
+// group's k best per token) and the last group merges every token's g lists.  A draft-level
+// call also expands the tree level in that last workgroup (tree_expand.h).
 #pragma once
 #include "device_utils.h"
 #include "tree_expand.h"
