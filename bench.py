@@ -9,13 +9,16 @@ resident in HBM before the timed region.  The headline line is M=8 (a level of t
 tree; the paper's tree expands the top 10 candidates per level); M=1,4,16 and the dense
 head are timed beside it and reported under "cases".
 
-Protocol: a cycle of R distinct hidden batches is captured once into a HIP graph and
-replayed; consecutive batches of a cycle select disjoint groups whenever the active set
-is smaller than the last-level cache, so the weight rows come from HBM and not from the
-256 MB cache.  The roofline of the dominant kernel (the one that streams the weight
-rows) is taken from HIP events the library records around that kernel on its stream.
-The fp64 CPU oracle is timed beside it on a few of the same batches (a reported
-baseline, not a target).
+Protocol: a cycle of R distinct hidden batches (R divides the step count, at most 24) is
+captured once into a HIP graph and replayed; consecutive batches of a cycle select
+disjoint groups whenever the active set is smaller than the last-level cache, so the
+weight rows come from HBM and not from the 256 MB cache.  The roofline of the dominant
+kernel (the one that streams the weight rows) is taken from HIP events on the launch
+stream: on the single-launch path the pair that brackets the timed region (nothing but
+that kernel runs inside it), elsewhere the pairs the library records around that kernel.
+The Qwen2.5-7B shape and the paper's own operating point (16 groups, top 2; contiguous
+against permuted groups) are timed beside the headline under "cases".  The fp64 CPU
+oracle is timed on a few of the same batches (a reported baseline, not a target).
 
 Prints ONE JSON line.
 """
@@ -45,8 +48,10 @@ def parse():
                     help="draft tokens per step of the headline line (the paper expands the top "
                          "10 candidates per tree level; 8 is the nearest configured value)")
     ap.add_argument("--cases", default="default",
-                    help="'default': also time the config's other M values and the dense head with "
-                         "fewer steps; 'none': headline only")
+                    help="'default': also time the config's other M values, the dense head, the other "
+                         "entry points and (for the headline config) the Qwen2.5-7B shape and the "
+                         "paper's operating point, with fewer steps; 'own': this config only; "
+                         "'none': headline only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="no HIP graph: one host call per step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -72,16 +77,33 @@ def dense_bytes(cfg, M):
     return cfg.V * cfg.H * w + M * cfg.H * w + M * cfg.k * 8
 
 
+def cycle_length(steps, most=24):
+    """Batches in the replayed cycle: the largest divisor of the step count up to `most`, so
+    that whole cycles make up the timed region; if the step count has no divisor of at
+    least 8 (or is smaller), min(steps, most) and the remainder runs as single calls."""
+    best = max(d for d in range(1, min(most, steps) + 1) if steps % d == 0)
+    return best if best >= min(8, steps) else min(steps, most)
+
+
 class Bench:
-    def __init__(self, cfg):
+    def __init__(self, cfg, share=None):
         import torch
         import paper_2502_16880_amd as coral
         from coral_inputs import make_head
         self.torch, self.coral, self.cfg = torch, coral, cfg
         t0 = time.time()
-        self.head = make_head(cfg)
-        self.gate_W = coral.device_tensor(self.head.gate_W, cfg.dtype)
-        self.lm_W = coral.device_tensor(self.head.lm_W, cfg.dtype)
+        if share is not None:
+            # the same seed and shape with another grouping: the weights are the same draws
+            from coral_inputs import Head, make_partition
+            o = share.cfg
+            assert (o.seed, o.dtype, o.H, o.V, o.G) == (cfg.seed, cfg.dtype, cfg.H, cfg.V, cfg.G)
+            off, rows = make_partition(cfg)
+            self.head = Head(cfg, share.head.lm_W, share.head.gate_W, share.head.gate_bias, off, rows)
+            self.gate_W, self.lm_W = share.gate_W, share.lm_W
+        else:
+            self.head = make_head(cfg)
+            self.gate_W = coral.device_tensor(self.head.gate_W, cfg.dtype)
+            self.lm_W = coral.device_tensor(self.head.lm_W, cfg.dtype)
         self.bias = None if self.head.gate_bias is None else torch.from_numpy(self.head.gate_bias).cuda()
         self.gi = coral.GroupIndex(self.head.group_offsets, self.head.group_rows)
         self.dt = {"f32": coral.CORAL_F32, "bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[cfg.dtype]
@@ -131,9 +153,9 @@ class Bench:
         return chosen
 
     # ---------------------------------------------------------------- timing
-    def time_grouped(self, M, steps, warmup, R=24, eager=False, event_steps=240, logprob=False):
+    def time_grouped(self, M, steps, warmup, eager=False, event_steps=240, logprob=False):
         torch, coral, cfg = self.torch, self.coral, self.cfg
-        sched = self.schedule(M, R)
+        sched = self.schedule(M, cycle_length(steps))
         R = len(sched)
         ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt)
         ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
@@ -146,18 +168,18 @@ class Bench:
                                        workspace=ws, events=events, logprob=logprob)
 
         total_ms = self._timed(call, steps, warmup, R, eager)
-        spread = self.last_spread
-        kernel_us = self._kernel_us(call, min(event_steps, steps))
+        spread, graph = self.last_spread, self.last_graph
+        region_us = self.last_event_ms * 1e3 / steps
+        pairs_us = self._kernel_us(call, min(event_steps, steps))
         path = (coral.coral_lmhead_logprob_path(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt) if logprob
                 else coral.coral_lmhead_path(False, M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt))
-        if path == 1:
-            # single launch: the events around the timed region time nothing but this kernel
-            # (launch gaps included); the pair around one launch adds the dispatch latency
-            kernel_us = min(kernel_us, self.last_event_ms * 1e3 / steps)
-        U = sum(len(c[3]) for c in sched) / R
-        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms, kernel_us=kernel_us,
+        # the batches the timed region ran, each as often as it ran
+        ran = [len(sched[i % R][3]) for i in range(steps)]
+        U = sum(ran) / steps
+        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms,
                     U=U, bytes=algorithmic_bytes(cfg, M, U), batches=R, sched=sched,
-                    out=(ids, z, sel), call=call, spread=spread, path=path)
+                    out=(ids, z, sel), call=call, spread=spread, path=path, graph=graph,
+                    **kernel_timers(path, region_us, pairs_us))
 
     def time_repeat(self, M, steps, warmup):
         """The same input every call: the activated rows may stay in the 256 MB last-level
@@ -176,12 +198,15 @@ class Bench:
         total_ms = self._timed(call, steps, warmup, 8, False)
         return total_ms * 1e3 / steps
 
-    def time_routed(self, M, steps, warmup, R=24):
+    def time_routed(self, M, steps, warmup):
         """The paper's full router in front of the head (Eq. 7): one step = the pre-mix
         u = act(W1 h) + h, then the grouped head with the router reading u.  Also times the
-        pre-mix alone over a cycle of W1 copies larger than the last-level cache."""
+        pre-mix alone, twice: over a cycle of W1 copies larger than the last-level cache
+        (every W1 byte from HBM), and with the one W1 every step (as in a draft loop, where
+        its 33.6 MB can stay in the 256 MB cache)."""
         torch, coral, cfg = self.torch, self.coral, self.cfg
         from coral_inputs import make_hidden, make_router_W1
+        R = cycle_length(steps)
         W1 = coral.device_tensor(make_router_W1(cfg), cfg.dtype)
         hs = [coral.device_tensor(make_hidden(cfg, M, b), cfg.dtype) for b in range(R)]
         us = [torch.empty_like(h) for h in hs]
@@ -203,17 +228,23 @@ class Bench:
         def premix(i, events=None):
             coral.coral_router_premix(hs[i % R], copies[i % len(copies)], "silu", out=us[i % R])
 
-        R2 = len(copies) * (R // len(copies) + 1)
-        premix_us = self._timed(premix, max(steps, R2), warmup, R2, False) * 1e3 / max(steps, R2)
-        bytes_premix = w1_bytes + 2 * M * cfg.H * weight_bytes_per_elt(cfg.dtype)
-        return dict(step_us=step_us, premix_us=premix_us, premix_bytes=bytes_premix)
+        def premix_resident(i, events=None):
+            coral.coral_router_premix(hs[i % R], W1, "silu", out=us[i % R])
 
-    def time_draft_level(self, M, n_next, steps, warmup, R=24):
+        R2 = len(copies) * (R // len(copies) + 1)
+        n2 = (max(steps, R2) + R2 - 1) // R2 * R2
+        premix_us = self._timed(premix, n2, warmup, R2, False) * 1e3 / n2
+        resident_us = self._timed(premix_resident, steps, warmup, R, False) * 1e3 / steps
+        bytes_premix = w1_bytes + 2 * M * cfg.H * weight_bytes_per_elt(cfg.dtype)
+        return dict(step_us=step_us, premix_us=premix_us, premix_resident_us=resident_us,
+                    premix_bytes=bytes_premix)
+
+    def time_draft_level(self, M, n_next, steps, warmup):
         """One level of tree drafting: the log-probability head for M nodes and the expansion
         to n_next nodes, as one call (coral_lmhead_draft_level) and as the two calls it
         stands for."""
         torch, coral, cfg = self.torch, self.coral, self.cfg
-        sched = self.schedule(M, R)
+        sched = self.schedule(M, cycle_length(steps))
         R = len(sched)
         ws = coral.alloc_workspace(M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, self.dt)
         ids = torch.empty((M, cfg.k), dtype=torch.int32, device="cuda")
@@ -266,11 +297,11 @@ class Bench:
                                      workspace=ws, events=events)
 
         total_ms = self._timed(call, steps, warmup, 4, eager)
-        kernel_us = self._kernel_us(call, min(event_steps, steps))
-        if coral.coral_lmhead_path(True, M, cfg.H, cfg.V, 0, 0, cfg.k, self.dt) == 1:
-            kernel_us = min(kernel_us, self.last_event_ms * 1e3 / steps)
-        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms, kernel_us=kernel_us,
-                    bytes=dense_bytes(cfg, M))
+        region_us = self.last_event_ms * 1e3 / steps
+        pairs_us = self._kernel_us(call, min(event_steps, steps))
+        path = coral.coral_lmhead_path(True, M, cfg.H, cfg.V, 0, 0, cfg.k, self.dt)
+        return dict(M=M, us_per_step=total_ms * 1e3 / steps, total_ms=total_ms,
+                    bytes=dense_bytes(cfg, M), path=path, **kernel_timers(path, region_us, pairs_us))
 
     def _timed(self, call, steps, warmup, R, eager):
         """Exactly `steps` steps between two device synchronisations; returns ms."""
@@ -303,6 +334,9 @@ class Bench:
         torch.cuda.synchronize()
         total_ms = (time.perf_counter() - t0) * 1e3
         self.last_event_ms = ev0.elapsed_time(ev1)
+        self.last_graph = {"captured": graph is not None, "cycle": R,
+                           "replays": steps // R if graph is not None else 0,
+                           "single_calls": steps - done}
         # spread: a few replays of the cycle timed one by one (outside the timed region)
         self.last_spread = None
         if graph is not None:
@@ -369,15 +403,72 @@ def parity_spot_check(bench, res):
 KERNEL_OF_PATH = {0: "k_logits", 1: "k_fused", 2: "k_tiles"}
 
 
+def kernel_timers(path, region_us, pairs_us):
+    """The two estimates of the weight-streaming kernel's average launch duration, and the
+    one the roofline uses.  Single-launch path: the event pair around the whole timed region
+    divided by the launches in it (only that kernel runs there; launch gaps are included).
+    Other paths: the pairs the library records around that kernel in every step (each pair
+    also includes the dispatch latency of one launch)."""
+    timer = "events_around_timed_region" if path == 1 else "event_pair_per_launch"
+    return {"kernel_us": region_us if path == 1 else pairs_us, "kernel_timer": timer,
+            "kernel_us_events_around_timed_region": region_us if path == 1 else None,
+            "kernel_us_event_pair_per_launch": pairs_us}
+
+
 def read_traffic(kernel, workload):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}_{workload}.txt")
+    """HBM bytes per launch of this kernel on this workload from the committed rocprofv3 --pmc
+    summary (FETCH_SIZE and WRITE_SIZE runs of their own, scaled by a copy kernel's
+    readings), if there is one: (bytes, file)."""
+    name = f"traffic_{kernel}_{workload}.txt"
+    path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
-    return None
+            return float(line.split(":")[1]), "profiles/" + name
+    return None, None
+
+
+def grouped_case(r, label="grouped"):
+    c = {"path": label, "M": r["M"], "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
+         "kernel_timer": r["kernel_timer"], "avg_activated_groups": r["U"],
+         "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
+         "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS,
+         "frac_whole_step": r["bytes"] / r["us_per_step"] / 1e3 / HBM_PEAK_GBPS,
+         "graph": r["graph"]["captured"]}
+    return c
+
+
+def dense_case(r, label="dense"):
+    return {"path": label, "M": r["M"], "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
+            "kernel_timer": r["kernel_timer"],
+            "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
+            "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS}
+
+
+def other_shapes(a, n, cases):
+    """The second shape the target names (Qwen2.5-7B) and the paper's own operating point
+    (Table 4's 16 groups, top 2, ten candidates per level) with contiguous and with permuted
+    groups, on the same clock as the headline."""
+    import gc
+    from coral_inputs import CONFIGS
+    torch = __import__("torch")
+    q = Bench(CONFIGS["qwen25_7b"])
+    for M in q.cfg.Ms:
+        r = q.time_grouped(M, n, 20, eager=a.eager, event_steps=48)
+        cases.append(grouped_case(r, "grouped, qwen25_7b (H=3584 V=152064 G=32x4752 g=4 k=10)"))
+    cases.append(dense_case(q.time_dense(1, max(24, n // 4), 4, eager=a.eager, event_steps=24),
+                            "dense, qwen25_7b"))
+    del q
+    gc.collect()
+    torch.cuda.empty_cache()
+    pp = Bench(CONFIGS["paper_point"])
+    pairs = [(pp, "grouped, paper_point (G=16x8016 g=2 k=10, contiguous groups)"),
+             (Bench(CONFIGS["paper_point_permuted"], share=pp),
+              "grouped, paper_point_permuted (same weights, permuted groups: gathered rows)")]
+    for b, label in pairs:
+        for M in b.cfg.Ms:
+            cases.append(grouped_case(b.time_grouped(M, n, 20, eager=a.eager, event_steps=48), label))
 
 
 def main():
@@ -406,8 +497,13 @@ def main():
     gbps_kernel = res["bytes"] / (res["kernel_us"] * 1e-6) / 1e9
     workload = f"{cfg.name}_M{a.M}"
     import paper_2502_16880_amd as coral
-    path = coral.coral_lmhead_path(False, a.M, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, bench.dt)
+    path = res["path"]
     kernel = KERNEL_OF_PATH[path]
+    traffic, traffic_file = read_traffic(kernel, workload)
+    g = res["graph"]
+    how = (f"HIP graph of {g['cycle']} distinct hidden batches replayed {g['replays']} times"
+           + (f" and {g['single_calls']} single calls" if g["single_calls"] else "")
+           if g["captured"] else f"{a.steps} single calls cycling {g['cycle']} distinct hidden batches")
     out = {
         "metric": "us per grouped LM-head draft step (Llama3-8B shape)" if a.config == "llama3_8b"
                   else f"us per grouped LM-head draft step ({cfg.name})",
@@ -415,55 +511,53 @@ def main():
         "warmup": a.warmup, "ms_per_step": res["us_per_step"] / 1e3, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: H={cfg.H} V={cfg.V} G={cfg.G}x{cfg.v} g={cfg.g} "
-                               f"M={a.M} k={cfg.k}, rotating cycle of {res['batches']} hidden batches",
-                   "avg_activated_groups": res["U"], "graph": not a.eager},
+                               f"M={a.M} k={cfg.k}; {how}",
+                   "avg_activated_groups": res["U"], "graph": g["captured"],
+                   "cycle_batches": g["cycle"], "graph_replays": g["replays"],
+                   "single_calls": g["single_calls"]},
         "achieved_GBps_whole_step": gbps_step,
+        "frac_whole_step": gbps_step / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "kernel": f"{kernel} ({coral.PATH_NAMES[path]} path)",
                      "achieved": gbps_kernel, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps_kernel / HBM_PEAK_GBPS, "kernel_us": res["kernel_us"],
+                     "kernel_timer": res["kernel_timer"],
+                     "kernel_us_events_around_timed_region": res["kernel_us_events_around_timed_region"],
+                     "kernel_us_event_pair_per_launch": res["kernel_us_event_pair_per_launch"],
                      "algorithmic_bytes": res["bytes"],
-                     "traffic": read_traffic(kernel, workload)},
+                     "traffic": traffic, "traffic_from_profile": traffic_file},
         "parity": parity_spot_check(bench, res),
     }
     if res["spread"]:
         out["us_per_step_spread"] = res["spread"]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(bench, res)
-    if a.cases == "default":
+    if a.cases in ("default", "own"):
         cases = []
         n = max(48, a.steps // 10)
         for M in cfg.Ms:
             if M == a.M:
                 continue
-            r = bench.time_grouped(M, n, min(a.warmup, 20), eager=a.eager, event_steps=48)
-            cases.append({"path": "grouped", "M": M, "us_per_step": r["us_per_step"],
-                          "kernel_us": r["kernel_us"], "avg_activated_groups": r["U"],
-                          "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
-                          "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+            cases.append(grouped_case(bench.time_grouped(M, n, min(a.warmup, 20), eager=a.eager,
+                                                         event_steps=48)))
         for M in sorted({1, max(cfg.Ms)}):
-            r = bench.time_dense(M, max(24, n // 4), 4, eager=a.eager, event_steps=24)
-            cases.append({"path": "dense", "M": M, "us_per_step": r["us_per_step"],
-                          "kernel_us": r["kernel_us"],
-                          "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
-                          "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+            cases.append(dense_case(bench.time_dense(M, max(24, n // 4), 4, eager=a.eager, event_steps=24)))
         r = bench.time_grouped(a.M, n, min(a.warmup, 20), eager=a.eager, event_steps=48, logprob=True)
         lp_kernel = {1: "single-launch kernel k_fused", 2: "tile path, k_tiles"}.get(r["path"], "multi-kernel path, k_logits")
-        cases.append({"path": f"grouped, log-probability output (Eq. 8; {lp_kernel})",
-                      "M": a.M, "us_per_step": r["us_per_step"], "kernel_us": r["kernel_us"],
-                      "avg_activated_groups": r["U"],
-                      "GBps_whole_step": r["bytes"] / r["us_per_step"] / 1e3,
-                      "frac_kernel": r["bytes"] / r["kernel_us"] / 1e3 / HBM_PEAK_GBPS})
+        cases.append(grouped_case(r, f"grouped, log-probability output (Eq. 8; {lp_kernel})"))
         r = bench.time_draft_level(a.M, a.M, n, min(a.warmup, 20))
         cases.append({"path": f"draft level in one call: log-probability head for {a.M} nodes + expansion to "
                               f"{a.M} nodes (coral_lmhead_draft_level)",
                       "M": a.M, "us_per_step": r["one_call_us"],
                       "us_per_step_as_two_calls": r["two_calls_us"]})
         r = bench.time_routed(a.M, n, min(a.warmup, 20))
-        cases.append({"path": "router pre-mix u = silu(W1 h) + h alone (Eq. 7; k_premix, W1 copies "
-                              "cycled past the last-level cache; launch gap included)",
+        cases.append({"path": "router pre-mix u = silu(W1 h) + h alone (Eq. 7; W1 copies cycled past the "
+                              "last-level cache: every byte from HBM; launch gap included)",
                       "M": a.M, "us_per_step": r["premix_us"],
                       "GBps_whole_step": r["premix_bytes"] / r["premix_us"] / 1e3,
                       "frac_whole_step": r["premix_bytes"] / r["premix_us"] / 1e3 / HBM_PEAK_GBPS})
+        cases.append({"path": "router pre-mix alone, the same W1 every step (cache-assisted: its 33.6 MB "
+                              "fit the 256 MB last-level cache, as in a draft loop)",
+                      "M": a.M, "us_per_step": r["premix_resident_us"]})
         cases.append({"path": "pre-mix, then grouped head with the router reading u (two calls)",
                       "M": a.M, "us_per_step": r["step_us"]})
         for (tm, tk, tn) in ((10, 10, 10), (64, 16, 64)):
@@ -473,6 +567,12 @@ def main():
         rep_M = min(cfg.Ms)
         cases.append({"path": "grouped, same input every call (cache-assisted)", "M": rep_M,
                       "us_per_step": bench.time_repeat(rep_M, max(48, n), 8)})
+        if a.cases == "default" and a.config == "llama3_8b":
+            del bench, res
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+            other_shapes(a, n, cases)
         out["cases"] = cases
     print(json.dumps(out))
 

@@ -8,7 +8,7 @@ the HIP path's tests feed from it, and neither of those imports the other.
 Shapes follow the draft heads of the paper's Table 1 (Llama2-7B, Llama3-8B,
 Qwen2.5-7B: hidden size d and vocabulary V); the (number of groups, active
 groups) pairs lie inside the grid of the router ablation (Table 4), and the
-candidate count follows the "top 10 candidates" of the tree-decoding
+candidate count is the ten candidates per draft token of the tree-decoding
 discussion in the appendix on the LM head router.
 
 Recipe (fixed; every draw comes from numpy's PCG64 seeded with

@@ -13,8 +13,10 @@
  * Conventions for every entry point
  *   - Pointers marked [device] are HIP device memory, [host] ordinary host memory.
  *   - All matrices are row-major and dense (no padding between rows).
- *   - Ownership: the caller owns every buffer.  The library allocates nothing,
- *     frees nothing and keeps no state between calls; inputs are only read.
+ *   - Ownership: the caller owns every buffer.  The library allocates nothing on the
+ *     device and frees nothing; inputs are only read.  The only state it keeps between
+ *     calls is a per-device cache of two device properties (the number of compute units,
+ *     and which kernels have been granted how much dynamic LDS), guarded by a mutex.
  *   - Execution: work is enqueued on `hip_stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and the call returns without
  *     synchronising.  Outputs are valid once the stream reaches that point.
@@ -56,9 +58,9 @@ typedef enum {
 } coral_dtype;
 
 /*
- * Partition of the vocabulary into G groups (section 3.3: "we divide the LM head
- * equally into N groups"; here any partition in CSR form, the equal contiguous
- * split being one case).  Group n owns vocabulary rows
+ * Partition of the vocabulary into G groups (section 3.3 divides the LM head into N
+ * groups of equal size; here any partition in CSR form, the equal contiguous split
+ * being one case).  Group n owns vocabulary rows
  *     group_rows[group_offsets[n] .. group_offsets[n+1])
  * The struct itself is host memory.  The offsets are needed on both sides: the
  * host copy sizes the launch, the device copy is read by the kernels; the two
@@ -98,7 +100,9 @@ size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
  * 2 = matrix-core tile path (bf16, H a multiple of 512, weights below 4 GiB: groups
  * shared by many tokens, the appendix's tree-decoding case, when the hidden vectors do
  * not fit on chip; dense head with 8 or more tokens and at least 65536 rows),
- * -1 = sizes not supported.  Host-only, no device work; for tests and benchmark reports.
+ * -1 = sizes not supported (outside the limits above, or a shape only the staged path
+ * could take whose token batch does not fit LDS: rows beyond about 10 000 values with 8 or
+ * more tokens).  Host-only, no device work; for tests and benchmark reports.
  */
 int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral_dtype dt);
 

@@ -12,12 +12,12 @@
  *             W2 projection of the router; softmax is monotone, so the
  *             selection below is taken on s itself)
  *   top-n     the g groups with the largest s[m,.]                (section
- *             4.2.3: "activate top-n" of the N groups)
+ *             4.2.3: the top-n of the N groups are activated)
  *   logits    z[m,r] = sum_j W[r,j] * h[m,j] for the rows r of token m's own
  *             selected groups only (section 3.3: only a subset of the LM-head
  *             parameters is activated; Eq. 8 gives zero mass outside them)
- *   top-k     the k largest z[m,.] among those rows (appendix: "top 10
- *             candidates" per draft token)
+ *   top-k     the k largest z[m,.] among those rows (appendix, tree
+ *             decoding: ten candidates per draft token)
  *   dense     the same with every vocabulary row a candidate (the "N/A" row
  *             of Table 4)
  *   lse / log p_router  per-group log-sum-exp and the router's log-softmax,

@@ -192,13 +192,16 @@ def coral_lmhead_workspace_init(workspace: torch.Tensor, stream=None) -> None:
                                           _stream_ptr(stream)))
 
 
-def alloc_workspace(M, H, V, G, g, k, dt, device="cuda") -> torch.Tensor:
-    """A prepared workspace (allocated through PyTorch, control words zeroed)."""
+def alloc_workspace(M, H, V, G, g, k, dt, device="cuda", stream=None) -> torch.Tensor:
+    """A prepared workspace (allocated through PyTorch, control words zeroed on `stream`, the
+    stream the head will be enqueued on; None = the current stream)."""
     n = coral_lmhead_workspace_bytes(M, H, V, G, g, k, dt)
     if n == 0:
         raise ValueError("invalid sizes for the workspace")
     ws = torch.empty(n, dtype=torch.uint8, device=device)
-    coral_lmhead_workspace_init(ws)
+    coral_lmhead_workspace_init(ws, stream)
+    if stream is not None:
+        ws.record_stream(stream)       # the caching allocator must not reuse it under that stream
     return ws
 
 
@@ -236,7 +239,7 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
     if topk_ids.shape != (M, k) or topk_logits.shape != (M, k) or sel_groups.shape != (M, g):
         raise ValueError("output shapes must be [M,k], [M,k], [M,g]")
     if workspace is None:
-        workspace = alloc_workspace(M, H, V, gi.G, g, k, dt, dev)
+        workspace = alloc_workspace(M, H, V, gi.G, g, k, dt, dev, stream)
     args = (_dev_ptr(hidden, "hidden"), _dev_ptr(gate_W, "gate_W"),
             _dev_ptr(gate_bias, "gate_bias", torch.float32), _dev_ptr(lm_W, "lm_W"), gi.struct(),
             M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
@@ -364,7 +367,7 @@ def coral_lmhead_dense(hidden: torch.Tensor, lm_W: torch.Tensor, k: int,
     if topk_ids.shape != (M, k) or topk_logits.shape != (M, k):
         raise ValueError("output shapes must be [M,k]")
     if workspace is None:
-        workspace = alloc_workspace(M, H, V, 0, 0, k, dt, dev)
+        workspace = alloc_workspace(M, H, V, 0, 0, k, dt, dev, stream)
     args = (_dev_ptr(hidden, "hidden"), _dev_ptr(lm_W, "lm_W"), M, H, V, k, dt,
             _dev_ptr(topk_ids, "topk_ids", torch.int32),
             _dev_ptr(topk_logits, "topk_logits", torch.float32), _dev_ptr(workspace, "workspace"),

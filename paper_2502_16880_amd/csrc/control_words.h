@@ -1,0 +1,31 @@
+// Map of the control words at the start of the workspace (32-bit words, all zero between
+// calls; coral_lmhead_workspace_init zeroes them once, every kernel that uses one leaves it
+// zero again).  Plain constants so that a host compiler can include this file too: a test
+// builds the table below and checks that no two entries overlap and all lie inside the
+// control area.
+#pragma once
+
+namespace coral_ctrl {
+
+struct Entry {
+    const char* name;
+    int first_word;
+    int n_words;
+};
+
+constexpr int kWords = 128;                 // size of the control area in words (512 bytes)
+constexpr int kFusedArrival = 0;            // single-launch path: workgroups that have published
+constexpr int kGateSelectArrival = 2;       // tile path: k_gate_select tiles that have finished
+constexpr int kTileQueue = 4;               // tile path: next block of k_tiles
+constexpr int kLpGroupArrival = 64;         // log-probability mode: one counter per activated
+constexpr int kLpGroupArrivalWords = 64;    //   group (at most 64 in the single-launch kernel)
+
+constexpr Entry kMap[] = {
+    {"fused_arrival", kFusedArrival, 1},
+    {"gate_select_arrival", kGateSelectArrival, 1},
+    {"tile_queue", kTileQueue, 1},
+    {"logprob_group_arrival", kLpGroupArrival, kLpGroupArrivalWords},
+};
+constexpr int kMapEntries = sizeof(kMap) / sizeof(kMap[0]);
+
+}  // namespace coral_ctrl

@@ -15,14 +15,17 @@
 //   - each wavefront keeps its running k best per token in registers (lane i holds
 //     rank i), so the logits row never leaves the chip; workgroup partial lists are
 //     merged by rank counting, then a last small kernel merges per token.
-// A group selected by several tokens is read once for all of them (the "activate
-// all the involved groups" of the appendix's tree-decoding paragraph).
+// A group selected by several tokens is read once for all of them (the union of the
+// tokens' groups that the appendix's tree-decoding paragraph activates).
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "coral_lmhead.h"
+#include "control_words.h"
 #include "device_utils.h"
 #include "fused_path.h"
 #include "router_premix.h"
@@ -41,8 +44,8 @@ inline bool is_16bit(coral_dtype dt) { return dt != CORAL_F32; }
 #define CORAL_PICK_DT(dt, f32, bf16, f16) ((dt) == CORAL_F32 ? (f32) : (dt) == CORAL_BF16 ? (bf16) : (f16))
 
 constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path's grid
-constexpr size_t kCtrlBytes = 512;     // control words at the start of the workspace
-static_assert(kCtrlBytes >= (kLpGroupCounters + kWave) * sizeof(unsigned int), "per-group counters");
+constexpr size_t kCtrlBytes = coral_ctrl::kWords * sizeof(unsigned int);   // control words at the start of the workspace
+static_assert(coral_ctrl::kLpGroupArrivalWords >= kWave, "one arrival counter per activated group");
 
 struct Layout {
     size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_table, total;
@@ -120,18 +123,57 @@ coral_status record(void* ev, hipStream_t stream) {
                                                                              : CORAL_ERR_HIP;
 }
 
-// Compute units of the current device (the single-launch path runs one workgroup on each).
+// The only state the library keeps between calls: per device, the number of compute units
+// (the single-launch path runs one workgroup on each) and the largest dynamic LDS size each
+// kernel has been allowed so far.  Both are properties of the device and of the loaded code
+// object, looked up once instead of on every call; a mutex guards them.
+constexpr int kMaxDevices = 64;
+constexpr int kMaxKernels = 96;
+struct DeviceCache {
+    int compute_units;
+    int n_kernels;
+    const void* kernel[kMaxKernels];
+    int lds_bytes[kMaxKernels];
+};
+DeviceCache g_cache[kMaxDevices];
+std::mutex g_cache_mutex;
+
 int compute_units() {
-    static int cached[64] = {0};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (g_cache[dev].compute_units == 0) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
-        cached[dev] = n;
+        g_cache[dev].compute_units = n;
     }
-    return cached[dev];
+    return g_cache[dev].compute_units;
+}
+
+// Lets kernel `fn` use `bytes` of dynamic LDS on the current device (needed above 64 KB).
+bool allow_lds(const void* fn, int bytes) {
+    if (bytes <= 64 * 1024) return true;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    DeviceCache* c = dev >= 0 && dev < kMaxDevices ? &g_cache[dev] : nullptr;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    int slot = -1;
+    if (c) {
+        for (int i = 0; i < c->n_kernels; ++i)
+            if (c->kernel[i] == fn) slot = i;
+        if (slot >= 0 && c->lds_bytes[slot] >= bytes) return true;
+    }
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return false;
+    if (c) {
+        if (slot < 0 && c->n_kernels < kMaxKernels) {
+            slot = c->n_kernels++;
+            c->kernel[slot] = fn;
+        }
+        if (slot >= 0) c->lds_bytes[slot] = bytes;
+    }
+    return true;
 }
 
 // Gate of the single-launch path: more than four tokens go through the matrix cores (16-bit
@@ -207,7 +249,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
         p.next_token = level->next_token;
         p.next_score = level->next_score;
     }
-    p.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl);
+    p.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kFusedArrival;
     p.topk_ids = topk_ids;
     p.topk_logits = topk_logits;
     p.M = M; p.V = V; p.G = G; p.g = g; p.k = k;
@@ -236,10 +278,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
         fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, false>), CORAL_FUSED_GATES(kBF16, false, false),
                            CORAL_FUSED_GATES(kF16, false, false));
 #undef CORAL_FUSED_GATES
-    if (F.total > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, F.total) != hipSuccess)
-        return CORAL_ERR_HIP;
+    if (!allow_lds(reinterpret_cast<const void*>(fn), F.total)) return CORAL_ERR_HIP;
     coral_status st;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(fn, dim3(P), dim3(kFusedBlock), F.total, stream, p);
@@ -267,9 +306,14 @@ bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_
 
 // Which path a call takes, decided in one place for the entry points and the path query.
 struct PathPlan {
-    int path;            // 0 staged, 1 single launch, 2 tiles
+    int path;            // 0 staged, 1 single launch, 2 tiles, -1 none (the staged path's
+                         // token batch and lists do not fit LDS: rows beyond about 10 K values)
     int tile_umax, tile_lds;
 };
+
+bool staged_fits(int M, int jp, int k) {
+    return logits_lds_bytes(M < kTokBatch ? M : kTokBatch, jp, k) <= (size_t)kLdsLimit;
+}
 
 PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_dtype dt,
                    bool logprob = false) {
@@ -277,7 +321,7 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     if (logprob) {     // the single-launch kernel where it fits, else the tile path, else the staged path
-        pl.path = 0;
+        pl.path = staged_fits(M, jp, k) ? 0 : -1;
         if (dense) return pl;
         if (fused_logprob_fits(M, G, g, k, jp, dt, kMaxWorkgroups)) {
             pl.path = 1;
@@ -302,7 +346,7 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
     else if (tiles_ok)
         pl.path = 2;
     else
-        pl.path = 0;
+        pl.path = staged_fits(M, jp, k) ? 0 : -1;
     return pl;
 }
 
@@ -327,7 +371,7 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.table = table;
     p.n_union = n_union;
     p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
-    p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 4;
+    p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileQueue;
     p.M = M; p.V = V; p.G = G; p.k = k;
     p.n_vec = H / 8;
     p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
@@ -338,9 +382,7 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     typedef void (*tiles_fn)(TileParams, int);
     const tiles_fn fn = lp_sel ? (dt == CORAL_F16 ? k_tiles<kF16, true> : k_tiles<kBF16, true>)
                                : (dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>);
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-        return CORAL_ERR_HIP;
+    if (!allow_lds(reinterpret_cast<const void*>(fn), lds)) return CORAL_ERR_HIP;
     coral_status st;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(fn, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
@@ -478,8 +520,10 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     PathPlan plan = plan_path(false, M, H, V, G, g, k, dt, logprob);
     if (logprob && plan.path == 1) {   // a device with few compute units: see fused_logprob_fits
         const int cu = compute_units();
-        if (2 * max_union(M, G, g) > (cu < kMaxWorkgroups ? cu : kMaxWorkgroups)) plan.path = 0;
+        if (2 * max_union(M, G, g) > (cu < kMaxWorkgroups ? cu : kMaxWorkgroups))
+            plan.path = staged_fits(M, ((H / (is_16bit(dt) ? 8 : 4)) + kWave - 1) / kWave, k) ? 0 : -1;
     }
+    if (plan.path < 0) return CORAL_ERR_UNSUPPORTED;       // before anything is enqueued
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
                             topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob, level);
@@ -500,7 +544,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         q.hidden = ghid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
         TileGroup* table = reinterpret_cast<TileGroup*>(ws + L.tile_table);
         q.group_mask = mask; q.offsets = gi->group_offsets; q.table = table; q.n_union = n_union;
-        q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + 2;
+        q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kGateSelectArrival;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
         if (logprob) {
             q.first_block = chunk_base;
@@ -548,8 +592,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     p.jp = (n_vec + kWave - 1) / kWave;
     p.tb_max = M < kTokBatch ? M : kTokBatch;
     p.part_stride = L.part_stride;
-    const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);
-    if (lds > 160 * 1024) return CORAL_ERR_UNSUPPORTED;
+    const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);       // fits: plan_path checked it
     const int chunks = (max_rows + kChunkRows - 1) / kChunkRows;
     const long long union_max = max_union(M, G, g);
     if (chunks < 1) return CORAL_ERR_SHAPE;
@@ -561,9 +604,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
                                 (k_logits<kF16, false, true>))
                 : CORAL_PICK_DT(dt, (k_logits<kF32, false, false>), (k_logits<kBF16, false, false>),
                                 (k_logits<kF16, false, false>));
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return CORAL_ERR_HIP;
+    if (!allow_lds(reinterpret_cast<const void*>(fn), (int)lds)) return CORAL_ERR_HIP;
     hipLaunchKernelGGL(fn, grid, dim3(kBlock), lds, stream, p);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
@@ -596,6 +637,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     char* ws = static_cast<char*>(workspace);
     const PathPlan plan = plan_path(true, M, H, V, 0, 0, k, dt);
+    if (plan.path < 0) return CORAL_ERR_UNSUPPORTED;
     // many tokens per row: the contraction is no longer cheap on the vector units
     if (plan.path == 2)
         return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, M, H, V, 0, k, dt,
@@ -614,14 +656,11 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     p.tb_max = M < kTokBatch ? M : kTokBatch;
     p.part_stride = L.part_stride;
     const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);
-    if (lds > 160 * 1024) return CORAL_ERR_UNSUPPORTED;
     const int chunks = (V + kChunkRows - 1) / kChunkRows;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     typedef void (*logits_fn)(LogitsParams);
     const logits_fn fn = CORAL_PICK_DT(dt, (k_logits<kF32, true>), (k_logits<kBF16, true>), (k_logits<kF16, true>));
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return CORAL_ERR_HIP;
+    if (!allow_lds(reinterpret_cast<const void*>(fn), (int)lds)) return CORAL_ERR_HIP;
     hipLaunchKernelGGL(fn, dim3(chunks), dim3(kBlock), lds, stream, p);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
@@ -718,9 +757,7 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
         if (lds <= (size_t)kLdsLimit) {
             p.tok_per_wg = tok;
             const premix_fn mf = dt == CORAL_F16 ? k_premix_mfma<kF16> : k_premix_mfma<kBF16>;
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(mf),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-                return CORAL_ERR_HIP;
+            if (!allow_lds(reinterpret_cast<const void*>(mf), (int)lds)) return CORAL_ERR_HIP;
             hipLaunchKernelGGL(mf, dim3(H / 16, (M + tok - 1) / tok), dim3(kBlock), lds, stream, p);
             return launch_status();
         }
@@ -736,10 +773,7 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
     if (gx > 2 * kMaxWorkgroups) gx = 2 * kMaxWorkgroups;
     const dim3 grid(gx, (M + tok - 1) / tok);
     const premix_fn fn = CORAL_PICK_DT(dt, k_premix<kF32>, k_premix<kBF16>, k_premix<kF16>);
-    if (lds > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void*>(fn),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-        return CORAL_ERR_HIP;
+    if (!allow_lds(reinterpret_cast<const void*>(fn), lds)) return CORAL_ERR_HIP;
     hipLaunchKernelGGL(fn, grid, dim3(kBlock), lds, stream, p);
     return launch_status();
 }

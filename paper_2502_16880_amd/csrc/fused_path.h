@@ -25,6 +25,7 @@
 // group's k best per token) and the last group merges every token's g lists.  A draft-level
 // call also expands the tree level in that last workgroup (tree_expand.h).
 #pragma once
+#include "control_words.h"
 #include "device_utils.h"
 #include "tree_expand.h"
 
@@ -40,7 +41,7 @@ constexpr int kLdsLimit = 160 * 1024;
 // token's dot products the latency is about this much.
 constexpr int kLpBaseCost = 10;
 constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp pieces, at most
-constexpr int kLpGroupCounters = 64;   // first of the 64 per-group arrival counters (control words)
+constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
 // gate rows loaded as 64-byte pieces (16 rows per wave load) or as whole 128-byte lines

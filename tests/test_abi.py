@@ -69,7 +69,8 @@ def test_path_selection_covers_the_three_paths():
     assert path(True, 1, 4096, 128256, 0, 0, 10, BF16) == 1
     assert path(False, 64, 512, 1040, 8, 1, 64, BF16) == 0         # k = 64: general path
     assert path(False, 4, 256, 8192, 16, 2, 8, F32) == 1
-    assert path(True, 64, 8192, 8192, 0, 0, 8, F32) == 0           # fp32 rows longer than 8 KB
+    assert path(True, 64, 4096, 8192, 0, 0, 8, F32) == 0           # fp32 rows longer than 8 KB
+    assert path(True, 64, 8192, 8192, 0, 0, 8, F32) == -1          # ... than the staged path's LDS
     assert path(False, 65, 256, 8192, 16, 2, 8, F32) == -1
 
 
@@ -192,3 +193,50 @@ def test_binding_rejects_host_tensors_and_mixed_dtypes():
         coral.coral_lmhead_dense(h, torch.zeros(128, 64, dtype=torch.bfloat16), 4)
     with pytest.raises(TypeError):
         coral.coral_lmhead_dense(h.double(), torch.zeros(128, 64).double(), 4)
+
+
+def test_rows_too_long_for_every_path_are_refused_before_any_launch():
+    """A shape that only the staged path could take (H no multiple of 512) and whose batch of
+    eight token vectors does not fit LDS: the path query says -1 and the call returns
+    UNSUPPORTED with nothing enqueued (the fake pointers would fault otherwise)."""
+    path, lp = coral.coral_lmhead_path, coral.coral_lmhead_logprob_path
+    assert path(False, 8, 10248, 8192, 16, 2, 8, BF16) == -1
+    assert path(True, 8, 10248, 8192, 0, 0, 8, BF16) == -1
+    assert lp(8, 10248, 8192, 16, 2, 8, BF16) == -1
+    assert path(False, 4, 10248, 8192, 16, 2, 8, BF16) == 0        # four token vectors do fit
+    assert path(False, 8, 10240, 8192, 16, 2, 8, BF16) == 2        # whole 512-column chunks: tiles
+    c = Call()
+    assert c.grouped(M=8, H=10248, dt=BF16) == UNSUPPORTED
+    assert c.dense(M=8, H=10248, dt=BF16) == UNSUPPORTED
+
+
+def test_control_words_do_not_overlap(tmp_path):
+    """The kernels' arrival counters and queues share the first words of the workspace; the
+    map (csrc/control_words.h) is compiled here with the host compiler and checked: entries
+    disjoint, inside the area that coral_lmhead_workspace_init zeroes, and the workspace of
+    every shape at least that large."""
+    import subprocess
+    src = tmp_path / "ctrl.cpp"
+    src.write_text('#include <cstdio>\n#include "control_words.h"\n'
+                   'int main() { std::printf("words %d\\n", coral_ctrl::kWords);\n'
+                   '  for (int i = 0; i < coral_ctrl::kMapEntries; ++i)\n'
+                   '    std::printf("%s %d %d\\n", coral_ctrl::kMap[i].name, coral_ctrl::kMap[i].first_word,\n'
+                   '                coral_ctrl::kMap[i].n_words);\n  return 0; }\n')
+    exe = tmp_path / "ctrl"
+    subprocess.run(["g++", "-std=c++17", "-I", os.path.join(ROOT, "paper_2502_16880_amd", "csrc"),
+                    str(src), "-o", str(exe)], check=True)
+    lines = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    words = int(lines[0].split()[1])
+    entries = [(p[0], int(p[1]), int(p[2])) for p in (l.split() for l in lines[1:] if l.strip())]
+    assert len(entries) >= 4 and len({e[0] for e in entries}) == len(entries)
+    owner = {}
+    for name, first, n in entries:
+        assert n >= 1 and 0 <= first and first + n <= words, name
+        for w in range(first, first + n):
+            assert w not in owner, f"word {w}: {name} overlaps {owner.get(w)}"
+            owner[w] = name
+    names = {e[0]: e for e in entries}
+    assert names["logprob_group_arrival"][2] >= 64          # one counter per activated group
+    assert coral.coral_lmhead_workspace_bytes(1, 8, 1, 0, 0, 1, BF16) >= 4 * words
+    # the preparation call insists on the whole area
+    assert coral._L.coral_lmhead_workspace_init(FAKE, 4 * words - 4, None) == WORKSPACE
