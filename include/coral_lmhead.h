@@ -166,6 +166,34 @@ coral_status coral_lmhead_grouped(const void *hidden, const void *gate_W,
                                   void *hip_stream);
 
 /*
+ * coral_lmhead_grouped for callers that cannot allocate device memory or pass a workspace
+ * along: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same operation, arguments, results (bit for bit) and errors as
+ * coral_lmhead_grouped, with no workspace argument: the kernels' scratch (published partial
+ * lists, arrival counters, the staged path's hand-over arrays) lives in a static device array
+ * of CORAL_NOALLOC_SCRATCH_BYTES inside the library, one copy per GPU, held until the
+ * process ends.  The call allocates and frees nothing.
+ *   - Shapes whose scratch need (coral_lmhead_workspace_bytes for the same sizes, without the
+ *     log-probability mode's tables) exceeds CORAL_NOALLOC_SCRATCH_BYTES are refused with
+ *     CORAL_ERR_WORKSPACE before anything is enqueued.  Every workload shape of Table 1 with up
+ *     to 16 tokens fits.
+ *   - All calls on one GPU share that GPU's array: calls that overlap on one GPU (two
+ *     streams, two threads) race and give unspecified results; calls on one stream, or
+ *     otherwise ordered, are safe.  Each call first clears the array's control words with a
+ *     small kernel on hip_stream (no memset node), so it may be captured and replayed.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress); it may
+ *     fail with CORAL_ERR_HIP if no device is current.
+ */
+#define CORAL_NOALLOC_SCRATCH_BYTES (8u << 20)
+
+coral_status coral_lmhead_grouped_noalloc(const void *hidden, const void *gate_W,
+                                          const float *gate_bias, const void *lm_W,
+                                          const coral_group_index *gi, int M, int H, int V,
+                                          int g, int k, coral_dtype dt, int32_t *topk_ids,
+                                          float *topk_logits, int32_t *sel_groups,
+                                          void *hip_stream);
+
+/*
  * Grouped LM head with the paper's probability composition (section 3.3, Eq. 7 and
  * Eq. 8).  Selection and logits as in coral_lmhead_grouped; then for each token m and
  * each row x of a selected group n

@@ -61,6 +61,10 @@ def _load():
                                        c.POINTER(_GroupIndexStruct)] + [c.c_int] * 6 + \
                                       [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
                                        c.c_void_p]
+    L.coral_lmhead_grouped_noalloc.restype = c.c_int
+    L.coral_lmhead_grouped_noalloc.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                               c.POINTER(_GroupIndexStruct)] + [c.c_int] * 6 + \
+                                              [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     L.coral_lmhead_dense.restype = c.c_int
     L.coral_lmhead_dense.argtypes = [c.c_void_p, c.c_void_p] + [c.c_int] * 5 + \
                                     [c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -270,6 +274,37 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
         st = fn(*args, events[0], events[1])
     _raise(st)
     return topk_ids, topk_logits, sel_groups
+
+
+NOALLOC_SCRATCH_BYTES = 8 << 20      # CORAL_NOALLOC_SCRATCH_BYTES of the header
+
+
+def coral_lmhead_grouped_noalloc(hidden: torch.Tensor, gate_W: torch.Tensor,
+                                 gate_bias: Optional[torch.Tensor], lm_W: torch.Tensor, gi: GroupIndex,
+                                 g: int, k: int, topk_ids: torch.Tensor, topk_logits: torch.Tensor,
+                                 sel_groups: Optional[torch.Tensor] = None, stream=None) -> None:
+    """coral_lmhead_grouped_noalloc of the C ABI: the grouped head on the library's static
+    scratch.  Nothing is allocated here either: the caller passes every output tensor."""
+    dt = _dtype_code(hidden)
+    if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
+        raise TypeError("hidden, gate_W and lm_W must share one dtype")
+    if hidden.dim() != 2 or gate_W.dim() != 2 or lm_W.dim() != 2:
+        raise ValueError("hidden, gate_W and lm_W must be 2-D")
+    M, H = hidden.shape
+    V = lm_W.shape[0]
+    if lm_W.shape[1] != H or gate_W.shape != (gi.G, H) or gi.V != V:
+        raise ValueError("inconsistent shapes")
+    if gate_bias is not None and gate_bias.shape != (gi.G,):
+        raise ValueError("gate_bias must be [G]")
+    if topk_ids.shape != (M, k) or topk_logits.shape != (M, k) or \
+            (sel_groups is not None and sel_groups.shape != (M, g)):
+        raise ValueError("output shapes must be [M,k], [M,k], [M,g]")
+    _raise(_L.coral_lmhead_grouped_noalloc(
+        _dev_ptr(hidden, "hidden"), _dev_ptr(gate_W, "gate_W"),
+        _dev_ptr(gate_bias, "gate_bias", torch.float32), _dev_ptr(lm_W, "lm_W"), gi.struct(),
+        M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
+        _dev_ptr(topk_logits, "topk_logits", torch.float32),
+        _dev_ptr(sel_groups, "sel_groups", torch.int32), _stream_ptr(stream)))
 
 
 ACTIVATIONS = {"silu": 0, "relu": 1, "identity": 2}

@@ -33,6 +33,12 @@
 #include "tile_path.h"
 #include "tree_expand.h"
 
+// Scratch memory of coral_lmhead_grouped_noalloc: what the other entry points take as their
+// caller-provided workspace.  One copy per GPU the library runs on, held until the process
+// ends; in host code the name is only a handle for hipGetSymbolAddress, never an address.
+constexpr size_t kStaticScratchBytes = (size_t)CORAL_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
 
 // ---------------------------------------------------------------- host side
@@ -131,6 +137,7 @@ constexpr int kMaxDevices = 64;
 constexpr int kMaxKernels = 96;
 struct DeviceCache {
     int compute_units;
+    void* scratch_ptr;          // this device's copy of `scratch`, looked up on first use
     int n_kernels;
     const void* kernel[kMaxKernels];
     int lds_bytes[kMaxKernels];
@@ -149,6 +156,20 @@ int compute_units() {
         g_cache[dev].compute_units = n;
     }
     return g_cache[dev].compute_units;
+}
+
+// Device address of this device's copy of the static scratch array.
+coral_status static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CORAL_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_cache_mutex);
+    if (!g_cache[dev].scratch_ptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CORAL_ERR_HIP;
+        g_cache[dev].scratch_ptr = ptr;
+    }
+    *out = g_cache[dev].scratch_ptr;
+    return CORAL_OK;
 }
 
 // Lets kernel `fn` use `bytes` of dynamic LDS on the current device (needed above 64 KB).
@@ -479,7 +500,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
                           int g, int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits,
                           int32_t* sel_groups, void* workspace, size_t workspace_bytes,
                           void* hip_stream, void* ev_before, void* ev_after, bool logprob,
-                          const LevelExpand* level = nullptr) {
+                          const LevelExpand* level = nullptr, bool static_workspace = false) {
     if (!gate_W || !gi) return CORAL_ERR_NULL;
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
@@ -511,12 +532,16 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         min_cand += smallest[i];
     }
     if ((long long)k > min_cand) return CORAL_ERR_SHAPE;
-    const Layout L = make_layout(M, V, G, g, k, layout_has_pair_pieces(M, H, G, g, k, dt));
-    st = check_workspace(workspace, workspace_bytes, L.total);
-    if (st != CORAL_OK) return st;
+    // (the static scratch serves the logit ranking only: no table of per-pair pieces)
+    const Layout L = make_layout(M, V, G, g, k, !static_workspace && layout_has_pair_pieces(M, H, G, g, k, dt));
+    if (static_workspace) {
+        if (logprob || L.total > kStaticScratchBytes) return CORAL_ERR_WORKSPACE;
+    } else {
+        st = check_workspace(workspace, workspace_bytes, L.total);
+        if (st != CORAL_OK) return st;
+    }
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    char* ws = static_cast<char*>(workspace);
     PathPlan plan = plan_path(false, M, H, V, G, g, k, dt, logprob);
     if (logprob && plan.path == 1) {   // a device with few compute units: see fused_logprob_fits
         const int cu = compute_units();
@@ -524,6 +549,15 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
             plan.path = staged_fits(M, ((H / (is_16bit(dt) ? 8 : 4)) + kWave - 1) / kWave, k) ? 0 : -1;
     }
     if (plan.path < 0) return CORAL_ERR_UNSUPPORTED;       // before anything is enqueued
+    if (static_workspace) {
+        // this device's copy of the array; its control words are cleared by a fill kernel on
+        // the call's stream (the array keeps whatever the last call on this GPU left there)
+        if ((st = static_scratch(&workspace)) != CORAL_OK) return st;
+        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(kCtrlBytes / 4), 0, stream,
+                           static_cast<unsigned int*>(workspace), (int)(kCtrlBytes / 4));
+        if ((st = launch_status()) != CORAL_OK) return st;
+    }
+    char* ws = static_cast<char*>(workspace);
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
                             topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob, level);
@@ -682,6 +716,17 @@ extern "C" coral_status coral_lmhead_grouped(const void* hidden, const void* gat
     return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
                         topk_logits, sel_groups, workspace, workspace_bytes, hip_stream, nullptr,
                         nullptr, false);
+}
+
+extern "C" coral_status coral_lmhead_grouped_noalloc(const void* hidden, const void* gate_W,
+                                                     const float* gate_bias, const void* lm_W,
+                                                     const coral_group_index* gi, int M, int H, int V,
+                                                     int g, int k, coral_dtype dt, int32_t* topk_ids,
+                                                     float* topk_logits, int32_t* sel_groups,
+                                                     void* hip_stream) {
+    return grouped_impl(hidden, nullptr, gate_W, gate_bias, lm_W, gi, M, H, V, g, k, dt, topk_ids,
+                        topk_logits, sel_groups, nullptr, 0, hip_stream, nullptr, nullptr, false,
+                        nullptr, true);
 }
 
 extern "C" coral_status coral_lmhead_grouped_routed(

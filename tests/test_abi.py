@@ -240,3 +240,29 @@ def test_control_words_do_not_overlap(tmp_path):
     assert coral.coral_lmhead_workspace_bytes(1, 8, 1, 0, 0, 1, BF16) >= 4 * words
     # the preparation call insists on the whole area
     assert coral._L.coral_lmhead_workspace_init(FAKE, 4 * words - 4, None) == WORKSPACE
+
+
+def test_noalloc_entry_point_checks_arguments_and_size_before_touching_the_device():
+    """coral_lmhead_grouped_noalloc: the same argument errors as coral_lmhead_grouped, and a
+    shape whose scratch need exceeds the library's static array is refused (WORKSPACE) with
+    nothing looked up or enqueued."""
+    c = Call()
+
+    def noalloc(**kw):
+        a = dict(c.a, **kw)
+        return coral._L.coral_lmhead_grouped_noalloc(
+            a["hidden"], a["gate_W"], a["gate_bias"], a["lm_W"], ctypes.byref(c.gi), a["M"], a["H"],
+            a["V"], a["g"], a["k"], a["dt"], a["ids"], a["logits"], a["sel"], None)
+
+    assert noalloc(hidden=None) == NULL
+    assert noalloc(ids=None) == NULL
+    assert noalloc(M=0) == SHAPE
+    assert noalloc(M=65) == UNSUPPORTED
+    assert noalloc(H=254) == UNSUPPORTED
+    assert noalloc(g=17) == SHAPE
+    # 64 tokens x 64 candidates: the published lists alone are 8 MiB
+    assert coral.coral_lmhead_workspace_bytes(64, 256, 8192, 16, 2, 64, F32) > coral.NOALLOC_SCRATCH_BYTES
+    assert noalloc(M=64, k=64) == WORKSPACE
+    header = open(HEADER).read()
+    m = re.search(r"#define\s+CORAL_NOALLOC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", header)
+    assert m and int(m.group(1)) << int(m.group(2)) == coral.NOALLOC_SCRATCH_BYTES
