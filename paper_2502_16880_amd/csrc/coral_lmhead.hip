@@ -241,16 +241,30 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
                const void* lm_W, const coral_group_index* gi, int M, int H, int V, int G, int g,
                int k, coral_dtype dt, int32_t* topk_ids, float* topk_logits, int32_t* sel_groups,
                char* ws, const Layout& L, hipStream_t stream, void* ev_before, void* ev_after,
-               bool logprob = false, const LevelExpand* level = nullptr) {
+               bool logprob = false, const LevelExpand* level = nullptr, int max_group_rows = 0) {
     const int n_vec = H / (is_16bit(dt) ? 8 : 4);
     const int jp = (n_vec + kWave - 1) / kWave;
     const int gate = fused_gate_mode(dense, M, G, g, k, jp, dt, logprob);
-    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate, logprob);
-    if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
+    // Collected candidates instead of per-wave lists, where a workgroup is sure to meet at
+    // most kCollectCap rows per token: it takes 16 consecutive row pairs out of every 16 P of
+    // the concatenated activated groups, so of any group (a run of at most `pairs` pairs) it
+    // meets no more than 16 * (pairs / 16P) + min(16, pairs % 16P), and a token has g groups.
+    bool collect = false;
+    if (!dense && !logprob && max_group_rows > 0) {
+        const long long period = (long long)kFusedWaves * P;
+        const long long pairs = ((long long)max_group_rows + kFusedRows - 1) / kFusedRows;
+        const long long rest = pairs % period;
+        const long long per_group = kFusedWaves * (pairs / period) + (rest < kFusedWaves ? rest : kFusedWaves);
+        collect = kFusedRows * per_group * g <= kCollectCap &&
+                  fused_lds_layout(M, G, g, k, jp, false, gate, false, true).total <= kLdsLimit;
+    }
+    const FusedLds F = fused_lds_layout(M, G, g, k, jp, dense, gate, logprob, collect);
+    if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     FusedParams p = {};
+    p.collect = collect ? 1 : 0;
     p.hidden = static_cast<const uint4*>(hidden);
     p.gate_hidden = static_cast<const uint4*>(gate_hidden);
     p.gate_W = static_cast<const uint4*>(gate_W);
@@ -487,7 +501,7 @@ extern "C" coral_status coral_lmhead_workspace_init(void* workspace, size_t work
                                                     void* hip_stream) {
     coral_status st = check_workspace(workspace, workspace_bytes, kCtrlBytes);
     if (st != CORAL_OK) return st;
-    hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(kCtrlBytes / 4), 0,
+    hipLaunchKernelGGL(k_zero_words, dim3((kCtrlBytes / 4 + 255) / 256), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), static_cast<unsigned int*>(workspace),
                        (int)(kCtrlBytes / 4));
     return launch_status();
@@ -553,14 +567,14 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         // this device's copy of the array; its control words are cleared by a fill kernel on
         // the call's stream (the array keeps whatever the last call on this GPU left there)
         if ((st = static_scratch(&workspace)) != CORAL_OK) return st;
-        hipLaunchKernelGGL(k_zero_words, dim3(1), dim3(kCtrlBytes / 4), 0, stream,
+        hipLaunchKernelGGL(k_zero_words, dim3((kCtrlBytes / 4 + 255) / 256), dim3(256), 0, stream,
                            static_cast<unsigned int*>(workspace), (int)(kCtrlBytes / 4));
         if ((st = launch_status()) != CORAL_OK) return st;
     }
     char* ws = static_cast<char*>(workspace);
     if (plan.path == 1)
         return launch_fused(false, hidden, gate_hidden, gate_W, gate_bias, lm_W, gi, M, H, V, G, g, k, dt, topk_ids,
-                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob, level);
+                            topk_logits, sel_groups, ws, L, stream, ev_before, ev_after, logprob, level, max_rows);
     float* s = reinterpret_cast<float*>(ws + L.s);
     int32_t* sel = sel_groups ? sel_groups : reinterpret_cast<int32_t*>(ws + L.sel);
     unsigned long long* mask = reinterpret_cast<unsigned long long*>(ws + L.mask);

@@ -238,4 +238,11 @@ __device__ __forceinline__ unsigned long long cand_key(float v, int id) {
     return ((unsigned long long)u << 32) | (unsigned)(~id);
 }
 
+// The candidate a key stands for (the value's -0.0 comes back as +0.0).
+__device__ __forceinline__ float key_value(unsigned long long key) {
+    const unsigned u = (unsigned)(key >> 32);
+    return __uint_as_float((u >> 31) ? (u ^ 0x80000000u) : ~u);
+}
+__device__ __forceinline__ int key_id(unsigned long long key) { return (int)~(unsigned)key; }
+
 }  // namespace

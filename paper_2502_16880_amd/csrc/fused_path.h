@@ -41,6 +41,11 @@ constexpr int kLdsLimit = 160 * 1024;
 // token's dot products the latency is about this much.
 constexpr int kLpBaseCost = 10;
 constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp pieces, at most
+// Collected candidates: where a workgroup meets few rows per token (the configured shapes:
+// g * v / 256, about 63), the waves append every logit to one buffer per token instead of
+// keeping sorted lists, and one wave per token ranks the buffer at the end.
+constexpr int kCollectCap = 128;       // entries per token
+constexpr int kSelectRounds = 8;       // up to this many groups per token the selection runs as rounds of a wave maximum
 constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
@@ -85,10 +90,11 @@ struct FusedParams {
     float* topk_logits;         // [M, k]
     int M, V, G, g, k;
     int n_vec, jp;
+    int collect;                // candidates are collected per token (see kCollectCap) instead of listed per wave
 };
 
 struct FusedLds {
-    int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags;
+    int o_hidden, o_lists, o_s, o_mask, o_ugroup, o_ustart, o_uend, o_uprefix, o_umask, o_flags, o_count;
     int o_keys, o_offsets, o_bias;
     int o_sel, o_wgstart;       // log-probability mode only
     int o_pieces, pieces_bytes; // same mode: the log-sum-exp pieces of a workgroup's pairs, if they fit
@@ -102,7 +108,8 @@ __host__ __device__ inline int hidden_lds_stride(int jp) { return jp * kWave + 1
 // Byte offsets of the kernel's regions in dynamic LDS (the host sizes the launch with the
 // same function the kernel lays its pointers out with).
 __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k, int jp, bool dense,
-                                                     int gate_mode, bool logprob = false) {
+                                                     int gate_mode, bool logprob = false,
+                                                     bool collect = false) {
     FusedLds L;
     int off = 0;
     auto take = [&](size_t bytes) {
@@ -116,7 +123,8 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     const size_t scratch_bytes = (size_t)kFusedWaves * kMergeAreaBytes;
     if (hidden_bytes < scratch_bytes) hidden_bytes = scratch_bytes;   // reused by the merges
     L.o_hidden = take(hidden_bytes);
-    size_t lists_bytes = (size_t)kFusedWaves * M * k * sizeof(Cand);
+    size_t lists_bytes = collect ? (size_t)M * kCollectCap * sizeof(unsigned long long)
+                                 : (size_t)kFusedWaves * M * k * sizeof(Cand);
     // the MFMA gate parks its per-wave partial tiles here before the lists are initialised
     const size_t gate_part_bytes =
         (!dense && gate_mode != kGateVector)
@@ -132,6 +140,7 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     L.o_uprefix = take((size_t)(um + 1) * sizeof(int));
     L.o_umask = take((size_t)um * sizeof(unsigned long long));
     L.o_flags = take(16);
+    L.o_count = take(collect ? (size_t)M * sizeof(int) : 0);      // collected candidates per token
     L.o_keys = take(dense ? 16 : (size_t)kFusedWaves * kWave * sizeof(unsigned long long));
     L.o_offsets = take(dense ? 16 : (size_t)(G + 1) * sizeof(int));
     L.o_bias = take(dense ? 16 : (size_t)G * sizeof(float));
@@ -244,6 +253,41 @@ __device__ __forceinline__ int wave_rank(unsigned long long* keys, float v, int 
 }
 
 __device__ __forceinline__ bool is_real(Cand c) { return c.id != INT_MAX; }
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max(float x) {
+    const int moved = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+    return fmaxf(x, __int_as_float(moved));
+}
+// Maximum over the 64 lanes (no NaN among the inputs), wave-uniform.
+__device__ __forceinline__ float wave_max(float x) {
+    x = dpp_max<0x111, 0xf>(x);   // row_shr:1
+    x = dpp_max<0x112, 0xf>(x);   // row_shr:2
+    x = dpp_max<0x114, 0xf>(x);   // row_shr:4
+    x = dpp_max<0x118, 0xf>(x);   // row_shr:8
+    x = dpp_max<0x142, 0xa>(x);   // row_bcast:15
+    x = dpp_max<0x143, 0xc>(x);   // row_bcast:31
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// Top-g selection among the scores of lanes [0, n), n <= 64, g <= n: the best remaining lane
+// (largest score, then lowest lane) is taken g times; returns the lane's position in the
+// selection, or g if it is not selected.  No LDS; about a dozen instructions per round, so it
+// is used for small g (the ranking by counting costs about five per lane of n).
+__device__ __forceinline__ int select_top(float v, int lane, int n, int g) {
+    bool alive = lane < n;
+    int pos = g;
+    for (int r = 0; r < g; ++r) {                      // wave-uniform
+        const float c = alive ? v : -INFINITY;
+        const float best = wave_max(c);
+        const int winner = __ffsll(__ballot(alive && c == best)) - 1;   // g <= n: some lane is alive
+        if (lane == winner) {
+            pos = r;
+            alive = false;
+        }
+    }
+    return pos;
+}
 
 // Order-preserving 32-bit key of a logit (0 is below every logit, used for padding).
 __device__ __forceinline__ unsigned ord32(float v) {
@@ -500,6 +544,7 @@ __device__ __forceinline__ float lse_finish(float m, float s) {
 
 template <int DT, int NT, bool LP>
 __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* hs, Cand* my_lists,
+                                             unsigned long long* collect_keys, int* collect_count,
                                              const uint4 (&w0)[kFusedSegs],
                                              const uint4 (&w1)[kFusedSegs],
                                              unsigned long long& rem, int rid0, int rid1, bool has1,
@@ -529,12 +574,21 @@ __device__ __forceinline__ void fused_tokens(const FusedParams& p, const uint4* 
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
         const float z0 = wave_sum(a0[i]);
-        lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z0, rid0, thr_v, thr_i, tok[i]);
         float z1 = -INFINITY;
-        if (has1) {                                    // uniform
-            z1 = wave_sum(a1[i]);
-            lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z1, rid1, thr_v, thr_i, tok[i]);
+        if (has1) z1 = wave_sum(a1[i]);                // uniform
+        if (!LP && p.collect) {                        // uniform: the token's buffer takes every logit
+            if (lane == 0) {
+                const int at = atomicAdd(&collect_count[tok[i]], has1 ? 2 : 1);
+                unsigned long long* dst = collect_keys + (size_t)tok[i] * kCollectCap + at;
+                if (at + 1 < kCollectCap) {            // holds by the host's bound on rows per token
+                    dst[0] = cand_key(z0, rid0);
+                    if (has1) dst[1] = cand_key(z1, rid1);
+                }
+            }
+            continue;
         }
+        lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z0, rid0, thr_v, thr_i, tok[i]);
+        if (has1) lds_list_insert(my_lists + tok[i] * p.k, p.k, lane, z1, rid1, thr_v, thr_i, tok[i]);
         if (LP && lane == tok[i]) pair_lse(lse_m, lse_s, z0, z1);   // lane t: token t's piece
     }
 }
@@ -544,7 +598,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     static_assert(!(LP && DENSE), "the log-probability mode belongs to the grouped head");
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
-    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, GATE, LP);
+    const FusedLds lay = fused_lds_layout(p.M, p.G, p.g, p.k, p.jp, DENSE, GATE, LP, p.collect != 0);
     uint4* hs = reinterpret_cast<uint4*>(lds + lay.o_hidden);
     Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
     float* s_lds = reinterpret_cast<float*>(lds + lay.o_s);
@@ -555,6 +609,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     int* uprefix = reinterpret_cast<int*>(lds + lay.o_uprefix);
     unsigned long long* umask = reinterpret_cast<unsigned long long*>(lds + lay.o_umask);
     int* flags = reinterpret_cast<int*>(lds + lay.o_flags);
+    int* collect_count = reinterpret_cast<int*>(lds + lay.o_count);                  // [M], collect mode only
+    unsigned long long* collect_keys = reinterpret_cast<unsigned long long*>(lds + lay.o_lists);   // [M][kCollectCap]
     int* off_lds = reinterpret_cast<int*>(lds + lay.o_offsets);
     float* bias_lds = reinterpret_cast<float*>(lds + lay.o_bias);
     int* sel_lds = reinterpret_cast<int*>(lds + lay.o_sel);          // LP: [M, g] selections
@@ -565,7 +621,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     const int hs_stride = hidden_lds_stride(p.jp);
     const int M = p.M, k = p.k;
 
-    if (threadIdx.x == 0) flags[2] = 0;                // row-pair counter, see step 3
+    // row-pair counter, see step 3: a wave's first pair is fixed (i = wave), the others are drawn
+    if (threadIdx.x == 0) flags[2] = LP ? 0 : kFusedWaves;
+    if (p.collect && (int)threadIdx.x < p.M) collect_count[threadIdx.x] = 0;     // (seen by all after the gate's barriers)
     // ---- 1. hidden vectors: requested first, written to LDS only after the grouped
     // variants have requested their first gate rows as well (loads return in order, so the
     // wait for the hidden vectors does not wait for the gate rows behind them)
@@ -804,23 +862,90 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             h_vec = tid - h_mm * row_vecs;
             hidden_request(0);
         }
+        // Log-probability mode: every workgroup streams rows of one group only (it keeps one
+        // list and one log-sum-exp state per token, Eq. 8 normalises per group), so the
+        // workgroups are shared out among the count <= 64 activated groups in proportion to
+        // their cost, row pairs x (kLpBaseCost + tokens that selected the group): one each,
+        // the rest by the groups' shares rounded down, what is then left one more each to the
+        // groups with the highest cost per workgroup.  The numbers add up to gridDim.x.
+        // One wave's work (activated group u in lane u), after it has written the tables of 2c.
+        auto share_out_workgroups = [&](int count, int all_pairs) {
+            const int P = gridDim.x;
+            const int nb_u = lane < count ? uprefix[lane + 1] - uprefix[lane] : 0;
+            // (row pairs scaled to 16 bits so that the products below stay in 31)
+            const int shift = max(0, 16 - __clz(all_pairs));
+            const unsigned cost =
+                lane < count ? (unsigned)(nb_u >> shift) * (unsigned)(kLpBaseCost + __popcll(umask[lane])) : 0u;
+            const unsigned total = (unsigned)__builtin_amdgcn_readlane(wave_scan_inclusive((int)cost), 63);
+            int n_wg = lane < count ? 1 + (int)(cost * (unsigned)(P - count) / (total ? total : 1u)) : 0;
+            const int left = P - __builtin_amdgcn_readlane(wave_scan_inclusive(n_wg), 63);
+            if (left > 0) {                            // wave-uniform
+                unsigned long long* rank_keys =
+                    reinterpret_cast<unsigned long long*>(lds + lay.o_keys) + (size_t)wave * kWave;
+                const int rank = wave_rank(rank_keys, lane < count ? (float)cost / (float)n_wg : -INFINITY,
+                                           lane, kWave, lane);
+                if (lane < count && rank < left) ++n_wg;
+            }
+            const int incl_wg = wave_scan_inclusive(n_wg);
+            if (lane < count) wgstart[lane] = incl_wg - n_wg;
+            if (lane == 0) wgstart[count] = P;
+        };
         // ---- 2b. per-token top-g by rank counting: group n of token m is selected iff
         // fewer than g groups beat it (larger score first, then lower group id); its rank
         // is its position in the selection
         if (p.G <= kWave) {
+            // group n in lane n.  gm: the tokens that selected this lane's group.
+            unsigned long long gm = 0ull;
             unsigned long long* sel_keys =
                 reinterpret_cast<unsigned long long*>(lds + lay.o_keys) + (size_t)wave * kWave;
-            for (int m = wave; m < M; m += kFusedWaves) {  // one wave per token, group n in lane n
+            for (int m = wave; m < M; m += kFusedWaves) {  // one wave per token
                 float v = lane < p.G ? s_lds[m * p.G + lane] : -INFINITY;
                 if (!(v == v)) v = -INFINITY;              // NaN: unspecified, but keep a total order
-                const int rank = wave_rank(sel_keys, v, lane, p.G, lane);
+                const int rank = p.g <= kSelectRounds ? select_top(v, lane, p.G, p.g)
+                                                      : wave_rank(sel_keys, v, lane, p.G, lane);
                 if (lane < p.G && rank < p.g) {
                     atomicOr(&mask_lds[lane], 1ull << m);
                     if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = lane;
                     if (LP) sel_lds[m * p.g + rank] = lane;
                 }
             }
+            __syncthreads();
+            if (lane < p.G) gm = mask_lds[lane];
+            // ---- 2c. activated groups in ascending id order, their row ranges and the row
+            // pairs before each.  Every wave builds the same tables and writes them to the
+            // same LDS words (equal values), then reads back only what it wrote itself: no
+            // barrier, no wave waits for another.
+            const unsigned long long act = __ballot(gm != 0ull);
+            const int count = __popcll(act);
+            const int at = __popcll(act & ((1ull << lane) - 1ull));
+            int lo = 0, hi = 0;
+            if (gm != 0ull) {
+                lo = off_lds[lane];
+                hi = off_lds[lane + 1];
+            }
+            const int nb = (hi - lo + kFusedRows - 1) / kFusedRows;       // 0 for the others
+            const int incl = wave_scan_inclusive(nb);
+            if (gm != 0ull) {
+                ugroup[at] = lane;
+                umask[at] = gm;
+                ustart[at] = lo;
+                uend[at] = hi;
+                uprefix[at] = incl - nb;
+            }
+            const int all_pairs = __builtin_amdgcn_readlane(incl, 63);
+            if (lane == 0) {
+                uprefix[count] = all_pairs;
+                flags[0] = count;
+            }
+            if (LP) share_out_workgroups(count, all_pairs);
+            if (ROUTED) {
+                hidden_commit(0);
+                hidden_rest();
+                __syncthreads();
+            }
+            total_batches = all_pairs;
         } else {
+            // more groups than lanes
             for (int idx = threadIdx.x; idx < M * p.G; idx += kFusedBlock) {
                 const int m = idx / p.G;
                 const int n = idx - m * p.G;
@@ -839,75 +964,49 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     if (LP) sel_lds[m * p.g + rank] = n;
                 }
             }
-        }
-        __syncthreads();
-        // ---- 2c. activated groups in ascending id order, their row ranges and batch prefix
-        if (wave == 0) {
-            int count = 0;
-            for (int base = 0; base < p.G; base += kWave) {
-                const int n = base + lane;
-                const unsigned long long gm = n < p.G ? mask_lds[n] : 0ull;
-                const unsigned long long b = __ballot(gm != 0ull);
-                if (gm != 0ull) {
-                    const int u = count + __popcll(b & ((1ull << lane) - 1ull));
-                    ugroup[u] = n;
-                    umask[u] = gm;
-                    ustart[u] = off_lds[n];
-                    uend[u] = off_lds[n + 1];
+            __syncthreads();
+            if (wave == 0) {
+                int count = 0;
+                for (int base = 0; base < p.G; base += kWave) {
+                    const int n = base + lane;
+                    const unsigned long long gm = n < p.G ? mask_lds[n] : 0ull;
+                    const unsigned long long b = __ballot(gm != 0ull);
+                    if (gm != 0ull) {
+                        const int u = count + __popcll(b & ((1ull << lane) - 1ull));
+                        ugroup[u] = n;
+                        umask[u] = gm;
+                        ustart[u] = off_lds[n];
+                        uend[u] = off_lds[n + 1];
+                    }
+                    count += __popcll(b);
                 }
-                count += __popcll(b);
-            }
-            int carry = 0;                             // row pairs before each activated group
-            for (int base = 0; base < count; base += kWave) {
-                const int u = base + lane;
-                const int nb = u < count ? (uend[u] - ustart[u] + kFusedRows - 1) / kFusedRows : 0;
-                const int incl = wave_scan_inclusive(nb);
-                if (u < count) uprefix[u] = carry + incl - nb;
-                carry += __builtin_amdgcn_readlane(incl, 63);
-            }
-            if (lane == 0) {
-                uprefix[count] = carry;
-                flags[0] = count;
-            }
-            if (LP) {
-                // Log-probability mode: every workgroup streams rows of one group only (it
-                // keeps one list and one log-sum-exp state per token, Eq. 8 normalises per
-                // group), so the workgroups are shared out among the count <= 64 activated
-                // groups in proportion to their cost, row pairs x (kLpBaseCost + tokens that
-                // selected the group): one each, the rest by the groups' shares rounded
-                // down, what is then left one more each to the groups with the highest cost
-                // per workgroup.  The numbers add up to gridDim.x.
-                const int P = gridDim.x;
-                const int nb = lane < count ? uprefix[lane + 1] - uprefix[lane] : 0;
-                // (row pairs scaled to 16 bits so that the products below stay in 31)
-                const int shift = max(0, 16 - __clz(carry));
-                const unsigned cost =
-                    lane < count ? (unsigned)(nb >> shift) * (unsigned)(kLpBaseCost + __popcll(umask[lane])) : 0u;
-                const unsigned total = (unsigned)__builtin_amdgcn_readlane(wave_scan_inclusive((int)cost), 63);
-                int n_wg = lane < count ? 1 + (int)(cost * (unsigned)(P - count) / (total ? total : 1u)) : 0;
-                const int left = P - __builtin_amdgcn_readlane(wave_scan_inclusive(n_wg), 63);
-                if (left > 0) {                        // wave-uniform
-                    unsigned long long* rank_keys = reinterpret_cast<unsigned long long*>(lds + lay.o_keys);
-                    const int rank = wave_rank(rank_keys, lane < count ? (float)cost / (float)n_wg : -INFINITY,
-                                               lane, kWave, lane);
-                    if (lane < count && rank < left) ++n_wg;
+                int carry = 0;                             // row pairs before each activated group
+                for (int base = 0; base < count; base += kWave) {
+                    const int u = base + lane;
+                    const int nb = u < count ? (uend[u] - ustart[u] + kFusedRows - 1) / kFusedRows : 0;
+                    const int incl = wave_scan_inclusive(nb);
+                    if (u < count) uprefix[u] = carry + incl - nb;
+                    carry += __builtin_amdgcn_readlane(incl, 63);
                 }
-                const int incl = wave_scan_inclusive(n_wg);
-                if (lane < count) wgstart[lane] = incl - n_wg;
-                if (lane == 0) wgstart[count] = P;
+                if (lane == 0) {
+                    uprefix[count] = carry;
+                    flags[0] = count;
+                }
+                if (LP) share_out_workgroups(count, carry);
             }
+            if (ROUTED) {
+                hidden_commit(0);
+                hidden_rest();
+            }
+            __syncthreads();
+            total_batches = uni(uprefix[uni(flags[0])]);
         }
-        if (ROUTED) {
-            hidden_commit(0);
-            hidden_rest();
-        }
-        __syncthreads();
-        total_batches = uni(uprefix[uni(flags[0])]);
     }
 
     // ---- 3./4. stream row pairs (the lists share LDS with the gate's partial tiles, so
     // they are emptied only now; each wave touches its own lists only)
-    for (int i = lane; i < M * k; i += kWave) my_lists[i] = sentinel();
+    if (LP || !p.collect)
+        for (int i = lane; i < M * k; i += kWave) my_lists[i] = sentinel();
     // The workgroup's row pairs are b(i) = (i / 16) * 16 * #workgroups + 16 * blockIdx + i % 16
     // for i = 0, 1, ...; its waves draw i from an LDS counter, so a wave that the memory
     // system serves faster takes more of them and all waves finish together.
@@ -971,7 +1070,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             bm = uni64(umask[u]);
         }
     };
-    int b = draw_batch();
+    // the first pair is fixed (i = wave), the others are drawn from the LDS counter
+    int b = LP ? draw_batch() : (int)(blockIdx.x * kFusedWaves + wave);
     int rid0 = 0, rid1 = 0;
     bool has1 = false;
     unsigned long long bm = 0ull;
@@ -1002,13 +1102,13 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         while (rem) {                                  // wave-uniform
             const int cnt = __popcll(rem);
             if (cnt >= 4)
-                fused_tokens<DT, 4, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                fused_tokens<DT, 4, LP>(p, hs, my_lists, collect_keys, collect_count, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
                                         lse_m, lse_s);
             else if (cnt >= 2)
-                fused_tokens<DT, 2, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                fused_tokens<DT, 2, LP>(p, hs, my_lists, collect_keys, collect_count, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
                                         lse_m, lse_s);
             else
-                fused_tokens<DT, 1, LP>(p, hs, my_lists, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
+                fused_tokens<DT, 1, LP>(p, hs, my_lists, collect_keys, collect_count, w0, w1, rem, rid0, rid1, has1, thr_v, thr_i,
                                         lse_m, lse_s);
         }
         if (LP && ((bm >> lane) & 1ull)) {             // token slot j of the group, pair b
@@ -1034,7 +1134,51 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     const int P = gridDim.x;
     // published lists are entry-major, part[(t*k + i)*P + workgroup]: the first entries of
     // all workgroups, which bound the result, are contiguous
-    if (!LP) {
+    if (!LP && p.collect) {
+        // The token's collected logits are ranked by counting (keys are distinct: distinct
+        // ids; a key of zero is below every logit) and the k best published.  With fewer
+        // tokens than waves, S waves share a token: each counts over a slice of the keys and
+        // the token's first wave adds the counts up.
+        const int S = M <= 1 ? 16 : M <= 2 ? 8 : M <= 4 ? 4 : M <= 8 ? 2 : 1;
+        unsigned short* partial = reinterpret_cast<unsigned short*>(lds + lay.o_hidden);   // [wave][2][64]
+        for (int base = 0; base < M; base += kFusedWaves / S) {    // block-uniform; one round if S > 1
+            const int t = base + wave / S, slice = wave % S;
+            const unsigned long long* keys = collect_keys + (size_t)(t < M ? t : 0) * kCollectCap;
+            const int n = t < M ? min(uni(collect_count[t]), kCollectCap) : 0;
+            const unsigned long long c0 = lane < n ? keys[lane] : 0ull;
+            const unsigned long long c1 = lane + kWave < n ? keys[lane + kWave] : 0ull;
+            const int per = (n + S - 1) / S;
+            const int j1 = min(n, (slice + 1) * per);
+            int r0 = 0, r1 = 0;
+            if (n <= kWave) {                          // wave-uniform
+#pragma unroll 8
+                for (int j = slice * per; j < j1; ++j) r0 += keys[j] > c0 ? 1 : 0;
+            } else {
+#pragma unroll 8
+                for (int j = slice * per; j < j1; ++j) {
+                    const unsigned long long o = keys[j];
+                    r0 += o > c0 ? 1 : 0;
+                    r1 += o > c1 ? 1 : 0;
+                }
+            }
+            if (S > 1) {                               // block-uniform
+                partial[wave * 2 * kWave + lane] = (unsigned short)r0;
+                partial[wave * 2 * kWave + kWave + lane] = (unsigned short)r1;
+                __syncthreads();
+                if (slice == 0)
+                    for (int q = 1; q < S; ++q) {
+                        r0 += partial[(wave + q) * 2 * kWave + lane];
+                        r1 += partial[(wave + q) * 2 * kWave + kWave + lane];
+                    }
+            }
+            if (t < M && slice == 0) {
+                Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
+                if (c0 != 0ull && r0 < k) publish_cand(dst + (size_t)r0 * P, key_value(c0), key_id(c0));
+                if (c1 != 0ull && r1 < k) publish_cand(dst + (size_t)r1 * P, key_value(c1), key_id(c1));
+                if (lane >= n && lane < k) publish_cand(dst + (size_t)lane * P, -INFINITY, INT_MAX);
+            }
+        }
+    } else if (!LP) {
         for (int t = wave; t < M; t += kFusedWaves) {
             Cand* dst = p.part + (size_t)t * k * P + blockIdx.x;
             wave_merge_topk(
