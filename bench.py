@@ -51,6 +51,7 @@ def parse():
                     help="'default': also time the config's other M values, the dense head, the other "
                          "entry points and (for the headline config) the Qwen2.5-7B shape and the "
                          "paper's operating point, with fewer steps; 'own': this config only; "
+                         "'routed': only the router pre-mix cases (for profiling that kernel); "
                          "'none': headline only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="no HIP graph: one host call per step")
@@ -531,6 +532,13 @@ def main():
         out["us_per_step_spread"] = res["spread"]
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(bench, res)
+    if a.cases == "routed":
+        r = bench.time_routed(a.M, max(48, a.steps // 10), min(a.warmup, 20))
+        out["cases"] = [{"path": "router pre-mix alone, W1 copies cycled", "M": a.M, "us_per_step": r["premix_us"]},
+                        {"path": "router pre-mix alone, the same W1 every step", "M": a.M,
+                         "us_per_step": r["premix_resident_us"]},
+                        {"path": "pre-mix, then grouped head with the router reading u", "M": a.M,
+                         "us_per_step": r["step_us"]}]
     if a.cases in ("default", "own"):
         cases = []
         n = max(48, a.steps // 10)
