@@ -91,6 +91,7 @@ struct FusedParams {
     int M, V, G, g, k;
     int n_vec, jp;
     int collect;                // candidates are collected per token (see kCollectCap) instead of listed per wave
+    int stream_waves;           // waves of a workgroup that stream weight rows (1..16)
 };
 
 struct FusedLds {
@@ -622,7 +623,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     const int M = p.M, k = p.k;
 
     // row-pair counter, see step 3: a wave's first pair is fixed (i = wave), the others are drawn
-    if (threadIdx.x == 0) flags[2] = LP ? 0 : kFusedWaves;
+    if (threadIdx.x == 0) flags[2] = LP ? 0 : p.stream_waves;
     if (p.collect && (int)threadIdx.x < p.M) collect_count[threadIdx.x] = 0;     // (seen by all after the gate's barriers)
     // ---- 1. hidden vectors: requested first, written to LDS only after the grouped
     // variants have requested their first gate rows as well (loads return in order, so the
@@ -1071,7 +1072,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
         }
     };
     // the first pair is fixed (i = wave), the others are drawn from the LDS counter
-    int b = LP ? draw_batch() : (int)(blockIdx.x * kFusedWaves + wave);
+    // (With few tokens the dense head's consecutive rows stream fastest with 64 to 160 KB in
+    // flight per compute unit rather than 256 KB: its waves beyond p.stream_waves sit out.)
+    int b = LP ? draw_batch() : wave < p.stream_waves ? (int)(blockIdx.x * kFusedWaves + wave) : total_batches;
     int rid0 = 0, rid1 = 0;
     bool has1 = false;
     unsigned long long bm = 0ull;
