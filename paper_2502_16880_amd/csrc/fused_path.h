@@ -45,7 +45,6 @@ constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp 
 // g * v / 256, about 63), the waves append every logit to one buffer per token instead of
 // keeping sorted lists, and one wave per token ranks the buffer at the end.
 constexpr int kCollectCap = 128;       // entries per token
-constexpr int kSelectRounds = 8;       // up to this many groups per token the selection runs as rounds of a wave maximum
 constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
@@ -269,25 +268,6 @@ __device__ __forceinline__ float wave_max(float x) {
     x = dpp_max<0x142, 0xa>(x);   // row_bcast:15
     x = dpp_max<0x143, 0xc>(x);   // row_bcast:31
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
-// Top-g selection among the scores of lanes [0, n), n <= 64, g <= n: the best remaining lane
-// (largest score, then lowest lane) is taken g times; returns the lane's position in the
-// selection, or g if it is not selected.  No LDS; about a dozen instructions per round, so it
-// is used for small g (the ranking by counting costs about five per lane of n).
-__device__ __forceinline__ int select_top(float v, int lane, int n, int g) {
-    bool alive = lane < n;
-    int pos = g;
-    for (int r = 0; r < g; ++r) {                      // wave-uniform
-        const float c = alive ? v : -INFINITY;
-        const float best = wave_max(c);
-        const int winner = __ffsll(__ballot(alive && c == best)) - 1;   // g <= n: some lane is alive
-        if (lane == winner) {
-            pos = r;
-            alive = false;
-        }
-    }
-    return pos;
 }
 
 // Order-preserving 32-bit key of a logit (0 is below every logit, used for padding).
@@ -902,8 +882,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             for (int m = wave; m < M; m += kFusedWaves) {  // one wave per token
                 float v = lane < p.G ? s_lds[m * p.G + lane] : -INFINITY;
                 if (!(v == v)) v = -INFINITY;              // NaN: unspecified, but keep a total order
-                const int rank = p.g <= kSelectRounds ? select_top(v, lane, p.G, p.g)
-                                                      : wave_rank(sel_keys, v, lane, p.G, lane);
+                const int rank = wave_rank(sel_keys, v, lane, p.G, lane);
                 if (lane < p.G && rank < p.g) {
                     atomicOr(&mask_lds[lane], 1ull << m);
                     if (p.sel_out && blockIdx.x == 0) p.sel_out[m * p.g + rank] = lane;

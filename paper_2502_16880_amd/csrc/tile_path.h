@@ -610,6 +610,11 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     if ((int)threadIdx.x + kFusedBlock <= p.G) off_r1 = p.offsets[threadIdx.x + kFusedBlock];
     const int n_tt = (p.M + 15) / 16;
     const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
+    float bias_r = 0.f;                                // (likewise: the bias of the score this thread will sum)
+    if (threadIdx.x < 256 && p.bias) {
+        const int gn = gt * 16 + ((threadIdx.x >> 2) >> 4) * 4 + (threadIdx.x & 3);
+        if (gn < p.G) bias_r = p.bias[gn];
+    }
     const int n_ks = (p.n_vec + 3) / 4;
     const int n = gt * 16 + mfma_load_row(lane), m = tt * 16 + mfma_load_row(lane);
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -642,7 +647,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         float sum = 0.f;
         for (int w = 0; w < kFusedWaves; ++w) sum += part[w][e];
         if (gn < p.G && tm < p.M)
-            __hip_atomic_store(p.s + (size_t)tm * p.G + gn, sum + (p.bias ? p.bias[gn] : 0.f),
+            __hip_atomic_store(p.s + (size_t)tm * p.G + gn, sum + bias_r,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the scores are out
@@ -658,15 +663,24 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) mask[g0] = 0ull;
     __syncthreads();
     if (p.G <= kWave) {
-        for (int tm = wave; tm < p.M; tm += kFusedWaves) {  // one wave per token, group in lane
-            float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
+        // one wave per token, group in lane; the scores of all the wave's tokens (up to four:
+        // M <= 64) are requested together, so that the selection costs one trip to memory
+        float sv[kMaxM / kFusedWaves];
+#pragma unroll
+        for (int j = 0; j < kMaxM / kFusedWaves; ++j) {
+            const int tm = wave + j * kFusedWaves;
+            sv[j] = (tm < p.M && lane < p.G) ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
+        }
+#pragma unroll
+        for (int j = 0; j < kMaxM / kFusedWaves; ++j) {
+            const int tm = wave + j * kFusedWaves;
+            if (tm >= p.M) break;                           // wave-uniform
+            float v = sv[j];
             if (!(v == v)) v = -INFINITY;
             const int rank = wave_rank(sel_keys[wave], v, lane, p.G, lane);
             float lse_s = 0.f;
             if (p.logp_sel) {                               // the router's softmax over all G scores (Eq. 7)
-                float smax = v;
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) smax = fmaxf(smax, __shfl_xor(smax, off));
+                const float smax = wave_max(v);
                 lse_s = smax + logf(wave_sum(lane < p.G ? expf(v - smax) : 0.f));
             }
             if (lane < p.G && rank < p.g) {
@@ -719,17 +733,37 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     // tiles (16 tokens each) first, then ascending group id; placed by rank counting.  The
     // table row of each carries its row range, token mask and the number of blocks before it.
     const int count = uni(ucount);
-    for (int u0 = threadIdx.x; u0 < count; u0 += kFusedBlock) {
-        const int g0 = ulist[u0];
-        const int w0 = (__popcll(mask[g0]) + 15) >> 4;
-        int rank = 0;
-        for (int v = 0; v < count; ++v) {
-            const int wv = (__popcll(mask[ulist[v]]) + 15) >> 4;
-            rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
+    if (count <= kWave) {
+        // a group has one to four token tiles (M <= 64): four ballots place it
+        if (wave == 0) {
+            const int g0 = lane < count ? ulist[lane] : 0;
+            const int w0 = lane < count ? (__popcll(mask[g0]) + 15) >> 4 : 0;
+            int rank = 0;
+#pragma unroll
+            for (int w = 4; w >= 1; --w) {
+                const unsigned long long b = __ballot(w0 == w);
+                if (w0 < w) rank += __popcll(b);
+                if (w0 == w) rank += __popcll(b & ((1ull << lane) - 1ull));
+            }
+            if (lane < count) {
+                order[rank] = g0;
+                rank_of[g0] = rank;
+                nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
+            }
         }
-        order[rank] = g0;
-        rank_of[g0] = rank;
-        nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
+    } else {
+        for (int u0 = threadIdx.x; u0 < count; u0 += kFusedBlock) {
+            const int g0 = ulist[u0];
+            const int w0 = (__popcll(mask[g0]) + 15) >> 4;
+            int rank = 0;
+            for (int v = 0; v < count; ++v) {
+                const int wv = (__popcll(mask[ulist[v]]) + 15) >> 4;
+                rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
+            }
+            order[rank] = g0;
+            rank_of[g0] = rank;
+            nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
+        }
     }
     __syncthreads();
     if (wave == 0) {
