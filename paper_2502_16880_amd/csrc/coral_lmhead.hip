@@ -265,10 +265,12 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     if (jp > kFusedSegs || F.total > kLdsLimit) return CORAL_ERR_UNSUPPORTED;   // not reached
     FusedParams p = {};
     p.collect = collect ? 1 : 0;
-    // measured at the Llama3 shape: dense head, one or two tokens: 6 waves 158 us against 165 us
-    // with all 16; four tokens: 10 waves 162 us against 168 us; the grouped head's gathered rows
-    // want all 16
-    p.stream_waves = !dense ? kFusedWaves : M <= 2 ? 6 : M <= 4 ? 10 : kFusedWaves;
+    // Measured with rows of 8 KB (Llama shapes): dense head, one or two tokens: 6 waves 158 us
+    // against 165 us with all 16 (Llama2: 46.5 against 48.5 us); four tokens: 10 waves 162 us
+    // against 168 us.  Rows of 7 KB (Qwen shape) and the grouped head's gathered rows are
+    // fastest with all 16 (Qwen dense: 163 us against 170 us with 6).
+    const bool rows_of_8k = ((size_t)n_vec * 16) % 8192 == 0;
+    p.stream_waves = !dense || !rows_of_8k ? kFusedWaves : M <= 2 ? 6 : M <= 4 ? 10 : kFusedWaves;
     p.hidden = static_cast<const uint4*>(hidden);
     p.gate_hidden = static_cast<const uint4*>(gate_hidden);
     p.gate_W = static_cast<const uint4*>(gate_W);
