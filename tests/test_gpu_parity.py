@@ -247,6 +247,24 @@ def test_all_groups_active_equals_dense_on_device(coral, M):
         assert M == 9 and np.max(np.abs(gz - dz)) < 1e-5
 
 
+@pytest.mark.parametrize("dtype,M", [("f32", 3), ("bf16", 1), ("bf16", 9)])
+def test_collected_candidates_beyond_one_wave(coral, dtype, M):
+    """Groups so long that a workgroup meets three of its 16-pair windows per token: about
+    96 rows per (workgroup, token), more than one candidate per lane in the final ranking,
+    still within the 128 the host's bound allows (four groups, every one selected)."""
+    cfg = HeadConfig("collect96", dtype, 64, 4 * 5000, 4, 4, (M,), 12, 120 + M, dtype != "f32")
+    dh = DeviceHead(coral, make_head(cfg))
+    for batch in (0, 1):
+        hidden = make_hidden(cfg, M, batch)
+        print(f"case {cfg.name} {dtype} M={M} batch={batch}", flush=True)
+        check_grouped(dh, hidden, cfg.g, cfg.k, run_grouped(coral, dh, hidden, cfg.g, cfg.k))
+    # one group more per token and the bound is exceeded: per-wave lists take over, same results
+    cfg5 = HeadConfig("lists160", dtype, 64, 5 * 4000, 5, 5, (M,), 12, 130 + M, dtype != "f32")
+    dh = DeviceHead(coral, make_head(cfg5))
+    hidden = make_hidden(cfg5, M, 0)
+    check_grouped(dh, hidden, cfg5.g, cfg5.k, run_grouped(coral, dh, hidden, cfg5.g, cfg5.k))
+
+
 def test_every_path_is_exercised(coral):
     """The scaled and full-size cases above cover all three kernel paths."""
     P = coral.coral_lmhead_path
