@@ -52,10 +52,11 @@ inline bool is_16bit(coral_dtype dt) { return dt != CORAL_F32; }
 constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path's grid
 constexpr size_t kCtrlBytes = coral_ctrl::kWords * sizeof(unsigned int);   // control words at the start of the workspace
 static_assert(coral_ctrl::kLpGroupArrivalWords >= kWave, "one arrival counter per activated group");
+static_assert(coral_ctrl::kTileTokenArrivalWords >= kMaxM, "one arrival counter per token");
 
 struct Layout {
-    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_table, total;
-    int part_stride;
+    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_table, tile_first_block, tile_z, tile_lists, tile_lse, total;
+    int part_stride, tile_list_stride;
 };
 
 bool sizes_ok(int M, int H, int V, int G, int g, int k) {
@@ -65,8 +66,11 @@ bool sizes_ok(int M, int H, int V, int G, int g, int k) {
 }
 
 // pair_pieces: the shape can take the single-launch kernel's log-probability mode (the table
-// of its per-pair pieces is the largest item and is left out otherwise).
-Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces) {
+// of its per-pair pieces is the largest item and is left out otherwise).  tiles: the shape
+// can take the matrix-core path (its logits buffer and span lists are left out otherwise).
+// tiles_only: a layout for a call that is known to take the matrix-core path (the other
+// paths' lists are left out).
+Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces, bool tiles, bool tiles_only = false) {
     Layout L;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -75,9 +79,10 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces) {
         return at;
     };
     L.ctrl = take(kCtrlBytes);
-    L.fused_part = take((size_t)kMaxWorkgroups * M * k * sizeof(Cand));
-    L.fused_lse = take((size_t)kMaxWorkgroups * M * sizeof(unsigned long long));   // log-probability mode
-    L.fused_glist = take((size_t)M * (g ? g : 1) * k * sizeof(Cand));
+    const size_t others = tiles_only ? 0 : 1;
+    L.fused_part = take(others * kMaxWorkgroups * M * k * sizeof(Cand));
+    L.fused_lse = take(others * kMaxWorkgroups * M * sizeof(unsigned long long));   // log-probability mode
+    L.fused_glist = take(others * M * (g ? g : 1) * k * sizeof(Cand));
     // one (max, sum) piece per (row pair of a selected group, token that selected it): a
     // token's g groups are distinct, so their pairs number V / 2 + g at most
     L.fused_pairs = take(pair_pieces ? (size_t)M * ((size_t)V / 2 + g) * sizeof(unsigned long long) : 0);
@@ -89,10 +94,18 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces) {
     L.chunk_base = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.slot_count = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.part_stride = (V + kChunkRows - 1) / kChunkRows + g;
-    L.part = take((size_t)M * L.part_stride * k * sizeof(Cand));
-    L.lse_part = take((size_t)M * L.part_stride * 2 * sizeof(float));     // log-probability mode
+    L.part = take(others * M * L.part_stride * k * sizeof(Cand));
+    L.lse_part = take(others * M * L.part_stride * 2 * sizeof(float));     // log-probability mode
     L.logp_sel = take((size_t)M * (g ? g : 1) * sizeof(float));
     L.tile_table = take((size_t)(G ? G : 1) * sizeof(TileGroup));
+    L.tile_first_block = take((size_t)(G ? G : 1) * sizeof(int32_t));
+    // a group's blocks and spans round up: V / 128 + G blocks and V / 2048 + g spans of one
+    // token's groups at most (+ 1: V itself rounds up; a group without rows still has a span)
+    const size_t tile_blocks = (size_t)V / kTileRows + G + 1;
+    L.tile_list_stride = V / kSpanRows + g + 1;
+    L.tile_z = take(tiles ? tile_blocks * M * kTileRows * sizeof(float) : 0);
+    L.tile_lists = take(tiles ? (size_t)M * L.tile_list_stride * k * sizeof(Cand) : 0);
+    L.tile_lse = take(tiles ? (size_t)M * L.tile_list_stride * sizeof(unsigned long long) : 0);
     L.total = off;
     return L;
 }
@@ -334,11 +347,11 @@ bool dense_prefers_tiles(int M, int V) { return M >= 8 && V >= 2 * kMaxWorkgroup
 
 // Matrix-core path: 16-bit storage, whole 512-column chunks, weights below 4 GiB, LDS plan within the limit.
 bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_max_out, int* lds_out) {
-    if (!is_16bit(dt) || k > kTileMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
+    if (!is_16bit(dt) || k > kMaxK || M > 64 || H % (kChunkVecs * 8) != 0) return false;
     if ((unsigned long long)V * H * 2ull >= (1ull << 32)) return false;   // 32-bit weight offsets
     long long um = (long long)M * g < G ? (long long)M * g : G;
     if (um < 1) um = 1;
-    const TileLds T = tile_lds_layout(M, k, (int)um);
+    const TileLds T = tile_lds_layout((int)um);
     if (T.total > kLdsLimit) return false;
     *u_max_out = (int)um;
     *lds_out = T.total;
@@ -366,11 +379,8 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
         if (dense) return pl;
         if (fused_logprob_fits(M, G, g, k, jp, dt, kMaxWorkgroups)) {
             pl.path = 1;
-        } else if (tiles_fit(M, H, V, G, g, k, dt, &pl.tile_umax, &pl.tile_lds) && G <= kWave &&
-                   (long long)M * g <= kGateSelMaxPairs &&
-                   // a block per slot of the per-chunk arrays: V / 128 + G blocks at most
-                   (long long)V / kTileRows + G <= (long long)(V + kChunkRows - 1) / kChunkRows + g) {
-            pl.path = 2;
+        } else if (tiles_fit(M, H, V, G, g, k, dt, &pl.tile_umax, &pl.tile_lds) && G <= kWave) {
+            pl.path = 2;                    // (k_gate_select leaves log p_router for up to 64 groups)
         }
         return pl;
     }
@@ -391,58 +401,77 @@ PathPlan plan_path(bool dense, int M, int H, int V, int G, int g, int k, coral_d
     return pl;
 }
 
-// Enqueues k_tiles and the merge of its published lists.  For the grouped head the masks
-// and the list of activated groups must already be enqueued (k_gate, k_select).
+// Whether a call with these sizes (grouped in either output mode, or dense when G = 0) can
+// take the matrix-core path: the workspace then holds its logits buffer and span lists.
+bool layout_has_tiles(int M, int H, int V, int G, int g, int k, coral_dtype dt) {
+    if (!dtype_ok(dt) || H % (is_16bit(dt) ? 8 : 4) != 0) return false;
+    if (plan_path(true, M, H, V, 0, 0, k, dt).path == 2) return true;
+    if (G < 1) return false;
+    return plan_path(false, M, H, V, G, g, k, dt).path == 2 ||
+           plan_path(false, M, H, V, G, g, k, dt, true).path == 2;
+}
+
+// Enqueues k_tiles and the ranking of the logits it leaves.  For the grouped head the gate
+// and selection kernel must already be enqueued (masks, table, first blocks; lp: log p_router
+// of the selection too).
 coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
                           const coral_group_index* gi, const TileGroup* table,
                           const int32_t* n_union, int M, int H, int V,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
-                          float* topk_logits, char* ws, const Layout& L, hipStream_t stream,
-                          void* ev_before, void* ev_after, const int32_t* lp_sel = nullptr, int g = 0) {
-    // lp_sel: log-probability mode (grouped): the selection k_gate_select wrote; its first
-    // blocks and log p_router sit in the workspace's chunk_base and logp_sel arrays
+                          float* topk_out, char* ws, const Layout& L, hipStream_t stream,
+                          void* ev_before, void* ev_after, const int32_t* sel = nullptr, int g = 0,
+                          int max_group_rows = 0, bool logprob = false) {
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
     TileParams p = {};
     p.hidden = static_cast<const uint4*>(hidden);
     p.lm_W = static_cast<const uint4*>(lm_W);
-    p.offsets = gi ? gi->group_offsets : nullptr;
     p.rows = gi ? gi->group_rows : nullptr;
     p.table = table;
     p.n_union = n_union;
-    p.part = reinterpret_cast<Cand*>(ws + L.fused_part);
+    p.z = reinterpret_cast<float*>(ws + L.tile_z);
     p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileQueue;
-    p.M = M; p.V = V; p.G = G; p.k = k;
+    p.M = M; p.V = V;
     p.n_vec = H / 8;
     p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
     p.u_max = u_max;
-    p.blk_part = reinterpret_cast<Cand*>(ws + L.part);
-    p.blk_lse = reinterpret_cast<float*>(ws + L.lse_part);
-    p.blk_stride = L.part_stride;
     typedef void (*tiles_fn)(TileParams, int);
-    const tiles_fn fn = lp_sel ? (dt == CORAL_F16 ? k_tiles<kF16, true> : k_tiles<kBF16, true>)
-                               : (dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>);
+    const tiles_fn fn = dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>;
     if (!allow_lds(reinterpret_cast<const void*>(fn), lds)) return CORAL_ERR_HIP;
     coral_status st;
     if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     hipLaunchKernelGGL(fn, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
     if ((st = launch_status()) != CORAL_OK) return st;
     if ((st = record(ev_after, stream)) != CORAL_OK) return st;
-    if (lp_sel) {
-        typedef void (*merge_fn)(const Cand*, const float*, int, const int32_t*, const int32_t*, const float*,
-                                 int, int, int32_t*, float*, unsigned int*);
-        const merge_fn mf = g > 4 ? k_merge_logprob<8> : k_merge_logprob<4>;
-        hipLaunchKernelGGL(mf, dim3(M), dim3(g > 4 ? 8 * kWave : kBlock), 0, stream, p.blk_part, p.blk_lse,
-                           L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count),
-                           reinterpret_cast<const int32_t*>(ws + L.chunk_base),
-                           reinterpret_cast<const float*>(ws + L.logp_sel), g, k, topk_ids, topk_logits,
-                           p.next_block);
-        return launch_status();
+
+    TileSelectParams q = {};
+    q.z = p.z;
+    q.sel = sel;
+    q.offsets = gi ? gi->group_offsets : nullptr;
+    q.rows = p.rows;
+    q.group_first_block = reinterpret_cast<const int32_t*>(ws + L.tile_first_block);
+    q.group_mask = reinterpret_cast<const unsigned long long*>(ws + L.mask);
+    q.logp_sel = reinterpret_cast<const float*>(ws + L.logp_sel);
+    q.lists = reinterpret_cast<Cand*>(ws + L.tile_lists);
+    q.lse = reinterpret_cast<unsigned long long*>(ws + L.tile_lse);
+    q.arrivals = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileTokenArrival;
+    q.next_block = p.next_block;
+    q.topk_ids = topk_ids;
+    q.topk_out = topk_out;
+    q.M = M; q.V = V; q.g = g; q.k = k;
+    q.list_stride = L.tile_list_stride;
+    if (dense) {
+        const int spans = (V + kSpanRows - 1) / kSpanRows;
+        hipLaunchKernelGGL((k_tile_select<true, false>), dim3(M, spans), dim3(kSelectThreads), 0, stream, q);
+    } else {
+        int spans = (max_group_rows + kSpanRows - 1) / kSpanRows;
+        if (spans < 1) spans = 1;
+        if (logprob)
+            hipLaunchKernelGGL((k_tile_select<false, true>), dim3(M * g, spans), dim3(kSelectThreads), 0, stream, q);
+        else
+            hipLaunchKernelGGL((k_tile_select<false, false>), dim3(M * g, spans), dim3(kSelectThreads), 0, stream, q);
     }
-    hipLaunchKernelGGL(k_merge_published, dim3((M + 3) / 4), dim3(256), 0, stream,
-                       reinterpret_cast<const Cand*>(ws + L.fused_part), P, M, k, topk_ids,
-                       topk_logits, p.next_block);
     return launch_status();
 }
 
@@ -486,7 +515,8 @@ extern "C" coral_status coral_group_index_validate(const int32_t* host_offsets,
 extern "C" size_t coral_lmhead_workspace_bytes(int M, int H, int V, int G, int g, int k,
                                                coral_dtype dt) {
     if (!sizes_ok(M, H, V, G, g, k)) return 0;
-    return make_layout(M, V, G, g, k, layout_has_pair_pieces(M, H, G, g, k, dt)).total;
+    return make_layout(M, V, G, g, k, layout_has_pair_pieces(M, H, G, g, k, dt),
+                       layout_has_tiles(M, H, V, G, g, k, dt)).total;
 }
 
 extern "C" int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k,
@@ -552,8 +582,12 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         min_cand += smallest[i];
     }
     if ((long long)k > min_cand) return CORAL_ERR_SHAPE;
-    // (the static scratch serves the logit ranking only: no table of per-pair pieces)
-    const Layout L = make_layout(M, V, G, g, k, !static_workspace && layout_has_pair_pieces(M, H, G, g, k, dt));
+    // (the static scratch serves the logit ranking only: no table of per-pair pieces, and the
+    // matrix-core path's buffers only if this very call takes that path)
+    const bool static_tiles = static_workspace && plan_path(false, M, H, V, G, g, k, dt).path == 2;
+    const Layout L = make_layout(M, V, G, g, k, !static_workspace && layout_has_pair_pieces(M, H, G, g, k, dt),
+                                 static_workspace ? static_tiles : layout_has_tiles(M, H, V, G, g, k, dt),
+                                 static_tiles);
     if (static_workspace) {
         if (logprob || L.total > kStaticScratchBytes) return CORAL_ERR_WORKSPACE;
     } else {
@@ -600,11 +634,8 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         q.group_mask = mask; q.offsets = gi->group_offsets; q.table = table; q.n_union = n_union;
         q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kGateSelectArrival;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
-        if (logprob) {
-            q.first_block = chunk_base;
-            q.block_count = reinterpret_cast<int32_t*>(ws + L.slot_count);
-            q.logp_sel = reinterpret_cast<float*>(ws + L.logp_sel);
-        }
+        q.group_first_block = reinterpret_cast<int32_t*>(ws + L.tile_first_block);
+        if (logprob) q.logp_sel = reinterpret_cast<float*>(ws + L.logp_sel);
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
         typedef void (*gate_select_fn)(GateSelParams);
         const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
@@ -612,7 +643,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         if ((st = launch_status()) != CORAL_OK) return st;
         st = launch_tiles(false, hidden, lm_W, gi, table, n_union, M, H, V, G, k, dt,
                           plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
-                          ev_after, logprob ? sel : nullptr, g);
+                          ev_after, sel, g, max_rows, logprob);
         if (st != CORAL_OK || !level) return st;
         hipLaunchKernelGGL(k_tree_expand, dim3(M), dim3(kWave), (size_t)M * k * sizeof(unsigned long long),
                            stream, level->parent_score, topk_ids, topk_logits, M, k, level->n_next,
@@ -684,7 +715,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     coral_status st = check_common(hidden, lm_W, M, H, V, k, dt, topk_ids, topk_logits);
     if (st != CORAL_OK) return st;
     if (k > V) return CORAL_ERR_SHAPE;
-    const Layout L = make_layout(M, V, 0, 0, k, false);
+    const Layout L = make_layout(M, V, 0, 0, k, false, layout_has_tiles(M, H, V, 0, 0, k, dt));
     st = check_workspace(workspace, workspace_bytes, L.total);
     if (st != CORAL_OK) return st;
 

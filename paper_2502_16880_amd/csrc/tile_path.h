@@ -2,9 +2,9 @@
 // the dense head with many tokens: the logits of a block of 128 weight rows for up to 64
 // tokens are 16x16 tiles of v_mfma_f32_16x16x32_bf16.
 //
-// One persistent workgroup of 8 waves per compute unit; wave = (row group rg = wave/2: 32
-// rows = two row tiles, half kq = wave%2 of every 512-column chunk).  Per block of 128
-// rows of one group:
+// k_tiles: one persistent workgroup of 8 waves per compute unit; wave = (row group rg =
+// wave/2: 32 rows = two row tiles, half kq = wave%2 of every 512-column chunk).  Per block of
+// 128 rows of one group:
 //   - the weight rows go from HBM into registers in whole 128-byte lines (a wave load
 //     covers 8 rows x 128 B), and pairs of such registers go through a wave-private LDS
 //     slice into the MFMA A operands of two 32-column steps; 16 KB per wave in flight,
@@ -13,10 +13,13 @@
 //     (512 columns, double buffered) in LDS and read as B operands, each fragment used for
 //     both row tiles of the wave;
 //   - the two half sums of each tile are added in a fixed order through LDS, which
-//     leaves, per token, the block's 128 logits two per lane of a wave; those that beat the
-//     token's current k-th are merged into the workgroup's running list by rank counting.
-// Each workgroup publishes its lists; a second small kernel merges them per token.
-// The logits row is never written to memory.
+//     leaves, per token, the block's 128 logits two per lane of a wave; they go to memory as
+//     they are, 512 bytes per (block, token): a few MB per step against the hundreds of MB of
+//     weight rows, and the workgroup is back in its next block's K loop within a microsecond.
+// k_tile_select: one workgroup per (token, span of 16 blocks of one of its groups) ranks the
+// span's logits (a bound from the threads' best candidates, then rank counting among what
+// reaches it); the workgroup that finishes a token's last span merges the spans' lists
+// (Eq. 8's offsets added per group in the log-probability mode).
 #pragma once
 #include "device_utils.h"
 #include "fused_path.h"
@@ -31,8 +34,11 @@ constexpr int kTileRows = 128;                   // weight rows per block (4 row
 constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-column chunk
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
-constexpr int kTileMaxK = 64;                    // a list occupies the lanes of one wave
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
+constexpr int kSpanBlocks = 16;                  // blocks whose logits one selection workgroup ranks
+constexpr int kSpanRows = kSpanBlocks * kTileRows;
+constexpr int kSelectThreads = 256;
+constexpr int kSelectPerThread = kSpanRows / kSelectThreads;
 // Strides (floats) of the accumulator tiles parked in LDS for the epilogue: token tile,
 // row tile of a wave, wave.  Modulo the 64 banks they are 16, 16 and 48.
 constexpr int kRedCt = 272, kRedTile = 4 * kRedCt + 16, kRedWave = 2 * kRedTile + 16;
@@ -53,29 +59,21 @@ struct TileGroup {
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* lm_W;                      // [V, n_vec]
-    const int32_t* offsets;                 // [G+1]   (grouped)
     const int32_t* rows;                    // [V]     (grouped)
     const struct TileGroup* table;          // [G]     (grouped) activated groups in working order
     const int32_t* n_union;                 // [1]     (grouped) how many
-    Cand* part;                             // [M, k, gridDim.x] published lists, entry-major
+    float* z;                               // [blocks, M, 128] out: logits of (block, token slot)
     unsigned int* next_block;               // block queue: zero before the launch
-    int M, V, G, k;
+    int M, V;
     int n_vec, n_chunks;
     int u_max;                              // capacity of the activated-group arrays
-    // Log-probability mode (Eq. 8 normalises per group, and a block is rows of one group):
-    // every block leaves, per token that selected its group, the k best of its rows by logit
-    // and the (max, sum of exp) of its logits, slot = the block's number in the working order.
-    Cand* blk_part;                         // [M, blk_stride, k]
-    float* blk_lse;                         // [M, blk_stride, 2]
-    int blk_stride;
 };
 
 struct TileLds {
-    int o_hbuf, o_lists, o_rowid, o_tokslot, o_scratch, o_ugroup, o_ustart, o_uend, o_uprefix,
-        o_umask, o_flags, total;
+    int o_hbuf, o_tokslot, o_scratch, o_ustart, o_uend, o_uprefix, o_umask, o_flags, total;
 };
 
-__host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
+__host__ __device__ inline TileLds tile_lds_layout(int u_max) {
     TileLds L;
     int off = 0;
     auto take = [&](size_t bytes) {
@@ -84,11 +82,8 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
         return at;
     };
     L.o_hbuf = take((size_t)2 * kHbBufVecs * sizeof(uint4));
-    L.o_lists = take((size_t)M * k * sizeof(Cand));
-    L.o_rowid = take(kTileRows * sizeof(int));
     L.o_tokslot = take(64 * sizeof(int));
     L.o_scratch = take((size_t)kTileWaves * kLinePairSlots * sizeof(uint4));
-    L.o_ugroup = take((size_t)u_max * sizeof(int));
     L.o_ustart = take((size_t)u_max * sizeof(int));
     L.o_uend = take((size_t)u_max * sizeof(int));
     L.o_uprefix = take((size_t)(u_max + 1) * sizeof(int));
@@ -96,104 +91,6 @@ __host__ __device__ inline TileLds tile_lds_layout(int M, int k, int u_max) {
     L.o_flags = take(16);
     L.total = off;
     return L;
-}
-
-// Merges a block's logits of one token (one per lane, padding = sentinel) into the
-// token's sorted list in LDS.  Only candidates that beat the list's k-th entry take part.
-// Every participant's new rank is counted directly: a candidate's rank is the number of
-// list entries and of other candidates that beat it, a list entry moves down by the number
-// of candidates that beat it.  Ranks are distinct, so all writes go to distinct slots.
-// keys: 128 wave-private 64-bit LDS words (ordering keys of the passing candidates, then of the list).
-__device__ __forceinline__ void tile_merge_token(Cand* list, int k, int lane, Cand c,
-                                                 unsigned long long* keys) {
-    const Cand tail = list[k - 1];                     // one address for all lanes: a broadcast
-    const bool pass = is_real(c) && better(c.v, c.id, tail.v, tail.id);
-    const unsigned long long b = __ballot(pass);
-    if (b == 0ull) return;                             // wave-uniform, the common case
-    Cand e = sentinel();
-    if (lane < k) e = list[lane];
-    const int np = __popcll(b);
-    const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
-    const unsigned long long ckey = cand_key(c.v, c.id), ekey = cand_key(e.v, e.id);
-    unsigned long long* ckeys = keys;
-    unsigned long long* lkeys = keys + kWave;
-    if (pass) ckeys[__popcll(b & ((1ull << lane) - 1ull))] = ckey;
-    if (lane < kr) lkeys[lane] = ekey;
-    int rc = count_above(lkeys, kr, ckey), re = lane;
-#pragma unroll 4
-    for (int j = 0; j < np; ++j) {                     // wave-uniform
-        const unsigned long long o = ckeys[j];
-        rc += o > ckey ? 1 : 0;
-        re += o > ekey ? 1 : 0;
-    }
-    if (pass && rc < k) list[rc] = c;
-    if (lane < kr && re < k) list[re] = e;
-}
-
-// The candidate an ordering key was made from (cand_key's inverse; -0.0 comes back as +0.0).
-__device__ __forceinline__ Cand cand_from_key(unsigned long long key) {
-    const unsigned o = (unsigned)(key >> 32);
-    Cand c;
-    c.v = __uint_as_float((o >> 31) ? (o ^ 0x80000000u) : ~o);
-    c.id = (int)~(unsigned)key;
-    return c;
-}
-
-// The two halves of a block's logits of one token (two candidates per lane) go into the
-// token's sorted list in LDS.  Candidates that do not beat the list's k-th entry drop out
-// first (the common case: none is left).  While the list is short, or early in the stream,
-// most candidates pass; the k-th largest of the lanes' better candidates then bounds the
-// result from below (k candidates reach it), and only candidates that reach it (ties kept)
-// stay.  The survivors' keys are compacted, one per lane; then one pass over them gives
-// every survivor its final position (list entries above it + survivors above it, two
-// ballots) and moves every list entry down by the number of survivors above it.
-// keys: 128 wave-private 64-bit LDS words, keys32: 64 more 32-bit words.
-__device__ __forceinline__ void tile_merge_pair(Cand* list, int k, int lane, Cand c0, Cand c1,
-                                                unsigned long long* keys, unsigned* keys32) {
-    const Cand tail = list[k - 1];                     // a broadcast
-    bool p0 = is_real(c0) && better(c0.v, c0.id, tail.v, tail.id);
-    bool p1 = is_real(c1) && better(c1.v, c1.id, tail.v, tail.id);
-    unsigned long long b0 = __ballot(p0), b1 = __ballot(p1);
-    if ((b0 | b1) == 0ull) return;                     // wave-uniform, the common case
-    if ((int)(__popcll(b0) + __popcll(b1)) > k + (k >> 1)) {  // wave-uniform
-        const unsigned o0 = p0 ? ord32(c0.v) : 0u, o1 = p1 ? ord32(c1.v) : 0u;
-        const unsigned tau = wave_kth_key(keys32, o0 > o1 ? o0 : o1, kWave, k, lane);
-        p0 = p0 && o0 >= tau;
-        p1 = p1 && o1 >= tau;
-        b0 = __ballot(p0);
-        b1 = __ballot(p1);
-    }
-    const int n0 = __popcll(b0), np = n0 + __popcll(b1);
-    if (np > kWave) {                                  // ties at the bound: one half at a time
-        if (!p0) c0 = sentinel();
-        if (!p1) c1 = sentinel();
-        tile_merge_token(list, k, lane, c0, keys);
-        tile_merge_token(list, k, lane, c1, keys);
-        return;
-    }
-    const unsigned long long below = (1ull << lane) - 1ull;
-    if (p0) keys[__popcll(b0 & below)] = cand_key(c0.v, c0.id);
-    if (p1) keys[n0 + __popcll(b1 & below)] = cand_key(c1.v, c1.id);
-    Cand e = sentinel();
-    if (lane < k) e = list[lane];
-    const int kr = __popcll(__ballot(lane < k && is_real(e)));   // real entries are a prefix
-    const bool is_e = lane < kr;
-    // lanes without an entry (a survivor) hold key 0, which is above nothing
-    const unsigned long long ekey = is_e ? cand_key(e.v, e.id) : 0ull;
-    const unsigned long long ckey = lane < np ? keys[lane] : 0ull;
-    int re = lane;
-    unsigned long long placed = 0ull;
-    for (int j = 0; j < np; ++j) {                     // wave-uniform
-        const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)ckey, j);
-        const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(ckey >> 32), j);
-        const unsigned long long kj = ((unsigned long long)hi << 32) | lo;
-        const bool e_above = ekey > kj;
-        const int rank = __popcll(__ballot(e_above)) + __popcll(__ballot(ckey > kj));
-        re += (is_e && !e_above) ? 1 : 0;              // keys are distinct
-        if (lane == rank) placed = kj;
-    }
-    if (is_e && re != lane && re < k) list[re] = e;
-    if (placed != 0ull && lane < k) list[lane] = cand_from_key(placed);
 }
 
 // One 512-column chunk of a block's K loop for NCT token tiles (a compile-time count: no
@@ -327,16 +224,13 @@ __device__ __forceinline__ void tile_k_loop(const TileParams& p, uint4 (&a)[kRin
     tile_chunk<DT, NCT, false>(p, p.n_chunks - 1, a, acc, wrow, hbuf, tokslot, n_t, my_slice);
 }
 
-template <int DT, bool LP = false>
+template <int DT>
 __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     extern __shared__ uint4 smem[];
     char* lds = reinterpret_cast<char*>(smem);
-    const TileLds lay = tile_lds_layout(p.M, p.k, p.u_max);
+    const TileLds lay = tile_lds_layout(p.u_max);
     uint4* hbuf = reinterpret_cast<uint4*>(lds + lay.o_hbuf);
-    Cand* lists = reinterpret_cast<Cand*>(lds + lay.o_lists);
-    int* rowid = reinterpret_cast<int*>(lds + lay.o_rowid);
     int* tokslot = reinterpret_cast<int*>(lds + lay.o_tokslot);
-    int* ugroup = reinterpret_cast<int*>(lds + lay.o_ugroup);
     int* ustart = reinterpret_cast<int*>(lds + lay.o_ustart);
     int* uend = reinterpret_cast<int*>(lds + lay.o_uend);
     int* uprefix = reinterpret_cast<int*>(lds + lay.o_uprefix);
@@ -346,15 +240,14 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int rg = wave / kTileSplit, kq = wave % kTileSplit;
-    const int M = p.M, k = p.k;
+    const int M = p.M;
     uint4* my_slice = reinterpret_cast<uint4*>(lds + lay.o_scratch) + (size_t)wave * kLinePairSlots;
 
-    // Blocks cost very different amounts (one to four token tiles), so they are handed
-    // out from a queue, most expensive groups first, rather than dealt round robin.
+    // Blocks cost different amounts (one to four token tiles), so they are handed out from
+    // a queue, most expensive groups first, rather than dealt round robin.
     unsigned int drawn = 0u;
     if (threadIdx.x == 0)
         drawn = __hip_atomic_fetch_add(p.next_block, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    for (int i = threadIdx.x; i < M * k; i += kTileBlock) lists[i] = sentinel();
     int total_blocks;
     if (dense) {
         total_blocks = (p.V + kTileRows - 1) / kTileRows;
@@ -368,7 +261,6 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             for (int u = lane; u < p.u_max; u += kWave) {
                 const TileGroup tg = p.table[u];
                 if (u < count) {
-                    ugroup[u] = tg.group;
                     umask[u] = tg.mask;
                     ustart[u] = tg.start;
                     uend[u] = tg.end;
@@ -403,8 +295,7 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         }
     };
     // This lane's four weight rows: row (lane / 8) of each 8-row octet o of the wave's 32
-    // rows (clamped inside the group; the duplicates are dropped when the candidates are
-    // formed).
+    // rows (clamped inside the group; the logits of the duplicates are never read).
     auto my_rows = [&](int first, int end, int (&rid)[4]) {
 #pragma unroll
         for (int o = 0; o < 4; ++o) {
@@ -443,15 +334,9 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
             drawn = __hip_atomic_fetch_add(p.next_block, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int n_t = __popcll(bm);
         const int n_ct = (n_t + 15) >> 4;
-        // token of every slot, and the vocabulary id of every row of the block
-        if (wave == 0) {
+        if (wave == 0) {                               // token of every slot
             const bool on = (bm >> lane) & 1ull;
             if (on) tokslot[__popcll(bm & ((1ull << lane) - 1ull))] = lane;
-        }
-        if (wave == 1 || wave == 2) {
-            const int j = (wave - 1) * kWave + lane;
-            const int idx = first + j;
-            rowid[j] = idx < end ? (dense ? idx : p.rows[idx]) : -1;
         }
         __syncthreads();
 
@@ -500,8 +385,9 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                         acc[t][ct];
         __syncthreads();
         // one wave per token slot, the block's rows in two halves of 64: lane = (row tile,
-        // row) -> 64 logits of the token
-        auto slot_logits = [&](int s, Cand (&cand)[2]) {
+        // row) -> 64 logits of the slot, 256 consecutive bytes of the block's logits
+        for (int s = wave; s < n_t; s += kTileWaves) {
+            float* dst = p.z + ((size_t)b * M + s) * kTileRows + lane;
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int tile = hf * 4 + (lane >> 4), row = lane & 15;   // row tile 0..7 of the block
@@ -511,52 +397,14 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 #pragma unroll
                 for (int q = 0; q < kTileSplit; ++q)
                     z += red[(w0 + q) * kRedWave + (tile & 1) * kRedTile + (s >> 4) * kRedCt + e];
-                cand[hf].v = z;
-                cand[hf].id = rowid[hf * kWave + lane];
-                if (cand[hf].id < 0) cand[hf] = sentinel();
+                dst[hf * kWave] = z;
             }
-        };
-        if (LP) {
-            // this block's share of the group's log-sum-exp for every token (a pass of its own:
-            // the merge below has no registers to spare), and fresh lists: the block's k best
-            // are its own (the tokens' LDS lists are scratch here)
-            for (int s = wave; s < n_t; s += kTileWaves) {
-                const int tok = tokslot[s];
-                Cand cand[2];
-                slot_logits(s, cand);
-                const float z0 = is_real(cand[0]) ? cand[0].v : -INFINITY;
-                const float z1 = is_real(cand[1]) ? cand[1].v : -INFINITY;
-                float wm = fmaxf(z0, z1);
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) wm = fmaxf(wm, __shfl_xor(wm, off));
-                const float tot = wave_sum(wm > -INFINITY ? expf(z0 - wm) + expf(z1 - wm) : 0.f);
-                if (lane < 2) p.blk_lse[uni(tok * p.blk_stride + b) * 2 + lane] = lane ? tot : wm;
-                if (lane < k) lists[tok * k + lane] = sentinel();
-            }
-        }
-        for (int s = wave; s < n_t; s += kTileWaves) {
-            const int tok = tokslot[s];
-            Cand cand[2];
-            slot_logits(s, cand);
-            tile_merge_pair(lists + (size_t)tok * k, k, lane, cand[0], cand[1],
-                            reinterpret_cast<unsigned long long*>(my_slice),
-                            reinterpret_cast<unsigned*>(my_slice) + 4 * kWave);
-            if (LP && lane < k)
-                p.blk_part[uni(tok * p.blk_stride + b) * k + lane] = lists[tok * k + lane];
         }
         __syncthreads();
         b = nb;
         first = nfirst;
         end = nend;
         bm = nbm;
-    }
-
-    if (LP) return;                                    // (every block has left its own lists)
-    // publish the workgroup's lists (all tokens; untouched ones are padding)
-    const int P = gridDim.x;
-    for (int i = threadIdx.x; i < M * k; i += kTileBlock) {
-        const Cand c = lists[i];
-        p.part[(size_t)i * P + blockIdx.x] = c;        // i = t*k + entry
     }
 }
 
@@ -565,7 +413,8 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 // (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at 8*(l/16));
 // the partial tiles are summed in wave order.  The workgroup that finishes last ranks
 // every token's scores by counting and writes the selection, the token mask of every
-// group and the ascending list of activated groups.
+// group, the table of activated groups in the order the tile kernel works through them,
+// and for every activated group the number of its first block in that order.
 struct GateSelParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* gate_W;                    // [G, n_vec]
@@ -576,14 +425,12 @@ struct GateSelParams {
     const int32_t* offsets;                 // [G+1] row ranges of the groups
     TileGroup* table;                       // [G] out: activated groups in working order
     int32_t* n_union;                       // [1]
+    int32_t* group_first_block;             // [G] out: first block of an activated group
     unsigned int* counter;                  // arrival counter, zero between calls
     int M, G, g, n_vec;
-    // log-probability mode (G <= 64, M * g <= kGateSelMaxPairs), else null:
-    int32_t* first_block;                   // [M, g] out: first block of the selected group
-    int32_t* block_count;                   // [M, g] out: how many blocks it has
     float* logp_sel;                        // [M, g] out: log p_router of the selected group
+                                            // (log-probability mode, G <= 64), else null
 };
-constexpr int kGateSelMaxPairs = 1024;
 
 __device__ __forceinline__ float load_score(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -598,8 +445,6 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ int order[kMaxG], nblk[kMaxG];
     __shared__ int is_last, ucount;
     __shared__ int off_lds[kMaxG + 1];
-    __shared__ int rank_of[kMaxG];
-    __shared__ int sel_lds[kGateSelMaxPairs];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     // the groups' row ranges travel with the first operand loads (requested here, put into LDS
@@ -686,10 +531,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             if (lane < p.G && rank < p.g) {
                 atomicOr(&mask[lane], 1ull << tm);
                 p.sel[tm * p.g + rank] = lane;
-                if (p.logp_sel) {
-                    p.logp_sel[tm * p.g + rank] = v - lse_s;
-                    sel_lds[tm * p.g + rank] = lane;
-                }
+                if (p.logp_sel) p.logp_sel[tm * p.g + rank] = v - lse_s;
             }
         }
     } else {
@@ -747,7 +589,6 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             }
             if (lane < count) {
                 order[rank] = g0;
-                rank_of[g0] = rank;
                 nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
             }
         }
@@ -761,7 +602,6 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                 rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
             }
             order[rank] = g0;
-            rank_of[g0] = rank;
             nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
         }
     }
@@ -781,45 +621,242 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                 tg.first_block = carry + incl - nb;
                 tg.mask = mask[g0];
                 p.table[r] = tg;
-            }
-            if (p.first_block && r < count) {
-                nblk[r] = carry + incl - nb;            // (now: blocks before it)
-                ulist[r] = nb;                          // (the list of activated groups is spent)
+                p.group_first_block[g0] = tg.first_block;
             }
             carry += __builtin_amdgcn_readlane(incl, 63);
         }
     }
-    if (p.first_block) {                               // block-uniform
-        __syncthreads();
-        for (int idx = threadIdx.x; idx < p.M * p.g; idx += kFusedBlock)
-        {
-            const int r = rank_of[sel_lds[idx]];
-            p.first_block[idx] = nblk[r];
-            p.block_count[idx] = ulist[r];
-        }
-    }
 }
 
-// Per token, merges the P published lists part[(t*k + i)*P + w] into the result.
-__global__ __launch_bounds__(256) void k_merge_published(const Cand* __restrict__ part, int P, int M,
-                                                         int k, int32_t* __restrict__ topk_ids,
-                                                         float* __restrict__ topk_logits,
-                                                         unsigned int* next_block) {
-    if (blockIdx.x == 0 && threadIdx.x == 0)           // the tile kernel's queue, for the next call
-        __hip_atomic_store(next_block, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __shared__ WaveScratch scratch_all[4];
+// Ranking behind k_tiles.  One workgroup per (token, span of kSpanBlocks blocks of one of the
+// groups the token selected; dense: of the vocabulary): grid = (token and group, span).  The span's logits (up to 2048, eight
+// per thread, with the rows' vocabulary ids) become 64-bit ordering keys, all distinct.  A
+// bound first: in every wave the k-th largest of the lanes' best keys (k keys of that wave
+// reach it), and the largest of the waves' bounds; keys that reach it are collected in LDS
+// (typically a few dozen) and ranked by counting, each thread one of them.  The list goes to
+// memory, the workgroup counts itself in on its token's counter, and the one that arrives
+// last merges the token's lists.  Log-probability mode (Eq. 8): a span also leaves the
+// (max, sum of exp) of its logits; the last workgroup combines them per group and adds
+// log p_router(n) - lse_n to the entries of group n's lists (inside a group the order by
+// logit is the order by log-probability).
+struct TileSelectParams {
+    const float* z;                         // [blocks, M, 128] what k_tiles left
+    const int32_t* sel;                     // [M, g] selected groups (grouped)
+    const int32_t* offsets;                 // [G+1]
+    const int32_t* rows;                    // [V]
+    const int32_t* group_first_block;       // [G] first block of an activated group
+    const unsigned long long* group_mask;   // [G] tokens that selected it
+    const float* logp_sel;                  // [M, g] log p_router (log-probability mode)
+    Cand* lists;                            // [M, list_stride, k] the spans' lists
+    unsigned long long* lse;                // [M, list_stride] the spans' (max, sum) pieces
+    unsigned int* arrivals;                 // [M] zero between calls
+    unsigned int* next_block;               // k_tiles' queue: left at zero for the next call
+    int32_t* topk_ids;                      // [M, k]
+    float* topk_out;                        // [M, k]
+    int M, V, g, k, list_stride;
+};
+
+template <bool DENSE, bool LP>
+__global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams p) {
+    constexpr int kWaves = kSelectThreads / kWave;
+    __shared__ __attribute__((aligned(16))) unsigned long long buf[kSpanRows];   // keys that reach the bound
+    __shared__ unsigned long long wkeys[kWaves][kWave];
+    __shared__ unsigned long long bound_w[kWaves];
+    __shared__ unsigned long long lse_w[kWaves];
+    __shared__ Cand list[kMaxK];
+    __shared__ int n_kept, is_last;
+    __shared__ WaveScratch merge_scratch;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int t = blockIdx.x * 4 + wave;
-    if (t >= M) return;                                // wave-uniform, no barriers below
-    const Cand* src = part + (size_t)t * k * P;
-    wave_merge_topk(
-        P, k, lane, scratch_all + wave,
-        [&](int l, int i) { return src[(size_t)i * P + l]; },
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int k = p.k;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+        __hip_atomic_store(p.next_block, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) n_kept = 0;
+    if ((int)threadIdx.x < k) list[threadIdx.x] = sentinel();
+
+    // where the span is: token, rows [start, start + n) of the row index (dense: of the
+    // vocabulary), its first block, the token's slot in those blocks, its list among the
+    // token's lists, and how many lists the token has in all
+    int t, start, n, first_block, slot, my_list, n_lists;
+    int span_base = 0, span_count = 0;                 // (LP: lane j = the token's j-th group)
+    const int span = blockIdx.y;
+    if (DENSE) {
+        t = blockIdx.x;
+        start = span * kSpanRows;
+        n = p.V - start < kSpanRows ? p.V - start : kSpanRows;
+        first_block = span * kSpanBlocks;
+        slot = t;
+        my_list = span;
+        n_lists = gridDim.y;
+    } else {
+        t = blockIdx.x / p.g;
+        const int j = blockIdx.x - t * p.g;
+        // every wave on its own: the token's groups, one per lane; a group has one span per
+        // 2048 rows and at least one, and the spans' lists are numbered group by group
+        int carry = 0, o0 = 0, o1 = 0, fb = 0, spans_j = 0, base_j = 0;
+        unsigned long long mk = 0ull;
+        for (int base = 0; base < p.g; base += kWave) {    // wave-uniform
+            const int jj = base + lane;
+            int lo = 0, hi = 0, gfb = 0, spans = 0;
+            unsigned long long gm = 0ull;
+            if (jj < p.g) {
+                const int grp = p.sel[t * p.g + jj];
+                lo = p.offsets[grp];
+                hi = p.offsets[grp + 1];
+                gfb = p.group_first_block[grp];
+                gm = p.group_mask[grp];
+                spans = (hi - lo + kSpanRows - 1) / kSpanRows;
+                if (spans < 1) spans = 1;
+            }
+            const int incl = wave_scan_inclusive(spans);
+            if (base == 0) {
+                span_base = incl - spans;
+                span_count = spans;
+            }
+            if (j >= base && j < base + kWave) {           // wave-uniform
+                const int src = j - base;
+                o0 = __builtin_amdgcn_readlane(lo, src);
+                o1 = __builtin_amdgcn_readlane(hi, src);
+                fb = __builtin_amdgcn_readlane(gfb, src);
+                spans_j = __builtin_amdgcn_readlane(spans, src);
+                base_j = carry + __builtin_amdgcn_readlane(incl - spans, src);
+                mk = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(gm >> 32), src) << 32) |
+                     (unsigned)__builtin_amdgcn_readlane((int)(unsigned)gm, src);
+            }
+            carry += __builtin_amdgcn_readlane(incl, kWave - 1);
+        }
+        if (span >= spans_j) return;                       // block-uniform: the group has fewer spans
+        start = o0 + span * kSpanRows;
+        n = o1 - start < kSpanRows ? o1 - start : kSpanRows;   // (0 for a group without rows)
+        first_block = fb + span * kSpanBlocks;
+        slot = __popcll(mk & ((1ull << t) - 1ull));
+        my_list = base_j + span;
+        n_lists = carry;
+    }
+
+    // the span's keys, eight per thread (absent: 0, which is below every key)
+    unsigned long long key[kSelectPerThread];
+    float zv[kSelectPerThread];
+#pragma unroll
+    for (int q = 0; q < kSelectPerThread; ++q) {
+        const int i = q * kSelectThreads + threadIdx.x;
+        key[q] = 0ull;
+        zv[q] = -INFINITY;
+        if (i < n) {
+            zv[q] = p.z[((size_t)(first_block + (i >> 7)) * p.M + slot) * kTileRows + (i & (kTileRows - 1))];
+            const int id = DENSE ? start + i : p.rows[start + i];
+            key[q] = cand_key(zv[q], id);
+        }
+    }
+    if (LP) {
+        // (max, sum of exp) of the span: per thread in row order, across the wave, then the
+        // waves in order
+        float m = -INFINITY, sum = 0.f;
+#pragma unroll
+        for (int q = 0; q < kSelectPerThread; ++q) {
+            const float nm = fmaxf(m, zv[q]);
+            if (nm > -INFINITY) sum = sum * expf(m - nm) + expf(zv[q] - nm);
+            m = nm;
+        }
+        const float wm = wave_max(m);
+        const float wsum = wave_sum(wm > -INFINITY ? sum * expf(m - wm) : 0.f);
+        if (lane == 0) lse_w[wave] = pack_lse(wm, wsum);
+    }
+    // the wave's bound: the k-th largest of its lanes' best keys, 0 if fewer than k lanes have one
+    unsigned long long best = key[0];
+#pragma unroll
+    for (int q = 1; q < kSelectPerThread; ++q) best = key[q] > best ? key[q] : best;
+    wkeys[wave][lane] = best;
+    {
+        const int above = count_above(wkeys[wave], kWave, best);
+        const unsigned long long at = __ballot(best != 0ull && above == k - 1);   // one lane or none
+        unsigned long long bound = 0ull;
+        if (at) {
+            const int src = __ffsll(at) - 1;
+            bound = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(best >> 32), src) << 32) |
+                    (unsigned)__builtin_amdgcn_readlane((int)(unsigned)best, src);
+        }
+        if (lane == 0) bound_w[wave] = bound;
+    }
+    __syncthreads();
+    unsigned long long bound = bound_w[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) bound = bound_w[w] > bound ? bound_w[w] : bound;
+    {
+        // the wave's keys that reach the bound, appended in one piece
+        int mine = 0;
+        unsigned long long pass[kSelectPerThread];
+#pragma unroll
+        for (int q = 0; q < kSelectPerThread; ++q) {
+            pass[q] = __ballot(key[q] != 0ull && key[q] >= bound);
+            mine += __popcll(pass[q]);
+        }
+        int at = 0;
+        if (lane == 0 && mine) at = atomicAdd(&n_kept, mine);
+        at = __builtin_amdgcn_readfirstlane(at);
+#pragma unroll
+        for (int q = 0; q < kSelectPerThread; ++q) {
+            if ((pass[q] >> lane) & 1ull) buf[at + __popcll(pass[q] & ((1ull << lane) - 1ull))] = key[q];
+            at += __popcll(pass[q]);
+        }
+    }
+    __syncthreads();
+    const int kept = uni(n_kept);
+    for (int i = threadIdx.x; i < kept; i += kSelectThreads) {
+        const unsigned long long mine = buf[i];
+        const int r = count_above(buf, kept, mine);
+        if (r < k) {
+            Cand c;
+            c.v = key_value(mine);
+            c.id = key_id(mine);
+            list[r] = c;
+        }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < k)
+        publish_cand(p.lists + ((size_t)t * p.list_stride + my_list) * k + threadIdx.x, list[threadIdx.x].v,
+                     list[threadIdx.x].id);
+    if (LP && threadIdx.x == 0) {
+        float m = -INFINITY, sum = 0.f;
+        for (int w = 0; w < kWaves; ++w) lse_take(m, sum, lse_w[w]);
+        __hip_atomic_store(p.lse + (size_t)t * p.list_stride + my_list, pack_lse(m, sum), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the list is out
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned int old = __hip_atomic_fetch_add(p.arrivals + t, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        is_last = old == (unsigned)(n_lists - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!uni(is_last) || wave != 0) return;            // the token's last span: its first wave merges
+
+    float* shift_of_list = reinterpret_cast<float*>(buf);      // (the keys are spent)
+    if (LP) {
+        // lane j: lse of the token's j-th group from its spans' pieces, in span order
+        if (lane < p.g) {
+            float m = -INFINITY, sum = 0.f;
+            for (int sp = 0; sp < span_count; ++sp)
+                lse_take(m, sum, __hip_atomic_load(p.lse + (size_t)t * p.list_stride + span_base + sp,
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            const float shift = p.logp_sel[t * p.g + lane] - (m + logf(sum));
+            for (int sp = 0; sp < span_count; ++sp) shift_of_list[span_base + sp] = shift;
+        }
+    }
+    const Cand* src = p.lists + (size_t)t * p.list_stride * k;
+    wave_merge_topk<true>(
+        n_lists, k, lane, &merge_scratch,
+        [&](int l, int i) {
+            Cand c = fetch_cand(src + (size_t)l * k + i);
+            if (LP && is_real(c)) c.v += shift_of_list[l];
+            return c;
+        },
         [&](int r, Cand c) {
-            topk_ids[(size_t)t * k + r] = c.id;
-            topk_logits[(size_t)t * k + r] = c.v;
+            p.topk_ids[(size_t)t * k + r] = c.id;
+            p.topk_out[(size_t)t * k + r] = c.v;
         });
+    if (lane == 0) __hip_atomic_store(p.arrivals + t, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace

@@ -67,7 +67,7 @@ def test_path_selection_covers_the_three_paths():
     assert path(True, 8, 4096, 32000, 0, 0, 10, BF16) == 1         # ... but a small vocabulary
     assert path(False, 64, 4160, 128256, 64, 8, 16, BF16) == 0     # H not a multiple of 512
     assert path(True, 1, 4096, 128256, 0, 0, 10, BF16) == 1
-    assert path(False, 64, 512, 1040, 8, 1, 64, BF16) == 0         # k = 64: general path
+    assert path(False, 64, 512, 1040, 8, 1, 64, BF16) == 2         # k = 64 on the tile path too
     assert path(False, 4, 256, 8192, 16, 2, 8, F32) == 1
     assert path(True, 64, 4096, 8192, 0, 0, 8, F32) == 0           # fp32 rows longer than 8 KB
     assert path(True, 64, 8192, 8192, 0, 0, 8, F32) == -1          # ... than the staged path's LDS

@@ -275,7 +275,8 @@ def test_every_path_is_exercised(coral):
     assert P(True, 16, 4096, 128256, 0, 0, 10, B) == 2              # dense, full size: tiles
     assert P(False, 64, 2048, 16 * 300, 16, 6, 20, B) == 2          # test_tile_path_shapes
     assert P(False, 64, 512, 16 * 300, 16, 6, 16, B) == 2
-    assert P(False, 64, 512, 8 * 130, 8, 1, 64, B) == 0             # extreme k: staged
+    assert P(False, 64, 512, 8 * 130, 8, 1, 64, B) == 2             # extreme k: tiles as well
+    assert P(False, 8, 4160, 32 * 203, 32, 4, 10, coral.CORAL_F16) == 0   # H = 4160: multi-kernel path
 
 
 @pytest.mark.parametrize("H,k", [(2048, 20), (512, 16), (1024, 21)])
