@@ -53,9 +53,10 @@ constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path'
 constexpr size_t kCtrlBytes = coral_ctrl::kWords * sizeof(unsigned int);   // control words at the start of the workspace
 static_assert(coral_ctrl::kLpGroupArrivalWords >= kWave, "one arrival counter per activated group");
 static_assert(coral_ctrl::kTileTokenArrivalWords >= kMaxM, "one arrival counter per token");
+static_assert(coral_ctrl::kGateSelectArrivalWords * 16 >= kMaxM, "one arrival counter per token tile");
 
 struct Layout {
-    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_table, tile_first_block, tile_z, tile_lists, tile_lse, total;
+    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_mask, tile_first_block, tile_z, tile_lists, tile_lse, total;
     int part_stride, tile_list_stride;
 };
 
@@ -97,7 +98,7 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces, bool til
     L.part = take(others * M * L.part_stride * k * sizeof(Cand));
     L.lse_part = take(others * M * L.part_stride * 2 * sizeof(float));     // log-probability mode
     L.logp_sel = take((size_t)M * (g ? g : 1) * sizeof(float));
-    L.tile_table = take((size_t)(G ? G : 1) * sizeof(TileGroup));
+    L.tile_mask = take((size_t)((kMaxM + 15) / 16) * (G ? G : 1) * sizeof(unsigned long long));
     L.tile_first_block = take((size_t)(G ? G : 1) * sizeof(int32_t));
     // a group's blocks and spans round up: V / 128 + G blocks and V / 2048 + g spans of one
     // token's groups at most (+ 1: V itself rounds up; a group without rows still has a span)
@@ -415,8 +416,7 @@ bool layout_has_tiles(int M, int H, int V, int G, int g, int k, coral_dtype dt) 
 // and selection kernel must already be enqueued (masks, table, first blocks; lp: log p_router
 // of the selection too).
 coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
-                          const coral_group_index* gi, const TileGroup* table,
-                          const int32_t* n_union, int M, int H, int V,
+                          const coral_group_index* gi, int M, int H, int V,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
                           float* topk_out, char* ws, const Layout& L, hipStream_t stream,
                           void* ev_before, void* ev_after, const int32_t* sel = nullptr, int g = 0,
@@ -428,11 +428,13 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.hidden = static_cast<const uint4*>(hidden);
     p.lm_W = static_cast<const uint4*>(lm_W);
     p.rows = gi ? gi->group_rows : nullptr;
-    p.table = table;
-    p.n_union = n_union;
+    p.offsets = gi ? gi->group_offsets : nullptr;
+    p.tile_mask = reinterpret_cast<const unsigned long long*>(ws + L.tile_mask);
+    p.group_mask = reinterpret_cast<unsigned long long*>(ws + L.mask);
+    p.group_first_block = reinterpret_cast<int32_t*>(ws + L.tile_first_block);
     p.z = reinterpret_cast<float*>(ws + L.tile_z);
     p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileQueue;
-    p.M = M; p.V = V;
+    p.M = M; p.V = V; p.G = G;
     p.n_vec = H / 8;
     p.n_chunks = (p.n_vec + kChunkVecs - 1) / kChunkVecs;
     p.u_max = u_max;
@@ -448,10 +450,10 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     TileSelectParams q = {};
     q.z = p.z;
     q.sel = sel;
-    q.offsets = gi ? gi->group_offsets : nullptr;
+    q.offsets = p.offsets;
     q.rows = p.rows;
-    q.group_first_block = reinterpret_cast<const int32_t*>(ws + L.tile_first_block);
-    q.group_mask = reinterpret_cast<const unsigned long long*>(ws + L.mask);
+    q.group_first_block = p.group_first_block;
+    q.group_mask = p.group_mask;
     q.logp_sel = reinterpret_cast<const float*>(ws + L.logp_sel);
     q.lists = reinterpret_cast<Cand*>(ws + L.tile_lists);
     q.lse = reinterpret_cast<unsigned long long*>(ws + L.tile_lse);
@@ -630,18 +632,16 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if (plan.path == 2) {
         GateSelParams q = {};
         q.hidden = ghid; q.gate_W = gw; q.bias = gate_bias; q.s = s; q.sel = sel;
-        TileGroup* table = reinterpret_cast<TileGroup*>(ws + L.tile_table);
-        q.group_mask = mask; q.offsets = gi->group_offsets; q.table = table; q.n_union = n_union;
-        q.counter = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kGateSelectArrival;
+        q.tile_mask = reinterpret_cast<unsigned long long*>(ws + L.tile_mask);
+        q.counters = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kGateSelectArrival;
         q.M = M; q.G = G; q.g = g; q.n_vec = n_vec;
-        q.group_first_block = reinterpret_cast<int32_t*>(ws + L.tile_first_block);
         if (logprob) q.logp_sel = reinterpret_cast<float*>(ws + L.logp_sel);
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
         typedef void (*gate_select_fn)(GateSelParams);
         const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
         hipLaunchKernelGGL(gs, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
-        st = launch_tiles(false, hidden, lm_W, gi, table, n_union, M, H, V, G, k, dt,
+        st = launch_tiles(false, hidden, lm_W, gi, M, H, V, G, k, dt,
                           plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
                           ev_after, sel, g, max_rows, logprob);
         if (st != CORAL_OK || !level) return st;
@@ -725,7 +725,7 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     if (plan.path < 0) return CORAL_ERR_UNSUPPORTED;
     // many tokens per row: the contraction is no longer cheap on the vector units
     if (plan.path == 2)
-        return launch_tiles(true, hidden, lm_W, nullptr, nullptr, nullptr, M, H, V, 0, k, dt,
+        return launch_tiles(true, hidden, lm_W, nullptr, M, H, V, 0, k, dt,
                             plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream,
                             ev_before, ev_after);
     if (plan.path == 1)

@@ -35,6 +35,7 @@ constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-colu
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
+constexpr int kGateExtractMax = 16;               // selection by rounds of a wave maximum up to this g
 constexpr int kSpanBlocks = 16;                  // blocks whose logits one selection workgroup ranks
 constexpr int kSpanRows = kSpanBlocks * kTileRows;
 constexpr int kSelectThreads = 256;
@@ -48,23 +49,17 @@ static_assert(kTileWaves * kRedWave * 4 <= 2 * kHbBufVecs * 16, "the parked tile
 // sink them to their first use, which defeats prefetching).
 __device__ __forceinline__ void keep_memory_order() { asm volatile("" ::: "memory"); }
 
-// One activated group as the gate kernel hands it to the tile kernel: a single read per
-// group instead of a chain of dependent ones (list -> masks and offsets -> prefix).
-struct TileGroup {
-    int32_t group, start, end;              // rows group_rows[start, end)
-    int32_t first_block;                    // blocks of the groups before it
-    unsigned long long mask;                // tokens that selected it
-};
-
 struct TileParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* lm_W;                      // [V, n_vec]
     const int32_t* rows;                    // [V]     (grouped)
-    const struct TileGroup* table;          // [G]     (grouped) activated groups in working order
-    const int32_t* n_union;                 // [1]     (grouped) how many
+    const int32_t* offsets;                 // [G+1]   (grouped)
+    const unsigned long long* tile_mask;    // [token tiles, G] (grouped) what k_gate_select left
+    unsigned long long* group_mask;         // [G] out (grouped): tokens that selected the group
+    int32_t* group_first_block;             // [G] out (grouped): first block of an activated group
     float* z;                               // [blocks, M, 128] out: logits of (block, token slot)
     unsigned int* next_block;               // block queue: zero before the launch
-    int M, V;
+    int M, V, G;
     int n_vec, n_chunks;
     int u_max;                              // capacity of the activated-group arrays
 };
@@ -254,23 +249,68 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         if (threadIdx.x == 0) flags[1] = (int)drawn;
         __syncthreads();
     } else {
+        // The activated groups in the order the workgroups go through them: most token
+        // tiles first (a block costs more the more tokens it serves), then ascending group id;
+        // each with its row range, token mask and the number of blocks before it.  Every
+        // workgroup builds the same table; the scratch arrays lie over the staging buffers,
+        // which are free until the first K loop.
+        unsigned long long* gmask = reinterpret_cast<unsigned long long*>(hbuf);      // [G]
+        int* off_lds = reinterpret_cast<int*>(gmask + p.G);                            // [G + 1]
+        int* ulist = off_lds + p.G + 1;                                                // [G]
+        int* order = ulist + p.G;                                                      // [G]
+        const int n_tt = (M + 15) / 16;
+        for (int g0 = threadIdx.x; g0 <= p.G; g0 += kTileBlock) {
+            off_lds[g0] = p.offsets[g0];
+            if (g0 < p.G) {
+                unsigned long long mk = 0ull;
+                for (int c = 0; c < n_tt; ++c) mk |= p.tile_mask[(size_t)c * p.G + g0];
+                gmask[g0] = mk;
+                if (blockIdx.x == 0) p.group_mask[g0] = mk;
+            }
+        }
+        __syncthreads();
         if (wave == 0) {
-            // the count and the table rows are requested together (rows past the count are
-            // stale but inside the table, which has u_max rows)
-            const int count = *p.n_union;
-            for (int u = lane; u < p.u_max; u += kWave) {
-                const TileGroup tg = p.table[u];
-                if (u < count) {
-                    umask[u] = tg.mask;
-                    ustart[u] = tg.start;
-                    uend[u] = tg.end;
-                    uprefix[u] = tg.first_block;
-                    if (u == count - 1)
-                        uprefix[count] = tg.first_block + (tg.end - tg.start + kTileRows - 1) / kTileRows;
+            int count = 0;
+            for (int base = 0; base < p.G; base += kWave) {    // wave-uniform
+                const int g0 = base + lane;
+                const bool on = g0 < p.G && gmask[g0] != 0ull;
+                const unsigned long long bal = __ballot(on);
+                if (on) ulist[count + __popcll(bal & ((1ull << lane) - 1ull))] = g0;
+                count += __popcll(bal);
+            }
+            if (count <= kWave) {
+                // a group has one to four token tiles (M <= 64): four ballots place it
+                const int g0 = lane < count ? ulist[lane] : 0;
+                const int w0 = lane < count ? (__popcll(gmask[g0]) + 15) >> 4 : 0;
+                int rank = 0;
+#pragma unroll
+                for (int w = 4; w >= 1; --w) {
+                    const unsigned long long bal = __ballot(w0 == w);
+                    if (w0 < w) rank += __popcll(bal);
+                    if (w0 == w) rank += __popcll(bal & ((1ull << lane) - 1ull));
                 }
+                if (lane < count) order[rank] = g0;
+            } else {
+                // (many groups: ascending id; the order only balances the load)
+                for (int r = lane; r < count; r += kWave) order[r] = ulist[r];
+            }
+            int carry = 0;
+            for (int base = 0; base < count; base += kWave) {  // wave-uniform
+                const int r = base + lane;
+                const int g0 = r < count ? order[r] : 0;
+                const int nb = r < count ? (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows : 0;
+                const int incl = wave_scan_inclusive(nb);
+                if (r < count) {
+                    ustart[r] = off_lds[g0];
+                    uend[r] = off_lds[g0 + 1];
+                    uprefix[r] = carry + incl - nb;
+                    umask[r] = gmask[g0];
+                    if (blockIdx.x == 0) p.group_first_block[g0] = carry + incl - nb;
+                }
+                carry += __builtin_amdgcn_readlane(incl, 63);
             }
             if (lane == 0) {                           // LDS is in order within a wave
-                if (count == 0) uprefix[0] = 0;
+                uprefix[count] = carry;
                 flags[0] = count;
                 flags[1] = (int)drawn;
             }
@@ -411,22 +451,19 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 // Gate and selection for the tile path (Eq. 7's W2 projection, then top-g): one workgroup
 // per tile of 16 groups x 16 tokens, the columns split over its 16 waves in steps of 32
 // (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at 8*(l/16));
-// the partial tiles are summed in wave order.  The workgroup that finishes last ranks
-// every token's scores by counting and writes the selection, the token mask of every
-// group, the table of activated groups in the order the tile kernel works through them,
-// and for every activated group the number of its first block in that order.
+// the partial tiles are summed in wave order.  The workgroups of one token tile count
+// themselves in on that tile's counter; the one that arrives last has all scores of its 16
+// tokens and ranks them by counting, one wave per token, writes the selection and, per
+// group, the mask of those of its tokens that selected it.  The tile kernel combines the
+// token tiles' masks itself, so the token tiles finish independently of each other.
 struct GateSelParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* gate_W;                    // [G, n_vec]
     const float* bias;                      // [G] or null
     float* s;                               // [M, G] scores (workspace)
     int32_t* sel;                           // [M, g]
-    unsigned long long* group_mask;         // [G]
-    const int32_t* offsets;                 // [G+1] row ranges of the groups
-    TileGroup* table;                       // [G] out: activated groups in working order
-    int32_t* n_union;                       // [1]
-    int32_t* group_first_block;             // [G] out: first block of an activated group
-    unsigned int* counter;                  // arrival counter, zero between calls
+    unsigned long long* tile_mask;          // [token tiles, G] out: tokens of the tile that selected the group
+    unsigned int* counters;                 // [token tiles] arrival counters, zero between calls
     int M, G, g, n_vec;
     float* logp_sel;                        // [M, g] out: log p_router of the selected group
                                             // (log-probability mode, G <= 64), else null
@@ -441,21 +478,12 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
     __shared__ unsigned long long mask[kMaxG];
     __shared__ unsigned long long sel_keys[kFusedWaves][kWave];
-    __shared__ int ulist[kMaxG];
-    __shared__ int order[kMaxG], nblk[kMaxG];
-    __shared__ int is_last, ucount;
-    __shared__ int off_lds[kMaxG + 1];
+    __shared__ int is_last;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    // the groups' row ranges travel with the first operand loads (requested here, put into LDS
-    // after the contraction): the workgroup that ends up building the table then has them
-    // without two more dependent trips to memory
-    int off_r0 = 0, off_r1 = 0;
-    if ((int)threadIdx.x <= p.G) off_r0 = p.offsets[threadIdx.x];
-    if ((int)threadIdx.x + kFusedBlock <= p.G) off_r1 = p.offsets[threadIdx.x + kFusedBlock];
-    const int n_tt = (p.M + 15) / 16;
+    const int n_tt = (p.M + 15) / 16, n_gt = (p.G + 15) / 16;
     const int gt = blockIdx.x / n_tt, tt = blockIdx.x - gt * n_tt;
-    float bias_r = 0.f;                                // (likewise: the bias of the score this thread will sum)
+    float bias_r = 0.f;                                // the bias of the score this thread will sum
     if (threadIdx.x < 256 && p.bias) {
         const int gn = gt * 16 + ((threadIdx.x >> 2) >> 4) * 4 + (threadIdx.x & 3);
         if (gn < p.G) bias_r = p.bias[gn];
@@ -482,8 +510,6 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
                                 mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave])), acc);
     }
     *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
-    if ((int)threadIdx.x <= p.G) off_lds[threadIdx.x] = off_r0;
-    if ((int)threadIdx.x + kFusedBlock <= p.G) off_lds[threadIdx.x + kFusedBlock] = off_r1;
     __syncthreads();
     if (threadIdx.x < 256) {
         const int e = threadIdx.x, l = e >> 2, i = e & 3;
@@ -498,33 +524,25 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the scores are out
     __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned int old = __hip_atomic_fetch_add(p.counter, 1u, __ATOMIC_RELAXED,
+        const unsigned int old = __hip_atomic_fetch_add(p.counters + tt, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);
-        is_last = old == gridDim.x - 1 ? 1 : 0;
+        is_last = old == (unsigned)(n_gt - 1) ? 1 : 0;
     }
     __syncthreads();
     if (!uni(is_last)) return;                         // block-uniform
 
+    // the token tile is complete: its tokens tt * 16 .. + 15
     for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) mask[g0] = 0ull;
     __syncthreads();
     if (p.G <= kWave) {
-        // one wave per token, group in lane; the scores of all the wave's tokens (up to four:
-        // M <= 64) are requested together, so that the selection costs one trip to memory
-        float sv[kMaxM / kFusedWaves];
-#pragma unroll
-        for (int j = 0; j < kMaxM / kFusedWaves; ++j) {
-            const int tm = wave + j * kFusedWaves;
-            sv[j] = (tm < p.M && lane < p.G) ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
-        }
-#pragma unroll
-        for (int j = 0; j < kMaxM / kFusedWaves; ++j) {
-            const int tm = wave + j * kFusedWaves;
-            if (tm >= p.M) break;                           // wave-uniform
-            float v = sv[j];
+        // one wave per token, group in lane
+        const int tm = tt * 16 + wave;
+        if (wave < 16 && tm < p.M) {                   // wave-uniform
+            float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
             if (!(v == v)) v = -INFINITY;
             const int rank = wave_rank(sel_keys[wave], v, lane, p.G, lane);
             float lse_s = 0.f;
-            if (p.logp_sel) {                               // the router's softmax over all G scores (Eq. 7)
+            if (p.logp_sel) {                          // the router's softmax over all G scores (Eq. 7)
                 const float smax = wave_max(v);
                 lse_s = smax + logf(wave_sum(lane < p.G ? expf(v - smax) : 0.f));
             }
@@ -535,9 +553,10 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
             }
         }
     } else {
-        for (int idx = threadIdx.x; idx < p.M * p.G; idx += kFusedBlock) {
-            const int tm = idx / p.G;
-            const int gn = idx - tm * p.G;
+        const int n_tok = p.M - tt * 16 < 16 ? p.M - tt * 16 : 16;
+        for (int idx = threadIdx.x; idx < n_tok * p.G; idx += kFusedBlock) {
+            const int tm = tt * 16 + idx / p.G;
+            const int gn = idx - (idx / p.G) * p.G;
             const float* row = p.s + (size_t)tm * p.G;
             float v = load_score(row + gn);
             if (!(v == v)) v = -INFINITY;
@@ -554,78 +573,9 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         }
     }
     __syncthreads();
-    for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) p.group_mask[g0] = mask[g0];
-    if (wave == 0) {
-        int count = 0;
-        for (int base = 0; base < p.G; base += kWave) {
-            const int g0 = base + lane;
-            const bool on = g0 < p.G && mask[g0] != 0ull;
-            const unsigned long long b = __ballot(on);
-            if (on) ulist[count + __popcll(b & ((1ull << lane) - 1ull))] = g0;
-            count += __popcll(b);
-        }
-        if (lane == 0) {
-            ucount = count;
-            *p.n_union = count;
-            __hip_atomic_store(p.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __syncthreads();
-    // The activated groups in the order the tile kernel works through them: most token
-    // tiles (16 tokens each) first, then ascending group id; placed by rank counting.  The
-    // table row of each carries its row range, token mask and the number of blocks before it.
-    const int count = uni(ucount);
-    if (count <= kWave) {
-        // a group has one to four token tiles (M <= 64): four ballots place it
-        if (wave == 0) {
-            const int g0 = lane < count ? ulist[lane] : 0;
-            const int w0 = lane < count ? (__popcll(mask[g0]) + 15) >> 4 : 0;
-            int rank = 0;
-#pragma unroll
-            for (int w = 4; w >= 1; --w) {
-                const unsigned long long b = __ballot(w0 == w);
-                if (w0 < w) rank += __popcll(b);
-                if (w0 == w) rank += __popcll(b & ((1ull << lane) - 1ull));
-            }
-            if (lane < count) {
-                order[rank] = g0;
-                nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
-            }
-        }
-    } else {
-        for (int u0 = threadIdx.x; u0 < count; u0 += kFusedBlock) {
-            const int g0 = ulist[u0];
-            const int w0 = (__popcll(mask[g0]) + 15) >> 4;
-            int rank = 0;
-            for (int v = 0; v < count; ++v) {
-                const int wv = (__popcll(mask[ulist[v]]) + 15) >> 4;
-                rank += (wv > w0 || (wv == w0 && v < u0)) ? 1 : 0;
-            }
-            order[rank] = g0;
-            nblk[rank] = (off_lds[g0 + 1] - off_lds[g0] + kTileRows - 1) / kTileRows;
-        }
-    }
-    __syncthreads();
-    if (wave == 0) {
-        int carry = 0;
-        for (int base = 0; base < count; base += kWave) {  // wave-uniform
-            const int r = base + lane;
-            const int nb = r < count ? nblk[r] : 0;
-            const int incl = wave_scan_inclusive(nb);
-            if (r < count) {
-                const int g0 = order[r];
-                TileGroup tg;
-                tg.group = g0;
-                tg.start = off_lds[g0];
-                tg.end = off_lds[g0 + 1];
-                tg.first_block = carry + incl - nb;
-                tg.mask = mask[g0];
-                p.table[r] = tg;
-                p.group_first_block[g0] = tg.first_block;
-            }
-            carry += __builtin_amdgcn_readlane(incl, 63);
-        }
-    }
+    for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) p.tile_mask[(size_t)tt * p.G + g0] = mask[g0];
+    if (threadIdx.x == 0)
+        __hip_atomic_store(p.counters + tt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Ranking behind k_tiles.  One workgroup per (token, span of kSpanBlocks blocks of one of the

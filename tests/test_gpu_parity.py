@@ -394,6 +394,30 @@ def test_equal_gate_scores_select_the_lower_group(coral):
         assert pos == sorted(pos)
 
 
+@pytest.mark.parametrize("g", [3, 20])
+def test_equal_gate_scores_on_the_tile_path(coral, g):
+    """The tile path's selection (rounds of a wave maximum up to 16 groups per token, rank
+    counting beyond): equal scores go to the lower group, for all 64 tokens."""
+    cfg = HeadConfig("gt_tiles", "bf16", 512, 32 * 140, 32, g, (64,), 16, 83, True, bias_std=1.0)
+    assert coral.coral_lmhead_path(False, 64, cfg.H, cfg.V, cfg.G, g, cfg.k, coral.CORAL_BF16) == 2
+    head = make_head(cfg)
+    head.gate_bias[4] += 2.0                               # (popular: many tokens select the three)
+    for twin in (9, 30):
+        head.gate_W[twin] = head.gate_W[4]
+        head.gate_bias[twin] = head.gate_bias[4]
+    dh = DeviceHead(coral, head)
+    hidden = make_hidden(cfg, 64)
+    out = run_grouped(coral, dh, hidden, g, cfg.k)
+    rep = check_grouped(dh, hidden, g, cfg.k, out)
+    assert rep.forced_tokens == 0                          # identical rows: identical fp32 scores
+    seen = 0
+    for row in out[2].tolist():                            # 4 before 9 before 30 whenever present
+        pos = [row.index(n) for n in (4, 9, 30) if n in row]
+        assert pos == sorted(pos)
+        seen += len(pos) > 1
+    assert seen > 0
+
+
 def test_two_runs_are_bit_identical(coral):
     cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
     dh = DeviceHead(coral, make_head(cfg))
