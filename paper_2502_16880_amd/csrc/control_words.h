@@ -13,22 +13,19 @@ struct Entry {
     int n_words;
 };
 
-constexpr int kWords = 192;                 // size of the control area in words (768 bytes)
+constexpr int kWords = 128;                 // size of the control area in words (512 bytes)
 constexpr int kFusedArrival = 0;            // single-launch path: workgroups that have published
 constexpr int kGateSelectArrival = 8;       // tile path: per token tile, k_gate_select workgroups that
 constexpr int kGateSelectArrivalWords = 4;  //   have stored their scores (at most 4 token tiles)
 constexpr int kTileQueue = 4;               // tile path: next block of k_tiles
 constexpr int kLpGroupArrival = 64;         // log-probability mode: one counter per activated
 constexpr int kLpGroupArrivalWords = 64;    //   group (at most 64 in the single-launch kernel)
-constexpr int kTileTokenArrival = 128;      // tile path: per token, spans of k_tile_select that
-constexpr int kTileTokenArrivalWords = 64;  //   have published their list (at most 64 tokens)
 
 constexpr Entry kMap[] = {
     {"fused_arrival", kFusedArrival, 1},
     {"gate_select_arrival", kGateSelectArrival, kGateSelectArrivalWords},
     {"tile_queue", kTileQueue, 1},
     {"logprob_group_arrival", kLpGroupArrival, kLpGroupArrivalWords},
-    {"tile_token_arrival", kTileTokenArrival, kTileTokenArrivalWords},
 };
 constexpr int kMapEntries = sizeof(kMap) / sizeof(kMap[0]);
 

@@ -52,12 +52,11 @@ inline bool is_16bit(coral_dtype dt) { return dt != CORAL_F32; }
 constexpr int kMaxWorkgroups = 256;    // upper bound of the single-launch path's grid
 constexpr size_t kCtrlBytes = coral_ctrl::kWords * sizeof(unsigned int);   // control words at the start of the workspace
 static_assert(coral_ctrl::kLpGroupArrivalWords >= kWave, "one arrival counter per activated group");
-static_assert(coral_ctrl::kTileTokenArrivalWords >= kMaxM, "one arrival counter per token");
 static_assert(coral_ctrl::kGateSelectArrivalWords * 16 >= kMaxM, "one arrival counter per token tile");
 
 struct Layout {
-    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_mask, tile_first_block, tile_z, tile_lists, tile_lse, total;
-    int part_stride, tile_list_stride;
+    size_t ctrl, fused_part, fused_lse, fused_glist, fused_pairs, s, sel, mask, union_list, n_union, chunk_base, slot_count, part, lse_part, logp_sel, tile_mask, tile_first_block, tile_z, tile_stat, total;
+    int part_stride;
 };
 
 bool sizes_ok(int M, int H, int V, int G, int g, int k) {
@@ -100,13 +99,10 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces, bool til
     L.logp_sel = take((size_t)M * (g ? g : 1) * sizeof(float));
     L.tile_mask = take((size_t)((kMaxM + 15) / 16) * (G ? G : 1) * sizeof(unsigned long long));
     L.tile_first_block = take((size_t)(G ? G : 1) * sizeof(int32_t));
-    // a group's blocks and spans round up: V / 128 + G blocks and V / 2048 + g spans of one
-    // token's groups at most (+ 1: V itself rounds up; a group without rows still has a span)
+    // a group's blocks round up: V / 128 + G blocks at most (+ 1: V itself rounds up)
     const size_t tile_blocks = (size_t)V / kTileRows + G + 1;
-    L.tile_list_stride = V / kSpanRows + g + 1;
     L.tile_z = take(tiles ? tile_blocks * M * kTileRows * sizeof(float) : 0);
-    L.tile_lists = take(tiles ? (size_t)M * L.tile_list_stride * k * sizeof(Cand) : 0);
-    L.tile_lse = take(tiles ? (size_t)M * L.tile_list_stride * sizeof(unsigned long long) : 0);
+    L.tile_stat = take(tiles ? tile_blocks * M * sizeof(float2) : 0);
     L.total = off;
     return L;
 }
@@ -354,6 +350,9 @@ bool tiles_fit(int M, int H, int V, int G, int g, int k, coral_dtype dt, int* u_
     if (um < 1) um = 1;
     const TileLds T = tile_lds_layout((int)um);
     if (T.total > kLdsLimit) return false;
+    // the ranking kernel keeps a few words per block of a token's groups in LDS
+    if ((long long)V / kTileRows + g + 1 > (1 << 16)) return false;
+    if (tile_select_lds_layout(g > 0 ? g : 1, V / kTileRows + g + 1).total > kLdsLimit) return false;
     *u_max_out = (int)um;
     *lds_out = T.total;
     return true;
@@ -420,7 +419,7 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,
                           float* topk_out, char* ws, const Layout& L, hipStream_t stream,
                           void* ev_before, void* ev_after, const int32_t* sel = nullptr, int g = 0,
-                          int max_group_rows = 0, bool logprob = false) {
+                          bool logprob = false) {
     int P = compute_units();
     if (P < 1) return CORAL_ERR_HIP;
     if (P > kMaxWorkgroups) P = kMaxWorkgroups;
@@ -433,6 +432,8 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     p.group_mask = reinterpret_cast<unsigned long long*>(ws + L.mask);
     p.group_first_block = reinterpret_cast<int32_t*>(ws + L.tile_first_block);
     p.z = reinterpret_cast<float*>(ws + L.tile_z);
+    p.stat = reinterpret_cast<float2*>(ws + L.tile_stat);
+    p.want_lse = logprob ? 1 : 0;
     p.next_block = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileQueue;
     p.M = M; p.V = V; p.G = G;
     p.n_vec = H / 8;
@@ -449,31 +450,24 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
 
     TileSelectParams q = {};
     q.z = p.z;
+    q.stat = p.stat;
     q.sel = sel;
     q.offsets = p.offsets;
     q.rows = p.rows;
     q.group_first_block = p.group_first_block;
     q.group_mask = p.group_mask;
     q.logp_sel = reinterpret_cast<const float*>(ws + L.logp_sel);
-    q.lists = reinterpret_cast<Cand*>(ws + L.tile_lists);
-    q.lse = reinterpret_cast<unsigned long long*>(ws + L.tile_lse);
-    q.arrivals = reinterpret_cast<unsigned int*>(ws + L.ctrl) + coral_ctrl::kTileTokenArrival;
     q.next_block = p.next_block;
     q.topk_ids = topk_ids;
     q.topk_out = topk_out;
     q.M = M; q.V = V; q.g = g; q.k = k;
-    q.list_stride = L.tile_list_stride;
-    if (dense) {
-        const int spans = (V + kSpanRows - 1) / kSpanRows;
-        hipLaunchKernelGGL((k_tile_select<true, false>), dim3(M, spans), dim3(kSelectThreads), 0, stream, q);
-    } else {
-        int spans = (max_group_rows + kSpanRows - 1) / kSpanRows;
-        if (spans < 1) spans = 1;
-        if (logprob)
-            hipLaunchKernelGGL((k_tile_select<false, true>), dim3(M * g, spans), dim3(kSelectThreads), 0, stream, q);
-        else
-            hipLaunchKernelGGL((k_tile_select<false, false>), dim3(M * g, spans), dim3(kSelectThreads), 0, stream, q);
-    }
+    q.max_blocks = V / kTileRows + g + 1;
+    const int select_lds = tile_select_lds_layout(dense ? 1 : g, q.max_blocks).total;
+    typedef void (*select_fn)(TileSelectParams);
+    const select_fn sf = dense ? k_tile_select<true, false>
+                               : logprob ? k_tile_select<false, true> : k_tile_select<false, false>;
+    if (!allow_lds(reinterpret_cast<const void*>(sf), select_lds)) return CORAL_ERR_HIP;
+    hipLaunchKernelGGL(sf, dim3(M), dim3(kSelectThreads), select_lds, stream, q);
     return launch_status();
 }
 
@@ -643,7 +637,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         if ((st = launch_status()) != CORAL_OK) return st;
         st = launch_tiles(false, hidden, lm_W, gi, M, H, V, G, k, dt,
                           plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,
-                          ev_after, sel, g, max_rows, logprob);
+                          ev_after, sel, g, logprob);
         if (st != CORAL_OK || !level) return st;
         hipLaunchKernelGGL(k_tree_expand, dim3(M), dim3(kWave), (size_t)M * k * sizeof(unsigned long long),
                            stream, level->parent_score, topk_ids, topk_logits, M, k, level->n_next,

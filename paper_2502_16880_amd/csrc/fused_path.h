@@ -332,9 +332,9 @@ __device__ __forceinline__ int wave_append(Cand* scratch, int* tag_scratch, int 
 // entries that reach it (ties kept); the few survivors are ranked by counting.  If a bound
 // does not exist (fewer than k lists, more than 256 lists) or too many survive (64), the
 // lists are streamed through a sorted register list instead.  No more than 64 candidates in
-// all are ranked directly; DIRECT (lists that are far away, in memory): no more than 256 are
-// fetched in one trip, bounded by a sample of themselves, and ranked.
-template <bool DIRECT = false, class Get, class Put>
+// all are ranked directly; DIRECT > 0 (lists that are far away, in memory): no more than
+// DIRECT per lane are fetched in one trip, bounded by a sample of themselves, and ranked.
+template <int DIRECT = 0, class Get, class Put>
 __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, WaveScratch* ws,
                                                 Get get, Put put) {
     constexpr int kCap = kWave;
@@ -355,31 +355,32 @@ __device__ __forceinline__ void wave_merge_topk(int n_lists, int k, int lane, Wa
         if (lane >= n_real && lane < k) put(lane, sentinel());
         return;
     }
-    if (DIRECT && n_lists * k <= 4 * kWave) {
-        // up to four candidates per lane, all requested at once; the k-th largest of the
+    if (DIRECT && n_lists * k <= DIRECT * kWave) {
+        // up to DIRECT candidates per lane, all requested at once; the k-th largest of the
         // lanes' best candidates (k lanes reach it) bounds the result's k-th entry, and what
         // reaches the bound is ranked by counting
+        constexpr int kPerLane = DIRECT > 0 ? DIRECT : 1;
         const int n_e = n_lists * k;
-        Cand c4[4];
+        Cand cd[kPerLane];
         unsigned sample = 0u;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kPerLane; ++u) {
             const int e = u * kWave + lane;
-            c4[u] = sentinel();
+            cd[u] = sentinel();
             if (e < n_e) {
                 const int l = div_small(e, inv_k);
-                c4[u] = get(l, e - l * k);
+                cd[u] = get(l, e - l * k);
             }
-            const unsigned o = cand_ord(c4[u]);
+            const unsigned o = cand_ord(cd[u]);
             sample = o > sample ? o : sample;
         }
         const unsigned bound = wave_kth_key(ws->keys32, sample, kWave, k, lane);
         int cnt = 0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < kPerLane; ++u)
             if (u * kWave < n_e)                       // uniform
-                cnt = wave_append(scratch, nullptr, cnt, kCap, is_real(c4[u]) && ord32(c4[u].v) >= bound,
-                                  c4[u], 0, lane);
+                cnt = wave_append(scratch, nullptr, cnt, kCap, is_real(cd[u]) && ord32(cd[u].v) >= bound,
+                                  cd[u], 0, lane);
         if (cnt <= kCap) {
             Cand s = sentinel();
             if (lane < cnt) s = scratch[lane];
@@ -1241,7 +1242,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                                                  __HIP_MEMORY_SCOPE_AGENT);
             }
             const Cand* src = p.part + (size_t)t * k * P + w0;
-            wave_merge_topk<true>(
+            wave_merge_topk<4>(
                 n_wg, k, lane, ws, [&](int l, int e) { return fetch_cand(src + (size_t)e * P + l); },
                 [&](int r, Cand c) { mine[r] = c; });
             float bm = -INFINITY, bs = 0.f;

@@ -475,7 +475,7 @@ __global__ __launch_bounds__(WAVES * kWave) void k_merge_logprob(const Cand* __r
         const float ws = wave_sum(wm > -INFINITY ? bs * expf(bm - wm) : 0.f);
         const float shift = logp_sel[m * g + i] - (wm + logf(ws));
         // the group's k best by logit, offset added
-        wave_merge_topk<true>(                          // (few slots: all candidates in one trip)
+        wave_merge_topk<4>(                          // (few slots: all candidates in one trip)
             n_slots, k, lane, &scratch[wave],
             [&](int l, int e) { return src[(size_t)(s0 + l) * k + e]; },
             [&](int r, Cand c) {

@@ -36,10 +36,6 @@ constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (p
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
 constexpr int kGateExtractMax = 16;               // selection by rounds of a wave maximum up to this g
-constexpr int kSpanBlocks = 16;                  // blocks whose logits one selection workgroup ranks
-constexpr int kSpanRows = kSpanBlocks * kTileRows;
-constexpr int kSelectThreads = 256;
-constexpr int kSelectPerThread = kSpanRows / kSelectThreads;
 // Strides (floats) of the accumulator tiles parked in LDS for the epilogue: token tile,
 // row tile of a wave, wave.  Modulo the 64 banks they are 16, 16 and 48.
 constexpr int kRedCt = 272, kRedTile = 4 * kRedCt + 16, kRedWave = 2 * kRedTile + 16;
@@ -58,6 +54,9 @@ struct TileParams {
     unsigned long long* group_mask;         // [G] out (grouped): tokens that selected the group
     int32_t* group_first_block;             // [G] out (grouped): first block of an activated group
     float* z;                               // [blocks, M, 128] out: logits of (block, token slot)
+    float2* stat;                           // [blocks, M] out: the slot's largest logit, and in the
+                                            // log-probability mode the sum of exp(z - largest)
+    int want_lse;
     unsigned int* next_block;               // block queue: zero before the launch
     int M, V, G;
     int n_vec, n_chunks;
@@ -426,8 +425,12 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
         __syncthreads();
         // one wave per token slot, the block's rows in two halves of 64: lane = (row tile,
         // row) -> 64 logits of the slot, 256 consecutive bytes of the block's logits
+        // and the slot's largest logit (rows past the group's end do not count): the ranking
+        // kernel reads the logits only of blocks whose largest can matter.  Log-probability
+        // mode: the sum of exp(z - largest) as well, the block's piece of the group's lse.
         for (int s = wave; s < n_t; s += kTileWaves) {
             float* dst = p.z + ((size_t)b * M + s) * kTileRows + lane;
+            float zs[2];
 #pragma unroll
             for (int hf = 0; hf < 2; ++hf) {
                 const int tile = hf * 4 + (lane >> 4), row = lane & 15;   // row tile 0..7 of the block
@@ -438,7 +441,13 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
                 for (int q = 0; q < kTileSplit; ++q)
                     z += red[(w0 + q) * kRedWave + (tile & 1) * kRedTile + (s >> 4) * kRedCt + e];
                 dst[hf * kWave] = z;
+                zs[hf] = first + hf * kWave + lane < end ? z : -INFINITY;
             }
+            const float wm = wave_max(fmaxf(zs[0], zs[1]));
+            float sum = 0.f;
+            if (p.want_lse)                            // block-uniform
+                sum = wave_sum(wm > -INFINITY ? expf(zs[0] - wm) + expf(zs[1] - wm) : 0.f);
+            if (lane == 0) p.stat[(size_t)b * M + s] = make_float2(wm, sum);
         }
         __syncthreads();
         b = nb;
@@ -578,235 +587,320 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         __hip_atomic_store(p.counters + tt, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Ranking behind k_tiles.  One workgroup per (token, span of kSpanBlocks blocks of one of the
-// groups the token selected; dense: of the vocabulary): grid = (token and group, span).  The span's logits (up to 2048, eight
-// per thread, with the rows' vocabulary ids) become 64-bit ordering keys, all distinct.  A
-// bound first: in every wave the k-th largest of the lanes' best keys (k keys of that wave
-// reach it), and the largest of the waves' bounds; keys that reach it are collected in LDS
-// (typically a few dozen) and ranked by counting, each thread one of them.  The list goes to
-// memory, the workgroup counts itself in on its token's counter, and the one that arrives
-// last merges the token's lists.  Log-probability mode (Eq. 8): a span also leaves the
-// (max, sum of exp) of its logits; the last workgroup combines them per group and adds
-// log p_router(n) - lse_n to the entries of group n's lists (inside a group the order by
-// logit is the order by log-probability).
+// Ranking behind k_tiles: one workgroup per token.  Its blocks are those of the groups it
+// selected (dense: all), and k_tiles left every block's largest logit.  The k-th largest of
+// these block maxima is a lower bound of the token's k-th logit (k blocks hold a logit that
+// reaches it), so only blocks whose largest reaches it can hold a result: about k of them,
+// out of 128 (wide draft tree) or a thousand (dense).  Their logits, 16 blocks (2048
+// candidates, eight per thread) at a time, are filtered by the bound and by the k-th entry
+// of the list so far, collected in LDS with the list, and ranked by counting (64-bit
+// ordering keys, all distinct).  Should more than 256 pass (equal logits, adversarial
+// inputs), the k-th largest of each wave's lanes' best keys and the largest of these four
+// is a second bound that leaves at most 4 (8 (k - 1) + 1).
+// Log-probability mode (Eq. 8): log p(x) = log p_router(n) + z[x] - lse_n; lse_n comes from
+// the (largest, sum of exp) pieces k_tiles left per block, combined in block order, and
+// bounds and keys are formed from z + (log p_router(n) - lse_n).
 struct TileSelectParams {
     const float* z;                         // [blocks, M, 128] what k_tiles left
+    const float2* stat;                     // [blocks, M]
     const int32_t* sel;                     // [M, g] selected groups (grouped)
     const int32_t* offsets;                 // [G+1]
     const int32_t* rows;                    // [V]
     const int32_t* group_first_block;       // [G] first block of an activated group
     const unsigned long long* group_mask;   // [G] tokens that selected it
     const float* logp_sel;                  // [M, g] log p_router (log-probability mode)
-    Cand* lists;                            // [M, list_stride, k] the spans' lists
-    unsigned long long* lse;                // [M, list_stride] the spans' (max, sum) pieces
-    unsigned int* arrivals;                 // [M] zero between calls
     unsigned int* next_block;               // k_tiles' queue: left at zero for the next call
     int32_t* topk_ids;                      // [M, k]
     float* topk_out;                        // [M, k]
-    int M, V, g, k, list_stride;
+    int M, V, g, k;
+    int max_blocks;                         // capacity of the per-block arrays in LDS
 };
+
+constexpr int kSelectThreads = 256;
+constexpr int kSelectWaves = kSelectThreads / kWave;
+constexpr int kSelectKeys = 8;                   // candidates per thread and chunk
+constexpr int kSelectChunkBlocks = kSelectKeys * kSelectThreads / kTileRows;
+constexpr int kKeptMax = kSelectKeys * kSelectThreads + kMaxK;   // a chunk's candidates and the list
+
+struct TileSelectLds {
+    int o_buf, o_list, o_wkeys, o_start, o_rows, o_fb, o_slot, o_nb, o_pre, o_shift, o_bst, o_binfo,
+        o_bval, o_qblk, o_qval, total;
+};
+__host__ __device__ inline TileSelectLds tile_select_lds_layout(int n_groups, int max_blocks) {
+    TileSelectLds L;
+    int off = 0;
+    auto take = [&](size_t bytes) {
+        int at = off;
+        off = (int)((off + bytes + 15) / 16 * 16);
+        return at;
+    };
+    L.o_buf = take((size_t)kKeptMax * sizeof(unsigned long long));
+    L.o_list = take((size_t)kMaxK * sizeof(unsigned long long));
+    L.o_wkeys = take((size_t)kSelectThreads * sizeof(unsigned long long));
+    L.o_start = take((size_t)n_groups * sizeof(int));
+    L.o_rows = take((size_t)n_groups * sizeof(int));
+    L.o_fb = take((size_t)n_groups * sizeof(int));
+    L.o_slot = take((size_t)n_groups * sizeof(int));
+    L.o_nb = take((size_t)n_groups * sizeof(int));
+    L.o_pre = take((size_t)(n_groups + 1) * sizeof(int));
+    L.o_shift = take((size_t)n_groups * sizeof(float));
+    L.o_bst = take((size_t)max_blocks * sizeof(float2));
+    L.o_binfo = take((size_t)max_blocks * sizeof(int));
+    L.o_bval = take((size_t)max_blocks * sizeof(unsigned));
+    L.o_qblk = take((size_t)max_blocks * sizeof(int));
+    L.o_qval = take((size_t)max_blocks * sizeof(unsigned));
+    L.total = off;
+    return L;
+}
 
 template <bool DENSE, bool LP>
 __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams p) {
-    constexpr int kWaves = kSelectThreads / kWave;
-    __shared__ __attribute__((aligned(16))) unsigned long long buf[kSpanRows];   // keys that reach the bound
-    __shared__ unsigned long long wkeys[kWaves][kWave];
-    __shared__ unsigned long long bound_w[kWaves];
-    __shared__ unsigned long long lse_w[kWaves];
-    __shared__ Cand list[kMaxK];
-    __shared__ int n_kept, is_last;
-    __shared__ WaveScratch merge_scratch;
+    extern __shared__ uint4 smem[];
+    char* lds = reinterpret_cast<char*>(smem);
+    const int n_groups = DENSE ? 1 : p.g;
+    const TileSelectLds lay = tile_select_lds_layout(n_groups, p.max_blocks);
+    unsigned long long* buf = reinterpret_cast<unsigned long long*>(lds + lay.o_buf);
+    unsigned long long* list = reinterpret_cast<unsigned long long*>(lds + lay.o_list);
+    unsigned long long* wkeys = reinterpret_cast<unsigned long long*>(lds + lay.o_wkeys);
+    int* g_start = reinterpret_cast<int*>(lds + lay.o_start);
+    int* g_rows = reinterpret_cast<int*>(lds + lay.o_rows);
+    int* g_fb = reinterpret_cast<int*>(lds + lay.o_fb);
+    int* g_slot = reinterpret_cast<int*>(lds + lay.o_slot);
+    int* g_nb = reinterpret_cast<int*>(lds + lay.o_nb);
+    int* g_pre = reinterpret_cast<int*>(lds + lay.o_pre);
+    float* g_shift = reinterpret_cast<float*>(lds + lay.o_shift);
+    float2* bst = reinterpret_cast<float2*>(lds + lay.o_bst);
+    int* binfo = reinterpret_cast<int*>(lds + lay.o_binfo);
+    int* qblk = reinterpret_cast<int*>(lds + lay.o_qblk);
+    unsigned* bval = reinterpret_cast<unsigned*>(lds + lay.o_bval);
+    unsigned* qval = reinterpret_cast<unsigned*>(lds + lay.o_qval);
+    __shared__ unsigned long long bound_w[kSelectWaves];
+    __shared__ unsigned tau_w[kSelectWaves];
+    __shared__ int n_kept, n_qual;
+
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int k = p.k;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    const int t = blockIdx.x, k = p.k;
+    if (blockIdx.x == 0 && threadIdx.x == 0)
         __hip_atomic_store(p.next_block, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (threadIdx.x == 0) n_kept = 0;
-    if ((int)threadIdx.x < k) list[threadIdx.x] = sentinel();
+    if (threadIdx.x == 0) {
+        n_kept = 0;
+        n_qual = 0;
+    }
 
-    // where the span is: token, rows [start, start + n) of the row index (dense: of the
-    // vocabulary), its first block, the token's slot in those blocks, its list among the
-    // token's lists, and how many lists the token has in all
-    int t, start, n, first_block, slot, my_list, n_lists;
-    int span_base = 0, span_count = 0;                 // (LP: lane j = the token's j-th group)
-    const int span = blockIdx.y;
+    // 1. the token's groups: row range, first block, the token's slot in the group's blocks
     if (DENSE) {
-        t = blockIdx.x;
-        start = span * kSpanRows;
-        n = p.V - start < kSpanRows ? p.V - start : kSpanRows;
-        first_block = span * kSpanBlocks;
-        slot = t;
-        my_list = span;
-        n_lists = gridDim.y;
+        if (threadIdx.x == 0) {
+            g_start[0] = 0;
+            g_rows[0] = p.V;
+            g_fb[0] = 0;
+            g_slot[0] = t;
+            g_nb[0] = (p.V + kTileRows - 1) / kTileRows;
+            g_shift[0] = 0.f;
+        }
     } else {
-        t = blockIdx.x / p.g;
-        const int j = blockIdx.x - t * p.g;
-        // every wave on its own: the token's groups, one per lane; a group has one span per
-        // 2048 rows and at least one, and the spans' lists are numbered group by group
-        int carry = 0, o0 = 0, o1 = 0, fb = 0, spans_j = 0, base_j = 0;
-        unsigned long long mk = 0ull;
-        for (int base = 0; base < p.g; base += kWave) {    // wave-uniform
-            const int jj = base + lane;
-            int lo = 0, hi = 0, gfb = 0, spans = 0;
-            unsigned long long gm = 0ull;
-            if (jj < p.g) {
-                const int grp = p.sel[t * p.g + jj];
-                lo = p.offsets[grp];
-                hi = p.offsets[grp + 1];
-                gfb = p.group_first_block[grp];
-                gm = p.group_mask[grp];
-                spans = (hi - lo + kSpanRows - 1) / kSpanRows;
-                if (spans < 1) spans = 1;
-            }
-            const int incl = wave_scan_inclusive(spans);
-            if (base == 0) {
-                span_base = incl - spans;
-                span_count = spans;
-            }
-            if (j >= base && j < base + kWave) {           // wave-uniform
-                const int src = j - base;
-                o0 = __builtin_amdgcn_readlane(lo, src);
-                o1 = __builtin_amdgcn_readlane(hi, src);
-                fb = __builtin_amdgcn_readlane(gfb, src);
-                spans_j = __builtin_amdgcn_readlane(spans, src);
-                base_j = carry + __builtin_amdgcn_readlane(incl - spans, src);
-                mk = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(gm >> 32), src) << 32) |
-                     (unsigned)__builtin_amdgcn_readlane((int)(unsigned)gm, src);
-            }
-            carry += __builtin_amdgcn_readlane(incl, kWave - 1);
+        for (int j = threadIdx.x; j < p.g; j += kSelectThreads) {
+            const int grp = p.sel[t * p.g + j];
+            const int lo = p.offsets[grp], hi = p.offsets[grp + 1];
+            const unsigned long long mk = p.group_mask[grp];
+            g_start[j] = lo;
+            g_rows[j] = hi - lo;
+            g_fb[j] = p.group_first_block[grp];
+            g_slot[j] = __popcll(mk & ((1ull << t) - 1ull));
+            g_nb[j] = (hi - lo + kTileRows - 1) / kTileRows;
+            g_shift[j] = 0.f;
         }
-        if (span >= spans_j) return;                       // block-uniform: the group has fewer spans
-        start = o0 + span * kSpanRows;
-        n = o1 - start < kSpanRows ? o1 - start : kSpanRows;   // (0 for a group without rows)
-        first_block = fb + span * kSpanBlocks;
-        slot = __popcll(mk & ((1ull << t) - 1ull));
-        my_list = base_j + span;
-        n_lists = carry;
-    }
-
-    // the span's keys, eight per thread (absent: 0, which is below every key)
-    unsigned long long key[kSelectPerThread];
-    float zv[kSelectPerThread];
-#pragma unroll
-    for (int q = 0; q < kSelectPerThread; ++q) {
-        const int i = q * kSelectThreads + threadIdx.x;
-        key[q] = 0ull;
-        zv[q] = -INFINITY;
-        if (i < n) {
-            zv[q] = p.z[((size_t)(first_block + (i >> 7)) * p.M + slot) * kTileRows + (i & (kTileRows - 1))];
-            const int id = DENSE ? start + i : p.rows[start + i];
-            key[q] = cand_key(zv[q], id);
-        }
-    }
-    if (LP) {
-        // (max, sum of exp) of the span: per thread in row order, across the wave, then the
-        // waves in order
-        float m = -INFINITY, sum = 0.f;
-#pragma unroll
-        for (int q = 0; q < kSelectPerThread; ++q) {
-            const float nm = fmaxf(m, zv[q]);
-            if (nm > -INFINITY) sum = sum * expf(m - nm) + expf(zv[q] - nm);
-            m = nm;
-        }
-        const float wm = wave_max(m);
-        const float wsum = wave_sum(wm > -INFINITY ? sum * expf(m - wm) : 0.f);
-        if (lane == 0) lse_w[wave] = pack_lse(wm, wsum);
-    }
-    // the wave's bound: the k-th largest of its lanes' best keys, 0 if fewer than k lanes have one
-    unsigned long long best = key[0];
-#pragma unroll
-    for (int q = 1; q < kSelectPerThread; ++q) best = key[q] > best ? key[q] : best;
-    wkeys[wave][lane] = best;
-    {
-        const int above = count_above(wkeys[wave], kWave, best);
-        const unsigned long long at = __ballot(best != 0ull && above == k - 1);   // one lane or none
-        unsigned long long bound = 0ull;
-        if (at) {
-            const int src = __ffsll(at) - 1;
-            bound = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(best >> 32), src) << 32) |
-                    (unsigned)__builtin_amdgcn_readlane((int)(unsigned)best, src);
-        }
-        if (lane == 0) bound_w[wave] = bound;
     }
     __syncthreads();
-    unsigned long long bound = bound_w[0];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) bound = bound_w[w] > bound ? bound_w[w] : bound;
-    {
-        // the wave's keys that reach the bound, appended in one piece
-        int mine = 0;
-        unsigned long long pass[kSelectPerThread];
-#pragma unroll
-        for (int q = 0; q < kSelectPerThread; ++q) {
-            pass[q] = __ballot(key[q] != 0ull && key[q] >= bound);
-            mine += __popcll(pass[q]);
+    if (wave == 0) {                                   // blocks before each group, in the token's order
+        int carry = 0;
+        for (int base = 0; base < n_groups; base += kWave) {   // wave-uniform
+            const int j = base + lane;
+            const int nb = j < n_groups ? g_nb[j] : 0;
+            const int incl = wave_scan_inclusive(nb);
+            if (j < n_groups) g_pre[j] = carry + incl - nb;
+            carry += __builtin_amdgcn_readlane(incl, kWave - 1);
         }
-        int at = 0;
-        if (lane == 0 && mine) at = atomicAdd(&n_kept, mine);
-        at = __builtin_amdgcn_readfirstlane(at);
+        if (lane == 0) g_pre[n_groups] = carry;
+    }
+    __syncthreads();
+    const int n_blocks = uni(g_pre[n_groups]);         // <= max_blocks: the groups are distinct
+
+    // 2. the blocks' statistics, one block per thread and trip
+    for (int i = threadIdx.x; i < n_blocks; i += kSelectThreads) {
+        int lo = 0, hi = n_groups;                     // the group j with g_pre[j] <= i < g_pre[j + 1]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (g_pre[mid] <= i) lo = mid; else hi = mid;
+        }
+        const int lb = i - g_pre[lo];
+        binfo[i] = (lo << 16) | lb;
+        bst[i] = p.stat[(size_t)(g_fb[lo] + lb) * p.M + g_slot[lo]];
+    }
+    __syncthreads();
+    if (LP) {
+        // lse of every group from its blocks' pieces, a wave per group (block in lane); the
+        // offset log p_router(n) - lse_n of its entries
+        for (int j = wave; j < n_groups; j += kSelectWaves) {          // wave-uniform
+            float m = -INFINITY, sum = 0.f;
+            for (int i = g_pre[j] + lane; i < g_pre[j + 1]; i += kWave) {
+                const float2 st = bst[i];
+                const float nm = fmaxf(m, st.x);
+                if (nm > -INFINITY) sum = sum * expf(m - nm) + st.y * expf(st.x - nm);
+                m = nm;
+            }
+            const float wm = wave_max(m);
+            const float wsum = wave_sum(wm > -INFINITY ? sum * expf(m - wm) : 0.f);
+            if (lane == 0) g_shift[j] = p.logp_sel[t * p.g + j] - (wm + logf(wsum));
+        }
+        __syncthreads();
+    }
+
+    // 3. the bound: a value that k block maxima reach.  A thread's best over its candidates
+    // (every 256th), the k-th largest of a wave's 64 bests (k threads, so k blocks reach it;
+    // 0 if fewer than k threads have one), the largest of the waves' values; blocks that
+    // reach it are the next round's candidates.  With one candidate per thread the bound
+    // leaves between k and 4 k blocks; with more (the dense head's thousand blocks) a second
+    // and third round tighten it.
+    for (int i = threadIdx.x; i < n_blocks; i += kSelectThreads)
+        bval[i] = ord32(bst[i].x + g_shift[binfo[i] >> 16]);
+    __syncthreads();
+    unsigned* keys32 = reinterpret_cast<unsigned*>(wkeys) + wave * kWave;
+    unsigned tau = 0u;
+    int n_q = n_blocks;
+    {
+        int* src_i = binfo;
+        unsigned* src_v = bval;
+        int* dst_i = qblk;
+        unsigned* dst_v = qval;
+        for (int round = 0; round < 3; ++round) {      // block-uniform
+            unsigned best = 0u;
+            for (int i = threadIdx.x; i < n_q; i += kSelectThreads) best = src_v[i] > best ? src_v[i] : best;
+            const unsigned kth = wave_kth_key(keys32, best, kWave, k, lane);
+            if (lane == 0) tau_w[wave] = kth;
+            __syncthreads();
+            tau = tau_w[0];
 #pragma unroll
-        for (int q = 0; q < kSelectPerThread; ++q) {
+            for (int w = 1; w < kSelectWaves; ++w) tau = tau_w[w] > tau ? tau_w[w] : tau;
+            for (int base = 0; base < n_q; base += kSelectThreads) {   // block-uniform
+                const int i = base + threadIdx.x;
+                const bool on = i < n_q && src_v[i] >= tau;
+                const unsigned long long bal = __ballot(on);
+                int at = 0;
+                if (lane == 0 && bal) at = atomicAdd(&n_qual, __popcll(bal));
+                at = __builtin_amdgcn_readfirstlane(at) + __popcll(bal & ((1ull << lane) - 1ull));
+                if (on) {
+                    dst_i[at] = src_i[i];
+                    dst_v[at] = src_v[i];
+                }
+            }
+            __syncthreads();
+            const bool tight = n_q <= kSelectThreads;
+            n_q = uni(n_qual);
+            __syncthreads();                           // (everyone has the count)
+            if (threadIdx.x == 0) n_qual = 0;
+            int* ti = src_i; src_i = dst_i; dst_i = ti;
+            unsigned* tv = src_v; src_v = dst_v; dst_v = tv;
+            if (tight) break;
+        }
+        qblk = src_i;                                  // the blocks whose largest reaches the bound
+    }
+
+    // 5. their candidates, 16 blocks at a time, merged with the list so far (buf[0, have))
+    int have = 0;                                      // entries of the list so far
+    unsigned long long list_kth = 0ull;                // its k-th key once it has k entries
+    for (int base = 0; base < n_q; base += kSelectChunkBlocks) {       // block-uniform
+        unsigned long long key[kSelectKeys];
+        {
+            float zv[kSelectKeys];
+            int idv[kSelectKeys], grp[kSelectKeys];
+            bool valid[kSelectKeys];
+#pragma unroll
+            for (int q = 0; q < kSelectKeys; ++q) {
+                const int e = q * kSelectThreads + threadIdx.x;
+                const int qb = base + (e >> 7), r = e & (kTileRows - 1);
+                const int info = qblk[qb < n_q ? qb : n_q - 1];
+                const int j = info >> 16, lb = info & 0xffff;
+                const int row = lb * kTileRows + r, n_rows = g_rows[j];
+                valid[q] = qb < n_q && row < n_rows;
+                grp[q] = j;
+                zv[q] = p.z[((size_t)(g_fb[j] + lb) * p.M + g_slot[j]) * kTileRows + r];
+                idv[q] = DENSE ? row : p.rows[g_start[j] + (row < n_rows ? row : n_rows - 1)];
+            }
+#pragma unroll
+            for (int q = 0; q < kSelectKeys; ++q) {
+                const float v = LP ? zv[q] + g_shift[grp[q]] : zv[q];
+                const unsigned long long kk = cand_key(v, idv[q]);
+                key[q] = valid[q] && ord32(v) >= tau && kk > list_kth ? kk : 0ull;
+            }
+        }
+        unsigned long long pass[kSelectKeys];
+        auto reserve = [&](unsigned long long bnd) {
+            int mine = 0;
+#pragma unroll
+            for (int q = 0; q < kSelectKeys; ++q) {
+                pass[q] = __ballot(key[q] != 0ull && key[q] >= bnd);
+                mine += __popcll(pass[q]);
+            }
+            int at = 0;
+            if (lane == 0 && mine) at = atomicAdd(&n_kept, mine);
+            return __builtin_amdgcn_readfirstlane(at);
+        };
+        int at = reserve(0ull);                        // (n_kept = have: the list comes first)
+        __syncthreads();
+        const int passed = uni(n_kept) - have;
+        if (passed > kSelectThreads) {                 // block-uniform: too many for one key per thread
+            unsigned long long best = key[0];
+#pragma unroll
+            for (int q = 1; q < kSelectKeys; ++q) best = key[q] > best ? key[q] : best;
+            unsigned long long* wk = wkeys + wave * kWave;
+            wk[lane] = best;
+            const int above = count_above(wk, kWave, best);
+            const unsigned long long hit = __ballot(best != 0ull && above == k - 1);   // one lane or none
+            unsigned long long bnd = 0ull;
+            if (hit) {
+                const int src = __ffsll((long long)hit) - 1;
+                bnd = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(best >> 32), src) << 32) |
+                      (unsigned)__builtin_amdgcn_readlane((int)(unsigned)best, src);
+            }
+            if (lane == 0) bound_w[wave] = bnd;
+            __syncthreads();                           // (every wave has read the count by now)
+            if (threadIdx.x == 0) n_kept = have;
+            __syncthreads();
+            bnd = bound_w[0];
+#pragma unroll
+            for (int w = 1; w < kSelectWaves; ++w) bnd = bound_w[w] > bnd ? bound_w[w] : bnd;
+            at = reserve(bnd);
+            __syncthreads();
+        }
+#pragma unroll
+        for (int q = 0; q < kSelectKeys; ++q) {
             if ((pass[q] >> lane) & 1ull) buf[at + __popcll(pass[q] & ((1ull << lane) - 1ull))] = key[q];
             at += __popcll(pass[q]);
         }
-    }
-    __syncthreads();
-    const int kept = uni(n_kept);
-    for (int i = threadIdx.x; i < kept; i += kSelectThreads) {
-        const unsigned long long mine = buf[i];
-        const int r = count_above(buf, kept, mine);
-        if (r < k) {
-            Cand c;
-            c.v = key_value(mine);
-            c.id = key_id(mine);
-            list[r] = c;
+        __syncthreads();
+        const int kept = uni(n_kept);
+        for (int i = threadIdx.x; i < kept; i += kSelectThreads) {
+            const unsigned long long mine = buf[i];
+            const int r = count_above(buf, kept, mine);
+            if (r < k) list[r] = mine;
         }
+        __syncthreads();
+        have = kept < k ? kept : k;
+        if ((int)threadIdx.x < have) buf[threadIdx.x] = list[threadIdx.x];
+        if (threadIdx.x == 0) n_kept = have;
+        list_kth = have == k ? list[k - 1] : 0ull;
+        __syncthreads();
     }
-    __syncthreads();
-    if ((int)threadIdx.x < k)
-        publish_cand(p.lists + ((size_t)t * p.list_stride + my_list) * k + threadIdx.x, list[threadIdx.x].v,
-                     list[threadIdx.x].id);
-    if (LP && threadIdx.x == 0) {
-        float m = -INFINITY, sum = 0.f;
-        for (int w = 0; w < kWaves; ++w) lse_take(m, sum, lse_w[w]);
-        __hip_atomic_store(p.lse + (size_t)t * p.list_stride + my_list, pack_lse(m, sum), __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the list is out
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int old = __hip_atomic_fetch_add(p.arrivals + t, 1u, __ATOMIC_RELAXED,
-                                                        __HIP_MEMORY_SCOPE_AGENT);
-        is_last = old == (unsigned)(n_lists - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!uni(is_last) || wave != 0) return;            // the token's last span: its first wave merges
-
-    float* shift_of_list = reinterpret_cast<float*>(buf);      // (the keys are spent)
-    if (LP) {
-        // lane j: lse of the token's j-th group from its spans' pieces, in span order
-        if (lane < p.g) {
-            float m = -INFINITY, sum = 0.f;
-            for (int sp = 0; sp < span_count; ++sp)
-                lse_take(m, sum, __hip_atomic_load(p.lse + (size_t)t * p.list_stride + span_base + sp,
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            const float shift = p.logp_sel[t * p.g + lane] - (m + logf(sum));
-            for (int sp = 0; sp < span_count; ++sp) shift_of_list[span_base + sp] = shift;
+    if ((int)threadIdx.x < k) {
+        Cand c = sentinel();
+        if ((int)threadIdx.x < have) {
+            c.v = key_value(buf[threadIdx.x]);
+            c.id = key_id(buf[threadIdx.x]);
         }
+        p.topk_ids[(size_t)t * k + threadIdx.x] = c.id;
+        p.topk_out[(size_t)t * k + threadIdx.x] = c.v;
     }
-    const Cand* src = p.lists + (size_t)t * p.list_stride * k;
-    wave_merge_topk<true>(
-        n_lists, k, lane, &merge_scratch,
-        [&](int l, int i) {
-            Cand c = fetch_cand(src + (size_t)l * k + i);
-            if (LP && is_real(c)) c.v += shift_of_list[l];
-            return c;
-        },
-        [&](int r, Cand c) {
-            p.topk_ids[(size_t)t * k + r] = c.id;
-            p.topk_out[(size_t)t * k + r] = c.v;
-        });
-    if (lane == 0) __hip_atomic_store(p.arrivals + t, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 }  // namespace

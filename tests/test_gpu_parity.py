@@ -418,6 +418,28 @@ def test_equal_gate_scores_on_the_tile_path(coral, g):
     assert seen > 0
 
 
+def test_equal_logits_on_the_tile_path(coral):
+    """All-zero hidden vectors: every logit is 0.0, so every block's largest logit reaches the
+    bound, all 2048 candidates of the first chunk pass it (more than one per thread: the
+    second bound from the waves' best keys takes over) and every later candidate loses to the
+    list by its id.  Dense (k = 64, a thousand blocks per token) and grouped (the gate sees
+    only its bias: all 64 tokens select the same groups, four token tiles each)."""
+    cfg = HeadConfig("dense_zero", "bf16", 512, 65536, 1, 1, (8,), 64, 131, False)
+    assert coral.coral_lmhead_path(True, 8, cfg.H, cfg.V, 0, 0, cfg.k, coral.CORAL_BF16) == 2
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = np.zeros_like(make_hidden(cfg, 8))
+    ids, z = run_dense(coral, dh, hidden, cfg.k)
+    assert (ids == np.arange(cfg.k)[None, :]).all() and (z == 0.0).all()
+    check_dense(dh, hidden, cfg.k, (ids, z))
+    wide = CONFIGS["wide_tree"].scaled(V=64 * 126)
+    assert coral.coral_lmhead_path(False, 64, wide.H, wide.V, wide.G, wide.g, wide.k, coral.CORAL_BF16) == 2
+    dh = DeviceHead(coral, make_head(wide))
+    hidden = np.zeros_like(make_hidden(wide, 64))
+    out = run_grouped(coral, dh, hidden, wide.g, wide.k)
+    assert (out[1] == 0.0).all() and (out[2] == out[2][0]).all()
+    check_grouped(dh, hidden, wide.g, wide.k, out)
+
+
 def test_two_runs_are_bit_identical(coral):
     cfg = CONFIGS["llama3_8b"].scaled(V=32 * 203)
     dh = DeviceHead(coral, make_head(cfg))
