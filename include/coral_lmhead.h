@@ -109,7 +109,7 @@ int coral_lmhead_path(int dense, int M, int H, int V, int G, int g, int k, coral
 /*
  * The same for coral_lmhead_grouped_logprob (Eq. 8's output): 1 = single-launch kernel
  * (at most 64 activated groups, min(M*g, G) <= 64, g <= 16, and its LDS plan fits),
- * 2 = matrix-core tile path (where that path's conditions hold, G <= 64 and M*g <= 1024),
+ * 2 = matrix-core tile path (where that path's conditions hold and G <= 64),
  * 0 = staged path, -1 = sizes not supported.  Host-only.
  */
 int coral_lmhead_logprob_path(int M, int H, int V, int G, int g, int k, coral_dtype dt);
@@ -141,7 +141,9 @@ coral_status coral_lmhead_workspace_init(void *workspace, size_t workspace_bytes
  *   output   = the k largest z[m,.] among those rows, best first; equal logits:
  *              lower vocabulary id first
  * Weight rows of a group selected by several tokens are read once for all of
- * them.  The logits row is never written to memory.
+ * them.  The logits row is never written to memory; on the tile path (see
+ * coral_lmhead_path) the logits of the activated rows, for the tokens that
+ * selected them, pass through the workspace between that path's kernels.
  *
  *   hidden      [device] [M,H]  draft hidden states
  *   gate_W      [device] [G,H]  router projection (paper's W2)
