@@ -840,6 +840,20 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
     p.n_vec = H / (w16 ? 8 : 4);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     typedef void (*premix_fn)(PremixParams);
+    if (w16 && M >= 4 && M <= 64 && H % (kPremixChunkVecs * 8) == 0 &&
+        H / (kPremixChunkVecs * 8) <= kPremixMaxChunks) {     // matrix cores, tokens staged in chunks
+        typedef void (*wide_fn)(PremixParams);
+        const int n_ct = (M + 15) / 16;
+        const bool f16 = dt == CORAL_F16;
+        const wide_fn wf = n_ct == 1 ? (f16 ? k_premix_wide<kF16, 1> : k_premix_wide<kBF16, 1>)
+                         : n_ct == 2 ? (f16 ? k_premix_wide<kF16, 2> : k_premix_wide<kBF16, 2>)
+                         : n_ct == 3 ? (f16 ? k_premix_wide<kF16, 3> : k_premix_wide<kBF16, 3>)
+                                     : (f16 ? k_premix_wide<kF16, 4> : k_premix_wide<kBF16, 4>);
+        const int lds = (int)premix_wide_lds_bytes();
+        if (!allow_lds(reinterpret_cast<const void*>(wf), lds)) return CORAL_ERR_HIP;
+        hipLaunchKernelGGL(wf, dim3(H / 16), dim3(kPremixWideBlock), lds, stream, p);
+        return launch_status();
+    }
     if (w16 && H % 64 == 0 && M >= 4) {                       // matrix cores
         int tok = M < kPremixTileTok ? M : kPremixTileTok;
         while (tok > 4 && premix_mfma_lds_bytes(tok, p.n_vec) > (size_t)kLdsLimit) --tok;

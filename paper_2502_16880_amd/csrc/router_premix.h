@@ -229,4 +229,122 @@ __global__ __launch_bounds__(kBlock) void k_premix_mfma(PremixParams p) {
     }
 }
 
+// More than 16 tokens: the token vectors no longer fit LDS whole, so they are staged in
+// 512-column chunks for all token tiles at once (two buffers), and a workgroup of eight waves
+// owns 16 output features: wave w takes the 64 columns w*64.. of every chunk, i.e. one
+// 128-byte line of each of the 16 rows per chunk, and requests all its lines up front (the
+// whole of W1 is in flight in one round).  A line pair's operands serve every token tile.
+// A later chunk's token vectors are requested at the top of a chunk and written to a free
+// buffer at its end.  From four tokens on; bf16 / fp16, H a multiple of 512, at most 8 chunks.
+constexpr int kPremixWideWaves = 8;
+constexpr int kPremixWideBlock = kPremixWideWaves * kWave;
+constexpr int kPremixChunkVecs = 64;             // 16-byte vectors per 512-column chunk
+constexpr int kPremixMaxChunks = 8;
+constexpr int kPremixHbStride = kPremixChunkVecs + 1;            // padded rows: conflict-free B reads
+constexpr int kPremixHbVecs = 64 * kPremixHbStride;              // one staging buffer: 64 token slots
+
+__host__ __device__ inline size_t premix_wide_lds_bytes() {
+    return ((size_t)2 * kPremixHbVecs + (size_t)kPremixWideWaves * kLinePairSlots) * sizeof(uint4);
+}
+
+template <int DT, int NCT>
+__global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p) {
+    // NB staging buffers of 16 NCT token slots, chunks staged NB - 1 ahead.  (With few tokens
+    // the space would hold more buffers; staging further ahead measured no faster.)
+    constexpr int NB = 2;
+    constexpr int D = NB - 1;
+    constexpr int kBufVecs = 16 * NCT * kPremixHbStride;
+    static_assert(NB * kBufVecs <= 2 * kPremixHbVecs, "the buffers fit the staging space");
+    extern __shared__ uint4 smem[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int r16 = lane & 15, q4 = lane >> 4;
+    uint4* hbuf = smem;
+    uint4* my_slice = smem + 2 * kPremixHbVecs + (size_t)wave * kLinePairSlots;
+    const int r0 = blockIdx.x * 16;
+    const int n_chunks = p.n_vec / kPremixChunkVecs;
+
+    // token of slot wave + 8 i; slots past the last token repeat it (never stored to u)
+    auto fetch = [&](int c, uint4 (&st)[2 * NCT]) {
+        const uint4* src = p.hidden + c * kPremixChunkVecs + lane;
+#pragma unroll
+        for (int i = 0; i < 2 * NCT; ++i) {
+            const int s = wave + i * kPremixWideWaves;
+            st[i] = load_vec(src + (size_t)(s < p.M ? s : p.M - 1) * p.n_vec);
+        }
+    };
+    auto stage = [&](int c, const uint4 (&st)[2 * NCT]) {
+        uint4* dst = hbuf + (size_t)(c % NB) * kBufVecs + (size_t)wave * kPremixHbStride + lane;
+#pragma unroll
+        for (int i = 0; i < 2 * NCT; ++i) store_vec(dst + (size_t)i * kPremixWideWaves * kPremixHbStride, st[i]);
+    };
+    uint4 first[D][2 * NCT];
+#pragma unroll
+    for (int c = 0; c < D; ++c)
+        if (c < n_chunks) fetch(c, first[c]);          // block-uniform
+    asm volatile("" ::: "memory");                     // (keeps the order: tokens first, they return first)
+    uint4 lo[kPremixMaxChunks], hi[kPremixMaxChunks];
+    const uint4* wlo = p.W1 + (size_t)(r0 + line_load_row(lane)) * p.n_vec + wave * 8 + line_load_chunk(lane);
+    const uint4* whi = wlo + (size_t)8 * p.n_vec;
+#pragma unroll
+    for (int c = 0; c < kPremixMaxChunks; ++c) {
+        lo[c] = make_uint4(0, 0, 0, 0);
+        hi[c] = make_uint4(0, 0, 0, 0);
+        if (c < n_chunks) {                            // block-uniform
+            lo[c] = load_stream(wlo + c * kPremixChunkVecs);
+            hi[c] = load_stream(whi + c * kPremixChunkVecs);
+        }
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int c = 0; c < D; ++c)
+        if (c < n_chunks) stage(c, first[c]);
+    __syncthreads();
+    f32x4_t acc[NCT];
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < kPremixMaxChunks; ++c) {
+        if (c < n_chunks) {                            // block-uniform
+            const bool more = c + D < n_chunks;
+            uint4 st[2 * NCT];
+            if (more) fetch(c + D, st);
+            asm volatile("" ::: "memory");
+            uint4 s0, s1;
+            mfma_operands_from_lines(lo[c], hi[c], lane, my_slice, s0, s1);
+            const uint4* hb = hbuf + (size_t)(c % NB) * kBufVecs + wave * 8 + q4;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const uint4 b0 = hb[(ct * 16 + r16) * kPremixHbStride];
+                const uint4 b1 = hb[(ct * 16 + r16) * kPremixHbStride + 4];
+                acc[ct] = mfma_tile<DT>(s0, b0, acc[ct]);
+                acc[ct] = mfma_tile<DT>(s1, b1, acc[ct]);
+            }
+            // buffer (c + D) % NB = (c - 1) % NB was last read in chunk c - 1, before its barrier
+            if (more) stage(c + D, st);
+            if (c + 1 < n_chunks) __syncthreads();
+        }
+    }
+    __syncthreads();                                   // every wave is done with the staging buffers
+    // the waves' partial tiles, summed in wave order; lane l of a tile holds features
+    // 4*(l/16)..+4 of token l%16
+    float* red = reinterpret_cast<float*>(hbuf);       // [wave][token tile][256]
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+        *reinterpret_cast<f32x4_t*>(red + ((size_t)wave * NCT + ct) * 256 + lane * 4) = acc[ct];
+    __syncthreads();
+    for (int e = threadIdx.x; e < NCT * 256; e += kPremixWideBlock) {
+        const int ct = e >> 8, l = (e & 255) >> 2, i = e & 3;
+        const int row = r0 + (l >> 4) * 4 + i, tok = ct * 16 + (l & 15);
+        float y = 0.f;
+#pragma unroll
+        for (int w = 0; w < kPremixWideWaves; ++w) y += red[((size_t)w * NCT + ct) * 256 + (e & 255)];
+        if (tok < p.M) {
+            const size_t at = (size_t)tok * p.H + row;
+            const unsigned short h = reinterpret_cast<const unsigned short*>(p.hidden)[at];
+            static_cast<unsigned short*>(p.out)[at] = narrow16<DT>(premix_act(y, p.act) + widen16<DT>(h));
+        }
+    }
+}
+
 }  // namespace

@@ -660,6 +660,10 @@ PREMIX_SHAPES = [
     # only fits part of a tile's tokens, fewer lines than waves, more than one batch of lines
     ("bf16", 4096, 5), ("bf16", 4096, 40), ("bf16", 8192, 16), ("bf16", 192, 20), ("bf16", 4480, 4),
     ("f16", 4096, 16), ("f16", 1000, 3), ("f16", 4096, 1),
+    # more than 16 tokens, H a multiple of 512 up to 4096: token vectors staged in chunks for
+    # two, three and four token tiles (40 tokens at H = 4096 is in the list above); one chunk;
+    # fp16
+    ("bf16", 4096, 64), ("bf16", 4096, 17), ("bf16", 1024, 33), ("bf16", 512, 64), ("f16", 2048, 48),
 ]
 
 
