@@ -360,6 +360,49 @@ def test_random_small_heads(coral, seed):
     check_dense(dh, hidden, k, run_dense(coral, dh, hidden, k))
 
 
+@pytest.mark.parametrize("seed", list(range(500, 524)))
+def test_random_tile_path_heads(coral, seed):
+    """Seeded random shapes, most of them on the matrix-core path: 17 to 64 tokens, up to 160 ragged groups
+    (more than 64: the gate kernel's general selection), a group of several thousand rows
+    (its candidates take several chunks of the ranking kernel), k up to 64, with and without
+    bias; both output modes where the log-probability mode takes this path."""
+    rng = np.random.default_rng(seed)
+    G = int(rng.integers(1, 161)) if seed % 3 == 0 else int(rng.integers(1, 65))
+    g = int(rng.integers(1, min(G, 24) + 1))
+    M = int(rng.integers(17, 65))
+    H = int(rng.choice([512, 1024, 2048]))
+    dtype = ("bf16", "f16")[seed % 2]
+    sizes = rng.integers(0, 200, G)
+    sizes[rng.integers(0, G)] += int(rng.integers(1000, 6000))    # one large group
+    if G > 3:
+        sizes[rng.integers(0, G, 2)] = (0, 1)
+    min_cand = int(np.sort(sizes)[:g].sum())
+    while min_cand < 1:                                           # the g smallest must hold a row
+        sizes[np.argsort(sizes)[0]] += 1
+        min_cand = int(np.sort(sizes)[:g].sum())
+    k = int(rng.integers(1, min(min_cand, 64) + 1))
+    V = int(sizes.sum())
+    cfg = HeadConfig(f"tile{seed}", dtype, H, V, G, g, (M,), k, seed, True, bias_std=float(rng.choice([0.3, 2.0])))
+    perm = rng.permutation(V).astype(np.int32)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    rows = np.concatenate([np.sort(perm[offsets[n]:offsets[n + 1]]) for n in range(G)]).astype(np.int32)
+    lm_W = to_storage(rng.standard_normal((V, H)).astype(np.float32) * np.float32(0.05), dtype)
+    gate_W = to_storage(rng.standard_normal((G, H)).astype(np.float32) * np.float32(0.05), dtype)
+    bias = (rng.standard_normal(G) * cfg.bias_std).astype(np.float32) if rng.integers(0, 2) else None
+    dt = {"bf16": coral.CORAL_BF16, "f16": coral.CORAL_F16}[dtype]
+    path = coral.coral_lmhead_path(False, M, H, V, G, g, k, dt)      # 2 for two in three of the seeds
+    dh = DeviceHead(coral, Head(cfg, lm_W, gate_W, bias, offsets, rows))
+    hidden = make_hidden(cfg, M, 1)
+    lp_path = coral.coral_lmhead_logprob_path(M, H, V, G, g, k, dt)
+    print(f"case seed={seed} {dtype} M={M} H={H} V={V} G={G} g={g} k={k} path {path} logprob path {lp_path}", flush=True)
+    check_grouped(dh, hidden, g, k, run_grouped(coral, dh, hidden, g, k))
+    if lp_path == 2:
+        out = run_logprob(coral, dh, hidden, g, k)
+        check_logprob(dh, hidden, g, k, out)
+        again = run_logprob(coral, dh, hidden, g, k)
+        assert all(np.array_equal(x, y) for x, y in zip(out, again))
+
+
 def test_duplicate_rows_tie_break_to_the_lower_id(coral):
     cfg = HeadConfig("dup", "bf16", 256, 4 * 96, 4, 4, (2,), 6, 80, True)
     head = make_head(cfg)
