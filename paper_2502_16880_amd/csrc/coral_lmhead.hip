@@ -412,8 +412,8 @@ bool layout_has_tiles(int M, int H, int V, int G, int g, int k, coral_dtype dt) 
 }
 
 // Enqueues k_tiles and the ranking of the logits it leaves.  For the grouped head the gate
-// and selection kernel must already be enqueued (masks, table, first blocks; lp: log p_router
-// of the selection too).
+// and selection kernel must already be enqueued (selection, the token tiles' masks; in the
+// log-probability mode log p_router of the selection too).
 coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
                           const coral_group_index* gi, int M, int H, int V,
                           int G, int k, coral_dtype dt, int u_max, int lds, int32_t* topk_ids,

@@ -14,12 +14,13 @@
 //     both row tiles of the wave;
 //   - the two half sums of each tile are added in a fixed order through LDS, which
 //     leaves, per token, the block's 128 logits two per lane of a wave; they go to memory as
-//     they are, 512 bytes per (block, token): a few MB per step against the hundreds of MB of
-//     weight rows, and the workgroup is back in its next block's K loop within a microsecond.
-// k_tile_select: one workgroup per (token, span of 16 blocks of one of its groups) ranks the
-// span's logits (a bound from the threads' best candidates, then rank counting among what
-// reaches it); the workgroup that finishes a token's last span merges the spans' lists
-// (Eq. 8's offsets added per group in the log-probability mode).
+//     they are, 512 bytes per (block, token), with the largest of them (and the sum of exp in
+//     the log-probability mode): a few MB per step against the hundreds of MB of weight rows,
+//     and the workgroup is back in its next block's K loop within a few microseconds.
+// k_gate_select in front of it: gate and selection per tile of 16 tokens.  k_tile_select behind
+// it: one workgroup per token bounds the token's k-th logit by the k-th largest block maximum,
+// reads the logits of the blocks that reach the bound and ranks them (Eq. 8's offsets added
+// per group in the log-probability mode).
 #pragma once
 #include "device_utils.h"
 #include "fused_path.h"
@@ -35,7 +36,6 @@ constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-colu
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
-constexpr int kGateExtractMax = 16;               // selection by rounds of a wave maximum up to this g
 // Strides (floats) of the accumulator tiles parked in LDS for the epilogue: token tile,
 // row tile of a wave, wave.  Modulo the 64 banks they are 16, 16 and 48.
 constexpr int kRedCt = 272, kRedTile = 4 * kRedCt + 16, kRedWave = 2 * kRedTile + 16;
