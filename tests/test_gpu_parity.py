@@ -461,6 +461,26 @@ def test_equal_gate_scores_on_the_tile_path(coral, g):
     assert seen > 0
 
 
+@pytest.mark.parametrize("M,V", [(9, 65536 + 77), (33, 65536 + 128 + 1)])
+def test_dense_head_on_the_tile_path_with_a_ragged_last_block(coral, M, V):
+    """The dense head takes the tile path from 8 tokens and 65536 rows on; the configured
+    vocabularies are multiples of the 128-row block, these are not (77 rows, one row)."""
+    cfg = HeadConfig("dense_ragged", "bf16", 512, V, 1, 1, (M,), 12, 140 + M, False)
+    assert coral.coral_lmhead_path(True, M, cfg.H, V, 0, 0, cfg.k, coral.CORAL_BF16) == 2
+    dh = DeviceHead(coral, make_head(cfg))
+    hidden = make_hidden(cfg, M)
+    hidden[0] = hidden[1]                                  # two tokens with the same lists
+    # the last rows must be reachable: make one of them every token's best
+    w = oracle.widen(dh.head.lm_W, "bf16")
+    mean = oracle.widen(hidden, "bf16").mean(axis=0)
+    w[V - 1] = (3.0 / (mean @ mean)) * mean              # logits of about 2 to 6 there, 2 elsewhere at most
+    dh.head.lm_W[:] = oracle.round_to_storage(w, "bf16")
+    dh = DeviceHead(coral, dh.head)
+    ids, z = run_dense(coral, dh, hidden, cfg.k)
+    assert (ids[:, 0] == V - 1).sum() >= M // 2
+    check_dense(dh, hidden, cfg.k, (ids, z))
+
+
 def test_equal_logits_on_the_tile_path(coral):
     """All-zero hidden vectors: every logit is 0.0, so every block's largest logit reaches the
     bound, all 2048 candidates of the first chunk pass it (more than one per thread: the
