@@ -475,6 +475,15 @@ def other_shapes(a, n, cases):
     for b, label in pairs:
         for M in b.cfg.Ms:
             cases.append(grouped_case(b.time_grouped(M, n, 20, eager=a.eager, event_steps=48), label))
+    del pp, pairs, b
+    gc.collect()
+    torch.cuda.empty_cache()
+    # the appendix's wide tree step (64 nodes, 64 groups, top 8, 16 candidates): the tile path
+    wt = Bench(CONFIGS["wide_tree"])
+    for logprob, mode in ((False, "logit ranking"), (True, "log-probability output (Eq. 8)")):
+        r = wt.time_grouped(64, n, 20, eager=a.eager, event_steps=48, logprob=logprob)
+        cases.append(grouped_case(r, f"grouped, wide_tree (G=64x2004 g=8 k=16; tile path: k_gate_select, k_tiles, "
+                                     f"k_tile_select; kernel_us is k_tiles alone), {mode}"))
 
 
 def main():
