@@ -86,7 +86,7 @@ Layout make_layout(int M, int V, int G, int g, int k, bool pair_pieces, bool til
     // one (max, sum) piece per (row pair of a selected group, token that selected it): a
     // token's g groups are distinct, so their pairs number V / 2 + g at most
     L.fused_pairs = take(pair_pieces ? (size_t)M * ((size_t)V / 2 + g) * sizeof(unsigned long long) : 0);
-    L.s = take((size_t)M * (G ? G : 1) * sizeof(float));
+    L.s = take((size_t)kGateParts * M * (G ? G : 1) * sizeof(float));
     L.sel = take((size_t)M * (g ? g : 1) * sizeof(int32_t));
     L.mask = take((size_t)(G ? G : 1) * sizeof(unsigned long long));
     L.union_list = take((size_t)(G ? G : 1) * sizeof(int32_t));
@@ -633,7 +633,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
         const int tiles = ((G + 15) / 16) * ((M + 15) / 16);
         typedef void (*gate_select_fn)(GateSelParams);
         const gate_select_fn gs = dt == CORAL_F16 ? k_gate_select<kF16> : k_gate_select<kBF16>;
-        hipLaunchKernelGGL(gs, dim3(tiles), dim3(kFusedBlock), 0, stream, q);
+        hipLaunchKernelGGL(gs, dim3(tiles, kGateParts), dim3(kFusedBlock), 0, stream, q);
         if ((st = launch_status()) != CORAL_OK) return st;
         st = launch_tiles(false, hidden, lm_W, gi, M, H, V, G, k, dt,
                           plan.tile_umax, plan.tile_lds, topk_ids, topk_logits, ws, L, stream, ev_before,

@@ -36,6 +36,7 @@ constexpr int kChunkVecs = 64;                   // 16-byte vectors per 512-colu
 constexpr int kHbStride = kChunkVecs + 1;        // LDS row stride in vectors (pad: no bank conflicts)
 constexpr int kHbBufVecs = 64 * kHbStride;       // one staging buffer: 64 token slots
 constexpr int kRing = 16;                        // weight loads of a wave per chunk = ring size
+constexpr int kGateParts = 2;                    // workgroups that share the columns of a gate tile
 // Strides (floats) of the accumulator tiles parked in LDS for the epilogue: token tile,
 // row tile of a wave, wave.  Modulo the 64 banks they are 16, 16 and 48.
 constexpr int kRedCt = 272, kRedTile = 4 * kRedCt + 16, kRedWave = 2 * kRedTile + 16;
@@ -458,9 +459,11 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 }
 
 // Gate and selection for the tile path (Eq. 7's W2 projection, then top-g): one workgroup
-// per tile of 16 groups x 16 tokens, the columns split over its 16 waves in steps of 32
-// (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at 8*(l/16));
-// the partial tiles are summed in wave order.  The workgroups of one token tile count
+// per tile of 16 groups x 16 tokens and half of the columns (two workgroups share a tile: 32
+// compute units pull the operands instead of 16), the columns split over its 16 waves in
+// steps of 32 (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at
+// 8*(l/16)); the partial tiles are summed in wave order and the two workgroups' sums by
+// whoever reads the scores, in a fixed order.  The workgroups of one token tile count
 // themselves in on that tile's counter; the one that arrives last has all scores of its 16
 // tokens and ranks them by counting, one wave per token, writes the selection and, per
 // group, the mask of those of its tokens that selected it.  The tile kernel combines the
@@ -469,7 +472,7 @@ struct GateSelParams {
     const uint4* hidden;                    // [M, n_vec]
     const uint4* gate_W;                    // [G, n_vec]
     const float* bias;                      // [G] or null
-    float* s;                               // [M, G] scores (workspace)
+    float* s;                               // [parts, M, G] scores (workspace)
     int32_t* sel;                           // [M, g]
     unsigned long long* tile_mask;          // [token tiles, G] out: tokens of the tile that selected the group
     unsigned int* counters;                 // [token tiles] arrival counters, zero between calls
@@ -500,11 +503,13 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     const int n_ks = (p.n_vec + 3) / 4;
     const int n = gt * 16 + mfma_load_row(lane), m = tt * 16 + mfma_load_row(lane);
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    for (int ks0 = wave; ks0 < n_ks; ks0 += kFusedWaves * 8) {      // wave-uniform
+    const int cpart = blockIdx.y, n_parts = gridDim.y;              // the columns are split over n_parts workgroups
+    const int kstride = kFusedWaves * n_parts;
+    for (int ks0 = cpart * kFusedWaves + wave; ks0 < n_ks; ks0 += kstride * 8) {      // wave-uniform
         uint4 a[8], b[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int ks = ks0 + kFusedWaves * i;
+            const int ks = ks0 + kstride * i;
             const int vec = ks * 4 + mfma_load_chunk(lane);
             a[i] = make_uint4(0, 0, 0, 0);
             b[i] = make_uint4(0, 0, 0, 0);
@@ -527,7 +532,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         float sum = 0.f;
         for (int w = 0; w < kFusedWaves; ++w) sum += part[w][e];
         if (gn < p.G && tm < p.M)
-            __hip_atomic_store(p.s + (size_t)tm * p.G + gn, sum + bias_r,
+            __hip_atomic_store(p.s + ((size_t)cpart * p.M + tm) * p.G + gn, cpart == 0 ? sum + bias_r : sum,
                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the scores are out
@@ -535,19 +540,24 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
     if (threadIdx.x == 0) {
         const unsigned int old = __hip_atomic_fetch_add(p.counters + tt, 1u, __ATOMIC_RELAXED,
                                                         __HIP_MEMORY_SCOPE_AGENT);
-        is_last = old == (unsigned)(n_gt - 1) ? 1 : 0;
+        is_last = old == (unsigned)(n_gt * n_parts - 1) ? 1 : 0;
     }
     __syncthreads();
     if (!uni(is_last)) return;                         // block-uniform
 
-    // the token tile is complete: its tokens tt * 16 .. + 15
+    // the token tile is complete: its tokens tt * 16 .. + 15; a score is the sum of its parts in order
+    auto score = [&](int tm, int gn) {
+        float v = load_score(p.s + (size_t)tm * p.G + gn);
+        for (int q = 1; q < n_parts; ++q) v += load_score(p.s + ((size_t)q * p.M + tm) * p.G + gn);
+        return v;
+    };
     for (int g0 = threadIdx.x; g0 < p.G; g0 += kFusedBlock) mask[g0] = 0ull;
     __syncthreads();
     if (p.G <= kWave) {
         // one wave per token, group in lane
         const int tm = tt * 16 + wave;
         if (wave < 16 && tm < p.M) {                   // wave-uniform
-            float v = lane < p.G ? load_score(p.s + (size_t)tm * p.G + lane) : -INFINITY;
+            float v = lane < p.G ? score(tm, lane) : -INFINITY;
             if (!(v == v)) v = -INFINITY;
             const int rank = wave_rank(sel_keys[wave], v, lane, p.G, lane);
             float lse_s = 0.f;
@@ -566,12 +576,11 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         for (int idx = threadIdx.x; idx < n_tok * p.G; idx += kFusedBlock) {
             const int tm = tt * 16 + idx / p.G;
             const int gn = idx - (idx / p.G) * p.G;
-            const float* row = p.s + (size_t)tm * p.G;
-            float v = load_score(row + gn);
+            float v = score(tm, gn);
             if (!(v == v)) v = -INFINITY;
             int rank = 0;
             for (int o = 0; o < p.G; ++o) {
-                float ov = load_score(row + o);
+                float ov = score(tm, o);
                 if (!(ov == ov)) ov = -INFINITY;
                 rank += better(ov, o, v, gn) ? 1 : 0;
             }
