@@ -600,12 +600,12 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
 // selected (dense: all), and k_tiles left every block's largest logit.  The k-th largest of
 // these block maxima is a lower bound of the token's k-th logit (k blocks hold a logit that
 // reaches it), so only blocks whose largest reaches it can hold a result: about k of them,
-// out of 128 (wide draft tree) or a thousand (dense).  Their logits, 16 blocks (2048
+// out of 128 (wide draft tree) or a thousand (dense).  Their logits, 32 blocks (4096
 // candidates, eight per thread) at a time, are filtered by the bound and by the k-th entry
 // of the list so far, collected in LDS with the list, and ranked by counting (64-bit
-// ordering keys, all distinct).  Should more than 256 pass (equal logits, adversarial
-// inputs), the k-th largest of each wave's lanes' best keys and the largest of these four
-// is a second bound that leaves at most 4 (8 (k - 1) + 1).
+// ordering keys, all distinct).  Should more than 512 pass (equal logits, adversarial
+// inputs), the k-th largest of each wave's lanes' best keys and the largest of these eight
+// is a second bound that leaves at most 8 (8 (k - 1) + 1).
 // Log-probability mode (Eq. 8): log p(x) = log p_router(n) + z[x] - lse_n; lse_n comes from
 // the (largest, sum of exp) pieces k_tiles left per block, combined in block order, and
 // bounds and keys are formed from z + (log p_router(n) - lse_n).
@@ -625,7 +625,7 @@ struct TileSelectParams {
     int max_blocks;                         // capacity of the per-block arrays in LDS
 };
 
-constexpr int kSelectThreads = 256;
+constexpr int kSelectThreads = 512;
 constexpr int kSelectWaves = kSelectThreads / kWave;
 constexpr int kSelectKeys = 8;                   // candidates per thread and chunk
 constexpr int kSelectChunkBlocks = kSelectKeys * kSelectThreads / kTileRows;
@@ -810,7 +810,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
             if (threadIdx.x == 0) n_qual = 0;
             int* ti = src_i; src_i = dst_i; dst_i = ti;
             unsigned* tv = src_v; src_v = dst_v; dst_v = tv;
-            if (tight) break;
+            if (tight && n_q <= kSelectChunkBlocks) break;     // (else once more: the candidates of one chunk)
         }
         qblk = src_i;                                  // the blocks whose largest reaches the bound
     }
