@@ -662,6 +662,18 @@ __host__ __device__ inline TileSelectLds tile_select_lds_layout(int n_groups, in
     return L;
 }
 
+// wave_kth_key for all 64 lanes with the keys read four at a time (keys32 16-byte aligned).
+__device__ __forceinline__ unsigned wave_kth_key4(unsigned* keys32, unsigned key, int k, int lane) {
+    keys32[lane] = key;
+    int above = 0;
+#pragma unroll 4
+    for (int j = 0; j < kWave / 4; ++j) {
+        const uint4 q = reinterpret_cast<const uint4*>(keys32)[j];
+        above += (q.x > key ? 1 : 0) + (q.y > key ? 1 : 0) + (q.z > key ? 1 : 0) + (q.w > key ? 1 : 0);
+    }
+    return wave_min_u32(above < k ? key : 0xffffffffu);
+}
+
 template <bool DENSE, bool LP>
 __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams p) {
     extern __shared__ uint4 smem[];
@@ -744,7 +756,9 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
         }
         const int lb = i - g_pre[lo];
         binfo[i] = (lo << 16) | lb;
-        bst[i] = p.stat[(size_t)(g_fb[lo] + lb) * p.M + g_slot[lo]];
+        const float2 st = p.stat[(size_t)(g_fb[lo] + lb) * p.M + g_slot[lo]];
+        if (LP) bst[i] = st;
+        else bval[i] = ord32(st.x);                    // (no offsets: the block's largest logit as it is)
     }
     __syncthreads();
     if (LP) {
@@ -771,9 +785,11 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
     // reach it are the next round's candidates.  With one candidate per thread the bound
     // leaves between k and 4 k blocks; with more (the dense head's thousand blocks) a second
     // and third round tighten it.
-    for (int i = threadIdx.x; i < n_blocks; i += kSelectThreads)
-        bval[i] = ord32(bst[i].x + g_shift[binfo[i] >> 16]);
-    __syncthreads();
+    if (LP) {
+        for (int i = threadIdx.x; i < n_blocks; i += kSelectThreads)
+            bval[i] = ord32(bst[i].x + g_shift[binfo[i] >> 16]);
+        __syncthreads();
+    }
     unsigned* keys32 = reinterpret_cast<unsigned*>(wkeys) + wave * kWave;
     unsigned tau = 0u;
     int n_q = n_blocks;
@@ -785,7 +801,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
         for (int round = 0; round < 3; ++round) {      // block-uniform
             unsigned best = 0u;
             for (int i = threadIdx.x; i < n_q; i += kSelectThreads) best = src_v[i] > best ? src_v[i] : best;
-            const unsigned kth = wave_kth_key(keys32, best, kWave, k, lane);
+            const unsigned kth = wave_kth_key4(keys32, best, k, lane);
             if (lane == 0) tau_w[wave] = kth;
             __syncthreads();
             tau = tau_w[0];
@@ -806,11 +822,11 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
             __syncthreads();
             const bool tight = n_q <= kSelectThreads;
             n_q = uni(n_qual);
-            __syncthreads();                           // (everyone has the count)
-            if (threadIdx.x == 0) n_qual = 0;
             int* ti = src_i; src_i = dst_i; dst_i = ti;
             unsigned* tv = src_v; src_v = dst_v; dst_v = tv;
             if (tight && n_q <= kSelectChunkBlocks) break;     // (else once more: the candidates of one chunk)
+            __syncthreads();                           // (everyone has the count)
+            if (threadIdx.x == 0) n_qual = 0;
         }
         qblk = src_i;                                  // the blocks whose largest reaches the bound
     }
@@ -896,6 +912,7 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
         }
         __syncthreads();
         have = kept < k ? kept : k;
+        if (base + kSelectChunkBlocks >= n_q) break;   // block-uniform: that was the last chunk
         if ((int)threadIdx.x < have) buf[threadIdx.x] = list[threadIdx.x];
         if (threadIdx.x == 0) n_kept = have;
         list_kth = have == k ? list[k - 1] : 0ull;
@@ -904,8 +921,8 @@ __global__ __launch_bounds__(kSelectThreads) void k_tile_select(TileSelectParams
     if ((int)threadIdx.x < k) {
         Cand c = sentinel();
         if ((int)threadIdx.x < have) {
-            c.v = key_value(buf[threadIdx.x]);
-            c.id = key_id(buf[threadIdx.x]);
+            c.v = key_value(list[threadIdx.x]);
+            c.id = key_id(list[threadIdx.x]);
         }
         p.topk_ids[(size_t)t * k + threadIdx.x] = c.id;
         p.topk_out[(size_t)t * k + threadIdx.x] = c.v;
