@@ -104,6 +104,11 @@ def test_workspace_bytes():
     assert wb(4, 256, 8192, 16, 0, 8, F32) == 0        # G without g
     assert wb(4, 256, 8192, 4, 5, 8, F32) == 0         # g > G
     assert b % 256 == 0
+    # shapes that can take the matrix-core path carry its logits buffer, 512 B per (128-row
+    # block, token) with V / 128 + G + 1 blocks; shapes that cannot (one token; fp32) do not
+    z_wide = (128256 // 128 + 64 + 1) * 64 * 512
+    assert wb(64, 4096, 128256, 64, 8, 16, BF16) - wb(64, 4096, 128256, 64, 8, 16, F32) >= z_wide
+    assert a < (128256 // 128 + 32 + 1) * 512
 
 
 class Call:
