@@ -690,7 +690,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     if (logprob)
         hipLaunchKernelGGL(k_merge_logprob<4>, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
                            L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count), chunk_base,
-                           logp_sel, g, k, topk_ids, topk_logits, nullptr);
+                           logp_sel, g, k, topk_ids, topk_logits);
     else
         hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, part, L.part_stride, sel,
                            gi->group_offsets, g, 0, k, topk_ids, topk_logits);

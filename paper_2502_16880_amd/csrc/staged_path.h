@@ -426,16 +426,15 @@ __global__ __launch_bounds__(kBlock) void k_merge(const Cand* __restrict__ part,
 
 
 // Final merge of the log-probability mode behind k_logits (a slot = a chunk of kChunkRows
-// rows) and behind k_tiles (a slot = a block of kTileRows rows): slot_count[m, i] slots from
-// chunk_base[m, i] on belong to token m's i-th selected group.
+// rows): slot_count[m, i] slots from chunk_base[m, i] on belong to token m's i-th selected
+// group.
 // Eq. 8: log p(x) = log p_router(n) + z[x] - lse_n
 // for x in the selected group n, where lse_n is the log of the sum of exp(z) over the
 // group's rows.  One workgroup per token; wave w takes the token's selected groups w, w + WAVES,
 // ...: it combines the (max, sum) pieces of the group's slots into lse_n, merges the group's
 // partial lists (sorted by logit, which inside a group is the order of log p as well) into
 // the group's k best, adds the offset log p_router(n) - lse_n and merges that list into its
-// running list.  The waves' running lists (WAVES = 4, or 8 when a token has more than four
-// groups) are merged at the end; equal values: lower id first.
+// running list.  The waves' running lists are merged at the end; equal values: lower id first.
 template <int WAVES>
 __global__ __launch_bounds__(WAVES * kWave) void k_merge_logprob(const Cand* __restrict__ part,
                                                           const float* __restrict__ lse_part,
@@ -444,8 +443,7 @@ __global__ __launch_bounds__(WAVES * kWave) void k_merge_logprob(const Cand* __r
                                                           const int32_t* __restrict__ chunk_base,
                                                           const float* __restrict__ logp_sel, int g,
                                                           int k, int32_t* __restrict__ topk_ids,
-                                                          float* __restrict__ topk_logprob,
-                                                          unsigned int* __restrict__ reset_word) {
+                                                          float* __restrict__ topk_logprob) {
     __shared__ Cand mbuf[WAVES * kMaxK];      // the waves' running lists
     __shared__ Cand fresh[WAVES * kMaxK];     // a group's k best, then the merged list
     __shared__ Cand outbuf[kMaxK];
@@ -507,8 +505,6 @@ __global__ __launch_bounds__(WAVES * kWave) void k_merge_logprob(const Cand* __r
         topk_ids[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].id;
         topk_logprob[(size_t)m * k + threadIdx.x] = outbuf[threadIdx.x].v;
     }
-    // (behind the tile kernel this launch also leaves its block queue ready for the next call)
-    if (reset_word && blockIdx.x == 0 && threadIdx.x == 0) *reset_word = 0u;
 }
 
 }  // namespace
