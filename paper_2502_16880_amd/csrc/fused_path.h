@@ -707,14 +707,8 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                     if (vec < p.n_vec && n < p.G) ga[i] = p.gate_W[(size_t)n * p.n_vec + vec];
                 }
             };
-            load_gate_tile(half);
-            hidden_commit(0);
-            small_commit();
-            hidden_rest();
-            __syncthreads();
-            for (int pair = 0; pair * 2 < n_gt; ++pair) {
-                if (pair) load_gate_tile(pair * 2 + half);
-                if (GATE == kGateMfmaLines) {                  // to the MFMA operand layout
+            auto to_operand_layout = [&]() {
+                if (GATE == kGateMfmaLines) {
 #pragma unroll
                     for (int i = 0; i < kSteps; i += 2) {
                         uint4 s0, s1;
@@ -725,6 +719,21 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                 } else {
 #pragma unroll
                     for (int i = 0; i < kSteps; ++i) ga[i] = mfma_operand_from_quads(ga[i], lane, my_slice);
+                }
+            };
+            load_gate_tile(half);
+            hidden_commit(0);
+            small_commit();
+            hidden_rest();
+            // The first tile's rows are moved to the operand layout before the barrier: that
+            // needs the wave's own rows and its own LDS slice only, and LDS is idle while the
+            // workgroup waits for its last wave's hidden vectors (1.6 us at 8 tokens).
+            to_operand_layout();
+            __syncthreads();
+            for (int pair = 0; pair * 2 < n_gt; ++pair) {
+                if (pair) {
+                    load_gate_tile(pair * 2 + half);
+                    to_operand_layout();
                 }
                 for (int tt = 0; tt < n_tt; ++tt) {            // uniform
                     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
