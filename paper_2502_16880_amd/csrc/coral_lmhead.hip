@@ -208,11 +208,10 @@ bool allow_lds(const void* fn, int bytes) {
 }
 
 // Gate of the single-launch path: more than four tokens go through the matrix cores (16-bit
-// storage only), with whole-line loads if their larger LDS slices still fit.
+// storage only).
 int fused_gate_mode(bool dense, int M, int G, int g, int k, int jp, coral_dtype dt, bool logprob = false) {
-    if (dense || !is_16bit(dt) || M <= 4) return kGateVector;
-    if (fused_lds_layout(M, G, g, k, jp, false, kGateMfmaLines, logprob).total <= kLdsLimit) return kGateMfmaLines;
-    return kGateMfmaQuads;
+    (void)G; (void)g; (void)k; (void)jp; (void)logprob;
+    return dense || !is_16bit(dt) || M <= 4 ? kGateVector : kGateMfma;
 }
 
 // Activated groups at most.
@@ -309,9 +308,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
     const bool routed = !dense && gate_hidden != hidden;
     fused_fn fn;
 #define CORAL_FUSED_GATES(DT, R, LP)                                                             \
-    (gate == kGateMfmaLines   ? k_fused<DT, false, kGateMfmaLines, R, LP>                        \
-     : gate == kGateMfmaQuads ? k_fused<DT, false, kGateMfmaQuads, R, LP>                        \
-                              : k_fused<DT, false, kGateVector, R, LP>)
+    (gate == kGateMfma ? k_fused<DT, false, kGateMfma, R, LP> : k_fused<DT, false, kGateVector, R, LP>)
     if (logprob && (dense || 2 * max_union(M, G, g) > P)) return CORAL_ERR_UNSUPPORTED;   // not reached
     if (logprob && routed)
         fn = CORAL_PICK_DT(dt, (k_fused<kF32, false, kGateVector, true, true>),

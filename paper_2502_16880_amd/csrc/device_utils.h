@@ -183,6 +183,44 @@ __device__ __forceinline__ void mfma_operands_from_lines(uint4 rows_lo, uint4 ro
     step1 = slice[src + 4];
 }
 
+// Transposition without LDS, for tiles loaded four rows x 256 contiguous bytes per wave
+// load: load t of four (t = 0..3) has lane 16 q + 4 a + c on row 4 a + t, 16-byte chunk
+// 4 q + c of the 256 bytes, so that every quad of lanes covers 64 contiguous bytes and every
+// row two whole lines.  Exchanging t and c inside every quad of lanes (a 4 x 4 transposition
+// of the four registers, two butterfly stages of DPP quad permutations) leaves in register c
+// lane 16 q + i with row i, chunk 4 q + c: the operand of the 32-column step that takes the
+// chunks {c, 4 + c, 8 + c, 12 + c} of the 256 bytes, as long as the other operand is read
+// with the same choice of columns.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_quad(unsigned x) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, true);   // (every source lane exists)
+}
+__device__ __forceinline__ void quad_transpose(unsigned& r0, unsigned& r1, unsigned& r2, unsigned& r3,
+                                               bool odd, bool up) {
+    // (the moves come first, with all lanes active: a DPP move under a divergent condition
+    // would not see the other lanes)
+    const unsigned x0 = dpp_quad<0xB1>(r0), x1 = dpp_quad<0xB1>(r1);   // quad_perm [1,0,3,2]
+    const unsigned x2 = dpp_quad<0xB1>(r2), x3 = dpp_quad<0xB1>(r3);
+    const unsigned a0 = odd ? x1 : r0, b0 = odd ? r1 : x0;
+    const unsigned a1 = odd ? x3 : r2, b1 = odd ? r3 : x2;
+    const unsigned ya0 = dpp_quad<0x4E>(a0), ya1 = dpp_quad<0x4E>(a1);  // quad_perm [2,3,0,1]
+    const unsigned yb0 = dpp_quad<0x4E>(b0), yb1 = dpp_quad<0x4E>(b1);
+    r0 = up ? ya1 : a0;
+    r2 = up ? a1 : ya0;
+    r1 = up ? yb1 : b0;
+    r3 = up ? b1 : yb0;
+    // (the results are wanted here, not where they are used: left to itself the compiler
+    // keeps both stages' values alive across the whole gate and runs out of registers)
+    asm volatile("" : "+v"(r0), "+v"(r1), "+v"(r2), "+v"(r3));
+}
+__device__ __forceinline__ void mfma_operands_from_quad_rows(uint4& r0, uint4& r1, uint4& r2, uint4& r3, int lane) {
+    const bool odd = lane & 1, up = lane & 2;
+    quad_transpose(r0.x, r1.x, r2.x, r3.x, odd, up);
+    quad_transpose(r0.y, r1.y, r2.y, r3.y, odd, up);
+    quad_transpose(r0.z, r1.z, r2.z, r3.z, odd, up);
+    quad_transpose(r0.w, r1.w, r2.w, r3.w, odd, up);
+}
+
 // Value of the lane below (lane 0 keeps its own): one DPP move, no LDS round trip.
 __device__ __forceinline__ int lane_below(int x) {
     return __builtin_amdgcn_update_dpp(x, x, 0x138 /* wave_shr:1 */, 0xf, 0xf, false);

@@ -46,14 +46,11 @@ constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp 
 // keeping sorted lists, and one wave per token ranks the buffer at the end.
 constexpr int kCollectCap = 128;       // entries per token
 constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
-constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile, or the operand transposer
-// How the gate (step 2a) is computed: on the vector units, or on the matrix cores with the
-// gate rows loaded as 64-byte pieces (16 rows per wave load) or as whole 128-byte lines
-// (8 rows per wave load, twice the LDS slice per wave, used when it fits).
-enum GateMode { kGateVector = 0, kGateMfmaQuads = 1, kGateMfmaLines = 2 };
-__host__ __device__ inline int gate_slice_floats(int mode) {
-    return mode == kGateMfmaLines ? kLinePairSlots * 4 : kGateSlice;
-}
+constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile (k_gate_select: or its operand transposer)
+// How the gate (step 2a) is computed: on the vector units, or on the matrix cores (16-bit
+// storage, more than four tokens).
+enum GateMode { kGateVector = 0, kGateMfma = 1 };
+constexpr int kGateTileFloats = 256;          // a wave's partial 16 x 16 tile
 // Wave-private LDS scratch of the merges: ranking keys, gathered candidates, list tags.
 struct WaveScratch {
     unsigned long long keys[kWave];
@@ -128,7 +125,7 @@ __host__ __device__ inline FusedLds fused_lds_layout(int M, int G, int g, int k,
     // the MFMA gate parks its per-wave partial tiles here before the lists are initialised
     const size_t gate_part_bytes =
         (!dense && gate_mode != kGateVector)
-            ? (size_t)kFusedWaves * ((M + 15) / 16) * gate_slice_floats(gate_mode) * sizeof(float)
+            ? (size_t)kFusedWaves * ((M + 15) / 16) * kGateTileFloats * sizeof(float)
             : 0;
     if (lists_bytes < gate_part_bytes) lists_bytes = gate_part_bytes;
     L.o_lists = take(lists_bytes);
@@ -676,58 +673,41 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
             // rows 4*(l/16)..+4, column l%16 of the tile); the waves' partial tiles are
             // summed in wave order.
             const int r16 = lane & 15, q4 = lane >> 4;
-            const int n_ks = (p.n_vec + 3) / 4;            // <= 128 because jp <= 8
             const int n_gt = (p.G + 15) / 16, n_tt = (M + 15) / 16;
-            constexpr int kSlice = GATE == kGateMfmaLines ? kLinePairSlots * 4 : kGateSlice;
+            constexpr int kSlice = kGateTileFloats;
             float* gpart = reinterpret_cast<float*>(lds + lay.o_lists);   // [wave][n_tt][kSlice]
-            uint4* my_slice = reinterpret_cast<uint4*>(gpart + (size_t)wave * n_tt * kSlice);
             // waves 0-7 work on the even tile of a pair of group tiles, waves 8-15 on the odd
-            // one; each takes two adjacent 32-column steps at a time (one 128-byte line per
-            // gate row) out of every 16
+            // one; wave kw of either half takes the 256-byte blocks kw, kw + 8, kw + 16, kw + 24
+            // of the gate rows (jp <= 8: a row has at most 32).  A block is four wave loads of
+            // four rows x 256 contiguous bytes, transposed in registers to the operands of four
+            // 32-column steps (mfma_operands_from_quad_rows in device_utils.h): register
+            // 4 B + c then feeds rows 0..15, 16-byte chunks {c, 4 + c, 8 + c, 12 + c} of block
+            // 8 B + kw, and the hidden vectors are read from LDS with the same choice.
             const int half = wave >> 3, kw = wave & 7;
             constexpr int kSteps = 2 * kFusedSegs;
             uint4 ga[kSteps];
             // (every workgroup sums the columns in the same order: the scores, and with them
             // the selection, must come out bit-identical in all of them)
-            auto step_of = [&](int i) { return 16 * (i >> 1) + 2 * kw + (i & 1); };
-            // (see device_utils.h for the two load shapes; with whole lines register 2 L + h
-            // holds rows 8 h .. 8 h + 7 of the tile for both steps of line L)
             auto load_gate_tile = [&](int gt) {
 #pragma unroll
                 for (int i = 0; i < kSteps; ++i) {
-                    int n, vec;
-                    if (GATE == kGateMfmaLines) {
-                        n = gt * 16 + (i & 1) * 8 + line_load_row(lane);
-                        vec = step_of(i & ~1) * 4 + line_load_chunk(lane);
-                    } else {
-                        n = gt * 16 + mfma_load_row(lane);
-                        vec = step_of(i) * 4 + mfma_load_chunk(lane);
-                    }
+                    const int n = gt * 16 + ((lane >> 2) & 3) * 4 + (i & 3);
+                    const int vec = ((i >> 2) * 8 + kw) * 16 + q4 * 4 + (lane & 3);
                     ga[i] = make_uint4(0, 0, 0, 0);
                     if (vec < p.n_vec && n < p.G) ga[i] = p.gate_W[(size_t)n * p.n_vec + vec];
                 }
             };
             auto to_operand_layout = [&]() {
-                if (GATE == kGateMfmaLines) {
 #pragma unroll
-                    for (int i = 0; i < kSteps; i += 2) {
-                        uint4 s0, s1;
-                        mfma_operands_from_lines(ga[i], ga[i + 1], lane, my_slice, s0, s1);
-                        ga[i] = s0;
-                        ga[i + 1] = s1;
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < kSteps; ++i) ga[i] = mfma_operand_from_quads(ga[i], lane, my_slice);
-                }
+                for (int i = 0; i < kSteps; i += 4)
+                    mfma_operands_from_quad_rows(ga[i], ga[i + 1], ga[i + 2], ga[i + 3], lane);
             };
             load_gate_tile(half);
             hidden_commit(0);
             small_commit();
             hidden_rest();
-            // The first tile's rows are moved to the operand layout before the barrier: that
-            // needs the wave's own rows and its own LDS slice only, and LDS is idle while the
-            // workgroup waits for its last wave's hidden vectors (1.6 us at 8 tokens).
+            // The first tile's rows are transposed before the barrier, while the workgroup
+            // waits for its last wave's hidden vectors (1.6 us at 8 tokens).
             to_operand_layout();
             __syncthreads();
             for (int pair = 0; pair * 2 < n_gt; ++pair) {
@@ -744,10 +724,10 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
                         uint4 hb[2];
 #pragma unroll
                         for (int u = 0; u < 2; ++u) {
-                            const int ks = step_of(i0 + u);
-                            const int vec = ks < n_ks ? ks * 4 + q4 : 0;   // rows are zero padded
-                            hb[u] = hs[mc * hs_stride + vec];
-                            if (m >= M || ks >= n_ks) hb[u] = make_uint4(0, 0, 0, 0);
+                            const int vec = (((i0 + u) >> 2) * 8 + kw) * 16 + q4 * 4 + ((i0 + u) & 3);
+                            const bool in = vec < p.n_vec;
+                            hb[u] = hs[mc * hs_stride + (in ? vec : 0)];
+                            if (m >= M || !in) hb[u] = make_uint4(0, 0, 0, 0);
                         }
 #pragma unroll
                         for (int u = 0; u < 2; ++u)
