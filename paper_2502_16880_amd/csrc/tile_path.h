@@ -500,28 +500,38 @@ __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
         const int gn = gt * 16 + ((threadIdx.x >> 2) >> 4) * 4 + (threadIdx.x & 3);
         if (gn < p.G) bias_r = p.bias[gn];
     }
-    const int n_ks = (p.n_vec + 3) / 4;
-    const int n = gt * 16 + mfma_load_row(lane), m = tt * 16 + mfma_load_row(lane);
+    // A wave takes 256-byte blocks of the columns (every kFusedWaves * n_parts-th), two per
+    // pass with all loads requested before the first is used: per block four wave loads of
+    // four rows x 256 contiguous bytes for each operand, transposed in registers to the
+    // operands of four 32-column steps (mfma_operands_from_quad_rows).
+    const int q4 = lane >> 4, a4 = (lane >> 2) & 3, c4 = lane & 3;
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int cpart = blockIdx.y, n_parts = gridDim.y;              // the columns are split over n_parts workgroups
-    const int kstride = kFusedWaves * n_parts;
-    for (int ks0 = cpart * kFusedWaves + wave; ks0 < n_ks; ks0 += kstride * 8) {      // wave-uniform
-        uint4 a[8], b[8];
+    const int n_blk = (p.n_vec + 15) / 16, bstride = kFusedWaves * n_parts;
+    for (int blk0 = cpart * kFusedWaves + wave; blk0 < n_blk; blk0 += 2 * bstride) {     // wave-uniform
+        uint4 a[2][4], b[2][4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int ks = ks0 + kstride * i;
-            const int vec = ks * 4 + mfma_load_chunk(lane);
-            a[i] = make_uint4(0, 0, 0, 0);
-            b[i] = make_uint4(0, 0, 0, 0);
-            if (ks < n_ks && vec < p.n_vec) {
-                if (n < p.G) a[i] = p.gate_W[(size_t)n * p.n_vec + vec];
-                if (m < p.M) b[i] = p.hidden[(size_t)m * p.n_vec + vec];
+        for (int u = 0; u < 2; ++u) {
+            const int vec = (blk0 + u * bstride) * 16 + q4 * 4 + c4;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int n = gt * 16 + a4 * 4 + t, m = tt * 16 + a4 * 4 + t;
+                a[u][t] = make_uint4(0, 0, 0, 0);
+                b[u][t] = make_uint4(0, 0, 0, 0);
+                if (vec < p.n_vec) {
+                    if (n < p.G) a[u][t] = p.gate_W[(size_t)n * p.n_vec + vec];
+                    if (m < p.M) b[u][t] = p.hidden[(size_t)m * p.n_vec + vec];
+                }
             }
         }
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            acc = mfma_tile<DT>(mfma_operand_from_quads(a[i], lane, reinterpret_cast<uint4*>(part[wave])),
-                                mfma_operand_from_quads(b[i], lane, reinterpret_cast<uint4*>(part[wave])), acc);
+        for (int u = 0; u < 2; ++u) {
+            if (blk0 + u * bstride >= n_blk) break;        // wave-uniform
+            mfma_operands_from_quad_rows(a[u][0], a[u][1], a[u][2], a[u][3], lane);
+            mfma_operands_from_quad_rows(b[u][0], b[u][1], b[u][2], b[u][3], lane);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc = mfma_tile<DT>(a[u][c], b[u][c], acc);
+        }
     }
     *reinterpret_cast<f32x4_t*>(&part[wave][lane * 4]) = acc;
     __syncthreads();
