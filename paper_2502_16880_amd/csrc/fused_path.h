@@ -48,7 +48,7 @@ constexpr int kCollectCap = 128;       // entries per token
 constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
 constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile (k_gate_select: or its operand transposer)
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores (16-bit
-// storage, more than four tokens).
+// storage, four tokens or more).
 enum GateMode { kGateVector = 0, kGateMfma = 1 };
 constexpr int kGateTileFloats = 256;          // a wave's partial 16 x 16 tile
 // Wave-private LDS scratch of the merges: ranking keys, gathered candidates, list tags.
