@@ -147,28 +147,15 @@ __device__ __forceinline__ int wave_scan_inclusive(int x) {
 
 // MFMA operand loads.  v_mfma_f32_16x16x32_bf16 wants lane l to hold row l%16, 16-byte
 // chunk l/16 of a 64-byte step; loading it that way makes neighbouring lanes touch
-// different rows, which the texture addresser handles at a quarter of its rate.  So lane p
-// loads row p/4, chunk p%4 (four neighbouring lanes cover 64 contiguous bytes) and the
-// registers are then moved to the layout the instruction wants: lane l takes lane
-// 4*(l%16) + l/16.
-__device__ __forceinline__ int mfma_load_row(int lane) { return lane >> 2; }
-__device__ __forceinline__ int mfma_load_chunk(int lane) { return lane & 3; }
-// The move goes through a wave-private LDS slice of kQuadSlots 16-byte slots: one
-// ds_write_b128 and one ds_read_b128 per operand (a slot of padding after every 16 keeps
-// both conflict-free); LDS operations of a wave execute in order, so no barrier is needed.
-constexpr int kQuadSlots = 68;
-__device__ __forceinline__ uint4 mfma_operand_from_quads(uint4 v, int lane, uint4* slice) {
-    slice[lane + (lane >> 4)] = v;
-    const int src = ((lane & 15) << 2) | (lane >> 4);
-    return slice[src + (src >> 4)];
-}
-
-// Whole-line variant for streams that would otherwise fetch every 128-byte line in two
-// halves: a wave load covers 8 rows x 128 bytes (lane p: row p/8, chunk p%8 of the line,
+// different rows, which the texture addresser handles at a quarter of its rate.  So tiles
+// are loaded with neighbouring lanes on contiguous bytes and moved to the layout the
+// instruction wants afterwards: in registers (mfma_operands_from_quad_rows below), or
+// through LDS:
+// a wave load covers 8 rows x 128 bytes (lane p: row p/8, chunk p%8 of the line,
 // i.e. both 32-column steps of a step pair), and the two registers that hold rows 0-7 and
 // 8-15 of a tile go through a slice of kLinePairSlots slots together, which yields the
 // operands of both steps (a slot of padding after every 8 keeps writes and reads
-// conflict-free).
+// conflict-free; LDS operations of a wave execute in order, so no barrier is needed).
 __device__ __forceinline__ int line_load_row(int lane) { return lane >> 3; }
 __device__ __forceinline__ int line_load_chunk(int lane) { return lane & 7; }
 constexpr int kLinePairSlots = 144;

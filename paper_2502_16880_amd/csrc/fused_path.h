@@ -46,7 +46,6 @@ constexpr int kLpPiecesMax = 16 * 1024;    // LDS for a workgroup's log-sum-exp 
 // keeping sorted lists, and one wave per token ranks the buffer at the end.
 constexpr int kCollectCap = 128;       // entries per token
 constexpr int kLpGroupCounters = coral_ctrl::kLpGroupArrival - coral_ctrl::kFusedArrival;   // from p.counter
-constexpr int kGateSlice = kQuadSlots * 4;    // floats: a partial tile (k_gate_select: or its operand transposer)
 // How the gate (step 2a) is computed: on the vector units, or on the matrix cores (16-bit
 // storage, four tokens or more).
 enum GateMode { kGateVector = 0, kGateMfma = 1 };

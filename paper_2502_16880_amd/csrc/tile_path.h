@@ -461,8 +461,8 @@ __global__ __launch_bounds__(kTileBlock) void k_tiles(TileParams p, int dense) {
 // Gate and selection for the tile path (Eq. 7's W2 projection, then top-g): one workgroup
 // per tile of 16 groups x 16 tokens and half of the columns (two workgroups share a tile: 32
 // compute units pull the operands instead of 16), the columns split over its 16 waves in
-// steps of 32 (MFMA operands straight from memory: lane l feeds row l%16, 8 columns at
-// 8*(l/16)); the partial tiles are summed in wave order and the two workgroups' sums by
+// blocks of 128 (256 bytes of a row: both operands are loaded four rows x 256 bytes per wave
+// load and transposed in registers); the partial tiles are summed in wave order and the two workgroups' sums by
 // whoever reads the scores, in a fixed order.  The workgroups of one token tile count
 // themselves in on that tile's counter; the one that arrives last has all scores of its 16
 // tokens and ranks them by counting, one wave per token, writes the selection and, per
@@ -487,7 +487,7 @@ __device__ __forceinline__ float load_score(const float* p) {
 
 template <int DT>
 __global__ __launch_bounds__(kFusedBlock) void k_gate_select(GateSelParams p) {
-    __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateSlice];
+    __shared__ __attribute__((aligned(16))) float part[kFusedWaves][kGateTileFloats];
     __shared__ unsigned long long mask[kMaxG];
     __shared__ unsigned long long sel_keys[kFusedWaves][kWave];
     __shared__ int is_last;
