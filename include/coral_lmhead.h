@@ -316,12 +316,14 @@ coral_status coral_lmhead_dense(const void *hidden, const void *lm_W, int M, int
 /*
  * Measurement variants: identical to coral_lmhead_grouped / coral_lmhead_grouped_logprob /
  * coral_lmhead_dense (same operation of section 3.3, same arguments, same results), and in addition
- * record two caller-created HIP events (hipEvent_t passed as void*, created with
- * timing enabled) on hip_stream: ev_before immediately before and ev_after
- * immediately after the launch of the kernel that streams the LM-head weight rows,
- * which is where the appendix paragraph "Backends" locates the head's time.
+ * bind two caller-created HIP events (hipEvent_t passed as void*, created with
+ * timing enabled) to the launch of the kernel that streams the LM-head weight rows,
+ * which is where the appendix paragraph "Backends" locates the head's time: ev_before
+ * takes the time at which that kernel starts, ev_after the time at which it ends.
  * hipEventElapsedTime(ev_before, ev_after) after synchronisation gives that
- * kernel's duration.  Both events are required (CORAL_ERR_NULL otherwise).
+ * kernel's duration, as a kernel trace reports it (no dispatch latency, no gap to the
+ * neighbouring launches).  Both events are required (CORAL_ERR_NULL otherwise).  Not for
+ * use under stream capture.
  */
 coral_status coral_lmhead_grouped_profiled(const void *hidden, const void *gate_W,
                                            const float *gate_bias, const void *lm_W,

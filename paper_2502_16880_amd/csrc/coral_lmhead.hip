@@ -18,6 +18,7 @@
 // A group selected by several tokens is read once for all of them (the union of the
 // tokens' groups that the appendix's tree-decoding paragraph activates).
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <limits.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -133,10 +134,19 @@ inline coral_status launch_status() {
     return hipGetLastError() == hipSuccess ? CORAL_OK : CORAL_ERR_HIP;
 }
 
-coral_status record(void* ev, hipStream_t stream) {
-    if (!ev) return CORAL_OK;
-    return hipEventRecord(static_cast<hipEvent_t>(ev), stream) == hipSuccess ? CORAL_OK
-                                                                             : CORAL_ERR_HIP;
+// Launch of the kernel that streams the weight rows.  The measurement entry points pass two
+// events: they are bound to this launch and take the kernel's own start and stop times (what
+// a kernel trace reports as its duration), not the times at which event records before and
+// after it would be reached, which include the dispatch latency.
+template <class F, class... Args>
+coral_status launch_timed(F fn, dim3 grid, dim3 block, size_t lds, hipStream_t stream, void* ev_before,
+                          void* ev_after, Args... args) {
+    if (ev_before && ev_after)
+        hipExtLaunchKernelGGL(fn, grid, block, (uint32_t)lds, stream, static_cast<hipEvent_t>(ev_before),
+                              static_cast<hipEvent_t>(ev_after), 0, args...);
+    else
+        hipLaunchKernelGGL(fn, grid, block, lds, stream, args...);
+    return launch_status();
 }
 
 // The only state the library keeps between calls: per device, the number of compute units
@@ -328,11 +338,7 @@ coral_status launch_fused(bool dense, const void* hidden, const void* gate_hidde
                            CORAL_FUSED_GATES(kF16, false, false));
 #undef CORAL_FUSED_GATES
     if (!allow_lds(reinterpret_cast<const void*>(fn), F.total)) return CORAL_ERR_HIP;
-    coral_status st;
-    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
-    hipLaunchKernelGGL(fn, dim3(P), dim3(kFusedBlock), F.total, stream, p);
-    if ((st = launch_status()) != CORAL_OK) return st;
-    return record(ev_after, stream);
+    return launch_timed(fn, dim3(P), dim3(kFusedBlock), F.total, stream, ev_before, ev_after, p);
 }
 
 // The dense head goes to the matrix-core path from 8 tokens on, if the vocabulary gives every
@@ -441,10 +447,9 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
     const tiles_fn fn = dt == CORAL_F16 ? k_tiles<kF16> : k_tiles<kBF16>;
     if (!allow_lds(reinterpret_cast<const void*>(fn), lds)) return CORAL_ERR_HIP;
     coral_status st;
-    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
-    hipLaunchKernelGGL(fn, dim3(P), dim3(kTileBlock), lds, stream, p, dense ? 1 : 0);
-    if ((st = launch_status()) != CORAL_OK) return st;
-    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
+    if ((st = launch_timed(fn, dim3(P), dim3(kTileBlock), lds, stream, ev_before, ev_after, p, dense ? 1 : 0)) !=
+        CORAL_OK)
+        return st;
 
     TileSelectParams q = {};
     q.z = p.z;
@@ -674,7 +679,6 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
     const long long union_max = max_union(M, G, g);
     if (chunks < 1) return CORAL_ERR_SHAPE;
     dim3 grid(chunks, (unsigned)union_max);
-    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     typedef void (*logits_fn)(LogitsParams);
     const logits_fn fn =
         logprob ? CORAL_PICK_DT(dt, (k_logits<kF32, false, true>), (k_logits<kBF16, false, true>),
@@ -682,9 +686,7 @@ coral_status grouped_impl(const void* hidden, const void* gate_hidden, const voi
                 : CORAL_PICK_DT(dt, (k_logits<kF32, false, false>), (k_logits<kBF16, false, false>),
                                 (k_logits<kF16, false, false>));
     if (!allow_lds(reinterpret_cast<const void*>(fn), (int)lds)) return CORAL_ERR_HIP;
-    hipLaunchKernelGGL(fn, grid, dim3(kBlock), lds, stream, p);
-    if ((st = launch_status()) != CORAL_OK) return st;
-    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
+    if ((st = launch_timed(fn, grid, dim3(kBlock), lds, stream, ev_before, ev_after, p)) != CORAL_OK) return st;
     if (logprob)
         hipLaunchKernelGGL(k_merge_logprob<4>, dim3(M), dim3(kBlock), 0, stream, part, p.lse_part,
                            L.part_stride, reinterpret_cast<const int32_t*>(ws + L.slot_count), chunk_base,
@@ -734,13 +736,10 @@ coral_status dense_impl(const void* hidden, const void* lm_W, int M, int H, int 
     p.part_stride = L.part_stride;
     const size_t lds = logits_lds_bytes(p.tb_max, p.jp, k);
     const int chunks = (V + kChunkRows - 1) / kChunkRows;
-    if ((st = record(ev_before, stream)) != CORAL_OK) return st;
     typedef void (*logits_fn)(LogitsParams);
     const logits_fn fn = CORAL_PICK_DT(dt, (k_logits<kF32, true>), (k_logits<kBF16, true>), (k_logits<kF16, true>));
     if (!allow_lds(reinterpret_cast<const void*>(fn), (int)lds)) return CORAL_ERR_HIP;
-    hipLaunchKernelGGL(fn, dim3(chunks), dim3(kBlock), lds, stream, p);
-    if ((st = launch_status()) != CORAL_OK) return st;
-    if ((st = record(ev_after, stream)) != CORAL_OK) return st;
+    if ((st = launch_timed(fn, dim3(chunks), dim3(kBlock), lds, stream, ev_before, ev_after, p)) != CORAL_OK) return st;
     hipLaunchKernelGGL(k_merge, dim3(M), dim3(kBlock), 0, stream, p.part, L.part_stride,
                        (const int32_t*)nullptr, (const int32_t*)nullptr, 0, chunks, k, topk_ids,
                        topk_logits);

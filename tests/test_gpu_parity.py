@@ -4,6 +4,8 @@ Bar: groups and ids bit-exact wherever the oracle's neighbouring values are more
 the float tolerance apart; logits within 2e-3 (bf16 storage, fp32 accumulation) or 1e-5
 (fp32 storage).  The rules are in oracle/compare.py.
 """
+import time
+
 import numpy as np
 import pytest
 
@@ -553,6 +555,40 @@ def test_caller_buffers_and_streams(coral):
     with pytest.raises(coral.CoralError) as e:
         coral.coral_lmhead_dense(d_hidden, dh.lm_W, cfg.k, workspace=small)
     assert e.value.status == 5
+
+
+@pytest.mark.parametrize("name,M", [("llama2_7b_scaled", 8), ("tiny_f32", 4), ("wide_tree_scaled", 64),
+                                    ("staged_f16", 8)])
+def test_measurement_entry_points_time_the_kernel_and_change_nothing(coral, name, M):
+    """The *_profiled variants return what the plain calls return, bit for bit, and the two
+    events they bind to the weight-streaming kernel read a plausible duration: positive, and
+    no longer than the whole call takes between two synchronisations."""
+    cfg = {"llama2_7b_scaled": CONFIGS["llama2_7b"].scaled(name="llama2_s", V=16 * 250),
+           "tiny_f32": CONFIGS["tiny_f32"],
+           "wide_tree_scaled": CONFIGS["wide_tree"].scaled(name="wide_s", V=64 * 130),
+           "staged_f16": CONFIGS["llama3_8b"].scaled(name="l3_h4160", dtype="f16", V=32 * 203, H=4160)}[name]
+    dh = DeviceHead(coral, make_head(cfg))
+    d_hidden = coral.device_tensor(make_hidden(cfg, M), cfg.dtype)
+    plain = coral.coral_lmhead_grouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k)
+    dense_plain = coral.coral_lmhead_dense(d_hidden, dh.lm_W, cfg.k)
+    torch.cuda.synchronize()
+    for which in ("grouped", "dense"):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(), b.record()                             # creates the handles
+        torch.cuda.synchronize()
+        for rep in range(2):                               # the second call is warm
+            t0 = time.perf_counter()
+            if which == "grouped":
+                out = coral.coral_lmhead_grouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                                 events=(a.cuda_event, b.cuda_event))
+            else:
+                out = coral.coral_lmhead_dense(d_hidden, dh.lm_W, cfg.k, events=(a.cuda_event, b.cuda_event))
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t0) * 1e3
+        kernel_ms = a.elapsed_time(b)
+        assert 0.0 < kernel_ms <= wall_ms, (which, kernel_ms, wall_ms)
+        for x, y in zip(out, plain if which == "grouped" else dense_plain):
+            assert torch.equal(x, y), which
 
 
 def test_many_calls_on_one_workspace_stay_consistent(coral):
