@@ -209,19 +209,11 @@ def alloc_workspace(M, H, V, G, g, k, dt, device="cuda", stream=None) -> torch.T
     return ws
 
 
-def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
-                         gate_bias: Optional[torch.Tensor], lm_W: torch.Tensor, gi: GroupIndex,
-                         g: int, k: int, topk_ids: Optional[torch.Tensor] = None,
-                         topk_logits: Optional[torch.Tensor] = None,
-                         sel_groups: Optional[torch.Tensor] = None,
-                         workspace: Optional[torch.Tensor] = None, stream=None, events=None,
-                         logprob: bool = False, gate_hidden: Optional[torch.Tensor] = None,
-                         level=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-    """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry.
-    logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x)).
-    gate_hidden: call coral_lmhead_grouped_routed (the router sees this [M,H] tensor).
-    level: (parent_score or None, n_next, next_parent, next_token, next_score): call
-    coral_lmhead_draft_level (see coral_lmhead_draft_level below)."""
+def _marshal_grouped(hidden, gate_W, gate_bias, lm_W, gi, g, k, topk_ids, topk_logits, sel_groups,
+                     workspace, stream, events, logprob, gate_hidden, level):
+    """Checks and marshals the arguments of the grouped entry points once: returns the entry
+    point, its arguments up to (not including) the stream, those behind the stream, and the
+    output tensors."""
     dt = _dtype_code(hidden)
     if gate_W.dtype != hidden.dtype or lm_W.dtype != hidden.dtype:
         raise TypeError("hidden, gate_W and lm_W must share one dtype")
@@ -249,31 +241,74 @@ def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
             M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
             _dev_ptr(topk_logits, "topk_logits", torch.float32),
             _dev_ptr(sel_groups, "sel_groups", torch.int32), _dev_ptr(workspace, "workspace"),
-            workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+            workspace.numel() * workspace.element_size())
     if gate_hidden is not None and (gate_hidden.dtype != hidden.dtype or gate_hidden.shape != hidden.shape):
         raise ValueError("gate_hidden must match hidden in dtype and shape")
+    behind = ()
     if level is not None:
         if events is not None:
             raise ValueError("the draft-level entry point has no measurement variant")
         parent_score, n_next, next_parent, next_token, next_score = level
-        st = _L.coral_lmhead_draft_level(
-            args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
-            _dev_ptr(parent_score, "parent_score", torch.float32), int(n_next), *args[11:14],
-            _dev_ptr(next_parent, "next_parent", torch.int32),
-            _dev_ptr(next_token, "next_token", torch.int32),
-            _dev_ptr(next_score, "next_score", torch.float32), *args[14:])
+        fn = _L.coral_lmhead_draft_level
+        args = (args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
+                _dev_ptr(parent_score, "parent_score", torch.float32), int(n_next), *args[11:14],
+                _dev_ptr(next_parent, "next_parent", torch.int32),
+                _dev_ptr(next_token, "next_token", torch.int32),
+                _dev_ptr(next_score, "next_score", torch.float32), *args[14:])
     elif gate_hidden is not None:
         if events is not None:
             raise ValueError("the routed entry point has no measurement variant")
-        st = _L.coral_lmhead_grouped_routed(args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11],
-                                            1 if logprob else 0, *args[11:])
+        fn = _L.coral_lmhead_grouped_routed
+        args = (args[0], _dev_ptr(gate_hidden, "gate_hidden"), *args[1:11], 1 if logprob else 0, *args[11:])
     elif events is None:
-        st = (_L.coral_lmhead_grouped_logprob if logprob else _L.coral_lmhead_grouped)(*args)
+        fn = _L.coral_lmhead_grouped_logprob if logprob else _L.coral_lmhead_grouped
     else:
         fn = _L.coral_lmhead_grouped_logprob_profiled if logprob else _L.coral_lmhead_grouped_profiled
-        st = fn(*args, events[0], events[1])
-    _raise(st)
-    return topk_ids, topk_logits, sel_groups
+        behind = (events[0], events[1])
+    keep = (hidden, gate_W, gate_bias, lm_W, gi, workspace, gate_hidden, level)
+    return fn, args, behind, (topk_ids, topk_logits, sel_groups), keep
+
+
+def coral_lmhead_grouped(hidden: torch.Tensor, gate_W: torch.Tensor,
+                         gate_bias: Optional[torch.Tensor], lm_W: torch.Tensor, gi: GroupIndex,
+                         g: int, k: int, topk_ids: Optional[torch.Tensor] = None,
+                         topk_logits: Optional[torch.Tensor] = None,
+                         sel_groups: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None, events=None,
+                         logprob: bool = False, gate_hidden: Optional[torch.Tensor] = None,
+                         level=None) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """events: optional (hipEvent_t, hipEvent_t) raw handles; selects the _profiled entry.
+    logprob: call coral_lmhead_grouped_logprob (the second result then holds log p(x)).
+    gate_hidden: call coral_lmhead_grouped_routed (the router sees this [M,H] tensor).
+    level: (parent_score or None, n_next, next_parent, next_token, next_score): call
+    coral_lmhead_draft_level (see coral_lmhead_draft_level below)."""
+    fn, args, behind, out, _ = _marshal_grouped(hidden, gate_W, gate_bias, lm_W, gi, g, k, topk_ids,
+                                                topk_logits, sel_groups, workspace, stream, events,
+                                                logprob, gate_hidden, level)
+    _raise(fn(*args, _stream_ptr(stream), *behind))
+    return out
+
+
+class PreparedGrouped:
+    """A grouped-head call whose arguments are checked and marshalled once, for loops that
+    issue the same call many times (a draft loop, a benchmark): calling the object only looks
+    the stream up and enters the library.  Takes coral_lmhead_grouped's arguments (a workspace
+    is required: the call must not allocate); .out holds the output tensors.  The tensors are
+    kept alive by the object and must not be resized or freed while it is in use."""
+
+    def __init__(self, hidden, gate_W, gate_bias, lm_W, gi, g, k, workspace, topk_ids=None,
+                 topk_logits=None, sel_groups=None, logprob=False, gate_hidden=None, level=None):
+        if workspace is None:
+            raise ValueError("a prepared call needs its workspace")
+        self._fn, self._args, _, self.out, self._keep = _marshal_grouped(
+            hidden, gate_W, gate_bias, lm_W, gi, g, k, topk_ids, topk_logits, sel_groups, workspace,
+            None, None, logprob, gate_hidden, level)
+
+    def __call__(self, stream=None):
+        st = self._fn(*self._args, _stream_ptr(stream))
+        if st:
+            _raise(st)
+        return self.out
 
 
 NOALLOC_SCRATCH_BYTES = 8 << 20      # CORAL_NOALLOC_SCRATCH_BYTES of the header

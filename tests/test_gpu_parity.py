@@ -591,6 +591,32 @@ def test_measurement_entry_points_time_the_kernel_and_change_nothing(coral, name
             assert torch.equal(x, y), which
 
 
+def test_prepared_call_is_the_plain_call(coral):
+    """PreparedGrouped marshals once and enters the same entry point: same results, bit for
+    bit, also on another stream and in the log-probability mode."""
+    cfg = CONFIGS["llama2_7b"].scaled(name="llama2_s", V=16 * 250)
+    dh = DeviceHead(coral, make_head(cfg))
+    d_hidden = coral.device_tensor(make_hidden(cfg, 8), cfg.dtype)
+    ws = coral.alloc_workspace(8, cfg.H, cfg.V, cfg.G, cfg.g, cfg.k, coral.CORAL_BF16)
+    for logprob in (False, True):
+        plain = coral.coral_lmhead_grouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k,
+                                           workspace=ws, logprob=logprob)
+        torch.cuda.synchronize()
+        plain = [t.clone() for t in plain]
+        prep = coral.PreparedGrouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k, ws,
+                                     logprob=logprob)
+        prep()
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(st):
+            out = prep()
+        st.synchronize()
+        for x, y in zip(out, plain):
+            assert torch.equal(x, y)
+    with pytest.raises(ValueError):
+        coral.PreparedGrouped(d_hidden, dh.gate_W, dh.bias, dh.lm_W, dh.gi, cfg.g, cfg.k, None)
+
+
 def test_many_calls_on_one_workspace_stay_consistent(coral):
     """The single-launch path hands partial lists between workgroups through memory and
     re-arms its counters itself: 300 back-to-back calls on one workspace, alternating two
