@@ -328,7 +328,7 @@ def test_random_small_heads(coral, seed):
     G = int(rng.integers(1, 65))
     g = int(rng.integers(1, min(G, 16) + 1))
     M = int(rng.integers(1, 25))
-    dtype = "f32" if seed < 300 else ("bf16", "f16")[seed % 2]  # 16-bit: matrix-core gate from 5 tokens on
+    dtype = "f32" if seed < 300 else ("bf16", "f16")[seed % 2]  # 16-bit: matrix-core gate from 4 tokens on
     H = int(rng.choice([32, 64, 100, 256, 516] if dtype == "f32" else [64, 104, 256, 512]))
     if seed >= 400:                                             # many tokens x long rows: the tile path
         M, H = int(rng.integers(41, 65)), 2048
