@@ -249,9 +249,15 @@ __host__ __device__ inline size_t premix_wide_lds_bytes() {
 
 template <int DT, int NCT>
 __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p) {
-    // NB staging buffers of 16 NCT token slots, chunks staged NB - 1 ahead.  (With few tokens
-    // the space would hold more buffers; staging further ahead measured no faster.)
-    constexpr int NB = 2;
+    // NB staging buffers of 16 NCT token slots.  Loads return in order, so a token chunk
+    // requested behind the weight lines would arrive only after the last of them: with one
+    // or two token tiles every chunk's tokens are therefore requested first of all (they fit
+    // the registers: 16 or 32 vectors per lane), staged as buffers come free, and the chunk
+    // loop waits for nothing but its own weight lines.  With more token tiles the next
+    // chunk's tokens are requested at the top of a chunk and staged at its end, behind the
+    // weight lines (there the tokens' share of the work dominates anyway).
+    constexpr int NB = NCT == 1 ? 8 : NCT == 2 ? 4 : 2;
+    constexpr bool kUpFront = NCT <= 2;
     constexpr int D = NB - 1;
     constexpr int kBufVecs = 16 * NCT * kPremixHbStride;
     static_assert(NB * kBufVecs <= 2 * kPremixHbVecs, "the buffers fit the staging space");
@@ -264,13 +270,28 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
     const int r0 = blockIdx.x * 16;
     const int n_chunks = p.n_vec / kPremixChunkVecs;
 
-    // token of slot wave + 8 i; slots past the last token repeat it (never stored to u)
+    // The residual term of the result this thread will write at the very end (feature and
+    // token as in the last loop below): requested now, so that no trip to memory is left
+    // behind the last weight line.
+    constexpr int kOutPerThread = (NCT * 256 + kPremixWideBlock - 1) / kPremixWideBlock;
+    unsigned short h_res[kOutPerThread];
+#pragma unroll
+    for (int j = 0; j < kOutPerThread; ++j) {
+        const int e = threadIdx.x + j * kPremixWideBlock;
+        const int ct = e >> 8, l = (e & 255) >> 2, i = e & 3;
+        const int row = r0 + (l >> 4) * 4 + i, tok = ct * 16 + (l & 15);
+        h_res[j] = 0;
+        if (e < NCT * 256 && tok < p.M)
+            h_res[j] = reinterpret_cast<const unsigned short*>(p.hidden)[(size_t)tok * p.H + row];
+    }
+    // token of slot wave + 8 i; slots past the last token hold zeros (never stored to u)
     auto fetch = [&](int c, uint4 (&st)[2 * NCT]) {
         const uint4* src = p.hidden + c * kPremixChunkVecs + lane;
 #pragma unroll
         for (int i = 0; i < 2 * NCT; ++i) {
             const int s = wave + i * kPremixWideWaves;
-            st[i] = load_vec(src + (size_t)(s < p.M ? s : p.M - 1) * p.n_vec);
+            st[i] = make_uint4(0, 0, 0, 0);
+            if (s < p.M) st[i] = load_vec(src + (size_t)s * p.n_vec);      // wave-uniform
         }
     };
     auto stage = [&](int c, const uint4 (&st)[2 * NCT]) {
@@ -278,10 +299,11 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
 #pragma unroll
         for (int i = 0; i < 2 * NCT; ++i) store_vec(dst + (size_t)i * kPremixWideWaves * kPremixHbStride, st[i]);
     };
-    uint4 first[D][2 * NCT];
+    constexpr int kHeld = kUpFront ? kPremixMaxChunks : D;
+    uint4 tk[kHeld][2 * NCT];
 #pragma unroll
-    for (int c = 0; c < D; ++c)
-        if (c < n_chunks) fetch(c, first[c]);          // block-uniform
+    for (int c = 0; c < kHeld; ++c)
+        if (c < n_chunks) fetch(c, tk[c]);             // block-uniform
     asm volatile("" ::: "memory");                     // (keeps the order: tokens first, they return first)
     uint4 lo[kPremixMaxChunks], hi[kPremixMaxChunks];
     const uint4* wlo = p.W1 + (size_t)(r0 + line_load_row(lane)) * p.n_vec + wave * 8 + line_load_chunk(lane);
@@ -297,8 +319,23 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
     }
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int c = 0; c < D; ++c)
-        if (c < n_chunks) stage(c, first[c]);
+    for (int c = 0; c < (kUpFront ? NB : D); ++c)
+        if (c < n_chunks) stage(c, tk[c]);
+    // The memory serves requests in the order it got them, and the other workgroups' weight
+    // lines are ahead of a late workgroup's tokens: the last tokens arrive when most of W1
+    // has (5 of 6.5 us at 8 tokens).  While the workgroup waits for them at the barrier, every
+    // wave moves the weight lines it has got to the operand layout (its own lines, its own
+    // LDS slice), so that only operand reads and matrix instructions are left behind it.
+    if (kUpFront) {
+#pragma unroll
+        for (int c = 0; c < kPremixMaxChunks; ++c)
+            if (c < n_chunks) {                        // block-uniform
+                uint4 s0, s1;
+                mfma_operands_from_lines(lo[c], hi[c], lane, my_slice, s0, s1);
+                lo[c] = s0;
+                hi[c] = s1;
+            }
+    }
     __syncthreads();
     f32x4_t acc[NCT];
 #pragma unroll
@@ -306,12 +343,12 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
 #pragma unroll
     for (int c = 0; c < kPremixMaxChunks; ++c) {
         if (c < n_chunks) {                            // block-uniform
-            const bool more = c + D < n_chunks;
+            const bool more = kUpFront ? c + NB < n_chunks : c + D < n_chunks;
             uint4 st[2 * NCT];
-            if (more) fetch(c + D, st);
+            if (!kUpFront && more) fetch(c + D, st);
             asm volatile("" ::: "memory");
-            uint4 s0, s1;
-            mfma_operands_from_lines(lo[c], hi[c], lane, my_slice, s0, s1);
+            uint4 s0 = lo[c], s1 = hi[c];
+            if (!kUpFront) mfma_operands_from_lines(lo[c], hi[c], lane, my_slice, s0, s1);
             const uint4* hb = hbuf + (size_t)(c % NB) * kBufVecs + wave * 8 + q4;
 #pragma unroll
             for (int ct = 0; ct < NCT; ++ct) {
@@ -320,9 +357,21 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
                 acc[ct] = mfma_tile<DT>(s0, b0, acc[ct]);
                 acc[ct] = mfma_tile<DT>(s1, b1, acc[ct]);
             }
-            // buffer (c + D) % NB = (c - 1) % NB was last read in chunk c - 1, before its barrier
-            if (more) stage(c + D, st);
-            if (c + 1 < n_chunks) __syncthreads();
+            if (kUpFront) {
+                // buffer c % NB is free once every wave has read chunk c: its next tenant,
+                // chunk c + NB, has been waiting in registers
+                if (more) {
+                    __syncthreads();
+                    if (c + NB < kPremixMaxChunks) stage(c + NB, tk[c + NB < kHeld ? c + NB : 0]);
+                    // (the next chunk's barrier, if it has one, also stands between this
+                    // write and the reads of chunk c + NB)
+                    if (!(c + 1 + NB < n_chunks)) __syncthreads();
+                }
+            } else {
+                // buffer (c + D) % NB = (c - 1) % NB was last read in chunk c - 1, before its barrier
+                if (more) stage(c + D, st);
+                if (c + 1 < n_chunks) __syncthreads();
+            }
         }
     }
     __syncthreads();                                   // every wave is done with the staging buffers
@@ -333,17 +382,18 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
     for (int ct = 0; ct < NCT; ++ct)
         *reinterpret_cast<f32x4_t*>(red + ((size_t)wave * NCT + ct) * 256 + lane * 4) = acc[ct];
     __syncthreads();
-    for (int e = threadIdx.x; e < NCT * 256; e += kPremixWideBlock) {
+#pragma unroll
+    for (int j = 0; j < kOutPerThread; ++j) {
+        const int e = threadIdx.x + j * kPremixWideBlock;
+        if (e >= NCT * 256) break;
         const int ct = e >> 8, l = (e & 255) >> 2, i = e & 3;
         const int row = r0 + (l >> 4) * 4 + i, tok = ct * 16 + (l & 15);
         float y = 0.f;
 #pragma unroll
         for (int w = 0; w < kPremixWideWaves; ++w) y += red[((size_t)w * NCT + ct) * 256 + (e & 255)];
-        if (tok < p.M) {
-            const size_t at = (size_t)tok * p.H + row;
-            const unsigned short h = reinterpret_cast<const unsigned short*>(p.hidden)[at];
-            static_cast<unsigned short*>(p.out)[at] = narrow16<DT>(premix_act(y, p.act) + widen16<DT>(h));
-        }
+        if (tok < p.M)
+            static_cast<unsigned short*>(p.out)[(size_t)tok * p.H + row] =
+                narrow16<DT>(premix_act(y, p.act) + widen16<DT>(h_res[j]));
     }
 }
 
