@@ -605,7 +605,7 @@ __global__ __launch_bounds__(kFusedBlock) void k_fused(FusedParams p) {
     // ---- 1. hidden vectors: requested first, written to LDS only after the grouped
     // variants have requested their first gate rows as well (loads return in order, so the
     // wait for the hidden vectors does not wait for the gate rows behind them)
-    constexpr int kHU = 8;
+    constexpr int kHU = 4;
     const int row_vecs = p.jp * kWave;                     // <= 512: at least 2 rows a pass
     int h_mm = threadIdx.x / row_vecs;
     int h_vec = threadIdx.x - h_mm * row_vecs;
