@@ -842,10 +842,16 @@ extern "C" coral_status coral_router_premix(const void* hidden, const void* W1, 
         typedef void (*wide_fn)(PremixParams);
         const int n_ct = (M + 15) / 16;
         const bool f16 = dt == CORAL_F16;
-        const wide_fn wf = n_ct == 1 ? (f16 ? k_premix_wide<kF16, 1> : k_premix_wide<kBF16, 1>)
-                         : n_ct == 2 ? (f16 ? k_premix_wide<kF16, 2> : k_premix_wide<kBF16, 2>)
-                         : n_ct == 3 ? (f16 ? k_premix_wide<kF16, 3> : k_premix_wide<kBF16, 3>)
-                                     : (f16 ? k_premix_wide<kF16, 4> : k_premix_wide<kBF16, 4>);
+        // (three or four token tiles at the full width of 8 chunks: both streams issued a few
+        // chunks ahead, see k_premix_wide)
+        const bool ring = n_ct >= 3 && p.n_vec / kPremixChunkVecs == kPremixMaxChunks;
+        const wide_fn wf =
+            n_ct == 1   ? (f16 ? k_premix_wide<kF16, 1> : k_premix_wide<kBF16, 1>)
+            : n_ct == 2 ? (f16 ? k_premix_wide<kF16, 2> : k_premix_wide<kBF16, 2>)
+            : n_ct == 3 ? (ring ? (f16 ? k_premix_wide<kF16, 3, true> : k_premix_wide<kBF16, 3, true>)
+                                : (f16 ? k_premix_wide<kF16, 3> : k_premix_wide<kBF16, 3>))
+                        : (ring ? (f16 ? k_premix_wide<kF16, 4, true> : k_premix_wide<kBF16, 4, true>)
+                                : (f16 ? k_premix_wide<kF16, 4> : k_premix_wide<kBF16, 4>));
         const int lds = (int)premix_wide_lds_bytes();
         if (!allow_lds(reinterpret_cast<const void*>(wf), lds)) return CORAL_ERR_HIP;
         hipLaunchKernelGGL(wf, dim3(H / 16), dim3(kPremixWideBlock), lds, stream, p);

@@ -247,7 +247,7 @@ __host__ __device__ inline size_t premix_wide_lds_bytes() {
     return ((size_t)2 * kPremixHbVecs + (size_t)kPremixWideWaves * kLinePairSlots) * sizeof(uint4);
 }
 
-template <int DT, int NCT>
+template <int DT, int NCT, bool RING = false>
 __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p) {
     // NB staging buffers of 16 NCT token slots.  Loads return in order, so a token chunk
     // requested behind the weight lines would arrive only after the last of them: with one
@@ -256,6 +256,12 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
     // loop waits for nothing but its own weight lines.  With more token tiles the next
     // chunk's tokens are requested at the top of a chunk and staged at its end, behind the
     // weight lines (there the tokens' share of the work dominates anyway).
+    // RING (three or four token tiles, H = 4096: every loop bound a constant, so that the
+    // compiler's wait counts are exact): the tokens do not fit the registers whole, so both
+    // streams are issued a few chunks ahead instead, interleaved in the order in which they
+    // are wanted: tokens of chunk c + 2, then weight lines of chunk c + 4, at the top of
+    // chunk c.  A wait for a chunk's tokens then leaves only younger requests outstanding.
+    static_assert(!RING || NCT >= 3, "the ring is for token batches that do not fit the registers");
     constexpr int NB = NCT == 1 ? 8 : NCT == 2 ? 4 : 2;
     constexpr bool kUpFront = NCT <= 2;
     constexpr int D = NB - 1;
@@ -299,6 +305,76 @@ __global__ __launch_bounds__(kPremixWideBlock) void k_premix_wide(PremixParams p
 #pragma unroll
         for (int i = 0; i < 2 * NCT; ++i) store_vec(dst + (size_t)i * kPremixWideWaves * kPremixHbStride, st[i]);
     };
+    if (RING) {
+        constexpr int kN = kPremixMaxChunks;
+        uint4 tka[2 * NCT], tkb[2 * NCT];              // token chunks: even ones in tka, odd ones in tkb
+        uint4 lo[kN], hi[kN];
+        const uint4* wlo = p.W1 + (size_t)(r0 + line_load_row(lane)) * p.n_vec + wave * 8 + line_load_chunk(lane);
+        const uint4* whi = wlo + (size_t)8 * p.n_vec;
+        auto lines = [&](int c) {
+            lo[c] = load_stream(wlo + c * kPremixChunkVecs);
+            hi[c] = load_stream(whi + c * kPremixChunkVecs);
+        };
+        fetch(0, tka);
+        asm volatile("" ::: "memory");
+        lines(0);
+        asm volatile("" ::: "memory");
+        fetch(1, tkb);
+        asm volatile("" ::: "memory");
+        lines(1);
+        lines(2);
+        lines(3);
+        asm volatile("" ::: "memory");
+        stage(0, tka);
+        __syncthreads();
+        f32x4_t acc[NCT];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct) acc[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < kN; ++c) {
+            if (c + 2 < kN) {                          // (chunk c's tokens left these registers before the last barrier)
+                if (c % 2 == 0) fetch(c + 2, tka); else fetch(c + 2, tkb);
+            }
+            asm volatile("" ::: "memory");
+            if (c + 4 < kN) lines(c + 4);
+            asm volatile("" ::: "memory");
+            uint4 s0, s1;
+            mfma_operands_from_lines(lo[c], hi[c], lane, my_slice, s0, s1);
+            const uint4* hb = hbuf + (size_t)(c % NB) * kBufVecs + wave * 8 + q4;
+#pragma unroll
+            for (int ct = 0; ct < NCT; ++ct) {
+                const uint4 b0 = hb[(ct * 16 + r16) * kPremixHbStride];
+                const uint4 b1 = hb[(ct * 16 + r16) * kPremixHbStride + 4];
+                acc[ct] = mfma_tile<DT>(s0, b0, acc[ct]);
+                acc[ct] = mfma_tile<DT>(s1, b1, acc[ct]);
+            }
+            // buffer (c + 1) % 2 was last read in chunk c - 1, before its barrier
+            if (c + 1 < kN) {
+                if ((c + 1) % 2 == 0) stage(c + 1, tka); else stage(c + 1, tkb);
+                __syncthreads();
+            }
+        }
+        __syncthreads();                               // every wave is done with the staging buffers
+        float* red = reinterpret_cast<float*>(hbuf);   // [wave][token tile][256]
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+            *reinterpret_cast<f32x4_t*>(red + ((size_t)wave * NCT + ct) * 256 + lane * 4) = acc[ct];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kOutPerThread; ++j) {
+            const int e = threadIdx.x + j * kPremixWideBlock;
+            if (e >= NCT * 256) break;
+            const int ct = e >> 8, l = (e & 255) >> 2, i = e & 3;
+            const int row = r0 + (l >> 4) * 4 + i, tok = ct * 16 + (l & 15);
+            float y = 0.f;
+#pragma unroll
+            for (int w = 0; w < kPremixWideWaves; ++w) y += red[((size_t)w * NCT + ct) * 256 + (e & 255)];
+            if (tok < p.M)
+                static_cast<unsigned short*>(p.out)[(size_t)tok * p.H + row] =
+                    narrow16<DT>(premix_act(y, p.act) + widen16<DT>(h_res[j]));
+        }
+        return;
+    }
     constexpr int kHeld = kUpFront ? kPremixMaxChunks : D;
     uint4 tk[kHeld][2 * NCT];
 #pragma unroll
