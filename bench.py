@@ -57,6 +57,10 @@ def parse():
                          "'none': headline only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="no HIP graph: one host call per step")
+    ap.add_argument("--read-yardstick", action="store_true",
+                    help="instead of the head: time the library's read-only kernel (coral_probe_read) in the "
+                         "single-launch path's shape on as many bytes as the configured steps move, and on "
+                         "the pre-mix's one round, buffers cycled past the last-level cache; prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run five 1 GiB device-to-device copies (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
@@ -498,8 +502,45 @@ def other_shapes(a, n, cases):
                                      f"k_tile_select; kernel_us is k_tiles alone), {mode}"))
 
 
+def read_yardstick():
+    """What a kernel that only reads takes for the bytes of the configured steps (the kernel's
+    own start-to-stop time by events bound to its launch; median of 50 launches per size)."""
+    import torch
+    import paper_2502_16880_amd as coral
+    from coral_inputs import CONFIGS
+    torch.cuda.set_device(0)
+    pool = torch.empty(3 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cfg = CONFIGS["llama3_8b"]
+    row = cfg.H * weight_bytes_per_elt(cfg.dtype)
+    sizes = [("pre-mix W1, one round of 8 waves per compute unit", cfg.H * row, 8)]
+    for M, U in ((1, 4.0), (4, 13.08), (8, 20.79), (16, 28.38)):
+        sizes.append((f"grouped step M={M} ({U} activated groups)", int(U * cfg.v) * row, 16))
+    sizes.append(("dense head", cfg.V * row, 16))
+    out = []
+    for label, nbytes, waves in sizes:
+        nbytes = nbytes // 16384 * 16384
+        copies = max(1, pool.numel() // nbytes)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(), b.record()
+        torch.cuda.synchronize()
+        ts = []
+        for it in range(60):
+            src = pool[(it % copies) * nbytes:]
+            coral.coral_probe_read(src, nbytes, waves, (a.cuda_event, b.cuda_event))
+            torch.cuda.synchronize()
+            if it >= 10:
+                ts.append(a.elapsed_time(b) * 1e3)
+        ts.sort()
+        us = ts[len(ts) // 2]
+        out.append({"what": label, "bytes": nbytes, "us_p50": us, "us_min": ts[0], "us_p90": ts[len(ts) * 9 // 10],
+                    "GBps": nbytes / us / 1e3, "frac_of_8TBps": nbytes / us / 1e3 / HBM_PEAK_GBPS})
+    print(json.dumps({"read_yardstick": out}))
+
+
 def main():
     a = parse()
+    if a.read_yardstick:
+        return read_yardstick()
     if a.gpus != 1:
         print(f"bench.py measures one GPU; --gpus {a.gpus} is not supported by this build "
               "(no collectives are part of it)", file=sys.stderr)

@@ -347,6 +347,20 @@ coral_status coral_lmhead_dense_profiled(const void *hidden, const void *lm_W, i
                                          void *hip_stream, void *ev_before,
                                          void *ev_after);
 
+/*
+ * Measurement aid, no part of the method: a kernel that only reads, in the launch shape of
+ * the single-launch path (one workgroup per compute unit, `waves` waves of 64 lanes each,
+ * 1..16; every wave takes 16 KB pieces of src, dealt round robin, 16 loads of 1 KB in flight
+ * per piece, non-temporal like the weight rows).  What it takes for as many bytes as a step
+ * of section 3.3 must move is the yardstick the bench line's figures are held against.
+ *   src   [device] at least `bytes` bytes, 16-byte aligned; read once, nothing is written
+ *   bytes a multiple of 16384
+ *   ev_before, ev_after  as for the *_profiled entry points (both required)
+ * Returns CORAL_OK, CORAL_ERR_NULL, CORAL_ERR_SHAPE, CORAL_ERR_UNSUPPORTED or CORAL_ERR_HIP.
+ */
+coral_status coral_probe_read(const void *src, size_t bytes, int waves, void *hip_stream,
+                              void *ev_before, void *ev_after);
+
 #ifdef __cplusplus
 }
 #endif

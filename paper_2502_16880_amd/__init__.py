@@ -76,6 +76,8 @@ def _load():
     L.coral_lmhead_grouped_logprob_profiled.argtypes = L.coral_lmhead_grouped_profiled.argtypes
     L.coral_lmhead_dense_profiled.restype = c.c_int
     L.coral_lmhead_dense_profiled.argtypes = L.coral_lmhead_dense.argtypes + [c.c_void_p] * 2
+    L.coral_probe_read.restype = c.c_int
+    L.coral_probe_read.argtypes = [c.c_void_p, c.c_size_t, c.c_int, c.c_void_p, c.c_void_p, c.c_void_p]
     L.coral_router_premix.restype = c.c_int
     L.coral_router_premix.argtypes = [c.c_void_p, c.c_void_p, c.c_int, c.c_int, c.c_int, c.c_int,
                                       c.c_void_p, c.c_void_p]
@@ -340,6 +342,14 @@ def coral_lmhead_grouped_noalloc(hidden: torch.Tensor, gate_W: torch.Tensor,
         M, H, V, g, k, dt, _dev_ptr(topk_ids, "topk_ids", torch.int32),
         _dev_ptr(topk_logits, "topk_logits", torch.float32),
         _dev_ptr(sel_groups, "sel_groups", torch.int32), _stream_ptr(stream)))
+
+
+def coral_probe_read(src: torch.Tensor, nbytes: int, waves: int, events, stream=None) -> None:
+    """coral_probe_read of the C ABI: a kernel that only reads the first nbytes of src."""
+    if not src.is_cuda or not src.is_contiguous() or src.numel() * src.element_size() < nbytes:
+        raise ValueError("src must be a contiguous device tensor of at least nbytes bytes")
+    _raise(_L.coral_probe_read(src.data_ptr(), int(nbytes), int(waves), _stream_ptr(stream),
+                               events[0], events[1]))
 
 
 ACTIVATIONS = {"silu": 0, "relu": 1, "identity": 2}

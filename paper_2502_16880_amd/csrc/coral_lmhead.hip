@@ -476,6 +476,39 @@ coral_status launch_tiles(bool dense, const void* hidden, const void* lm_W,
 
 }  // namespace
 
+// Yardstick for the bench line: a kernel that only reads, in the single-launch path's shape.
+// One workgroup per compute unit, `waves` waves each; a wave takes consecutive 16 KB pieces
+// dealt round robin over waves and workgroups, 16 non-temporal 1 KB loads in flight per piece.
+namespace {
+__global__ __launch_bounds__(kFusedBlock) void k_probe_read(const uint4* __restrict__ src, unsigned long long pieces) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const unsigned long long stride = (unsigned long long)gridDim.x * (blockDim.x / kWave);
+    unsigned x = 0u;
+    for (unsigned long long q = (unsigned long long)blockIdx.x * (blockDim.x / kWave) + wave; q < pieces; q += stride) {
+        const uint4* p = src + q * 1024 + lane;
+        uint4 v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = load_stream(p + i * kWave);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x ^= v[i].x ^ v[i].y ^ v[i].z ^ v[i].w;
+    }
+    asm volatile("" ::"v"(x));                          // (keeps the loads: nothing is written)
+}
+}  // namespace
+
+extern "C" coral_status coral_probe_read(const void* src, size_t bytes, int waves, void* hip_stream,
+                                         void* ev_before, void* ev_after) {
+    if (!src || !ev_before || !ev_after) return CORAL_ERR_NULL;
+    if (bytes < 16384 || bytes % 16384 != 0 || waves < 1 || waves > kFusedWaves) return CORAL_ERR_SHAPE;
+    if ((uintptr_t)src & 15u) return CORAL_ERR_UNSUPPORTED;
+    int P = compute_units();
+    if (P < 1) return CORAL_ERR_HIP;
+    if (P > kMaxWorkgroups) P = kMaxWorkgroups;
+    return launch_timed(k_probe_read, dim3(P), dim3(waves * kWave), 0, static_cast<hipStream_t>(hip_stream),
+                        ev_before, ev_after, static_cast<const uint4*>(src), (unsigned long long)(bytes / 16384));
+}
+
 extern "C" const char* coral_status_string(coral_status st) {
     switch (st) {
         case CORAL_OK: return "ok";

@@ -34,6 +34,15 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
 
+def test_probe_read_checks_its_arguments_on_the_host():
+    L = coral._L
+    assert L.coral_probe_read(None, 16384, 16, None, 1, 1) == 1               # CORAL_ERR_NULL
+    assert L.coral_probe_read(4096, 16384, 16, None, None, 1) == 1
+    assert L.coral_probe_read(4096, 1000, 16, None, 1, 1) == 2                # CORAL_ERR_SHAPE
+    assert L.coral_probe_read(4096, 16384, 17, None, 1, 1) == 2
+    assert L.coral_probe_read(4100, 16384, 16, None, 1, 1) == 4               # CORAL_ERR_UNSUPPORTED
+
+
 def test_status_strings():
     seen = {coral.coral_status_string(i) for i in range(7)}
     assert len(seen) == 7 and coral.coral_status_string(0) == "ok"

@@ -591,6 +591,26 @@ def test_measurement_entry_points_time_the_kernel_and_change_nothing(coral, name
             assert torch.equal(x, y), which
 
 
+def test_probe_read_runs_and_times_itself(coral):
+    """The read-only yardstick kernel: launches, leaves its source alone, and its events read
+    a duration that grows with the bytes."""
+    src = torch.arange(1 << 30, dtype=torch.uint8, device="cuda")     # (far beyond the last-level cache)
+    keep = src.clone()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(), b.record()
+    torch.cuda.synchronize()
+    times = []
+    for nbytes in (1 << 20, 1 << 30):
+        for _ in range(3):
+            coral.coral_probe_read(src, nbytes, 16, (a.cuda_event, b.cuda_event))
+            torch.cuda.synchronize()
+        times.append(a.elapsed_time(b))
+    assert 0.0 < times[0] < times[1]
+    assert torch.equal(src, keep)
+    with pytest.raises(coral.CoralError):
+        coral.coral_probe_read(src, 1000, 16, (a.cuda_event, b.cuda_event))
+
+
 def test_prepared_call_is_the_plain_call(coral):
     """PreparedGrouped marshals once and enters the same entry point: same results, bit for
     bit, also on another stream and in the log-probability mode."""
